@@ -1,0 +1,186 @@
+/*
+ * nqkv.h -- C ABI of the NQKV hot path for AMD MI355X (gfx950).
+ *
+ * NQKV (arXiv 2505.16210) stores the key/value cache of a transformer decoder as k-bit
+ * indices into a small table of normal-distribution quantile points, one table look-up
+ * range ("block") at a time, and dequantizes the cache when attention needs it
+ * (paper Sec. 3.2 and Fig. 5).  This library implements exactly that path for one GPU:
+ *
+ *   nqkv_build_codebook    the quantile table                        (Sec. 1, Sec. 3.2)
+ *   nqkv_quantize_kv       fp16 K or V -> packed indices + scales    (Sec. 3.2 prefill eqs;
+ *   nqkv_quantize_kv_pair  K and V in one launch                      decoding-phase append)
+ *   nqkv_dequantize_kv     indices -> fp16                           (Sec. 3.2, X' = dequantize(I))
+ *   nqkv_decode_attention  softmax(q K'^T) V' read straight from the packed cache
+ *                                                                    (Sec. 3.2 decoding phase)
+ *
+ * General rules
+ *   - Every function returns NQKV_OK (0) or a negative NQKV_E* code.  Nothing throws,
+ *     prints or exits.  All argument checks happen on the host before any GPU work, so a
+ *     call that returns an error other than NQKV_EHIP has launched nothing.
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary memory.  The library allocates no device memory and keeps no state between
+ *     calls (nqkv_set_tuning aside).  Device pointers must be 16-byte aligned.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on that stream and return; they never synchronise.
+ *   - fp16 means IEEE binary16.  Inputs must be finite (not checked).
+ *   - Results are bitwise reproducible for equal arguments (no floating-point atomics).
+ *
+ * Cache layout (one tensor, K or V), for B batch rows, H heads, head dimension D, k bits,
+ * block size `block`, capacity cap_tokens:
+ *   codes  : uint8  [B][H][cap_tokens][D*k/8]   element i of a (b,h,token) row owns bits
+ *                                               [k*i, k*i+k) of that row's little-endian
+ *                                               bit stream (bit n = bit n&7 of byte n>>3)
+ *   scales : fp16   [B][H][cap_tokens][D/block] max |x| over `block` consecutive head-dim
+ *                                               elements of one token of one head
+ * A block never spans tokens or heads (Fig. 5 caption: every token is cut into blocks).
+ *
+ * Quantization rule (the paper leaves rounding details open; this is the library's
+ * contract): with s = the block's fp16 scale, t_j = (c[j-1] + c[j]) * 0.5f the fp32
+ * mid-points of the ascending table c[0..2^k-1],
+ *     code(x) = number of j in [1, 2^k - 1] with  (float)x > fl32(t_j * (float)s)
+ * i.e. nearest table entry, ties to the lower index.  An all-zero block gets code 0
+ * everywhere and scale 0.
+ */
+#ifndef NQKV_H_
+#define NQKV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  NQKV_OK = 0,
+  NQKV_EINVAL = -1,        /* null / misaligned pointer, size or range out of bounds        */
+  NQKV_EUNSUPPORTED = -2,  /* well-formed but outside what the kernels are built for        */
+  NQKV_EWORKSPACE = -3,    /* workspace smaller than nqkv_decode_workspace_bytes reports    */
+  NQKV_EHIP = -4           /* a HIP runtime call (kernel launch) failed                     */
+};
+
+/* Static, NUL-terminated description of a status code. */
+const char* nqkv_strerror(int status);
+
+/* Library ABI version (major * 100 + minor). */
+int nqkv_version(void);
+
+/*
+ * Experiment switches for benchmarking, process-wide, not thread-safe: set them while no call
+ * is in flight.  They never change results (codes stay bit-identical, attention stays within
+ * its tolerance), only which kernel variant or launch shape is used.
+ *   knob 0  quantizer: 0 = cell-table code search (default), 1 = plain scan of all thresholds
+ *   knob 1  decode attention: workgroups aimed for when num_splits == 0 (0 = default)
+ * Returns NQKV_EINVAL for an unknown knob or value.
+ */
+int nqkv_set_tuning(int knob, int value);
+
+/*
+ * Quantile table (Sec. 1: "quantile points from a normal distribution as data points").
+ * Host only; touches no GPU.
+ *   k          bits per index, 1..8 (the kernels accept tables for k = 2, 3, 4)
+ *   variant    0: symmetric table, level i = Phi^-1((i + 1/2) / 2^k) divided by the largest
+ *                 level, i.e. the medians of 2^k equal-probability slices of N(0,1);
+ *                 levels_out[i] == -levels_out[2^k-1-i] exactly
+ *              1: zero-preserving table in the NormalFloat style the paper cites for its
+ *                 4-bit runs: 2^(k-1) positive levels, an exact 0 and 2^(k-1)-1 negative
+ *                 levels, each side from evenly spaced probabilities in (1/2, 1 - 2^-(k+1)]
+ *                 pushed through Phi^-1 and divided by the largest (k >= 2)
+ *   levels_out host float[2^k], ascending, levels_out[0] = -1, levels_out[2^k-1] = +1
+ */
+int nqkv_build_codebook(int k, int variant, float* levels_out);
+
+/* Geometry of one cache tensor.  Plain data, read during the call only. */
+typedef struct nqkv_cache_desc {
+  int32_t B;           /* batch rows, >= 1                                                   */
+  int32_t H;           /* heads, >= 1; B*H <= 65535                                          */
+  int32_t D;           /* head dimension: 64 or 128                                          */
+  int32_t k;           /* bits per index: 2, 3 or 4                                          */
+  int32_t block;       /* elements per scale: 64 or 128, must divide D                       */
+  int32_t reserved;    /* must be 0                                                          */
+  int64_t cap_tokens;  /* token capacity of the codes / scales arrays, >= 1                  */
+} nqkv_cache_desc;
+
+/*
+ * Quantize n_tokens tokens of one tensor into cache rows
+ * [dst_token_offset, dst_token_offset + n_tokens)  (Sec. 3.2: I = quantize(X) at prefill;
+ * at decode the new token's indices are appended and older entries never change -- prefill
+ * and append are this same call with different offsets).
+ *   levels  host float[2^k], ascending (from nqkv_build_codebook or the caller's own)
+ *   src     device fp16, logical shape [B][H][n_tokens][D]; element (b,h,t,d) is at
+ *           src + b*stride_b + h*stride_h + t*stride_t + d (strides in elements, D contiguous,
+ *           stride_t a multiple of 8)
+ *   codes, scales  device, layouts above; rows outside the written range are untouched
+ * Errors: NQKV_EINVAL for null/misaligned pointers, n_tokens < 0, a range outside
+ * [0, cap_tokens], a non-ascending table; NQKV_EUNSUPPORTED for D/k/block outside the lists
+ * above.  n_tokens == 0 is a successful no-op whatever the data pointers are.
+ */
+int nqkv_quantize_kv(const nqkv_cache_desc* desc, const float* levels,
+                     const void* src, int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                     int64_t n_tokens, int64_t dst_token_offset,
+                     void* codes, void* scales, void* hip_stream);
+
+/*
+ * The same for a key tensor and a value tensor of equal geometry and strides in ONE kernel
+ * launch (the decode-step append of Sec. 3.2 quantizes t_K and t_V together).
+ */
+int nqkv_quantize_kv_pair(const nqkv_cache_desc* desc, const float* levels,
+                          const void* k_src, const void* v_src,
+                          int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                          int64_t n_tokens, int64_t dst_token_offset,
+                          void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                          void* hip_stream);
+
+/*
+ * Dequantize cache rows [token_offset, token_offset + n_tokens) to fp16
+ * (Fig. 5 caption: indices are looked up in the table and restored to FP16):
+ *     dst = fp16_round_to_nearest_even( fl32( levels[code] * (float)scale ) )
+ *   dst  device fp16, logical [B][H][n_tokens][D], strides as for nqkv_quantize_kv.
+ */
+int nqkv_dequantize_kv(const nqkv_cache_desc* desc, const float* levels,
+                       const void* codes, const void* scales,
+                       int64_t token_offset, int64_t n_tokens,
+                       void* dst, int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                       void* hip_stream);
+
+/*
+ * Workspace needed by nqkv_decode_attention for a given sequence length.
+ *   num_splits  0: the library chooses how many pieces each (b,h) sequence is cut into;
+ *               >0: use exactly this many (1..1024, at most seq_len)
+ *   bytes_out   receives the workspace size in bytes (0 when one piece is used)
+ *   splits_out  receives the number of pieces that will be used (may be NULL)
+ * Host only.
+ */
+int nqkv_decode_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, int num_splits,
+                                size_t* bytes_out, int* splits_out);
+
+/*
+ * Attention of one new query per (batch, head) over the first seq_len cached tokens
+ * (Sec. 3.2 decoding phase: A = Softmax(t_Q X_K'^T), t_O = A X_V', with X' the dequantized
+ * cache), computed without materialising X':
+ *     z_t   = softmax_scale * sum_d q[d] * levels[Kcode[t,d]] * Kscale[t, d/block]
+ *     out_d = sum_t exp(z_t - max z) * levels[Vcode[t,d]] * Vscale[t, d/block] / sum_t exp(z_t - max z)
+ * The token appended in this decode step must already be in the cache (append first, then
+ * attend, as in the paper).  K and V caches share `desc`.
+ *   q, out        device fp16 [B][H][D] contiguous
+ *   workspace     device memory of at least the size reported by nqkv_decode_workspace_bytes
+ *                 for the same (desc, seq_len, num_splits); may be NULL when that size is 0
+ * Arithmetic: table entries are rounded to fp16 for the look-up, products accumulate in
+ * fp32, exp in fp32; the result is within 2e-3 (relative to the largest |out| of the row)
+ * of the same formula evaluated in fp64.  Different num_splits give results that differ
+ * by rounding only; equal arguments give equal bits.
+ * Errors: as above, plus NQKV_EINVAL for seq_len outside [1, cap_tokens] and
+ * NQKV_EWORKSPACE for a short workspace.
+ */
+int nqkv_decode_attention(const nqkv_cache_desc* desc, const float* levels,
+                          const void* q,
+                          const void* k_codes, const void* k_scales,
+                          const void* v_codes, const void* v_scales,
+                          int64_t seq_len, float softmax_scale, void* out,
+                          void* workspace, size_t workspace_bytes, int num_splits,
+                          void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NQKV_H_ */

@@ -1,0 +1,353 @@
+// Host side of libnqkv: the C ABI declared in include/nqkv.h -- argument validation, the
+// quantile table, split planning and kernel dispatch.  Every check runs before any HIP call,
+// so error paths are testable on a machine without a GPU.
+#include "../../include/nqkv.h"
+#include "nqkv_internal.h"
+
+#include <cmath>
+#include <cstring>
+
+namespace {
+
+using namespace nqkv;
+
+// Experiment switches (see nqkv_set_tuning).  Plain ints: set them before issuing work.
+int g_quantize_impl = 0;       // 0 cell table, 1 threshold scan
+int g_decode_target_wgs = 0;   // 0 = default
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_desc(const nqkv_cache_desc* d) {
+  if (!d) return NQKV_EINVAL;
+  if (d->B < 1 || d->H < 1 || d->cap_tokens < 1 || d->reserved != 0) return NQKV_EINVAL;
+  if (d->D < 1 || d->k < 1 || d->block < 1) return NQKV_EINVAL;
+  if (d->k != 2 && d->k != 3 && d->k != 4) return NQKV_EUNSUPPORTED;
+  if (d->D != 64 && d->D != 128) return NQKV_EUNSUPPORTED;
+  if (d->block != 64 && d->block != 128) return NQKV_EUNSUPPORTED;
+  if (d->D % d->block != 0) return NQKV_EINVAL;
+  if ((int64_t)d->B * d->H > 65535) return NQKV_EUNSUPPORTED;
+  if (d->cap_tokens > (int64_t)1 << 31) return NQKV_EUNSUPPORTED;
+  return NQKV_OK;
+}
+
+int check_levels(const float* levels, int k, LevelTable* out) {
+  if (!levels) return NQKV_EINVAL;
+  const int L = 1 << k;
+  for (int i = 0; i < L; ++i) {
+    if (!std::isfinite(levels[i])) return NQKV_EINVAL;
+    if (i > 0 && !(levels[i] > levels[i - 1])) return NQKV_EINVAL;
+  }
+  std::memset(out, 0, sizeof(*out));
+  for (int i = 0; i < L; ++i) out->v[i] = levels[i];
+  return NQKV_OK;
+}
+
+int check_strided(const nqkv_cache_desc* d, int64_t sb, int64_t sh, int64_t st, int64_t n_tokens) {
+  if (sb < 0 || sh < 0 || st < 0) return NQKV_EINVAL;
+  if ((sb % 8) || (sh % 8) || (st % 8)) return NQKV_EINVAL;   // every row 16-byte aligned
+  if (n_tokens > 1 && st < d->D) return NQKV_EINVAL;
+  // offsets inside one (b,h) slab are formed in 32 bits of chunk index
+  if (n_tokens * (d->D / 8) >= ((int64_t)1 << 31) - 4096) return NQKV_EUNSUPPORTED;
+  return NQKV_OK;
+}
+
+int check_range(const nqkv_cache_desc* d, int64_t off, int64_t n) {
+  if (n < 0 || off < 0 || off > d->cap_tokens || n > d->cap_tokens - off) return NQKV_EINVAL;
+  return NQKV_OK;
+}
+
+// Upper-tail normal quantile by Newton's method on Q(x) = erfc(x / sqrt 2) / 2, started at 0.
+// Q is convex and decreasing on x >= 0, so the iterates climb monotonically to the root.
+double normal_upper_quantile(double tail) {
+  const double inv_sqrt2 = 0.70710678118654752440;
+  const double inv_sqrt_2pi = 0.39894228040143267794;
+  double x = 0.0;
+  for (int it = 0; it < 200; ++it) {
+    const double q = 0.5 * std::erfc(x * inv_sqrt2);
+    const double pdf = inv_sqrt_2pi * std::exp(-0.5 * x * x);
+    const double step = (q - tail) / pdf;
+    x += step;
+    if (std::fabs(step) <= 1e-17 * (1.0 + x)) break;
+  }
+  return x;
+}
+
+// ---- fp16 look-up table for the attention kernel ---------------------------------------
+// binary32 -> binary16 bits, round to nearest even (host rounding mode is the default one).
+uint16_t f32_to_f16_bits(float x) {
+  const uint16_t sign = std::signbit(x) ? 0x8000u : 0u;
+  const double a = std::fabs((double)x);
+  if (a == 0.0) return sign;
+  int e2;
+  const double m = std::frexp(a, &e2);      // a = m * 2^e2, m in [0.5, 1)
+  int E = e2 - 1;                           // a = (2m) * 2^E, 2m in [1, 2)
+  if (E < -14) {                            // subnormal half: units of 2^-24
+    const double qd = std::nearbyint(std::ldexp(a, 24));
+    return (uint16_t)(sign | (uint16_t)qd); // 1024 encodes the smallest normal, as it should
+  }
+  double qd = std::nearbyint(std::ldexp(m, 11));   // 2m * 1024 in [1024, 2048]
+  if (qd >= 2048.0) { qd = 1024.0; ++E; }
+  if (E > 15) return (uint16_t)(sign | 0x7c00u);
+  return (uint16_t)(sign | ((uint32_t)(E + 15) << 10) | ((uint32_t)qd - 1024u));
+}
+
+double f16_bits_to_f64(uint16_t h) {
+  const int e = (h >> 10) & 31, m = h & 1023;
+  const double v = e ? std::ldexp(1024.0 + m, e - 25) : std::ldexp((double)m, -24);
+  return (h & 0x8000u) ? -v : v;
+}
+
+// Picks gamma (itself an fp16 number in [1/4, 8)) minimising the worst relative error of
+// fp16(gamma * level[i]) over the table, and returns those fp16 entries.  The last result is
+// remembered per thread, so repeated calls with one table cost a 64-byte compare.
+struct LutChoice {
+  int L = 0;
+  float levels[kMaxLevels];
+  uint16_t bits[kMaxLevels];
+  float gamma = 1.0f;
+};
+
+const LutChoice& choose_lut_scale(const float* levels, int L) {
+  static thread_local LutChoice memo;
+  if (memo.L == L && std::memcmp(memo.levels, levels, sizeof(float) * L) == 0) return memo;
+  double best_err = 1e30, best_gamma = 1.0;
+  for (int E = -2; E <= 2; ++E) {
+    for (int m = 0; m < 1024; ++m) {
+      const double gamma = std::ldexp(1024.0 + m, E - 10);
+      double worst = 0.0;
+      for (int i = 0; i < L && worst < best_err; ++i) {
+        const double exact = gamma * (double)levels[i];
+        if (exact == 0.0) continue;
+        const double got = f16_bits_to_f64(f32_to_f16_bits((float)exact));
+        worst = std::fmax(worst, std::fabs(got - exact) / std::fabs(exact));
+      }
+      if (worst < best_err || (worst == best_err && std::fabs(gamma - 1.0) < std::fabs(best_gamma - 1.0))) {
+        best_err = worst;
+        best_gamma = gamma;
+      }
+    }
+  }
+  memo.L = L;
+  std::memcpy(memo.levels, levels, sizeof(float) * L);
+  memo.gamma = (float)best_gamma;
+  for (int i = 0; i < L; ++i) memo.bits[i] = f32_to_f16_bits((float)(best_gamma * (double)levels[i]));
+  return memo;
+}
+
+int plan_splits(const nqkv_cache_desc* d, int64_t seq_len, int num_splits, int* splits) {
+  if (seq_len < 1 || seq_len > d->cap_tokens) return NQKV_EINVAL;
+  if (num_splits < 0 || num_splits > 1024) return NQKV_EINVAL;
+  if (num_splits > 0) {
+    if ((int64_t)num_splits > seq_len) return NQKV_EINVAL;
+    *splits = num_splits;
+    return NQKV_OK;
+  }
+  // Aim for several resident workgroups on each of the 256 compute units, but keep every
+  // workgroup long enough (two trips per wave) that the table set-up and the merge stay small.
+  const int64_t bh = (int64_t)d->B * d->H;
+  const int64_t target = g_decode_target_wgs > 0 ? g_decode_target_wgs : 1536;
+  const int64_t trip = (int64_t)decode_chunk_tokens(d->D) * 4;      // tokens per workgroup trip
+  int64_t want = (target + bh - 1) / bh;
+  int64_t longest = seq_len / (2 * trip);
+  if (longest < 1) longest = 1;
+  if (want > longest) want = longest;
+  if (want > 1024) want = 1024;
+  if (want < 1) want = 1;
+  *splits = (int)want;
+  return NQKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* nqkv_strerror(int status) {
+  switch (status) {
+    case NQKV_OK: return "ok";
+    case NQKV_EINVAL: return "invalid argument (null or misaligned pointer, size or range out of bounds)";
+    case NQKV_EUNSUPPORTED: return "configuration not supported by the gfx950 kernels";
+    case NQKV_EWORKSPACE: return "workspace too small";
+    case NQKV_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int nqkv_version(void) { return 100; }
+
+int nqkv_set_tuning(int knob, int value) {
+  switch (knob) {
+    case 0: if (value != 0 && value != 1) return NQKV_EINVAL; g_quantize_impl = value; return NQKV_OK;
+    case 1: if (value < 0 || value > 65536) return NQKV_EINVAL; g_decode_target_wgs = value; return NQKV_OK;
+    default: return NQKV_EINVAL;
+  }
+}
+
+int nqkv_build_codebook(int k, int variant, float* levels_out) {
+  if (k < 1 || k > 8 || !levels_out) return NQKV_EINVAL;
+  if (variant != 0 && variant != 1) return NQKV_EINVAL;
+  const int L = 1 << k;
+  double lev[256];
+  if (variant == 0) {
+    // level i = median of the i-th of L equal-probability slices of N(0,1), over the largest
+    const double top = normal_upper_quantile(1.0 / (2.0 * L));
+    const int half = L / 2;
+    for (int m = 0; m < half; ++m) {          // m-th positive level, counted from the centre
+      const double tail = (2.0 * (half - 1 - m) + 1.0) / (2.0 * L);
+      const double v = (m == half - 1) ? 1.0 : normal_upper_quantile(tail) / top;
+      lev[half + m] = v;
+      lev[half - 1 - m] = -v;
+    }
+  } else {
+    if (k < 2) return NQKV_EINVAL;
+    const double delta = std::ldexp(1.0, -(k + 1));
+    const int n_pos = L / 2, n_neg = L / 2 - 1;
+    const double top = normal_upper_quantile(delta);
+    lev[n_neg] = 0.0;
+    for (int m = 1; m <= n_pos; ++m) {
+      const double tail = 0.5 - m * (0.5 - delta) / n_pos;
+      lev[n_neg + m] = (m == n_pos) ? 1.0 : normal_upper_quantile(tail) / top;
+    }
+    for (int m = 1; m <= n_neg; ++m) {
+      const double tail = 0.5 - m * (0.5 - delta) / n_neg;
+      lev[n_neg - m] = (m == n_neg) ? -1.0 : -normal_upper_quantile(tail) / top;
+    }
+  }
+  for (int i = 0; i < L; ++i) levels_out[i] = (float)lev[i];
+  return NQKV_OK;
+}
+
+int nqkv_quantize_kv_pair(const nqkv_cache_desc* desc, const float* levels,
+                          const void* k_src, const void* v_src,
+                          int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                          int64_t n_tokens, int64_t dst_token_offset,
+                          void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                          void* hip_stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  QuantParams p;
+  std::memset(&p, 0, sizeof(p));
+  if ((rc = check_levels(levels, desc->k, &p.levels))) return rc;
+  if ((rc = check_range(desc, dst_token_offset, n_tokens))) return rc;
+  if ((rc = check_strided(desc, stride_b, stride_h, stride_t, n_tokens))) return rc;
+  if (n_tokens == 0) return NQKV_OK;           // nothing to do: pointers are not looked at
+  const bool pair = v_src || v_codes || v_scales;
+  if (!k_src || !k_codes || !k_scales || !aligned16(k_src) || !aligned16(k_codes) || !aligned16(k_scales))
+    return NQKV_EINVAL;
+  if (pair && (!v_src || !v_codes || !v_scales || !aligned16(v_src) || !aligned16(v_codes) || !aligned16(v_scales)))
+    return NQKV_EINVAL;
+  if (pair && (int64_t)desc->B * 2 > 65535) return NQKV_EUNSUPPORTED;
+  p.t[0].src = static_cast<const uint16_t*>(k_src);
+  p.t[0].codes = static_cast<uint8_t*>(k_codes);
+  p.t[0].scales = static_cast<uint16_t*>(k_scales);
+  p.t[1].src = static_cast<const uint16_t*>(v_src);
+  p.t[1].codes = static_cast<uint8_t*>(v_codes);
+  p.t[1].scales = static_cast<uint16_t*>(v_scales);
+  p.n_tensors = pair ? 2 : 1;
+  p.B = desc->B;
+  p.H = desc->H;
+  p.stride_b = stride_b;
+  p.stride_h = stride_h;
+  p.stride_t = stride_t;
+  p.n_tokens = n_tokens;
+  p.tok_off = dst_token_offset;
+  p.cap_tokens = desc->cap_tokens;
+  p.impl = (g_quantize_impl == 0 && build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) ? 0 : 1;
+  const hipError_t e = launch_quantize(p, desc->D, desc->k, desc->block, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
+}
+
+int nqkv_quantize_kv(const nqkv_cache_desc* desc, const float* levels,
+                     const void* src, int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                     int64_t n_tokens, int64_t dst_token_offset,
+                     void* codes, void* scales, void* hip_stream) {
+  return nqkv_quantize_kv_pair(desc, levels, src, nullptr, stride_b, stride_h, stride_t, n_tokens,
+                               dst_token_offset, codes, scales, nullptr, nullptr, hip_stream);
+}
+
+int nqkv_dequantize_kv(const nqkv_cache_desc* desc, const float* levels,
+                       const void* codes, const void* scales,
+                       int64_t token_offset, int64_t n_tokens,
+                       void* dst, int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                       void* hip_stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  QuantParams p;
+  std::memset(&p, 0, sizeof(p));
+  if ((rc = check_levels(levels, desc->k, &p.levels))) return rc;
+  if ((rc = check_range(desc, token_offset, n_tokens))) return rc;
+  if ((rc = check_strided(desc, stride_b, stride_h, stride_t, n_tokens))) return rc;
+  if (n_tokens == 0) return NQKV_OK;           // nothing to do: pointers are not looked at
+  if (!codes || !scales || !dst || !aligned16(codes) || !aligned16(scales) || !aligned16(dst)) return NQKV_EINVAL;
+  p.t[0].codes = const_cast<uint8_t*>(static_cast<const uint8_t*>(codes));
+  p.t[0].scales = const_cast<uint16_t*>(static_cast<const uint16_t*>(scales));
+  p.t[0].dst = static_cast<uint16_t*>(dst);
+  p.n_tensors = 1;
+  p.B = desc->B;
+  p.H = desc->H;
+  p.stride_b = stride_b;
+  p.stride_h = stride_h;
+  p.stride_t = stride_t;
+  p.n_tokens = n_tokens;
+  p.tok_off = token_offset;
+  p.cap_tokens = desc->cap_tokens;
+  const hipError_t e = launch_dequantize(p, desc->D, desc->k, desc->block, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
+}
+
+int nqkv_decode_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, int num_splits,
+                                size_t* bytes_out, int* splits_out) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!bytes_out) return NQKV_EINVAL;
+  int splits = 1;
+  if ((rc = plan_splits(desc, seq_len, num_splits, &splits))) return rc;
+  *bytes_out = splits > 1 ? (size_t)desc->B * desc->H * splits * (desc->D + 2) * sizeof(float) : 0;
+  if (splits_out) *splits_out = splits;
+  return NQKV_OK;
+}
+
+int nqkv_decode_attention(const nqkv_cache_desc* desc, const float* levels,
+                          const void* q,
+                          const void* k_codes, const void* k_scales,
+                          const void* v_codes, const void* v_scales,
+                          int64_t seq_len, float softmax_scale, void* out,
+                          void* workspace, size_t workspace_bytes, int num_splits,
+                          void* hip_stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  DecodeParams p;
+  std::memset(&p, 0, sizeof(p));
+  LevelTable checked;
+  if ((rc = check_levels(levels, desc->k, &checked))) return rc;
+  int splits = 1;
+  if ((rc = plan_splits(desc, seq_len, num_splits, &splits))) return rc;
+  if (!std::isfinite(softmax_scale)) return NQKV_EINVAL;
+  const void* ptrs[] = {q, k_codes, k_scales, v_codes, v_scales, out};
+  for (const void* ptr : ptrs) {
+    if (!ptr || !aligned16(ptr)) return NQKV_EINVAL;
+  }
+  const size_t need = splits > 1 ? (size_t)desc->B * desc->H * splits * (desc->D + 2) * sizeof(float) : 0;
+  if (need > 0) {
+    if (!workspace || !aligned16(workspace)) return NQKV_EINVAL;
+    if (workspace_bytes < need) return NQKV_EWORKSPACE;
+  }
+  p.q = static_cast<const uint16_t*>(q);
+  p.k_codes = static_cast<const uint8_t*>(k_codes);
+  p.k_scales = static_cast<const uint16_t*>(k_scales);
+  p.v_codes = static_cast<const uint8_t*>(v_codes);
+  p.v_scales = static_cast<const uint16_t*>(v_scales);
+  p.out = static_cast<uint16_t*>(out);
+  p.workspace = static_cast<float*>(workspace);
+  p.BH = desc->B * desc->H;
+  p.splits = splits;
+  p.cap_tokens = desc->cap_tokens;
+  p.seq_len = seq_len;
+  const LutChoice& lut = choose_lut_scale(checked.v, 1 << desc->k);
+  std::memcpy(p.lut_levels, lut.bits, sizeof(uint16_t) * (1 << desc->k));
+  p.inv_gamma = 1.0f / lut.gamma;
+  p.scale_log2e = (float)((double)softmax_scale * 1.44269504088896340736 / (double)lut.gamma);
+  const hipError_t e = launch_decode_attention(p, desc->D, desc->k, desc->block, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,69 @@
+// Internal declarations shared by the host layer and the kernel translation units of
+// libnqkv.  Nothing here is part of the public ABI (see include/nqkv.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nqkv {
+
+constexpr int kMaxLevels = 16;  // kernels take tables for k <= 4
+constexpr int kQuantCells = 65;  // index cells of the quantizer's code search
+
+// The quantile table travels to the kernels by value (64 bytes of kernel arguments).
+struct LevelTable {
+  float v[kMaxLevels];
+};
+
+// One tensor's worth of pointers for the quantizer / dequantizer.
+struct TensorPtrs {
+  const uint16_t* src;   // fp16 source (quantize) -- unused by dequantize
+  uint16_t* dst;         // fp16 destination (dequantize) -- unused by quantize
+  uint8_t* codes;
+  uint16_t* scales;
+};
+
+struct QuantParams {
+  TensorPtrs t[2];       // [0] = K (or the only tensor), [1] = V
+  int n_tensors;         // 1 or 2
+  int B, H;
+  int64_t stride_b, stride_h, stride_t;  // fp16 tensor strides, in elements
+  int64_t n_tokens;      // tokens to process
+  int64_t tok_off;       // first cache row
+  int64_t cap_tokens;
+  LevelTable levels;
+  int impl;              // 0 = cell-table quantizer, 1 = plain threshold scan
+  uint32_t cell_thr[kQuantCells];    // impl 0: fp32 bits of the threshold that may lie in the cell
+  uint32_t cell_below[kQuantCells];  //         thresholds certainly below the cell
+};
+
+struct DecodeParams {
+  const uint16_t* q;         // [B*H][D] fp16
+  const uint8_t* k_codes;
+  const uint16_t* k_scales;
+  const uint8_t* v_codes;
+  const uint16_t* v_scales;
+  uint16_t* out;             // [B*H][D] fp16
+  float* workspace;          // [B*H][splits][D+2] fp32 (m, l, o[D]) when splits > 1
+  int BH;
+  int splits;
+  int64_t cap_tokens;
+  int64_t seq_len;
+  float scale_log2e;         // softmax_scale * log2(e) / gamma
+  float inv_gamma;           // 1 / gamma: undoes the table scaling on the value side
+  uint16_t lut_levels[kMaxLevels];   // fp16 bits of gamma * level[i] (see choose_lut_scale)
+};
+
+// Each returns hipSuccess or the launch error.  D in {64,128}, k in {2,3,4}, blk in {64,128}.
+hipError_t launch_quantize(const QuantParams& p, int D, int k, int blk, hipStream_t stream);
+hipError_t launch_dequantize(const QuantParams& p, int D, int k, int blk, hipStream_t stream);
+hipError_t launch_decode_attention(const DecodeParams& p, int D, int k, int blk, hipStream_t stream);
+
+// Tokens one wave of the attention kernel consumes per main-loop trip; split boundaries are
+// multiples of this.
+int decode_chunk_tokens(int D);
+
+// Fills the quantizer's cell table; false when the table does not admit one (then use impl 1).
+bool build_cell_table(const float* levels, int k, uint32_t* thr_bits, uint32_t* below);
+
+}  // namespace nqkv

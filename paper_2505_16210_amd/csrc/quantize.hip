@@ -1,0 +1,266 @@
+// Block-wise quantile quantization of a K or V tensor into the packed cache
+// (paper Sec. 3.2: I = quantize(X); Fig. 5: every token is cut into blocks and each block
+// is quantized on its own).  gfx950 only.
+//
+// Work decomposition: one lane owns one 16-byte chunk = 8 consecutive fp16 of a token row,
+// so a 64-element block is shared by 8 neighbouring lanes (16 for a 128-element block) and
+// the block's max |x| is an all-reduce over those lanes done with DPP lane permutes -- no
+// LDS, no barrier.  Loads are 128-bit and fully coalesced (a wave reads 1 KiB contiguous);
+// each lane stores the 8 codes it produced as one 32-bit word (k = 4), or lanes of a pair /
+// quad merge their 16- / 24-bit pieces first (k = 2 / 3) so that stores are whole dwords.
+//
+// Deciding the code.  The contract is  code = #{ j : x > fl32(t_j * s) }  over the fp32
+// mid-point thresholds t_j.  Scanning all 2^k - 1 thresholds costs about two VALU
+// operations per threshold and element, which at k = 4 would make the kernel ALU-bound
+// well below HBM speed.  The "cell table" path gets the same codes with about eight
+// operations per element: u = x * (32 / s) + 32.5 lands in one of 65 unit cells; for each
+// cell a table (built once per workgroup in LDS from the thresholds) holds how many
+// thresholds lie safely below the cell and the single threshold that may fall inside it,
+// so one exact comparison against fl32(t * s) finishes the count.  The index u is only
+// approximate (reciprocal, rounding), therefore a threshold counts as "inside" a cell when
+// it is within the cell widened by a margin larger than any error u can carry; a table for
+// which some widened cell would hold two thresholds is routed to the plain scan instead.
+#include "nqkv_internal.h"
+
+#include <cstring>
+
+namespace nqkv {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;       // chunks per lane, all loads issued before any use
+
+// Cell grid of the fast path: u = 32 * x/s + 32.5 in [0.5, 64.5], cell = floor(u).
+constexpr int kCells = kQuantCells;
+constexpr float kCellScale = 32.0f;
+constexpr float kCellBias = 32.5f;
+// u is produced by an fma whose result is forced onto a 1/8 grid (error <= 1/16) from a
+// reciprocal good to 1 ulp (error < 1e-5 in u); 0.08 leaves > 5e-4 of slack in x/s, far more
+// than the 2^-24 relative rounding of fl32(t * s).
+constexpr float kCellMargin = 0.08f;
+// Adding 2^20 puts the integer part of u in mantissa bits [3, 10): (bits & 0x3f8) is then
+// the byte offset of an 8-byte table entry.
+constexpr float kCellMagic = 1048576.0f + kCellBias;
+
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(us2, a),
+                                                                __builtin_bit_cast(us2, b)));
+}
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+// DPP controls: lane permutes inside a row of 16 lanes.
+constexpr int kQuadXor1 = 0xB1;       // quad_perm [1,0,3,2]
+constexpr int kQuadXor2 = 0x4E;       // quad_perm [2,3,0,1]
+constexpr int kRowHalfMirror = 0x141; // lane i <-> 7-i within 8
+constexpr int kRowMirror = 0x140;     // lane i <-> 15-i within 16
+constexpr int kQuadNext = 0xF9;       // quad_perm [1,2,3,3]: value of the next lane in the quad
+constexpr int kQuadOdd = 0xF5;        // quad_perm [1,1,3,3]: value of the odd lane of each pair
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h) {
+  return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+}
+
+// The cell table is built on the host (build_cell_table below) and arrives in the kernel
+// arguments; each workgroup copies it into LDS once.
+__device__ __forceinline__ void stage_cells(const QuantParams& p, uint2* cells) {
+  if (threadIdx.x < kCells) cells[threadIdx.x] = make_uint2(p.cell_thr[threadIdx.x], p.cell_below[threadIdx.x]);
+  __syncthreads();
+}
+
+// Codes of the 8 fp16 values in w against scale bits s_bits, packed LSB-first, KBITS each.
+template <int KBITS, bool FAST>
+__device__ __forceinline__ uint32_t encode_chunk(const uint4& w, uint32_t s_bits, const LevelTable& lv,
+                                                 const uint2* cells) {
+  const float s32 = half_bits_to_float(s_bits);
+  const uint32_t words[4] = {w.x, w.y, w.z, w.w};
+  uint32_t packed = 0;
+  if (FAST) {
+    const float inv = s_bits ? kCellScale * __builtin_amdgcn_rcpf(s32) : 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t h = (e & 1) ? (words[e >> 1] >> 16) : (words[e >> 1] & 0xffffu);
+      const float x = half_bits_to_float(h);
+      const float u = __builtin_fmaf(x, inv, kCellMagic);
+      const uint32_t off = __float_as_uint(u) & 0x3f8u;
+      const uint2 ent = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(cells) + off);
+      const float T = __uint_as_float(ent.x) * s32;        // fl32(t * s): one rounding
+      const uint32_t code = ent.y + ((x > T) ? 1u : 0u);
+      packed |= code << (KBITS * e);
+    }
+  } else {
+    float T[(1 << KBITS) - 1];
+#pragma unroll
+    for (int j = 1; j < (1 << KBITS); ++j) {
+      const float t = (lv.v[j - 1] + lv.v[j]) * 0.5f;
+      T[j - 1] = t * s32;                                  // fl32(t * s): one rounding
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t h = (e & 1) ? (words[e >> 1] >> 16) : (words[e >> 1] & 0xffffu);
+      const float x = half_bits_to_float(h);
+      uint32_t code = 0;
+#pragma unroll
+      for (int j = 0; j < (1 << KBITS) - 1; ++j) code += (x > T[j]) ? 1u : 0u;
+      packed |= code << (KBITS * e);
+    }
+  }
+  // all-zero block: every scaled threshold is +-0 and 0 > +-0 is false -> code 0
+  return s_bits ? packed : 0u;
+}
+
+// grid: SLAB  x = chunk tiles of one (b,h) slab, y = h, z = b + B * tensor
+//       FLAT  x = chunk tiles over all rows of a tensor,  z = tensor   (few tokens: append)
+template <int KBITS, int D, int BLK, bool FAST, bool FLAT>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantParams p) {
+  constexpr int CPR = D / 8;      // chunks per token row
+  constexpr int LPB = BLK / 8;    // lanes that share one block
+  constexpr int NB = D / BLK;
+  __shared__ uint2 cells[FAST ? 128 : 1];   // 128 >= kCells: any 7-bit index stays inside
+  if (FAST) stage_cells(p, cells);
+
+  const int tensor = FLAT ? (int)blockIdx.z : (int)(blockIdx.z >= (unsigned)p.B);
+  const TensorPtrs tp = p.t[tensor];
+  const uint32_t n = (uint32_t)p.n_tokens;
+  const uint32_t tile0 = blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+
+  uint4 w[kUnroll];
+  bool valid[kUnroll];
+  uint32_t bh_[kUnroll], t_[kUnroll], part_[kUnroll];
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t c = tile0 + u * kThreads;
+    uint32_t bh, t, b, h;
+    if (FLAT) {
+      const uint32_t row = c / CPR;
+      bh = row / n;
+      t = row - bh * n;
+      b = bh / (uint32_t)p.H;
+      h = bh - b * (uint32_t)p.H;
+      valid[u] = bh < (uint32_t)(p.B * p.H);
+    } else {
+      b = blockIdx.z - (tensor ? (uint32_t)p.B : 0u);
+      h = blockIdx.y;
+      bh = b * (uint32_t)p.H + h;
+      t = c / CPR;
+      valid[u] = t < n;
+    }
+    const uint32_t part = c % CPR;
+    bh_[u] = bh; t_[u] = t; part_[u] = part;
+    w[u] = make_uint4(0, 0, 0, 0);
+    if (valid[u]) {
+      const uint16_t* src = tp.src + (int64_t)b * p.stride_b + (int64_t)h * p.stride_h +
+                            (int64_t)t * p.stride_t + part * 8;
+      w[u] = *reinterpret_cast<const uint4*>(src);
+    }
+  }
+
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    // block scale: max |x| as fp16 bits (for non-negative finite fp16, value order == bit order)
+    const uint32_t M = 0x7fff7fffu;
+    const uint32_t a = pk_max_u16(pk_max_u16(w[u].x & M, w[u].y & M), pk_max_u16(w[u].z & M, w[u].w & M));
+    uint32_t s_bits = max(a & 0xffffu, a >> 16);
+    s_bits = max(s_bits, dpp<kQuadXor1>(s_bits));
+    s_bits = max(s_bits, dpp<kQuadXor2>(s_bits));
+    s_bits = max(s_bits, dpp<kRowHalfMirror>(s_bits));
+    if (LPB == 16) s_bits = max(s_bits, dpp<kRowMirror>(s_bits));
+
+    const uint32_t packed = encode_chunk<KBITS, FAST>(w[u], s_bits, p.levels, cells);
+
+    // destination chunk index inside the (b,h) slab of the cache
+    const int64_t slab_row0 = (int64_t)bh_[u] * p.cap_tokens + p.tok_off;
+    const int64_t chunk = (slab_row0 + t_[u]) * CPR + part_[u];
+    uint32_t* codes32 = reinterpret_cast<uint32_t*>(tp.codes);
+    if (KBITS == 4) {
+      if (valid[u]) codes32[chunk] = packed;
+    } else if (KBITS == 2) {
+      const uint32_t odd = dpp<kQuadOdd>(packed);
+      if (valid[u] && !(threadIdx.x & 1)) codes32[chunk >> 1] = packed | (odd << 16);
+    } else {  // KBITS == 3: four lanes hold 4 x 24 bits = three dwords
+      const uint32_t next = dpp<kQuadNext>(packed);
+      const uint32_t q = threadIdx.x & 3;
+      const uint32_t word = (packed >> (8 * q)) | (next << (24 - 8 * q));
+      if (valid[u] && q != 3) codes32[(chunk >> 2) * 3 + q] = word;
+    }
+    if (valid[u] && (part_[u] % LPB) == 0) {
+      tp.scales[(slab_row0 + t_[u]) * NB + part_[u] / LPB] = (uint16_t)s_bits;
+    }
+  }
+}
+
+template <int KBITS, int D, int BLK>
+hipError_t launch_one(const QuantParams& p, hipStream_t stream) {
+  constexpr int CPR = D / 8;
+  const int64_t chunks_per_slab = p.n_tokens * CPR;
+  const bool flat = chunks_per_slab < 2 * kThreads;
+  const bool fast = p.impl == 0;
+  const int tile = kThreads * kUnroll;
+  dim3 grid;
+  if (flat) {
+    const int64_t total = chunks_per_slab * p.B * p.H;
+    grid = dim3((unsigned)((total + tile - 1) / tile), 1, (unsigned)p.n_tensors);
+  } else {
+    grid = dim3((unsigned)((chunks_per_slab + tile - 1) / tile), (unsigned)p.H,
+                (unsigned)(p.B * p.n_tensors));
+  }
+  if (flat) {
+    if (fast) hipLaunchKernelGGL((quantize_kernel<KBITS, D, BLK, true, true>), grid, dim3(kThreads), 0, stream, p);
+    else      hipLaunchKernelGGL((quantize_kernel<KBITS, D, BLK, false, true>), grid, dim3(kThreads), 0, stream, p);
+  } else {
+    if (fast) hipLaunchKernelGGL((quantize_kernel<KBITS, D, BLK, true, false>), grid, dim3(kThreads), 0, stream, p);
+    else      hipLaunchKernelGGL((quantize_kernel<KBITS, D, BLK, false, false>), grid, dim3(kThreads), 0, stream, p);
+  }
+  return hipGetLastError();
+}
+
+template <int KBITS>
+hipError_t launch_k(const QuantParams& p, int D, int blk, hipStream_t stream) {
+  if (D == 64 && blk == 64) return launch_one<KBITS, 64, 64>(p, stream);
+  if (D == 128 && blk == 64) return launch_one<KBITS, 128, 64>(p, stream);
+  if (D == 128 && blk == 128) return launch_one<KBITS, 128, 128>(p, stream);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+// Entry c = { the one threshold that may lie in cell c widened by the margin (2.0 when there is
+// none: never exceeded, since |x| <= s), number of thresholds certainly below the cell }.
+// Returns false when some widened cell would hold two thresholds or the table leaves [-1, 1]:
+// such tables take the threshold scan.
+bool build_cell_table(const float* levels, int k, uint32_t* thr_bits, uint32_t* below) {
+  const int L = 1 << k;
+  if (!(levels[0] >= -1.0f && levels[L - 1] <= 1.0f)) return false;
+  for (int c = 0; c < kCells; ++c) {
+    const float lo = (float)c - kCellMargin;
+    const float hi = (float)c + 1.0f + kCellMargin;
+    int inside = 0;
+    uint32_t n_below = 0;
+    float cand = 2.0f;
+    for (int j = 1; j < L; ++j) {
+      const float t = (levels[j - 1] + levels[j]) * 0.5f;
+      const float tau = t * kCellScale + kCellBias;
+      if (tau < lo) ++n_below;
+      if (tau >= lo && tau <= hi) { cand = t; ++inside; }
+    }
+    if (inside > 1) return false;
+    std::memcpy(&thr_bits[c], &cand, 4);
+    below[c] = n_below;
+  }
+  return true;
+}
+
+hipError_t launch_quantize(const QuantParams& p, int D, int k, int blk, hipStream_t stream) {
+  switch (k) {
+    case 2: return launch_k<2>(p, D, blk, stream);
+    case 3: return launch_k<3>(p, D, blk, stream);
+    case 4: return launch_k<4>(p, D, blk, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace nqkv

@@ -1,0 +1,194 @@
+"""Thin ctypes binding of libnqkv (include/nqkv.h): argument marshalling only.
+
+Every step of the path -- code search, bit packing, table look-up, attention -- runs in the
+library's HIP kernels.  torch is used for device memory and the stream handle, nothing else.
+Importing this module loads `libnqkv.so` from the package directory and raises if it is not
+there: there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnqkv.so")
+
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+
+EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_set_tuning", "nqkv_build_codebook",
+           "nqkv_quantize_kv", "nqkv_quantize_kv_pair", "nqkv_dequantize_kv",
+           "nqkv_decode_workspace_bytes", "nqkv_decode_attention")
+
+
+class CacheDesc(ctypes.Structure):
+    """Mirror of nqkv_cache_desc."""
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("k", ctypes.c_int32), ("block", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("cap_tokens", ctypes.c_int64)]
+
+
+class NqkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, strerror(status), status))
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libnqkv.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(or python paper_2505_16210_amd/build.py) first; there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, i64, i32 = c.c_void_p, c.c_int64, c.c_int
+    dp = c.POINTER(CacheDesc)
+    fp = c.POINTER(c.c_float)
+    lib.nqkv_strerror.restype = c.c_char_p
+    lib.nqkv_strerror.argtypes = [i32]
+    lib.nqkv_version.restype = i32
+    lib.nqkv_set_tuning.restype = i32
+    lib.nqkv_set_tuning.argtypes = [i32, i32]
+    lib.nqkv_build_codebook.restype = i32
+    lib.nqkv_build_codebook.argtypes = [i32, i32, fp]
+    lib.nqkv_quantize_kv.restype = i32
+    lib.nqkv_quantize_kv.argtypes = [dp, fp, vp, i64, i64, i64, i64, i64, vp, vp, vp]
+    lib.nqkv_quantize_kv_pair.restype = i32
+    lib.nqkv_quantize_kv_pair.argtypes = [dp, fp, vp, vp, i64, i64, i64, i64, i64, vp, vp, vp, vp, vp]
+    lib.nqkv_dequantize_kv.restype = i32
+    lib.nqkv_dequantize_kv.argtypes = [dp, fp, vp, vp, i64, i64, vp, i64, i64, i64, vp]
+    lib.nqkv_decode_workspace_bytes.restype = i32
+    lib.nqkv_decode_workspace_bytes.argtypes = [dp, i64, i32, c.POINTER(c.c_size_t), c.POINTER(i32)]
+    lib.nqkv_decode_attention.restype = i32
+    lib.nqkv_decode_attention.argtypes = [dp, fp, vp, vp, vp, vp, vp, i64, c.c_float, vp, vp,
+                                          c.c_size_t, i32, vp]
+    return lib
+
+
+lib = _load()
+
+
+def strerror(status: int) -> str:
+    return lib.nqkv_strerror(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib.nqkv_version())
+
+
+def set_tuning(knob: int, value: int) -> None:
+    rc = lib.nqkv_set_tuning(knob, value)
+    if rc:
+        raise NqkvError(rc, "nqkv_set_tuning")
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != OK:
+        raise NqkvError(rc, where)
+
+
+def _levels_ptr(levels):
+    lv = np.ascontiguousarray(levels, dtype=np.float32)
+    return lv, lv.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev_ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def build_codebook(k: int, variant: int = 0) -> np.ndarray:
+    """nqkv_build_codebook -> numpy float32 [2^k] (host)."""
+    out = np.zeros(1 << max(int(k), 0) if 0 <= int(k) <= 8 else 1, np.float32)
+    rc = lib.nqkv_build_codebook(int(k), int(variant), out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    _check(rc, "nqkv_build_codebook")
+    return out
+
+
+def make_desc(B: int, H: int, D: int, k: int, block: int, cap_tokens: int) -> CacheDesc:
+    return CacheDesc(B, H, D, k, block, 0, cap_tokens)
+
+
+def alloc_cache(desc: CacheDesc, device="cuda"):
+    """Device buffers of the documented layout: (codes uint8 [B,H,cap,D*k/8], scales fp16 [B,H,cap,D/block])."""
+    codes = torch.zeros(desc.B, desc.H, desc.cap_tokens, desc.D * desc.k // 8, dtype=torch.uint8, device=device)
+    scales = torch.zeros(desc.B, desc.H, desc.cap_tokens, desc.D // desc.block, dtype=torch.float16, device=device)
+    return codes, scales
+
+
+def _src_strides(x: torch.Tensor):
+    assert x.dtype == torch.float16 and x.dim() == 4 and x.stride(3) == 1
+    return x.stride(0), x.stride(1), x.stride(2)
+
+
+def quantize_kv(desc: CacheDesc, levels, src: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor,
+                dst_token_offset: int = 0, stream=None) -> None:
+    """nqkv_quantize_kv: src fp16 [B,H,n,D] (D contiguous) -> cache rows [off, off+n)."""
+    lv, lvp = _levels_ptr(levels)
+    sb, sh, st = _src_strides(src)
+    rc = lib.nqkv_quantize_kv(ctypes.byref(desc), lvp, _dev_ptr(src), sb, sh, st, src.shape[2],
+                              dst_token_offset, _dev_ptr(codes), _dev_ptr(scales), _stream(stream))
+    _check(rc, "nqkv_quantize_kv")
+
+
+def quantize_kv_pair(desc: CacheDesc, levels, k_src: torch.Tensor, v_src: torch.Tensor,
+                     k_codes, k_scales, v_codes, v_scales, dst_token_offset: int = 0, stream=None) -> None:
+    """nqkv_quantize_kv_pair: K and V of equal shape and strides in one launch."""
+    lv, lvp = _levels_ptr(levels)
+    sb, sh, st = _src_strides(k_src)
+    assert _src_strides(v_src) == (sb, sh, st) and v_src.shape == k_src.shape
+    rc = lib.nqkv_quantize_kv_pair(ctypes.byref(desc), lvp, _dev_ptr(k_src), _dev_ptr(v_src), sb, sh, st,
+                                   k_src.shape[2], dst_token_offset, _dev_ptr(k_codes), _dev_ptr(k_scales),
+                                   _dev_ptr(v_codes), _dev_ptr(v_scales), _stream(stream))
+    _check(rc, "nqkv_quantize_kv_pair")
+
+
+def dequantize_kv(desc: CacheDesc, levels, codes, scales, token_offset: int, n_tokens: int,
+                  out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """nqkv_dequantize_kv -> fp16 [B,H,n_tokens,D]."""
+    lv, lvp = _levels_ptr(levels)
+    if out is None:
+        out = torch.empty(desc.B, desc.H, n_tokens, desc.D, dtype=torch.float16, device=codes.device)
+    sb, sh, st = _src_strides(out)
+    rc = lib.nqkv_dequantize_kv(ctypes.byref(desc), lvp, _dev_ptr(codes), _dev_ptr(scales), token_offset,
+                                n_tokens, _dev_ptr(out), sb, sh, st, _stream(stream))
+    _check(rc, "nqkv_dequantize_kv")
+    return out
+
+
+def decode_workspace_bytes(desc: CacheDesc, seq_len: int, num_splits: int = 0):
+    """nqkv_decode_workspace_bytes -> (bytes, splits)."""
+    nbytes = ctypes.c_size_t(0)
+    splits = ctypes.c_int(0)
+    rc = lib.nqkv_decode_workspace_bytes(ctypes.byref(desc), seq_len, num_splits,
+                                         ctypes.byref(nbytes), ctypes.byref(splits))
+    _check(rc, "nqkv_decode_workspace_bytes")
+    return int(nbytes.value), int(splits.value)
+
+
+def decode_attention(desc: CacheDesc, levels, q: torch.Tensor, k_codes, k_scales, v_codes, v_scales,
+                     seq_len: int, softmax_scale: float = 1.0, out: torch.Tensor | None = None,
+                     workspace: torch.Tensor | None = None, num_splits: int = 0, stream=None) -> torch.Tensor:
+    """nqkv_decode_attention: q fp16 [B,H,D] -> out fp16 [B,H,D]."""
+    lv, lvp = _levels_ptr(levels)
+    assert q.dtype == torch.float16 and q.is_contiguous()
+    if out is None:
+        out = torch.empty_like(q)
+    ws_bytes = 0
+    if workspace is None:
+        need, _ = decode_workspace_bytes(desc, seq_len, num_splits)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    if workspace is not None:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    rc = lib.nqkv_decode_attention(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_codes), _dev_ptr(k_scales),
+                                   _dev_ptr(v_codes), _dev_ptr(v_scales), seq_len, float(softmax_scale),
+                                   _dev_ptr(out), _dev_ptr(workspace), ws_bytes, num_splits, _stream(stream))
+    _check(rc, "nqkv_decode_attention")
+    return out

@@ -1,0 +1,308 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same fp16 bits.
+
+Codes, packing, scales and dequantized fp16 must be bit-exact.  Attention must satisfy, per
+(batch, head) row,  max_d |out - ref| <= 2e-3 * max_d |ref|  against the fp64 oracle.
+Sizes here are small enough for the oracle to finish in seconds yet span several workgroup
+tiles and a ragged tail; full benchmark sizes live in test_gpu_fullsize.py."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+COMBOS = [(4, 64, 64), (4, 128, 64), (4, 128, 128), (3, 64, 64), (3, 128, 64), (3, 128, 128),
+          (2, 64, 64), (2, 128, 64), (2, 128, 128)]       # (k, D, block)
+
+
+@pytest.fixture(scope="module")
+def nqkv():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2505_16210_amd import nqkv as mod
+    return mod
+
+
+def h2n(t: torch.Tensor) -> np.ndarray:
+    """device tensor -> numpy (fp16 as uint16 bit patterns)."""
+    a = t.detach().cpu().numpy()
+    return a.view(np.uint16) if a.dtype == np.float16 else a
+
+
+def attn_err(out: np.ndarray, ref: np.ndarray) -> float:
+    """worst per-row relative error, rows = (batch, head)."""
+    out = out.astype(np.float64)
+    num = np.abs(out - ref).max(axis=-1)
+    den = np.abs(ref).max(axis=-1)
+    return float((num / den).max())
+
+
+def rand_kv(shape, seed, chan_spread=True):
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    x = torch.randn(shape, device="cuda", generator=g)
+    if chan_spread:
+        chan = torch.exp(0.5 * torch.randn(shape[1], 1, shape[3], device="cuda", generator=g))
+        chan[:, :, :2] *= 10.0
+        x = x * chan
+    return x.to(torch.float16)
+
+
+# --------------------------------------------------------------------------- quantize
+@pytest.mark.parametrize("impl", [0, 1])
+@pytest.mark.parametrize("k,D,blk", COMBOS)
+def test_quantize_bit_exact(nqkv, oracle, k, D, blk, impl):
+    B, H, n, cap, off = 2, 3, 1061, 1100, 19       # 1061 tokens: several tiles plus a ragged tail
+    lv = nqkv.build_codebook(k)
+    x = rand_kv((B, H, n, D), seed=100 * k + D + blk)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    codes, scales = nqkv.alloc_cache(desc)
+    nqkv.set_tuning(0, impl)
+    try:
+        nqkv.quantize_kv(desc, lv, x, codes, scales, dst_token_offset=off)
+        torch.cuda.synchronize()
+    finally:
+        nqkv.set_tuning(0, 0)
+    rc, rs = oracle.new_cache(B, H, D, k, blk, cap)
+    oracle.quantize_kv(h2n(x), k, blk, lv, rc, rs, dst_off=off, n_threads=8)
+    assert np.array_equal(h2n(scales), rs)
+    assert np.array_equal(h2n(codes), rc)           # rows outside [off, off+n) stay zero on both sides
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("k,D,blk", [(4, 128, 64), (3, 128, 128), (2, 64, 64)])
+def test_quantize_edge_values_bit_exact(nqkv, oracle, k, D, blk, variant):
+    """Zero blocks, signed zeros, subnormals, the largest fp16, exact ties on scaled thresholds,
+    blocks of equal magnitude, tiny and huge scales -- for both tables."""
+    lv = nqkv.build_codebook(k, variant)
+    rng = np.random.default_rng(7 + k)
+    n = 600
+    x = rng.standard_normal((1, 2, n, D)).astype(np.float32)
+    x[0, 0, 0] = 0.0                                           # all-zero row
+    x[0, 0, 1] = -0.0
+    x[0, 0, 2, ::2] = 0.0                                       # zeros inside a non-zero block
+    x[0, 0, 3] *= 6e-8                                          # subnormal range
+    x[0, 0, 4] *= 3e-5
+    x[0, 0, 5] = 65504.0 * np.sign(x[0, 0, 5])                  # every element at +-max
+    x[0, 0, 6] *= 2.0e4
+    x[0, 0, 6] = np.clip(x[0, 0, 6], -65504, 65504)
+    x[0, 0, 7] = 1.0                                            # constant block
+    x16 = x.astype(np.float16)
+    # exact ties: put elements exactly on fp16-representable scaled thresholds
+    thr = ((lv[:-1] + lv[1:]).astype(np.float32) * np.float32(0.5)).astype(np.float32)
+    for row, s in ((8, 1.0), (9, 0.5), (10, 1024.0), (11, 2.0 ** -14)):
+        vals = (thr * np.float32(s)).astype(np.float32)
+        v16 = vals.astype(np.float16)
+        fill = np.resize(np.concatenate([v16, -v16, np.nextafter(v16, np.float16(1)), np.nextafter(v16, np.float16(-1))]), D)
+        fill = np.clip(fill, -s, s).astype(np.float16)
+        fill[::blk] = np.float16(s)                             # pin the scale of every block
+        x16[0, 0, row] = fill
+    xt = torch.from_numpy(x16).cuda()
+    desc = nqkv.make_desc(1, 2, D, k, blk, n)
+    for impl in (0, 1):
+        codes, scales = nqkv.alloc_cache(desc)
+        nqkv.set_tuning(0, impl)
+        try:
+            nqkv.quantize_kv(desc, lv, xt, codes, scales)
+            torch.cuda.synchronize()
+        finally:
+            nqkv.set_tuning(0, 0)
+        rc, rs = oracle.new_cache(1, 2, D, k, blk, n)
+        oracle.quantize_kv(x16, k, blk, lv, rc, rs)
+        assert np.array_equal(h2n(scales), rs)
+        assert np.array_equal(h2n(codes), rc)
+
+
+def test_quantize_all_fp16_values_against_many_scales(nqkv, oracle):
+    """Every finite fp16 magnitude as an element, under scales spread over the whole exponent
+    range: the cell-table search must agree with the threshold scan everywhere."""
+    k, D, blk = 4, 64, 64
+    lv = nqkv.build_codebook(k)
+    mags = np.arange(0, 0x7C00, dtype=np.uint16).view(np.float16)          # 31744 values, ascending
+    rows = []
+    for s_bits in list(range(1, 0x7C00, 997)) + [0x7BFF, 0x0001, 0x03FF, 0x0400]:
+        s = np.uint16(s_bits).view(np.float16)
+        m = mags[mags <= s]
+        # rows of 63 elements + the scale itself, alternating signs
+        pad = (-len(m)) % 63
+        m = np.concatenate([m, np.zeros(pad, np.float16)]).reshape(-1, 63)
+        m = m * np.where(np.arange(63) % 2 == 0, 1, -1).astype(np.float16)
+        rows.append(np.concatenate([np.full((m.shape[0], 1), s, np.float16), m], axis=1))
+    x16 = np.concatenate(rows, axis=0)
+    n = x16.shape[0]
+    x16 = x16.reshape(1, 1, n, D)
+    xt = torch.from_numpy(x16).cuda()
+    desc = nqkv.make_desc(1, 1, D, k, blk, n)
+    codes, scales = nqkv.alloc_cache(desc)
+    nqkv.quantize_kv(desc, lv, xt, codes, scales)
+    torch.cuda.synchronize()
+    rc, rs = oracle.new_cache(1, 1, D, k, blk, n)
+    oracle.quantize_kv(x16, k, blk, lv, rc, rs, n_threads=8)
+    assert np.array_equal(h2n(scales), rs)
+    assert np.array_equal(h2n(codes), rc)
+
+
+def test_quantize_strided_source_append_and_pair(nqkv, oracle):
+    k, D, blk = 4, 64, 64
+    B, H, S, cap = 3, 5, 40, 48
+    lv = nqkv.build_codebook(k)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    storage_k = torch.randn(B, S, H, D, device="cuda", generator=g).to(torch.float16)   # projection-output order
+    storage_v = torch.randn(B, S, H, D, device="cuda", generator=g).to(torch.float16)
+    Kv, Vv = storage_k.permute(0, 2, 1, 3), storage_v.permute(0, 2, 1, 3)              # [B,H,S,D] views
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    kc, ks = nqkv.alloc_cache(desc)
+    vc, vs = nqkv.alloc_cache(desc)
+    # prefill 33 tokens with the pair call, then append one token at a time (flat small-launch path)
+    nqkv.quantize_kv_pair(desc, lv, Kv[:, :, :33], Vv[:, :, :33], kc, ks, vc, vs, 0)
+    for t in range(33, S):
+        nqkv.quantize_kv_pair(desc, lv, Kv[:, :, t:t + 1], Vv[:, :, t:t + 1], kc, ks, vc, vs, t)
+    torch.cuda.synchronize()
+    for dev_c, dev_s, src in ((kc, ks, Kv), (vc, vs, Vv)):
+        rc, rs = oracle.new_cache(B, H, D, k, blk, cap)
+        oracle.quantize_kv(h2n(src.contiguous()), k, blk, lv, rc, rs)
+        assert np.array_equal(h2n(dev_s), rs) and np.array_equal(h2n(dev_c), rc)
+    # single-tensor call gives the same bytes as the pair call
+    kc2, ks2 = nqkv.alloc_cache(desc)
+    nqkv.quantize_kv(desc, lv, Kv, kc2, ks2)
+    torch.cuda.synchronize()
+    assert torch.equal(kc2, kc) and torch.equal(ks2, ks)
+    # empty call is a no-op
+    nqkv.quantize_kv(desc, lv, Kv[:, :, :0], kc2, ks2, 7)
+
+
+# --------------------------------------------------------------------------- dequantize
+@pytest.mark.parametrize("k,D,blk", COMBOS)
+def test_dequantize_bit_exact(nqkv, oracle, k, D, blk):
+    B, H, n, cap, off = 2, 2, 517, 530, 5
+    lv = nqkv.build_codebook(k)
+    x = rand_kv((B, H, n, D), seed=3 * k + D)
+    x[0, 0, 0] = 0
+    x[0, 0, 1] *= 1e-6
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    codes, scales = nqkv.alloc_cache(desc)
+    nqkv.quantize_kv(desc, lv, x, codes, scales, off)
+    got = nqkv.dequantize_kv(desc, lv, codes, scales, off, n)
+    torch.cuda.synchronize()
+    ref = oracle.dequantize_kv(h2n(codes), h2n(scales), k, blk, lv, off, n, n_threads=8)
+    assert np.array_equal(h2n(got), ref)
+    # strided destination
+    out = torch.zeros(B, n, H, D, dtype=torch.float16, device="cuda").permute(0, 2, 1, 3)
+    nqkv.dequantize_kv(desc, lv, codes, scales, off, n, out=out)
+    torch.cuda.synchronize()
+    assert np.array_equal(h2n(out.contiguous()), ref)
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_dequantize_every_scale(nqkv, oracle, k):
+    """All 31744 finite non-negative fp16 scales x every code."""
+    D = blk = 64
+    L = 1 << k
+    lv = nqkv.build_codebook(k)
+    n = 0x7C00
+    row_codes = (np.arange(D) % L).astype(np.uint8)
+    codes = np.tile(oracle.pack_bits(row_codes, k), (n, 1)).reshape(1, 1, n, D * k // 8)
+    scales = np.arange(n, dtype=np.uint16).reshape(1, 1, n, 1)
+    desc = nqkv.make_desc(1, 1, D, k, blk, n)
+    got = nqkv.dequantize_kv(desc, lv, torch.from_numpy(codes).cuda(),
+                             torch.from_numpy(scales.view(np.float16)).cuda(), 0, n)
+    torch.cuda.synchronize()
+    ref = oracle.dequantize_kv(codes, scales, k, blk, lv, 0, n, n_threads=8)
+    assert np.array_equal(h2n(got), ref)
+
+
+# --------------------------------------------------------------------------- decode attention
+def _build_cache(nqkv, k, D, blk, B, H, S, cap, seed):
+    lv = nqkv.build_codebook(k)
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    Kx = rand_kv((B, H, S, D), seed)
+    Vx = torch.randn(B, H, S, D, device="cuda", generator=g).to(torch.float16)
+    q = (torch.randn(B, H, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    kc, ks = nqkv.alloc_cache(desc)
+    vc, vs = nqkv.alloc_cache(desc)
+    nqkv.quantize_kv_pair(desc, lv, Kx, Vx, kc, ks, vc, vs, 0)
+    return lv, desc, q, kc, ks, vc, vs
+
+
+@pytest.mark.parametrize("k,D,blk", COMBOS)
+def test_decode_attention_matches_oracle(nqkv, oracle, k, D, blk):
+    B, H, S, cap = 2, 3, 1237, 1300
+    lv, desc, q, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, S, cap, seed=11 * k + D + blk)
+    # poison the rows beyond S: they must not influence anything
+    kc[:, :, S:] = 0xFF
+    ks[:, :, S:] = 60000.0
+    vs[:, :, S:] = 60000.0
+    torch.cuda.synchronize()
+    hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+    for seq in (1, 2, 63, 64, 65, 129, 1000, S):
+        ref = oracle.decode_attention(hk[0], hk[1], hk[2], hk[3], hk[4], k, blk, lv, seq, 0.9, n_threads=8)
+        for ns in (0, 1, 2, 7, 64):
+            if ns > seq:
+                continue
+            out = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, seq, 0.9, num_splits=ns)
+            torch.cuda.synchronize()
+            err = attn_err(h2n(out).view(np.float16), ref)
+            assert err <= ATTN_TOL, (k, D, blk, seq, ns, err)
+
+
+def test_decode_attention_repeatable_and_split_consistent(nqkv):
+    k, D, blk = 4, 128, 64
+    B, H, S = 2, 4, 3000
+    lv, desc, q, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, S, S, seed=77)
+    outs = {}
+    for ns in (1, 2, 7, 64):
+        a = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, 1.0, num_splits=ns)
+        b = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, 1.0, num_splits=ns)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b)                         # same arguments -> same bits
+        outs[ns] = a.float()
+    for ns in (2, 7, 64):
+        d = (outs[ns] - outs[1]).abs().amax(-1) / outs[1].abs().amax(-1)
+        assert d.max().item() <= 2e-3
+
+
+def test_decode_attention_peaked_and_flat_scores(nqkv, oracle):
+    """Softmax extremes: one dominant token (large scale factor) and near-uniform weights."""
+    k, D, blk = 4, 64, 64
+    B, H, S = 1, 4, 700
+    lv, desc, q, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, S, S, seed=5)
+    hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+    for scale in (8.0, 1e-3, 0.0):
+        ref = oracle.decode_attention(hk[0], hk[1], hk[2], hk[3], hk[4], k, blk, lv, S, scale, n_threads=4)
+        for ns in (1, 5):
+            out = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, scale, num_splits=ns)
+            torch.cuda.synchronize()
+            assert attn_err(h2n(out).view(np.float16), ref) <= ATTN_TOL, (scale, ns)
+
+
+def test_decode_steps_append_then_attend(nqkv, oracle):
+    """The paper's decode loop: quantize the new token, append, attend over everything
+    including it -- GPU cache and oracle cache evolve side by side."""
+    k, D, blk = 4, 64, 64
+    B, H, S0, steps = 2, 4, 200, 12
+    cap = S0 + steps
+    lv = nqkv.build_codebook(k)
+    g = torch.Generator(device="cuda").manual_seed(9)
+    Kx = rand_kv((B, H, cap, D), 9)
+    Vx = torch.randn(B, H, cap, D, device="cuda", generator=g).to(torch.float16)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    kc, ks = nqkv.alloc_cache(desc)
+    vc, vs = nqkv.alloc_cache(desc)
+    nqkv.quantize_kv_pair(desc, lv, Kx[:, :, :S0], Vx[:, :, :S0], kc, ks, vc, vs, 0)
+    okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
+    ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
+    Kh, Vh = h2n(Kx), h2n(Vx)
+    oracle.quantize_kv(Kh[:, :, :S0], k, blk, lv, okc, oks)
+    oracle.quantize_kv(Vh[:, :, :S0], k, blk, lv, ovc, ovs)
+    for i in range(steps):
+        pos = S0 + i
+        q = (torch.randn(B, H, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+        nqkv.quantize_kv_pair(desc, lv, Kx[:, :, pos:pos + 1], Vx[:, :, pos:pos + 1], kc, ks, vc, vs, pos)
+        out = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, pos + 1, 1.0)
+        torch.cuda.synchronize()
+        oracle.quantize_kv(Kh[:, :, pos:pos + 1], k, blk, lv, okc, oks, dst_off=pos)
+        oracle.quantize_kv(Vh[:, :, pos:pos + 1], k, blk, lv, ovc, ovs, dst_off=pos)
+        ref = oracle.decode_attention(h2n(q), okc, oks, ovc, ovs, k, blk, lv, pos + 1, 1.0)
+        assert attn_err(h2n(out).view(np.float16), ref) <= ATTN_TOL
+    assert np.array_equal(h2n(kc), okc) and np.array_equal(h2n(vs), ovs)

@@ -1,0 +1,163 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+its host-side quantile table equals the oracle's, and every argument error is reported before
+any GPU work (so these run on a machine without a GPU)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def nqkv():
+    from paper_2505_16210_amd import nqkv as mod
+    return mod
+
+
+def test_library_exports_every_declared_symbol(nqkv):
+    header = open(os.path.join(ROOT, "include", "nqkv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(nqkv_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(nqkv.EXPORTS)
+    raw = ctypes.CDLL(nqkv.LIB_PATH)
+    for name in declared:
+        assert hasattr(raw, name), name
+    assert nqkv.version() == 100
+    assert nqkv.strerror(0) == "ok" and "workspace" in nqkv.strerror(nqkv.EWORKSPACE)
+
+
+def test_desc_struct_layout(nqkv):
+    assert ctypes.sizeof(nqkv.CacheDesc) == 32
+    assert nqkv.CacheDesc.cap_tokens.offset == 24
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("k", range(1, 9))
+def test_codebook_equals_oracle_table(nqkv, oracle, k, variant):
+    if variant == 1 and k < 2:
+        with pytest.raises(nqkv.NqkvError):
+            nqkv.build_codebook(k, variant)
+        return
+    got = nqkv.build_codebook(k, variant)
+    _, want, _ = oracle.codebook(k, variant)
+    assert got.dtype == np.float32 and np.array_equal(got, want)
+
+
+def test_codebook_errors(nqkv):
+    for k, v in ((0, 0), (9, 0), (4, 2), (-1, 0)):
+        with pytest.raises(nqkv.NqkvError) as e:
+            nqkv.build_codebook(k, v)
+        assert e.value.status == nqkv.EINVAL
+    assert nqkv.lib.nqkv_build_codebook(4, 0, None) == nqkv.EINVAL
+
+
+# ---------------------------------------------------------------- argument validation (no launch)
+FAKE = 0x10000   # non-null, 16-byte aligned; never dereferenced because validation fails first
+
+
+def _levels(nqkv, k=4):
+    lv = nqkv.build_codebook(k)
+    return lv, lv.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _quant(nqkv, desc, lvp, src=FAKE, sb=0, sh=0, st=64, n=1, off=0, codes=FAKE, scales=FAKE):
+    return nqkv.lib.nqkv_quantize_kv(ctypes.byref(desc) if desc is not None else None, lvp,
+                                     src, sb, sh, st, n, off, codes, scales, None)
+
+
+def test_quantize_argument_errors(nqkv):
+    lv, lvp = _levels(nqkv)
+    good = nqkv.make_desc(2, 4, 64, 4, 64, 16)
+    assert _quant(nqkv, None, lvp) == nqkv.EINVAL
+    assert _quant(nqkv, good, None) == nqkv.EINVAL
+    assert _quant(nqkv, good, lvp, src=None) == nqkv.EINVAL
+    assert _quant(nqkv, good, lvp, codes=None) == nqkv.EINVAL
+    assert _quant(nqkv, good, lvp, scales=None) == nqkv.EINVAL
+    assert _quant(nqkv, good, lvp, src=FAKE + 2) == nqkv.EINVAL          # misaligned
+    assert _quant(nqkv, good, lvp, codes=FAKE + 8) == nqkv.EINVAL
+    assert _quant(nqkv, good, lvp, n=-1) == nqkv.EINVAL
+    assert _quant(nqkv, good, lvp, n=2, off=15) == nqkv.EINVAL           # past capacity
+    assert _quant(nqkv, good, lvp, n=1, off=17) == nqkv.EINVAL
+    assert _quant(nqkv, good, lvp, off=-1) == nqkv.EINVAL
+    assert _quant(nqkv, good, lvp, st=60) == nqkv.EINVAL                 # rows not 16-byte aligned
+    assert _quant(nqkv, good, lvp, n=2, st=32) == nqkv.EINVAL            # rows overlap
+    assert _quant(nqkv, good, lvp, sb=-8) == nqkv.EINVAL
+    assert _quant(nqkv, good, lvp, n=0) == nqkv.OK                       # empty: success, nothing launched
+    for bad in (dict(B=0), dict(H=0), dict(cap_tokens=0), dict(reserved=1), dict(D=0)):
+        d = nqkv.make_desc(2, 4, 64, 4, 64, 16)
+        for f, v in bad.items():
+            setattr(d, f, v)
+        assert _quant(nqkv, d, lvp) == nqkv.EINVAL
+    for bad in (dict(k=5), dict(k=1), dict(D=96), dict(D=256), dict(block=32), dict(B=4096, H=16)):
+        d = nqkv.make_desc(2, 4, 64, 4, 64, 16)
+        for f, v in bad.items():
+            setattr(d, f, v)
+        assert _quant(nqkv, d, lvp) == nqkv.EUNSUPPORTED
+    d = nqkv.make_desc(2, 4, 64, 4, 128, 16)                             # block does not divide D
+    assert _quant(nqkv, d, lvp) == nqkv.EINVAL
+    # tables must be finite and strictly ascending
+    for bad in (lv[::-1].copy(), np.where(np.arange(16) == 3, np.nan, lv).astype(np.float32),
+                np.where(np.arange(16) == 3, lv[2], lv).astype(np.float32)):
+        assert _quant(nqkv, good, bad.ctypes.data_as(ctypes.POINTER(ctypes.c_float))) == nqkv.EINVAL
+
+
+def test_quantize_pair_and_dequantize_argument_errors(nqkv):
+    lv, lvp = _levels(nqkv)
+    d = nqkv.make_desc(2, 4, 128, 4, 64, 16)
+    f = nqkv.lib.nqkv_quantize_kv_pair
+    assert f(ctypes.byref(d), lvp, FAKE, None, 0, 0, 128, 1, 0, FAKE, FAKE, FAKE, FAKE, None) == nqkv.EINVAL
+    assert f(ctypes.byref(d), lvp, FAKE, FAKE, 0, 0, 128, 1, 0, FAKE, FAKE, None, FAKE, None) == nqkv.EINVAL
+    assert f(ctypes.byref(d), lvp, FAKE, FAKE, 0, 0, 128, 0, 0, FAKE, FAKE, FAKE, FAKE, None) == nqkv.OK
+    g = nqkv.lib.nqkv_dequantize_kv
+    assert g(ctypes.byref(d), lvp, None, FAKE, 0, 1, FAKE, 0, 0, 128, None) == nqkv.EINVAL
+    assert g(ctypes.byref(d), lvp, FAKE, FAKE, 16, 1, FAKE, 0, 0, 128, None) == nqkv.EINVAL
+    assert g(ctypes.byref(d), lvp, FAKE, FAKE, 0, 1, FAKE + 4, 0, 0, 128, None) == nqkv.EINVAL
+    assert g(ctypes.byref(d), lvp, FAKE, FAKE, 3, 0, FAKE, 0, 0, 128, None) == nqkv.OK
+
+
+def test_workspace_planning(nqkv):
+    d = nqkv.make_desc(1, 32, 128, 4, 64, 32768)
+    nbytes, splits = nqkv.decode_workspace_bytes(d, 32768, 0)
+    assert splits > 1 and nbytes == 32 * splits * 130 * 4
+    assert nqkv.decode_workspace_bytes(d, 32768, 1) == (0, 1)
+    assert nqkv.decode_workspace_bytes(d, 32768, 7) == (32 * 7 * 130 * 4, 7)
+    assert nqkv.decode_workspace_bytes(d, 5, 0) == (0, 1)               # short sequence: one piece
+    big = nqkv.make_desc(32, 32, 128, 4, 64, 2048)
+    assert nqkv.decode_workspace_bytes(big, 2048, 0)[1] <= 2
+    for seq, ns in ((0, 0), (32769, 0), (10, 11), (10, -1), (4000, 1025)):
+        with pytest.raises(nqkv.NqkvError) as e:
+            nqkv.decode_workspace_bytes(d, seq, ns)
+        assert e.value.status == nqkv.EINVAL
+    assert nqkv.lib.nqkv_decode_workspace_bytes(ctypes.byref(d), 100, 0, None, None) == nqkv.EINVAL
+
+
+def test_decode_argument_errors(nqkv):
+    lv, lvp = _levels(nqkv)
+    d = nqkv.make_desc(1, 32, 128, 4, 64, 32768)
+    f = nqkv.lib.nqkv_decode_attention
+
+    def call(q=FAKE, kc=FAKE, ks=FAKE, vc=FAKE, vs=FAKE, seq=32768, scale=1.0, out=FAKE, ws=FAKE,
+             ws_bytes=1 << 30, ns=0, desc=d, levels=lvp):
+        return f(ctypes.byref(desc), levels, q, kc, ks, vc, vs, seq, scale, out, ws, ws_bytes, ns, None)
+
+    assert call(q=None) == nqkv.EINVAL
+    assert call(out=None) == nqkv.EINVAL
+    assert call(vs=FAKE + 2) == nqkv.EINVAL
+    assert call(seq=0) == nqkv.EINVAL
+    assert call(seq=32769) == nqkv.EINVAL
+    assert call(scale=float("inf")) == nqkv.EINVAL
+    assert call(ns=8, ws=None) == nqkv.EINVAL                    # split-K needs a workspace
+    assert call(ns=8, ws_bytes=100) == nqkv.EWORKSPACE
+    assert call(ns=2000) == nqkv.EINVAL
+    assert call(levels=None) == nqkv.EINVAL
+
+
+def test_tuning_knobs(nqkv):
+    assert nqkv.lib.nqkv_set_tuning(0, 2) == nqkv.EINVAL
+    assert nqkv.lib.nqkv_set_tuning(9, 0) == nqkv.EINVAL
+    nqkv.set_tuning(0, 1)
+    nqkv.set_tuning(0, 0)
+    nqkv.set_tuning(1, 0)
