@@ -1,0 +1,303 @@
+#!/usr/bin/env python3
+"""Benchmark of the NQKV hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over the OPT-1.3B-shaped workload
+(batch 8, 32 heads, head_dim 64, 4-bit codes, block 64): quantize a 2048-token prefill
+cache (K and V), then 128 decode steps, each appending one token (K and V, one launch) and
+running the fused decode attention over everything cached so far.  Inputs are synthetic
+(seeded, distributions of paper_2505_16210_amd/workloads.py) and resident in HBM before the
+timed region.  To keep the 256 MB last-level cache from serving repeat reads, the step
+rotates over 32 independent copies of the cache ("layers") and 8 copies of the fp16 prefill
+source, so every launch streams from HBM.
+
+Prints ONE JSON line.  `value` is effective fp16 KV GB/s: 2 bytes x (K and V elements
+quantized + K and V elements attended over) per second of the step.  `roofline` describes the
+dominant kernel of the step (the fused decode attention); `kernels` adds per-kernel figures
+for the larger single-GPU configurations; `cpu_baseline` times the CPU oracle on a bounded
+sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--configs", default="C2,C3,C4,C5",
+                    help="configurations whose kernels are timed for the `kernels` section")
+    ap.add_argument("--sweep", action="store_true", help="C5: also time k in {2,3} and block 128")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--kernel-iters", type=int, default=30)
+    ap.add_argument("--cold", type=int, default=1, help="1: rotate buffers to defeat the last-level cache")
+    ap.add_argument("--skip-step", action="store_true",
+                    help="profiling aid: skip the timed C2 step, only run the kernels of --configs")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path shards by batch/head with no "
+              "exchange); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2505_16210_amd import nqkv, workloads
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream()
+
+    def timed(fn, iters, warm=2):
+        """average milliseconds per call of fn(i), events on the launch stream"""
+        for i in range(warm):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(iters):
+            fn(warm + i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    if args.skip_step:
+        kern = {}
+        for name in [c for c in args.configs.split(",") if c and c != "C2"]:
+            base = workloads.CONFIGS[name]
+            variants = [(base.bits, base.block)]
+            if name == "C5" and args.sweep:
+                variants = [(kb, bl) for kb in (4, 3, 2) for bl in (64, 128)]
+            bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, timed, args.kernel_iters, args.cold)
+        print(json.dumps({"kernels": kern}))
+        return
+
+    # ------------------------------------------------------------------ the step (C2)
+    cfg = workloads.C2
+    B, H, D, S, steps_dec = cfg.B, cfg.H, cfg.D, cfg.S, cfg.decode_steps
+    k, blk, cap = cfg.bits, cfg.block, cfg.cap_tokens
+    lv = nqkv.build_codebook(k)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    R_CACHE = 32 if args.cold else 1
+    R_SRC = 8 if args.cold else 1
+    g = workloads.make_generator(cfg, dev)
+    srcs = [workloads.make_kv(cfg, dev, g, n_tokens=S) for _ in range(R_SRC)]
+    Knew, Vnew = workloads.make_kv(cfg, dev, g, n_tokens=steps_dec)
+    qs = [workloads.make_q(cfg, dev, g) for _ in range(steps_dec)]
+    caches = []
+    fill_k, fill_v = workloads.make_kv(cfg, dev, g, n_tokens=cap)
+    for r in range(R_CACHE):
+        kc, ks = nqkv.alloc_cache(desc, dev)
+        vc, vs = nqkv.alloc_cache(desc, dev)
+        # every copy starts fully populated so that any position read later holds valid codes
+        nqkv.quantize_kv_pair(desc, lv, fill_k.roll(r, 2), fill_v.roll(r, 2), kc, ks, vc, vs, 0)
+        caches.append((kc, ks, vc, vs))
+    del fill_k, fill_v
+    out = torch.empty(B, H, D, dtype=torch.float16, device=dev)
+    ws_bytes, splits = nqkv.decode_workspace_bytes(desc, cap, 0)
+    ws = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    new_views = [(Knew[:, :, i:i + 1], Vnew[:, :, i:i + 1]) for i in range(steps_dec)]
+
+    def prefill(s):
+        ksrc, vsrc = srcs[s % R_SRC]
+        kc, ks, vc, vs = caches[s % R_CACHE]
+        nqkv.quantize_kv_pair(desc, lv, ksrc, vsrc, kc, ks, vc, vs, 0, stream=stream)
+
+    def append(i):
+        kc, ks, vc, vs = caches[i % R_CACHE]
+        kn, vn = new_views[i % steps_dec]
+        nqkv.quantize_kv_pair(desc, lv, kn, vn, kc, ks, vc, vs, S + (i % steps_dec), stream=stream)
+
+    def attend(i):
+        kc, ks, vc, vs = caches[i % R_CACHE]
+        j = i % steps_dec
+        nqkv.decode_attention(desc, lv, qs[j], kc, ks, vc, vs, S + j + 1, 1.0, out=out,
+                              workspace=ws, stream=stream)
+
+    def step(s):
+        prefill(s)
+        for i in range(steps_dec):
+            append(i)
+            attend(i)
+
+    for s in range(args.warmup):
+        step(s)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_host0 = time.perf_counter()
+    e0.record(stream)
+    for s in range(args.steps):
+        step(args.warmup + s)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    host_ms = (time.perf_counter() - t_host0) * 1e3 / args.steps
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+
+    elems_quant = 2 * B * H * D * (S + steps_dec)                       # K and V, prefill + appended
+    elems_attn = 2 * B * H * D * sum(S + i + 1 for i in range(steps_dec))
+    eff_bytes = 2 * (elems_quant + elems_attn)
+    value = eff_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ------------------------------------------------------------------ per-kernel timings, C2
+    it = args.kernel_iters
+    kern = {}
+    t_pre = timed(prefill, it)
+    qb = workloads.quantize_bytes_per_element(k, blk)
+    kern["C2.quantize_prefill"] = kernel_entry(2 * B * H * S * D * qb, t_pre)
+    t_app = timed(append, steps_dec * 2)
+    kern["C2.quantize_append"] = kernel_entry(2 * B * H * D * qb, t_app)
+    t_att = timed(attend, steps_dec * 4, warm=steps_dec)
+    mean_seq = S + (steps_dec + 1) / 2.0
+    dec_bytes = B * H * (mean_seq * workloads.decode_bytes_per_token_head(D, k, blk) + 4 * D) \
+        + (2 * B * H * splits * (D + 2) * 4 if splits > 1 else 0)      # partials written and re-read
+    kern["C2.decode_attention"] = kernel_entry(dec_bytes, t_att, splits=splits)
+    t_decode_step = t_app + t_att
+    tokens_per_s_layer = B / (t_decode_step * 1e-3)
+
+    roofline = {"kernel": "decode_kernel<4,64,64>", "bound": "hbm",
+                "achieved": round(dec_bytes / (t_att * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(dec_bytes / (t_att * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "bytes_per_launch": int(dec_bytes), "avg_launch_us": round(t_att * 1e3, 2),
+                "traffic": None}
+
+    # free the C2 buffers before the big configurations
+    del srcs, caches, Knew, Vnew, qs, new_views
+    torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ larger configurations
+    for name in [c for c in args.configs.split(",") if c and c != "C2"]:
+        base = workloads.CONFIGS[name]
+        variants = [(base.bits, base.block)]
+        if name == "C5" and args.sweep:
+            variants = [(kb, bl) for kb in (4, 3, 2) for bl in (64, 128)]
+        bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, timed, it, args.cold)
+
+    result = {
+        "metric": "effective KV GB/s (quantize + fused decode attn) & decode tokens/s/layer",
+        "value": round(value, 1), "unit": "GB/s (fp16-equivalent KV bytes processed per second)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "C2 OPT-1.3B-shaped layer: B8 H32 D64, 4-bit block 64, quantize 2048-token "
+                               "prefill + 128 x (append 1 token + fused decode attention); "
+                               "%d cache copies rotated" % R_CACHE,
+                   "storage": "fp16 in/out, %d-bit codes, fp16 scales" % k},
+        "decode_tokens_per_s_per_layer": round(tokens_per_s_layer, 1),
+        "decode_step_us": round(t_decode_step * 1e3, 2),
+        "host_ms_per_step": round(host_ms, 4),
+        "roofline": roofline,
+        "kernels": kern,
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(workloads)
+    print(json.dumps(result))
+
+
+def kernel_entry(nbytes, ms, **extra):
+    gbps = nbytes / (ms * 1e-3) / 1e9
+    e = {"us": round(ms * 1e3, 2), "algorithmic_bytes": int(nbytes), "GBps": round(gbps, 1),
+         "frac_of_8TBps": round(gbps / HBM_PEAK_GBPS, 4)}
+    e.update(extra)
+    return e
+
+
+def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, timed, iters, cold):
+    """quantize (K and V in one launch) and one fused decode attention at full size."""
+    B, H, D, S = base.B, base.H, base.D, base.S
+    fp16_bytes = 2 * B * H * S * D * 2
+    # rotate so that copies x working set >= 1 GiB (sources) / packed caches likewise
+    r_src = max(1, min(8, -(-(1 << 30) // fp16_bytes))) if cold else 1
+    g = workloads.make_generator(base, dev)
+    srcs = [workloads.make_kv(base, dev, g) for _ in range(r_src)]
+    q = workloads.make_q(base, dev, g)
+    out = torch.empty_like(q)
+    for (kb, bl) in variants:
+        lv = nqkv.build_codebook(kb)
+        desc = nqkv.make_desc(B, H, D, kb, bl, S)
+        packed = B * H * S * workloads.decode_bytes_per_token_head(D, kb, bl)
+        r_cache = max(1, min(16, -(-(1 << 30) // packed))) if cold else 1
+        caches = []
+        for r in range(r_cache):
+            kc, ks = nqkv.alloc_cache(desc, dev)
+            vc, vs = nqkv.alloc_cache(desc, dev)
+            caches.append((kc, ks, vc, vs))
+        ws_bytes, splits = nqkv.decode_workspace_bytes(desc, S, 0)
+        ws = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+
+        def quant(i):
+            ksrc, vsrc = srcs[i % r_src]
+            kc, ks, vc, vs = caches[i % r_cache]
+            nqkv.quantize_kv_pair(desc, lv, ksrc, vsrc, kc, ks, vc, vs, 0, stream=stream)
+
+        def attend(i):
+            kc, ks, vc, vs = caches[i % r_cache]
+            nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, 1.0, out=out, workspace=ws, stream=stream)
+
+        for r in range(r_cache):
+            quant(r)
+        n_it = max(5, min(iters, int(2000.0 / max(1.0, fp16_bytes / 1e9 * 0.4))))
+        t_q = timed(quant, n_it, warm=max(2, r_cache))
+        t_a = timed(attend, n_it * 2, warm=max(2, r_cache))
+        tag = "%s.k%d.b%d" % (base.name.split("-")[0], kb, bl)
+        qbytes = 2 * B * H * S * D * workloads.quantize_bytes_per_element(kb, bl)
+        dbytes = packed + B * H * 4 * D + (2 * B * H * splits * (D + 2) * 4 if splits > 1 else 0)
+        kern[tag + ".quantize"] = kernel_entry(qbytes, t_q, src_copies=r_src)
+        kern[tag + ".decode_attention"] = kernel_entry(dbytes, t_a, splits=splits, cache_copies=r_cache,
+                                                       tokens_per_s_per_layer=round(B / (t_a * 1e-3), 1))
+        del caches, ws
+        torch.cuda.empty_cache()
+
+
+def cpu_baseline(workloads):
+    """The CPU oracle, as it stands, on a bounded sample of the C2 workload: the full
+    B8 x H32 prefill quantize (K and V, 2048 tokens), then the first 32 of the 128 decode steps
+    (append + attention).  Same definition of effective GB/s as the GPU figure."""
+    import numpy as np
+    from oracle import nqkv_oracle as oracle
+
+    cfg = workloads.C2
+    B, H, D, S, k, blk = cfg.B, cfg.H, cfg.D, cfg.S, cfg.bits, cfg.block
+    n_steps = 32
+    cap = S + n_steps
+    rng = np.random.default_rng(0)
+    K = rng.standard_normal((B, H, cap, D)).astype(np.float16)
+    V = rng.standard_normal((B, H, cap, D)).astype(np.float16)
+    q = (rng.standard_normal((n_steps, B, H, D)) / np.sqrt(D)).astype(np.float16)
+    _, lv, _ = oracle.codebook(k)
+    threads = oracle.hardware_threads()
+    kc, ks = oracle.new_cache(B, H, D, k, blk, cap)
+    vc, vs = oracle.new_cache(B, H, D, k, blk, cap)
+    t0 = time.perf_counter()
+    oracle.quantize_kv(K[:, :, :S], k, blk, lv, kc, ks, 0, threads)
+    oracle.quantize_kv(V[:, :, :S], k, blk, lv, vc, vs, 0, threads)
+    t1 = time.perf_counter()
+    for i in range(n_steps):
+        oracle.quantize_kv(K[:, :, S + i:S + i + 1], k, blk, lv, kc, ks, S + i, threads)
+        oracle.quantize_kv(V[:, :, S + i:S + i + 1], k, blk, lv, vc, vs, S + i, threads)
+        oracle.decode_attention(q[i], kc, ks, vc, vs, k, blk, lv, S + i + 1, 1.0, threads)
+    t2 = time.perf_counter()
+    elems = 2 * B * H * D * (S + n_steps) + 2 * B * H * D * sum(S + i + 1 for i in range(n_steps))
+    return {"value": round(2 * elems / (t2 - t0) / 1e9, 4), "unit": "GB/s (fp16-equivalent KV bytes processed per second)",
+            "cores": threads, "kind": "oracle",
+            "sample": "C2 (B8 H32 D64): prefill quantize of 2048 tokens + first %d of 128 decode steps; "
+                      "quantize %.2fs, decode %.2fs" % (n_steps, t1 - t0, t2 - t1),
+            "quantize_Melem_per_s": round(2 * B * H * D * S / (t1 - t0) / 1e6, 2),
+            "decode_tokens_per_s_per_layer": round(B * n_steps / (t2 - t1), 3)}
+
+
+if __name__ == "__main__":
+    main()

@@ -150,6 +150,11 @@ int nqkv_dequantize_kv(const nqkv_cache_desc* desc, const float* levels,
  *   bytes_out   receives the workspace size in bytes (0 when one piece is used)
  *   splits_out  receives the number of pieces that will be used (may be NULL)
  * Host only.
+ *
+ * Workspace contract: the first 256 KiB hold arrival counters that must be ZERO when a call
+ * starts.  Zero-fill the workspace once after allocating it (hipMemset); every call leaves the
+ * counters zero again, so the same workspace can be reused by later calls on the same stream
+ * with any geometry.  Calls that share a workspace must not overlap in time.
  */
 int nqkv_decode_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, int num_splits,
                                 size_t* bytes_out, int* splits_out);
@@ -164,7 +169,8 @@ int nqkv_decode_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, in
  * attend, as in the paper).  K and V caches share `desc`.
  *   q, out        device fp16 [B][H][D] contiguous
  *   workspace     device memory of at least the size reported by nqkv_decode_workspace_bytes
- *                 for the same (desc, seq_len, num_splits); may be NULL when that size is 0
+ *                 for the same (desc, seq_len, num_splits), zero-filled before its first use
+ *                 (see there); may be NULL when that size is 0
  * Arithmetic: table entries are rounded to fp16 for the look-up, products accumulate in
  * fp32, exp in fp32; the result is within 2e-3 (relative to the largest |out| of the row)
  * of the same formula evaluated in fp64.  Different num_splits give results that differ

@@ -4,40 +4,49 @@
 // registers between the HBM read of the packed codes and the dot products, so a decode step
 // moves only the packed bytes.  gfx950 only; no matrix cores (one query row per head).
 //
-// Mapping.  One workgroup of four waves serves one (batch*head, split) pair and streams its
-// token range once.  A lane owns 32 consecutive head-dim elements of a token (4*k bytes of
+// Mapping.  The grid is persistent: at most two eight-wave workgroups per compute unit, each
+// building the look-up table once and then walking over work items (batch*head, split) with the
+// grid as stride; an item's token range is streamed once.  A lane owns 32 consecutive head-dim elements of a token (4*k bytes of
 // codes, one block scale), so LPT = D/32 adjacent lanes hold one token and a wave load covers
 // 64/LPT tokens with one fully coalesced request (1 KiB at k = 4).  Four such loads of K and
-// four of V are in flight per wave; the next trip's K loads are issued before the current
-// trip's V arithmetic.
+// four of V are in flight per wave; the first trip's loads are issued before the look-up table
+// is built and the next trip's K loads before the current trip's V arithmetic.
 //
-// Table precision.  The look-up table holds fp16 numbers.  Rounding the levels themselves to
-// fp16 would put a systematic relative error of up to 2^-11 on whole classes of elements, which
-// the exponential amplifies by the score range; instead the host picks a factor gamma such that
-// all gamma * level[i] are (nearly) exact in fp16, stores those, and folds 1/gamma into the score
+// Look-up.  Codes become values through an LDS table indexed by a whole byte of codes
+// (k = 4: two codes -> two fp16 levels in one dword; k = 2: four codes -> four fp16 in two
+// dwords; k = 3: a 6-bit pair -> one dword).  The kernel is bound by VALU issue as much as by
+// HBM, so the address of a look-up must cost one instruction: for k = 4 and k = 2 every table
+// row is 256 bytes (one private copy per lane, hence no bank conflicts), which lets a single
+// v_perm_b32 assemble  address = code_byte * 256 + lane_offset  from the code dword and a
+// per-lane constant.  (k = 3 pairs are not byte aligned: bfe + shift-or, 128-byte rows.)
+//
+// Table precision.  The table holds fp16 numbers.  Rounding the levels themselves to fp16 would
+// put a systematic relative error of up to 2^-11 on whole classes of elements, which the
+// exponential amplifies by the score range; instead the host picks a factor gamma such that all
+// gamma * level[i] are (nearly) exact in fp16, stores those, and folds 1/gamma into the score
 // scale and the output normalisation.
 //
-// Arithmetic.  Codes are turned into values by an LDS table indexed by a whole byte (k = 4: two
-// codes -> two fp16 levels in one dword; k = 2: four codes -> four fp16; k = 3: a 6-bit pair).
-// Each table is stored once per LDS bank (entry * 128 + bank * 4), so every lane reads its own
-// bank and look-ups never conflict.  K side: v_dot2_f32_f16 of the looked-up pair with the
-// query pair, fp32 accumulate, block scale applied once per 32 elements.  V side: fp32
-// accumulators, v_fma_mix_f32 with the weight p_t * scale.  Softmax is the running-maximum form
-// per wave: scores of a trip (64 or 128 tokens) are reduced to a wave maximum with DPP, the
-// accumulators are rescaled only when the maximum grows (a wave-uniform branch), and the
-// exponentials use exp2 with log2(e) folded into the score scale.  At the end the waves merge
-// through LDS and write either fp16 output or an fp32 partial (m, l, o[D]) for the combine
-// kernel.
+// Arithmetic.  K side: v_dot2_f32_f16 of the looked-up pair with the query pair, fp32
+// accumulate, block scale applied once per 32 elements.  V side: fp32 accumulators,
+// v_fma_mix_f32 with the weight p_t * scale.  Softmax is the running-maximum form per wave:
+// scores of a trip (64 or 128 tokens) are reduced to a wave maximum with DPP, the accumulators
+// are rescaled only when the maximum grows (a wave-uniform branch), and the exponentials use
+// exp2 with log2(e) folded into the score scale.  At the end of an item the next item's first
+// loads are issued, then the 16 (or 32) token groups of each wave are summed with a
+// reduce-scatter over lanes (v_permlane32_swap / v_permlane16_swap / DPP / ds_swizzle), the eight
+// waves meet in 4 KiB of LDS, and the workgroup writes fp16 output or an fp32 partial
+// (m, l, o[D]).  With split-K the workgroup that finishes an item's last partial (an integer
+// ticket per batch*head, no floating-point atomics) combines all of them in split order, so the
+// result does not depend on which workgroup that was.
 #include "nqkv_internal.h"
 
 namespace nqkv {
 namespace {
 
-constexpr int kWaves = 4;
+constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
 constexpr int kRounds = 4;               // wave loads of K (and of V) in flight per trip
-constexpr int kLdsRowStride = kThreads + 1;
-constexpr int kLdsWords = 32 * kLdsRowStride + 64;   // merge scratch (>= 8192-word look-up table)
+constexpr int kLutWords = 16384;         // 64 KiB: 256 rows of 256 bytes (k = 4, 2); k = 3 uses 2048
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
@@ -83,29 +92,67 @@ __device__ __forceinline__ uint32_t field(const uint32_t (&w)[NDW], int pos, int
 }
 
 // ------------------------------------------------------------------ look-up tables in LDS
-// k = 4: entry = byte (2 codes)  -> dword {fp16 level[lo nibble], fp16 level[hi nibble]}, 32 copies
-// k = 3: entry = 6 bits (2 codes)-> dword {level[lo 3 bits], level[hi 3 bits]},           32 copies
-// k = 2: entry = byte (4 codes)  -> 2 dwords {l[c0], l[c1]}, {l[c2], l[c3]},              16 copies
-// Copy c of entry e sits at byte  e * 128 + c * (4 or 8): lane L reads copy L & 31 (L & 15).
+// k = 4: row = byte (2 codes), 256 B: 64 copies of dword {fp16 level[lo nibble], level[hi nibble]}
+// k = 2: row = byte (4 codes), 256 B: 32 copies of 2 dwords {l[c0], l[c1]}, {l[c2], l[c3]}
+// k = 3: row = 6 bits (2 codes), 128 B: 32 copies of dword {level[lo 3 bits], level[hi 3 bits]}
+// Lane L reads copy L (k = 4), L & 31 (k = 2, 3).
+//
+// Built from the 16 fp16 levels in the kernel arguments: every index that depends only on the
+// loop counter is a compile-time constant (a scalar register), the per-thread ones are picked
+// once with a short select chain -- no LDS reads, one barrier.
+__device__ __forceinline__ uint32_t pick_level(const DecodeParams& p, uint32_t idx, int n) {
+  uint32_t v = 0;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    if (j < n) v = (idx == (uint32_t)j) ? (uint32_t)p.lut_levels[j] : v;
+  }
+  return v;
+}
+
 template <int KBITS>
 __device__ __forceinline__ void build_lut(const DecodeParams& p, uint32_t* smem) {
-  __shared__ unsigned short lv16[16];
-  if (threadIdx.x < (1 << KBITS)) lv16[threadIdx.x] = p.lut_levels[threadIdx.x];
-  __syncthreads();
-  constexpr int kEntries = (KBITS == 3) ? 64 : 256;
-  const uint32_t copy = threadIdx.x & 31;
-  for (uint32_t e = threadIdx.x >> 5; e < kEntries; e += kThreads / 32) {
-    if (KBITS == 2) {
-      const uint32_t lo = lv16[e & 3] | ((uint32_t)lv16[(e >> 2) & 3] << 16);
-      const uint32_t hi = lv16[(e >> 4) & 3] | ((uint32_t)lv16[(e >> 6) & 3] << 16);
-      // 16 copies of 8 bytes: word index e*32 + (copy>>1)*2 + (copy&1)
-      smem[e * 32 + copy] = (copy & 1) ? hi : lo;
-    } else {
-      const uint32_t mask = (1u << KBITS) - 1u;
-      smem[e * 32 + copy] = lv16[e & mask] | ((uint32_t)lv16[(e >> KBITS) & mask] << 16);
+  if constexpr (KBITS == 4) {
+    // word index = e * 64 + copy; thread t writes entries e = (t >> 6) + 8 i, copy = t & 63:
+    // low nibble (t >> 6) + 8 (i & 1), high nibble i >> 1
+    const uint32_t copy = threadIdx.x & 63, e0 = threadIdx.x >> 6;       // e0 in [0, 8)
+    const uint32_t lo_even = pick_level(p, e0, 16), lo_odd = pick_level(p, e0 + 8, 16);
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      const uint32_t hi = p.lut_levels[i >> 1];
+      smem[(e0 + 8 * i) * 64 + copy] = ((i & 1) ? lo_odd : lo_even) | (hi << 16);
+    }
+  } else if constexpr (KBITS == 3) {
+    // word index = e * 32 + copy; thread t: e = (t >> 5) + 16 i (6 bits), copy = t & 31:
+    // low code (t >> 5) & 7, high code (t >> 8) + 2 i
+    const uint32_t copy = threadIdx.x & 31, e0 = threadIdx.x >> 5;       // e0 in [0, 16)
+    const uint32_t lo = pick_level(p, e0 & 7, 8);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t hi_a = p.lut_levels[2 * i], hi_b = p.lut_levels[2 * i + 1];
+      smem[(e0 + 16 * i) * 32 + copy] = lo | (((e0 >> 3) ? hi_b : hi_a) << 16);
+    }
+  } else {
+    // word index = e * 64 + c; thread t: e = (t >> 6) + 8 i, c = t & 63 (dword of the row: even
+    // dwords hold {c0, c1}, odd dwords {c2, c3});
+    // c0 = e0 & 3, c1 = (e0 >> 2) + 2 (i & 1), c2 = (i >> 1) & 3, c3 = i >> 3
+    const uint32_t c = threadIdx.x & 63, e0 = threadIdx.x >> 6;          // e0 in [0, 8)
+    const uint32_t c0 = pick_level(p, e0 & 3, 4);
+    const uint32_t c1_even = pick_level(p, e0 >> 2, 4), c1_odd = pick_level(p, (e0 >> 2) + 2, 4);
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      const uint32_t lo = c0 | (((i & 1) ? c1_odd : c1_even) << 16);
+      const uint32_t hi = (uint32_t)p.lut_levels[(i >> 1) & 3] | ((uint32_t)p.lut_levels[i >> 3] << 16);
+      smem[(e0 + 8 * i) * 64 + c] = (c & 1) ? hi : lo;
     }
   }
   __syncthreads();
+}
+
+// LDS byte address of the table row selected by byte B (0..3) of code dword w, this lane's
+// copy:  v_perm_b32 -> byte0 = lane_off byte0, byte1 = w byte B, bytes 2 and 3 = 0.
+template <int B>
+__device__ __forceinline__ uint32_t row_addr(uint32_t w, uint32_t lane_off) {
+  return __builtin_amdgcn_perm(w, lane_off, 0x0c0c0000u | ((4u + B) << 8));
 }
 
 // ------------------------------------------------------------------ per-lane 32-element pieces
@@ -114,18 +161,33 @@ template <int KBITS>
 __device__ __forceinline__ float k_dot(const uint32_t (&w)[KBITS], const uint32_t (&q2)[16],
                                        const char* lut, uint32_t lane_off) {
   float acc = 0.0f;
-  if (KBITS == 2) {
+  if constexpr (KBITS == 4) {
 #pragma unroll
-    for (int b = 0; b < 8; ++b) {
-      const uint32_t byte = field<KBITS>(w, 8 * b, 8);
-      const uint2 v = *reinterpret_cast<const uint2*>(lut + ((byte << 7) | lane_off));
-      acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, v.x), __builtin_bit_cast(half2_t, q2[2 * b]), acc, false);
-      acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, v.y), __builtin_bit_cast(half2_t, q2[2 * b + 1]), acc, false);
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t a[4] = {row_addr<0>(w[i], lane_off), row_addr<1>(w[i], lane_off),
+                             row_addr<2>(w[i], lane_off), row_addr<3>(w[i], lane_off)};
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const uint32_t v = *reinterpret_cast<const uint32_t*>(lut + a[b]);
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, v), __builtin_bit_cast(half2_t, q2[4 * i + b]), acc, false);
+      }
+    }
+  } else if constexpr (KBITS == 2) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const uint32_t a[4] = {row_addr<0>(w[i], lane_off), row_addr<1>(w[i], lane_off),
+                             row_addr<2>(w[i], lane_off), row_addr<3>(w[i], lane_off)};
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const uint2 v = *reinterpret_cast<const uint2*>(lut + a[b]);
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, v.x), __builtin_bit_cast(half2_t, q2[8 * i + 2 * b]), acc, false);
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, v.y), __builtin_bit_cast(half2_t, q2[8 * i + 2 * b + 1]), acc, false);
+      }
     }
   } else {
 #pragma unroll
     for (int pr = 0; pr < 16; ++pr) {
-      const uint32_t f = field<KBITS>(w, 2 * KBITS * pr, 2 * KBITS);
+      const uint32_t f = field<KBITS>(w, 6 * pr, 6);
       const uint32_t v = *reinterpret_cast<const uint32_t*>(lut + ((f << 7) | lane_off));
       acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, v), __builtin_bit_cast(half2_t, q2[pr]), acc, false);
     }
@@ -137,214 +199,350 @@ __device__ __forceinline__ float k_dot(const uint32_t (&w)[KBITS], const uint32_
 template <int KBITS>
 __device__ __forceinline__ void v_axpy(const uint32_t (&w)[KBITS], float wgt, float (&acc)[32],
                                        const char* lut, uint32_t lane_off) {
-  if (KBITS == 2) {
+  if constexpr (KBITS == 4) {
 #pragma unroll
-    for (int b = 0; b < 8; ++b) {
-      const uint32_t byte = field<KBITS>(w, 8 * b, 8);
-      const uint2 v = *reinterpret_cast<const uint2*>(lut + ((byte << 7) | lane_off));
-      const half2_t a = __builtin_bit_cast(half2_t, v.x), c = __builtin_bit_cast(half2_t, v.y);
-      acc[4 * b + 0] = __builtin_fmaf((float)a.x, wgt, acc[4 * b + 0]);
-      acc[4 * b + 1] = __builtin_fmaf((float)a.y, wgt, acc[4 * b + 1]);
-      acc[4 * b + 2] = __builtin_fmaf((float)c.x, wgt, acc[4 * b + 2]);
-      acc[4 * b + 3] = __builtin_fmaf((float)c.y, wgt, acc[4 * b + 3]);
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t a[4] = {row_addr<0>(w[i], lane_off), row_addr<1>(w[i], lane_off),
+                             row_addr<2>(w[i], lane_off), row_addr<3>(w[i], lane_off)};
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const half2_t h = __builtin_bit_cast(half2_t, *reinterpret_cast<const uint32_t*>(lut + a[b]));
+        acc[8 * i + 2 * b + 0] = __builtin_fmaf((float)h.x, wgt, acc[8 * i + 2 * b + 0]);
+        acc[8 * i + 2 * b + 1] = __builtin_fmaf((float)h.y, wgt, acc[8 * i + 2 * b + 1]);
+      }
+    }
+  } else if constexpr (KBITS == 2) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const uint32_t a[4] = {row_addr<0>(w[i], lane_off), row_addr<1>(w[i], lane_off),
+                             row_addr<2>(w[i], lane_off), row_addr<3>(w[i], lane_off)};
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const uint2 v = *reinterpret_cast<const uint2*>(lut + a[b]);
+        const half2_t x = __builtin_bit_cast(half2_t, v.x), y = __builtin_bit_cast(half2_t, v.y);
+        const int e = 16 * i + 4 * b;
+        acc[e + 0] = __builtin_fmaf((float)x.x, wgt, acc[e + 0]);
+        acc[e + 1] = __builtin_fmaf((float)x.y, wgt, acc[e + 1]);
+        acc[e + 2] = __builtin_fmaf((float)y.x, wgt, acc[e + 2]);
+        acc[e + 3] = __builtin_fmaf((float)y.y, wgt, acc[e + 3]);
+      }
     }
   } else {
 #pragma unroll
     for (int pr = 0; pr < 16; ++pr) {
-      const uint32_t f = field<KBITS>(w, 2 * KBITS * pr, 2 * KBITS);
-      const uint32_t v = *reinterpret_cast<const uint32_t*>(lut + ((f << 7) | lane_off));
-      const half2_t a = __builtin_bit_cast(half2_t, v);
-      acc[2 * pr + 0] = __builtin_fmaf((float)a.x, wgt, acc[2 * pr + 0]);
-      acc[2 * pr + 1] = __builtin_fmaf((float)a.y, wgt, acc[2 * pr + 1]);
+      const uint32_t f = field<KBITS>(w, 6 * pr, 6);
+      const half2_t h = __builtin_bit_cast(half2_t, *reinterpret_cast<const uint32_t*>(lut + ((f << 7) | lane_off)));
+      acc[2 * pr + 0] = __builtin_fmaf((float)h.x, wgt, acc[2 * pr + 0]);
+      acc[2 * pr + 1] = __builtin_fmaf((float)h.y, wgt, acc[2 * pr + 1]);
     }
   }
 }
 
+// ------------------------------------------------------------------ HBM loads
+// All cache reads are raw buffer loads: a scalar descriptor per item (base = first token of the
+// item's range, num_records = bytes of the range), one per-lane byte offset in a VGPR and the
+// trip/round offset in a scalar register.  That keeps addresses out of the vector ALU and out
+// of vector registers.  Only voffset (not the scalar offset) takes part in the hardware range
+// check, so trip offsets are added into voffset: lanes past the end of the range then read
+// zeros -- code 0, scale 0 -- and never touch memory outside the range.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x3_t __attribute__((ext_vector_type(3)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+constexpr int kBufferFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
+
+template <int KBITS>
+__device__ __forceinline__ void load_codes(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff, uint32_t soff,
+                                           uint32_t (&w)[KBITS]) {
+  if constexpr (KBITS == 4) {
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 0);
+    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+  } else if constexpr (KBITS == 3) {
+    const u32x3_t v = __builtin_amdgcn_raw_buffer_load_b96(rsrc, voff, soff, 0);
+    w[0] = v.x; w[1] = v.y; w[2] = v.z;
+  } else {
+    const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff, soff, 0);
+    w[0] = v.x; w[1] = v.y;
+  }
+}
+
+// Device-wide visible 32-bit store / load of a float (write-through / cache-bypassing).
+__device__ __forceinline__ void store_agent(uint32_t* p, float v) {
+  __hip_atomic_store(p, __builtin_bit_cast(uint32_t, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_agent(const uint32_t* p) {
+  return __builtin_bit_cast(float, __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+
+// ------------------------------------------------------------------ in-wave reduce-scatter
+// Sums acc[0..31] over the token groups of a wave (lanes with equal lane % LPT).  Each step
+// halves the number of values a lane holds and sums across one lane bit:
+//   bit 5: v_permlane32_swap, bit 4: v_permlane16_swap, bit 3: DPP row_ror:8, bit 2: ds_swizzle
+//   xor 4, (LPT == 2 only) bit 1: DPP quad_perm xor 2.
+// Afterwards a lane holds elements  e = 16 b5 + 8 b4 + 4 b3 + 2 b2 + i  (i = 0, 1; LPT == 4) or
+// e = 16 b5 + 8 b4 + 4 b3 + 2 b2 + b1 (LPT == 2) of head-dim slice j = lane % LPT, where b_n is
+// bit n of the lane index.
+// The swaps are written as inline assembly: with the compiler builtin for these instructions
+// the sum of the two results came out as (first + first) in this toolchain.  v_permlane32_swap
+// exchanges lanes 32..63 of its first operand with lanes 0..31 of its second (v_permlane16_swap:
+// odd 16-lane rows of the first with even rows of the second), so first + second afterwards is
+// the sum over that lane bit, with the low half-lanes holding `a` and the high ones `b`.  The
+// s_nop covers the wait states these instructions need after a VALU write of their operands.
+__device__ __forceinline__ float swap32_add(float a, float b) {
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  return a + b;
+}
+__device__ __forceinline__ float swap16_add(float a, float b) {
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  return a + b;
+}
+constexpr int kRowRor8 = 0x128;
+constexpr int kSwizzleXor4 = 0x101F;
+
+template <int LPT>
+__device__ __forceinline__ void reduce_groups(const float (&acc)[32], uint32_t lane, float (&out)[2]) {
+  float a16[16], a8[8], a4[4];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) a16[i] = swap32_add(acc[i], acc[i + 16]);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a8[i] = swap16_add(a16[i], a16[i + 8]);
+  const bool b3 = lane & 8, b2 = lane & 4, b1 = lane & 2;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float send = b3 ? a8[i] : a8[i + 4], keep = b3 ? a8[i + 4] : a8[i];
+    a4[i] = keep + dpp_f<kRowRor8>(send);
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const float send = b2 ? a4[i] : a4[i + 2], keep = b2 ? a4[i + 2] : a4[i];
+    out[i] = keep + __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, send), kSwizzleXor4));
+  }
+  if (LPT == 2) {
+    const float send = b1 ? out[0] : out[1], keep = b1 ? out[1] : out[0];
+    out[0] = keep + dpp_f<kQuadXor2>(send);
+  }
+}
+
 // ------------------------------------------------------------------ main kernel
-// grid: x = split, y = batch*head
+// grid: x = persistent workgroups; item i -> (bh = i / splits, split = i % splits)
 template <int KBITS, int D, int BLK>
-__global__ __launch_bounds__(kThreads) void decode_kernel(const DecodeParams p) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) void decode_kernel(const DecodeParams p) {   // 128 VGPRs: two workgroups per CU
   constexpr int LPT = D / 32;             // lanes per token
   constexpr int TPR = 64 / LPT;           // tokens per wave load
   constexpr int CHUNK = kRounds * TPR;    // tokens per wave trip
   constexpr int NB = D / BLK;
-  __shared__ __attribute__((aligned(16))) uint32_t smem[kLdsWords];
+  constexpr int ROW = LPT * KBITS;        // dwords of codes per token
+  __shared__ __attribute__((aligned(16))) uint32_t smem[kLutWords];
+  __shared__ float xw[kWaves][D];
   __shared__ float wave_m[kWaves], wave_l[kWaves];
+  __shared__ uint32_t ticket_sh;
 
-  build_lut<KBITS>(p, smem);
   const char* lut = reinterpret_cast<const char*>(smem);
-
-  const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t lane = threadIdx.x & 63;
+  // the wave index as a scalar, so that everything derived from it (token ranges, the full-trip
+  // test) is uniform control flow for the compiler
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t j = lane % LPT, g = lane / LPT;
-  const uint32_t lane_off = (KBITS == 2) ? ((lane & 15) << 3) : ((lane & 31) << 2);
-  const int64_t bh = blockIdx.y;
-  // split i covers tokens [floor(i*S/splits), floor((i+1)*S/splits)): never empty for splits <= S
-  const int64_t t0 = ((int64_t)blockIdx.x * p.seq_len) / p.splits;
-  const int64_t t_end = (((int64_t)blockIdx.x + 1) * p.seq_len) / p.splits;
+  const uint32_t lane_off = (KBITS == 4) ? (lane << 2) : (KBITS == 2) ? ((lane & 31) << 3) : ((lane & 31) << 2);
+  const int32_t stride = kWaves * CHUNK;
 
-  // query pairs for this lane's 32 dims
+  uint32_t kw[kRounds][KBITS], vw[kRounds][KBITS];
+  uint16_t ksc[kRounds], vsc[kRounds];
   uint32_t q2[16];
-  {
-    const uint4* qp = reinterpret_cast<const uint4*>(p.q + bh * D + j * 32);
+
+  // Item geometry.  Split sp of a sequence covers sp * split_base + min(sp, split_rem) onwards,
+  // split_base (+1 for the first split_rem splits) tokens: never empty.  Token counts below are
+  // relative to the item's first token and fit 32 bits with room to spare (host-checked).
+  constexpr uint32_t kRowBytes = ROW * 4, kScaleRowBytes = NB * 2;
+  const uint32_t code_voff = g * kRowBytes + j * (KBITS * 4);            // this lane's slice of a token row
+  const uint32_t scale_voff = g * kScaleRowBytes + ((j * 32) / BLK) * 2;
+  uint32_t bh = 0, sp = 0;
+  int32_t n_tok = 0, base = 0;      // tokens in the item; this wave's current trip start (item-relative)
+  __amdgpu_buffer_rsrc_t kc_r, vc_r, ks_r, vs_r;
+  auto set_item = [&](uint32_t item) {
+    bh = item / (uint32_t)p.splits;
+    sp = item - bh * (uint32_t)p.splits;
+    const int64_t t0 = (int64_t)sp * p.split_base + min((int32_t)sp, p.split_rem);
+    n_tok = p.split_base + ((int32_t)sp < p.split_rem ? 1 : 0);
+    base = (int32_t)wave * CHUNK;
+    const int64_t row0 = (int64_t)bh * p.cap_tokens + t0;
+    kc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.k_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
+    vc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.v_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
+    ks_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.k_scales) + row0 * NB, 0, n_tok * (int)kScaleRowBytes, kBufferFlags);
+    vs_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.v_scales) + row0 * NB, 0, n_tok * (int)kScaleRowBytes, kBufferFlags);
+  };
+
+  // Loads of one trip starting at item-relative token tb (uniform).  The trip offset goes into
+  // voffset, which is what the hardware range-checks: tokens past the end of the item (the
+  // ragged last trip, or a whole trip that does not exist) read zeros and touch no memory.  That
+  // lets every trip issue exactly the same loads unconditionally, which matters because the
+  // memory counter is positional: loads issued under a branch make the compiler wait for the
+  // worst case at the join.
+  auto load_trip = [&](__amdgpu_buffer_rsrc_t codes, __amdgpu_buffer_rsrc_t scales, int32_t tb,
+                       uint32_t (&w)[kRounds][KBITS], uint16_t (&sc)[kRounds]) {
+    const uint32_t cv = code_voff + (uint32_t)tb * kRowBytes;
+    const uint32_t sv = scale_voff + (uint32_t)tb * kScaleRowBytes;
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+      load_codes<KBITS>(codes, cv + r * TPR * kRowBytes, 0, w[r]);
+      sc[r] = __builtin_amdgcn_raw_buffer_load_b16(scales, sv + r * TPR * kScaleRowBytes, 0, 0);
+    }
+  };
+  auto load_q = [&]() {
+    const uint4* qp = reinterpret_cast<const uint4*>(p.q + (int64_t)bh * D + j * 32);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint4 v = qp[i];
       q2[4 * i] = v.x; q2[4 * i + 1] = v.y; q2[4 * i + 2] = v.z; q2[4 * i + 3] = v.w;
     }
-  }
-
-  const int64_t slab = bh * p.cap_tokens;
-  const uint32_t* kc = reinterpret_cast<const uint32_t*>(p.k_codes) + slab * (LPT * KBITS);
-  const uint32_t* vc = reinterpret_cast<const uint32_t*>(p.v_codes) + slab * (LPT * KBITS);
-  const uint16_t* ks = p.k_scales + slab * NB;
-  const uint16_t* vs = p.v_scales + slab * NB;
-  const uint32_t blk_of_lane = (j * 32) / BLK;
-
-  float acc[32];
-#pragma unroll
-  for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
-  float m_run = -INFINITY;   // wave-uniform, log2 domain
-  float l_run = 0.0f;        // per lane; every lane of a token group adds the same p
-
-  uint32_t kw[kRounds][KBITS], vw[kRounds][KBITS];
-  uint16_t ksc[kRounds], vsc[kRounds];
-
-  auto load_k = [&](int64_t base) {
-#pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-      const int64_t tc = min(base + r * TPR + g, t_end - 1);
-      const uint32_t* src = kc + (tc * LPT + j) * KBITS;
-      if constexpr (KBITS == 4) {
-        const uint4 v = *reinterpret_cast<const uint4*>(src);
-        kw[r][0] = v.x; kw[r][1] = v.y; kw[r][2] = v.z; kw[r][3] = v.w;
-      } else if constexpr (KBITS == 2) {
-        const uint2 v = *reinterpret_cast<const uint2*>(src);
-        kw[r][0] = v.x; kw[r][1] = v.y;
-      } else {
-#pragma unroll
-        for (int i = 0; i < KBITS; ++i) kw[r][i] = src[i];
-      }
-      ksc[r] = ks[tc * NB + blk_of_lane];
-    }
-  };
-  auto load_v = [&](int64_t base) {
-#pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-      const int64_t tc = min(base + r * TPR + g, t_end - 1);
-      const uint32_t* src = vc + (tc * LPT + j) * KBITS;
-      if constexpr (KBITS == 4) {
-        const uint4 v = *reinterpret_cast<const uint4*>(src);
-        vw[r][0] = v.x; vw[r][1] = v.y; vw[r][2] = v.z; vw[r][3] = v.w;
-      } else if constexpr (KBITS == 2) {
-        const uint2 v = *reinterpret_cast<const uint2*>(src);
-        vw[r][0] = v.x; vw[r][1] = v.y;
-      } else {
-#pragma unroll
-        for (int i = 0; i < KBITS; ++i) vw[r][i] = src[i];
-      }
-      vsc[r] = vs[tc * NB + blk_of_lane];
-    }
   };
 
-  const int64_t stride = (int64_t)kWaves * CHUNK;
-  int64_t base = t0 + (int64_t)wave * CHUNK;
-  if (base < t_end) load_k(base);
-  for (; base < t_end; base += stride) {
-    load_v(base);
+  // The first item's K loads and query slice go out before anything else, so HBM latency
+  // overlaps the table build.
+  uint32_t item = blockIdx.x;
+  set_item(item);
+  load_trip(kc_r, ks_r, base, kw, ksc);
+  load_q();
+  build_lut<KBITS>(p, smem);
+  // Make the query registers "arrived" here, outside the trip loop: otherwise the wait for
+  // them is re-imposed at the top of every trip (it is pending on the loop-entry path only), and
+  // because the memory counter is positional that stalls each trip on its own fresh V loads.
+  auto settle_q = [&]() {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) asm volatile("" ::"v"(q2[i]));
+  };
+  settle_q();
 
-    // scores of this trip's tokens (log2 domain)
-    float z[kRounds];
+  while (true) {
+    float acc[32];
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-      float part = k_dot<KBITS>(kw[r], q2, lut, lane_off);
-      part *= (float)__builtin_bit_cast(_Float16, ksc[r]);
-      part += dpp_f<kQuadXor1>(part);
-      if (LPT == 4) part += dpp_f<kQuadXor2>(part);
-      const bool valid = base + r * TPR + g < t_end;
-      z[r] = valid ? part * p.scale_log2e : -INFINITY;
-    }
-    float m_trip = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
-    m_trip = wave_max(m_trip);
-    if (m_trip > m_run) {            // uniform across the wave
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_trip);
+    for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
+    float m_run = -INFINITY;   // wave-uniform, log2 domain
+    float l_run = 0.0f;        // per lane; every lane of a token group adds the same p
+
+    for (; base < n_tok; base += stride) {
+      const bool full = base + CHUNK <= n_tok;
+      load_trip(vc_r, vs_r, base, vw, vsc);
+
+      // scores of this trip's tokens (log2 domain)
+      float z[kRounds];
 #pragma unroll
-      for (int i = 0; i < 32; ++i) acc[i] *= alpha;
-      l_run *= alpha;
-      m_run = m_trip;
-    }
-    float pw[kRounds];
+      for (int r = 0; r < kRounds; ++r) {
+        float part = k_dot<KBITS>(kw[r], q2, lut, lane_off);
+        part *= (float)__builtin_bit_cast(_Float16, ksc[r]);
+        part += dpp_f<kQuadXor1>(part);
+        if (LPT == 4) part += dpp_f<kQuadXor2>(part);
+        const bool valid = full || (base + r * TPR + (int32_t)g < n_tok);
+        z[r] = valid ? part * p.scale_log2e : -INFINITY;
+      }
+      float m_trip = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+      m_trip = wave_max(m_trip);
+      if (m_trip > m_run) {            // uniform across the wave
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_trip);
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-      pw[r] = __builtin_amdgcn_exp2f(z[r] - m_run);
-      l_run += pw[r];
+        for (int i = 0; i < 32; ++i) acc[i] *= alpha;
+        l_run *= alpha;
+        m_run = m_trip;
+      }
+      float pw[kRounds];
+#pragma unroll
+      for (int r = 0; r < kRounds; ++r) {
+        pw[r] = __builtin_amdgcn_exp2f(z[r] - m_run);
+        l_run += pw[r];
+      }
+
+      load_trip(kc_r, ks_r, base + stride, kw, ksc);     // past the end on the last trip: reads zeros
+
+#pragma unroll
+      for (int r = 0; r < kRounds; ++r) {
+        const float wgt = pw[r] * (float)__builtin_bit_cast(_Float16, vsc[r]);
+        v_axpy<KBITS>(vw[r], wgt, acc, lut, lane_off);
+      }
     }
 
-    if (base + stride < t_end) load_k(base + stride);
-
-#pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-      const float wgt = pw[r] * (float)__builtin_bit_cast(_Float16, vsc[r]);
-      v_axpy<KBITS>(vw[r], wgt, acc, lut, lane_off);
+    // ---- this item is streamed; remember where its result goes, then start the next item's
+    // first K loads so that they fly during the merge
+    const uint32_t cur_bh = bh, cur_sp = sp;
+    const uint32_t next_item = item + gridDim.x;
+    const bool more = next_item < (uint32_t)p.n_items;
+    if (more) {
+      set_item(next_item);
+      load_trip(kc_r, ks_r, base, kw, ksc);
+      load_q();
     }
+
+    // ---- merge: token groups inside each wave, then the eight waves through LDS
+    float red[2];
+    reduce_groups<LPT>(acc, lane, red);
+    const float l_wave = wave_sum(l_run) * (1.0f / LPT);
+    {
+      const uint32_t e = ((lane >> 5) & 1) * 16 + ((lane >> 4) & 1) * 8 + ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2;
+      if (LPT == 4) {
+        xw[wave][j * 32 + e] = red[0];
+        xw[wave][j * 32 + e + 1] = red[1];
+      } else {
+        xw[wave][j * 32 + e + ((lane >> 1) & 1)] = red[0];
+      }
+      if (lane == 0) { wave_m[wave] = m_run; wave_l[wave] = l_wave; }
+    }
+    __syncthreads();
+    float m_all = wave_m[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) m_all = fmaxf(m_all, wave_m[w]);
+    float l_all = 0.0f, o = 0.0f;
+    if (threadIdx.x < D) {
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const float f = __builtin_amdgcn_exp2f(wave_m[w] - m_all);   // 0 for a wave that saw no token
+        l_all += wave_l[w] * f;
+        o += xw[w][threadIdx.x] * f;
+      }
+      if (p.splits == 1) {
+        p.out[(int64_t)cur_bh * D + threadIdx.x] = __builtin_bit_cast(unsigned short, (_Float16)(o * p.inv_gamma / l_all));
+      } else {
+        // Partials travel between workgroups, possibly on different XCDs whose L2 caches are not
+        // coherent with each other: write them through (agent-scope stores) rather than paying
+        // for a whole-L2 write-back fence per item.
+        uint32_t* ws = reinterpret_cast<uint32_t*>(p.partials + ((int64_t)cur_bh * p.splits + cur_sp) * (D + 2));
+        store_agent(ws + 2 + threadIdx.x, o);
+        if (threadIdx.x == 0) { store_agent(ws, m_all); store_agent(ws + 1, l_all); }
+      }
+    }
+    if (p.splits > 1) {
+      // Once every store above is acknowledged, take a ticket; the workgroup holding the last
+      // ticket of this (b,h) combines all partials in split order (reading them past the
+      // caches) and re-arms the ticket counter.
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (threadIdx.x == 0) ticket_sh = __hip_atomic_fetch_add(p.tickets + cur_bh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __syncthreads();
+      if (ticket_sh == (uint32_t)p.splits - 1u) {
+        if (threadIdx.x < D) {
+          const uint32_t* ws = reinterpret_cast<const uint32_t*>(p.partials + (int64_t)cur_bh * p.splits * (D + 2));
+          float mm = -INFINITY;
+          for (int s2 = 0; s2 < p.splits; ++s2) mm = fmaxf(mm, load_agent(ws + s2 * (D + 2)));
+          float oo = 0.0f, ll = 0.0f;
+          for (int s2 = 0; s2 < p.splits; ++s2) {
+            const float f = __builtin_amdgcn_exp2f(load_agent(ws + s2 * (D + 2)) - mm);
+            ll += f * load_agent(ws + s2 * (D + 2) + 1);
+            oo += f * load_agent(ws + s2 * (D + 2) + 2 + threadIdx.x);
+          }
+          p.out[(int64_t)cur_bh * D + threadIdx.x] = __builtin_bit_cast(unsigned short, (_Float16)(oo * p.inv_gamma / ll));
+        }
+        if (threadIdx.x == 0) __hip_atomic_store(p.tickets + cur_bh, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    settle_q();           // before the exit test, so that every path back to the loop head has it
+    if (!more) break;
+    item = next_item;
+    __syncthreads();      // xw / wave_m / ticket_sh are reused by the next item
   }
-
-  // ---- merge the four waves -------------------------------------------------------------
-  const float l_wave = wave_sum(l_run) * (1.0f / LPT);
-  if (lane == 0) { wave_m[wave] = m_run; wave_l[wave] = l_wave; }
-  __syncthreads();                      // everyone is done with the look-up table
-  float m_all = wave_m[0];
-#pragma unroll
-  for (int w = 1; w < kWaves; ++w) m_all = fmaxf(m_all, wave_m[w]);
-  float l_all = 0.0f;
-#pragma unroll
-  for (int w = 0; w < kWaves; ++w) l_all += wave_l[w] * __builtin_amdgcn_exp2f(wave_m[w] - m_all);
-  const float f = __builtin_amdgcn_exp2f(m_run - m_all);   // 0 for a wave that saw no token
-  float* scratch = reinterpret_cast<float*>(smem);
-#pragma unroll
-  for (int i = 0; i < 32; ++i) scratch[i * kLdsRowStride + threadIdx.x] = acc[i] * f;
-  __syncthreads();
-  if (threadIdx.x < D) {
-    const uint32_t d = threadIdx.x, dj = d / 32, di = d % 32;
-    float o = 0.0f;
-    for (uint32_t gg = 0; gg < kThreads / LPT; ++gg) o += scratch[di * kLdsRowStride + gg * LPT + dj];
-    if (p.splits == 1) {
-      p.out[bh * D + d] = __builtin_bit_cast(unsigned short, (_Float16)(o * p.inv_gamma / l_all));
-    } else {
-      float* ws = p.workspace + (bh * p.splits + blockIdx.x) * (D + 2);
-      ws[2 + d] = o;
-      if (d == 0) { ws[0] = m_all; ws[1] = l_all; }
-    }
-  }
-}
-
-// Split-K combine: out = sum_i 2^(m_i - M) o_i / sum_i 2^(m_i - M) l_i.  grid x = batch*head.
-template <int D>
-__global__ __launch_bounds__(D) void combine_kernel(const DecodeParams p) {
-  const int64_t bh = blockIdx.x;
-  const uint32_t d = threadIdx.x;
-  const float* ws = p.workspace + bh * p.splits * (D + 2);
-  float m_all = -INFINITY;
-  for (int s = 0; s < p.splits; ++s) m_all = fmaxf(m_all, ws[s * (D + 2)]);
-  float o = 0.0f, l = 0.0f;
-  for (int s = 0; s < p.splits; ++s) {
-    const float f = __builtin_amdgcn_exp2f(ws[s * (D + 2)] - m_all);
-    l += f * ws[s * (D + 2) + 1];
-    o += f * ws[s * (D + 2) + 2 + d];
-  }
-  p.out[bh * D + d] = __builtin_bit_cast(unsigned short, (_Float16)(o * p.inv_gamma / l));
 }
 
 template <int KBITS, int D, int BLK>
 hipError_t launch_one(const DecodeParams& p, hipStream_t stream) {
-  dim3 grid((unsigned)p.splits, (unsigned)p.BH, 1);
-  hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK>), grid, dim3(kThreads), 0, stream, p);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  if (p.splits > 1) {
-    hipLaunchKernelGGL((combine_kernel<D>), dim3((unsigned)p.BH), dim3(D), 0, stream, p);
-    e = hipGetLastError();
-  }
-  return e;
+  const int wgs = p.n_items < p.max_workgroups ? p.n_items : p.max_workgroups;
+  hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, p);
+  return hipGetLastError();
 }
 
 template <int KBITS>
@@ -358,6 +556,7 @@ hipError_t launch_k(const DecodeParams& p, int D, int blk, hipStream_t stream) {
 }  // namespace
 
 int decode_chunk_tokens(int D) { return kRounds * (64 / (D / 32)); }
+int decode_waves_per_workgroup() { return kWaves; }
 
 hipError_t launch_decode_attention(const DecodeParams& p, int D, int k, int blk, hipStream_t stream) {
   switch (k) {

@@ -14,6 +14,7 @@ using namespace nqkv;
 // Experiment switches (see nqkv_set_tuning).  Plain ints: set them before issuing work.
 int g_quantize_impl = 0;       // 0 cell table, 1 threshold scan
 int g_decode_target_wgs = 0;   // 0 = default
+int g_decode_grid_limit = 0;   // 0 = default (persistent grid); > 0 = at most this many workgroups
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -25,8 +26,8 @@ int check_desc(const nqkv_cache_desc* d) {
   if (d->D != 64 && d->D != 128) return NQKV_EUNSUPPORTED;
   if (d->block != 64 && d->block != 128) return NQKV_EUNSUPPORTED;
   if (d->D % d->block != 0) return NQKV_EINVAL;
-  if ((int64_t)d->B * d->H > 65535) return NQKV_EUNSUPPORTED;
-  if (d->cap_tokens > (int64_t)1 << 31) return NQKV_EUNSUPPORTED;
+  if ((int64_t)d->B * d->H > 65535) return NQKV_EUNSUPPORTED;   // grid dimension and ticket table
+  if (d->cap_tokens > ((int64_t)1 << 31) - 1) return NQKV_EUNSUPPORTED;
   return NQKV_OK;
 }
 
@@ -134,6 +135,24 @@ const LutChoice& choose_lut_scale(const float* levels, int L) {
   return memo;
 }
 
+size_t workspace_need(const nqkv_cache_desc* d, int splits) {
+  if (splits <= 1) return 0;
+  return kTicketBytes + (size_t)d->B * d->H * splits * (d->D + 2) * sizeof(float);
+}
+
+// Persistent grid size: two eight-wave workgroups fit on a compute unit (64 KiB table each).
+int max_decode_workgroups() {
+  static int cached = 0;
+  if (cached == 0) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+    cached = 2 * cus;
+  }
+  return cached;
+}
+
 int plan_splits(const nqkv_cache_desc* d, int64_t seq_len, int num_splits, int* splits) {
   if (seq_len < 1 || seq_len > d->cap_tokens) return NQKV_EINVAL;
   if (num_splits < 0 || num_splits > 1024) return NQKV_EINVAL;
@@ -142,14 +161,15 @@ int plan_splits(const nqkv_cache_desc* d, int64_t seq_len, int num_splits, int* 
     *splits = num_splits;
     return NQKV_OK;
   }
-  // Aim for several resident workgroups on each of the 256 compute units, but keep every
-  // workgroup long enough (two trips per wave) that the table set-up and the merge stay small.
+  // Every item (one piece of one (b,h) sequence) costs a few microseconds of set-up, merge and,
+  // when a sequence is cut, publishing a partial result; measured on MI355X the best cut gives
+  // about one item per compute unit when B*H alone does not, and no cut otherwise.  Never cut
+  // below one trip of one wave.
   const int64_t bh = (int64_t)d->B * d->H;
-  const int64_t target = g_decode_target_wgs > 0 ? g_decode_target_wgs : 1536;
-  const int64_t trip = (int64_t)decode_chunk_tokens(d->D) * 4;      // tokens per workgroup trip
-  int64_t want = (target + bh - 1) / bh;
-  int64_t longest = seq_len / (2 * trip);
-  if (longest < 1) longest = 1;
+  const int64_t target = g_decode_target_wgs > 0 ? g_decode_target_wgs : 256;
+  const int64_t trip = (int64_t)decode_chunk_tokens(d->D);
+  int64_t want = target / bh;
+  int64_t longest = seq_len / trip;
   if (want > longest) want = longest;
   if (want > 1024) want = 1024;
   if (want < 1) want = 1;
@@ -178,6 +198,7 @@ int nqkv_set_tuning(int knob, int value) {
   switch (knob) {
     case 0: if (value != 0 && value != 1) return NQKV_EINVAL; g_quantize_impl = value; return NQKV_OK;
     case 1: if (value < 0 || value > 65536) return NQKV_EINVAL; g_decode_target_wgs = value; return NQKV_OK;
+    case 2: if (value < 0) return NQKV_EINVAL; g_decode_grid_limit = value; return NQKV_OK;
     default: return NQKV_EINVAL;
   }
 }
@@ -301,7 +322,7 @@ int nqkv_decode_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, in
   if (!bytes_out) return NQKV_EINVAL;
   int splits = 1;
   if ((rc = plan_splits(desc, seq_len, num_splits, &splits))) return rc;
-  *bytes_out = splits > 1 ? (size_t)desc->B * desc->H * splits * (desc->D + 2) * sizeof(float) : 0;
+  *bytes_out = workspace_need(desc, splits);
   if (splits_out) *splits_out = splits;
   return NQKV_OK;
 }
@@ -326,7 +347,7 @@ int nqkv_decode_attention(const nqkv_cache_desc* desc, const float* levels,
   for (const void* ptr : ptrs) {
     if (!ptr || !aligned16(ptr)) return NQKV_EINVAL;
   }
-  const size_t need = splits > 1 ? (size_t)desc->B * desc->H * splits * (desc->D + 2) * sizeof(float) : 0;
+  const size_t need = workspace_need(desc, splits);
   if (need > 0) {
     if (!workspace || !aligned16(workspace)) return NQKV_EINVAL;
     if (workspace_bytes < need) return NQKV_EWORKSPACE;
@@ -337,11 +358,14 @@ int nqkv_decode_attention(const nqkv_cache_desc* desc, const float* levels,
   p.v_codes = static_cast<const uint8_t*>(v_codes);
   p.v_scales = static_cast<const uint16_t*>(v_scales);
   p.out = static_cast<uint16_t*>(out);
-  p.workspace = static_cast<float*>(workspace);
-  p.BH = desc->B * desc->H;
+  p.tickets = static_cast<uint32_t*>(workspace);
+  p.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kTicketBytes);
+  p.n_items = desc->B * desc->H * splits;
   p.splits = splits;
+  p.split_base = (int)(seq_len / splits);
+  p.split_rem = (int)(seq_len % splits);
+  p.max_workgroups = g_decode_grid_limit > 0 ? g_decode_grid_limit : max_decode_workgroups();
   p.cap_tokens = desc->cap_tokens;
-  p.seq_len = seq_len;
   const LutChoice& lut = choose_lut_scale(checked.v, 1 << desc->k);
   std::memcpy(p.lut_levels, lut.bits, sizeof(uint16_t) * (1 << desc->k));
   p.inv_gamma = 1.0f / lut.gamma;

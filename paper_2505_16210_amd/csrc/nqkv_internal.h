@@ -44,15 +44,21 @@ struct DecodeParams {
   const uint8_t* v_codes;
   const uint16_t* v_scales;
   uint16_t* out;             // [B*H][D] fp16
-  float* workspace;          // [B*H][splits][D+2] fp32 (m, l, o[D]) when splits > 1
-  int BH;
+  uint32_t* tickets;         // split-K: one arrival counter per (b,h), zero between calls
+  float* partials;           // split-K: [B*H][splits][D+2] fp32 (m, l, o[D])
+  int n_items;               // B*H*splits
   int splits;
+  int split_base, split_rem; // seq_len = splits * split_base + split_rem
+  int max_workgroups;        // persistent grid size limit (2 per compute unit)
   int64_t cap_tokens;
-  int64_t seq_len;
   float scale_log2e;         // softmax_scale * log2(e) / gamma
   float inv_gamma;           // 1 / gamma: undoes the table scaling on the value side
   uint16_t lut_levels[kMaxLevels];   // fp16 bits of gamma * level[i] (see choose_lut_scale)
 };
+
+// Bytes at the start of the split-K workspace that hold the ticket counters (one uint32 per
+// (b,h), room for the largest supported B*H), before the partial results.
+constexpr size_t kTicketBytes = 65536 * sizeof(uint32_t);
 
 // Each returns hipSuccess or the launch error.  D in {64,128}, k in {2,3,4}, blk in {64,128}.
 hipError_t launch_quantize(const QuantParams& p, int D, int k, int blk, hipStream_t stream);
@@ -62,6 +68,7 @@ hipError_t launch_decode_attention(const DecodeParams& p, int D, int k, int blk,
 // Tokens one wave of the attention kernel consumes per main-loop trip; split boundaries are
 // multiples of this.
 int decode_chunk_tokens(int D);
+int decode_waves_per_workgroup();
 
 // Fills the quantizer's cell table; false when the table does not admit one (then use impl 1).
 bool build_cell_table(const float* levels, int k, uint32_t* thr_bits, uint32_t* below);

@@ -184,7 +184,7 @@ def decode_attention(desc: CacheDesc, levels, q: torch.Tensor, k_codes, k_scales
     if workspace is None:
         need, _ = decode_workspace_bytes(desc, seq_len, num_splits)
         if need:
-            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+            workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)   # counters start at zero
     if workspace is not None:
         ws_bytes = workspace.numel() * workspace.element_size()
     rc = lib.nqkv_decode_attention(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_codes), _dev_ptr(k_scales),

@@ -121,9 +121,9 @@ def test_quantize_pair_and_dequantize_argument_errors(nqkv):
 def test_workspace_planning(nqkv):
     d = nqkv.make_desc(1, 32, 128, 4, 64, 32768)
     nbytes, splits = nqkv.decode_workspace_bytes(d, 32768, 0)
-    assert splits > 1 and nbytes == 32 * splits * 130 * 4
+    assert splits > 1 and nbytes == 262144 + 32 * splits * 130 * 4
     assert nqkv.decode_workspace_bytes(d, 32768, 1) == (0, 1)
-    assert nqkv.decode_workspace_bytes(d, 32768, 7) == (32 * 7 * 130 * 4, 7)
+    assert nqkv.decode_workspace_bytes(d, 32768, 7) == (262144 + 32 * 7 * 130 * 4, 7)
     assert nqkv.decode_workspace_bytes(d, 5, 0) == (0, 1)               # short sequence: one piece
     big = nqkv.make_desc(32, 32, 128, 4, 64, 2048)
     assert nqkv.decode_workspace_bytes(big, 2048, 0)[1] <= 2
