@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--kernel-iters", type=int, default=30)
     ap.add_argument("--cold", type=int, default=1, help="1: rotate buffers to defeat the last-level cache")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch the step's 257 kernels one by one from Python instead of replaying a HIP graph")
     ap.add_argument("--skip-step", action="store_true",
                     help="profiling aid: skip the timed C2 step, only run the kernels of --configs")
     return ap.parse_args()
@@ -115,42 +117,23 @@ def main():
     def prefill(s):
         ksrc, vsrc = srcs[s % R_SRC]
         kc, ks, vc, vs = caches[s % R_CACHE]
-        nqkv.quantize_kv_pair(desc, lv, ksrc, vsrc, kc, ks, vc, vs, 0, stream=stream)
+        nqkv.quantize_kv_pair(desc, lv, ksrc, vsrc, kc, ks, vc, vs, 0)
 
     def append(i):
         kc, ks, vc, vs = caches[i % R_CACHE]
         kn, vn = new_views[i % steps_dec]
-        nqkv.quantize_kv_pair(desc, lv, kn, vn, kc, ks, vc, vs, S + (i % steps_dec), stream=stream)
+        nqkv.quantize_kv_pair(desc, lv, kn, vn, kc, ks, vc, vs, S + (i % steps_dec))
 
     def attend(i):
         kc, ks, vc, vs = caches[i % R_CACHE]
         j = i % steps_dec
-        nqkv.decode_attention(desc, lv, qs[j], kc, ks, vc, vs, S + j + 1, 1.0, out=out,
-                              workspace=ws, stream=stream)
+        nqkv.decode_attention(desc, lv, qs[j], kc, ks, vc, vs, S + j + 1, 1.0, out=out, workspace=ws)
 
     def step(s):
         prefill(s)
         for i in range(steps_dec):
             append(i)
             attend(i)
-
-    for s in range(args.warmup):
-        step(s)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t_host0 = time.perf_counter()
-    e0.record(stream)
-    for s in range(args.steps):
-        step(args.warmup + s)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    host_ms = (time.perf_counter() - t_host0) * 1e3 / args.steps
-    ms_per_step = e0.elapsed_time(e1) / args.steps
-
-    elems_quant = 2 * B * H * D * (S + steps_dec)                       # K and V, prefill + appended
-    elems_attn = 2 * B * H * D * sum(S + i + 1 for i in range(steps_dec))
-    eff_bytes = 2 * (elems_quant + elems_attn)
-    value = eff_bytes / (ms_per_step * 1e-3) / 1e9
 
     # ------------------------------------------------------------------ per-kernel timings, C2
     it = args.kernel_iters
@@ -165,8 +148,53 @@ def main():
     dec_bytes = B * H * (mean_seq * workloads.decode_bytes_per_token_head(D, k, blk) + 4 * D) \
         + (2 * B * H * splits * (D + 2) * 4 if splits > 1 else 0)      # partials written and re-read
     kern["C2.decode_attention"] = kernel_entry(dec_bytes, t_att, splits=splits)
-    t_decode_step = t_app + t_att
+
+    # The step is 1 + 2 * 128 kernel launches of 5-35 us each: issued one by one from Python the
+    # host cannot keep up, so the step is captured once into a HIP graph (kernel nodes only) and
+    # replayed.  Replays are checked against the eager result before timing.
+    step(0)
+    torch.cuda.synchronize()
+    eager_out = out.clone()
+    graph = None
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step(0)
+        for _ in range(3):
+            out.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager_out), "graph replay differs from eager step"
+            prefill(1)                      # eager work between replays
+            torch.cuda.synchronize()
+        run_step = lambda s_: graph.replay()
+    else:
+        run_step = step
+
+    for s in range(args.warmup):
+        run_step(s)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_host0 = time.perf_counter()
+    e0.record(stream)
+    for s in range(args.steps):
+        run_step(args.warmup + s)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    host_ms = (time.perf_counter() - t_host0) * 1e3 / args.steps
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+
+    # decode-step time as it runs inside the step (graph: no launch gaps)
+    t_decode_step = max(ms_per_step - t_pre, 0.0) / steps_dec
     tokens_per_s_layer = B / (t_decode_step * 1e-3)
+
+    elems_quant = 2 * B * H * D * (S + steps_dec)                       # K and V, prefill + appended
+    elems_attn = 2 * B * H * D * sum(S + i + 1 for i in range(steps_dec))
+    eff_bytes = 2 * (elems_quant + elems_attn)
+    value = eff_bytes / (ms_per_step * 1e-3) / 1e9
 
     roofline = {"kernel": "decode_kernel<4,64,64>", "bound": "hbm",
                 "achieved": round(dec_bytes / (t_att * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
@@ -199,6 +227,7 @@ def main():
         "decode_tokens_per_s_per_layer": round(tokens_per_s_layer, 1),
         "decode_step_us": round(t_decode_step * 1e3, 2),
         "host_ms_per_step": round(host_ms, 4),
+        "launch": "eager (Python, one call per kernel)" if args.no_graph else "HIP graph replay (257 kernel nodes per step)",
         "roofline": roofline,
         "kernels": kern,
     }

@@ -1,0 +1,122 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
+(library-chosen split counts, K and V quantized in one launch).
+
+C1-C4 are compared in full against the oracle.  For C5 (3.8 G elements per tensor) the GPU runs
+the full tensors and the oracle checks whole (batch, head) slabs of two batch rows (first and
+last) -- the path is independent per (batch, head), so a slab is a complete unit of work."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+THREADS = 16
+
+
+@pytest.fixture(scope="module")
+def env():
+    assert torch.cuda.is_available()
+    from paper_2505_16210_amd import nqkv, workloads
+    return nqkv, workloads
+
+
+def bits(t):
+    a = t.detach().cpu().numpy()
+    return a.view(np.uint16) if a.dtype == np.float16 else a
+
+
+def attn_err(out, ref):
+    out = out.astype(np.float64)
+    return float((np.abs(out - ref).max(-1) / np.abs(ref).max(-1)).max())
+
+
+def quantize_and_attend(nqkv, workloads, cfg, k, blk, oracle, batch_rows=None):
+    dev = torch.device("cuda:0")
+    g = workloads.make_generator(cfg, dev)
+    K, V = workloads.make_kv(cfg, dev, g)
+    q = workloads.make_q(cfg, dev, g)
+    lv = nqkv.build_codebook(k)
+    desc = nqkv.make_desc(cfg.B, cfg.H, cfg.D, k, blk, cfg.S)
+    kc, ks = nqkv.alloc_cache(desc, dev)
+    vc, vs = nqkv.alloc_cache(desc, dev)
+    nqkv.quantize_kv_pair(desc, lv, K, V, kc, ks, vc, vs, 0)
+    out = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, cfg.S, 1.0)
+    torch.cuda.synchronize()
+    rows = range(cfg.B) if batch_rows is None else batch_rows
+    worst = 0.0
+    for b in rows:
+        sl = slice(b, b + 1)
+        okc, oks = oracle.new_cache(1, cfg.H, cfg.D, k, blk, cfg.S)
+        ovc, ovs = oracle.new_cache(1, cfg.H, cfg.D, k, blk, cfg.S)
+        oracle.quantize_kv(bits(K[sl]), k, blk, lv, okc, oks, n_threads=THREADS)
+        oracle.quantize_kv(bits(V[sl]), k, blk, lv, ovc, ovs, n_threads=THREADS)
+        assert np.array_equal(bits(ks[sl]), oks) and np.array_equal(bits(vs[sl]), ovs), (cfg.name, k, blk, b)
+        assert np.array_equal(bits(kc[sl]), okc) and np.array_equal(bits(vc[sl]), ovc), (cfg.name, k, blk, b)
+        ref = oracle.decode_attention(bits(q[sl]), okc, oks, ovc, ovs, k, blk, lv, cfg.S, 1.0, n_threads=THREADS)
+        worst = max(worst, attn_err(out[sl].cpu().numpy(), ref))
+    assert worst <= ATTN_TOL, (cfg.name, k, blk, worst)
+    return worst
+
+
+def test_c1_full(env, oracle):
+    nqkv, workloads = env
+    quantize_and_attend(nqkv, workloads, workloads.C1, 4, 64, oracle)
+
+
+def test_c3_full(env, oracle):
+    nqkv, workloads = env
+    quantize_and_attend(nqkv, workloads, workloads.C3, 4, 64, oracle)
+
+
+def test_c4_full_long_context_split_k(env, oracle):
+    nqkv, workloads = env
+    cfg = workloads.C4
+    desc = nqkv.make_desc(cfg.B, cfg.H, cfg.D, 4, 64, cfg.S)
+    assert nqkv.decode_workspace_bytes(desc, cfg.S, 0)[1] > 1        # the bench configuration cuts the sequence
+    quantize_and_attend(nqkv, workloads, cfg, 4, 64, oracle)
+
+
+@pytest.mark.parametrize("k,blk", [(4, 64), (4, 128), (3, 64), (3, 128), (2, 64), (2, 128)])
+def test_c5_sweep_sampled_slabs(env, oracle, k, blk):
+    nqkv, workloads = env
+    cfg = workloads.C5
+    quantize_and_attend(nqkv, workloads, cfg, k, blk, oracle, batch_rows=(0, cfg.B - 1))
+    torch.cuda.empty_cache()
+
+
+def test_c2_prefill_then_128_decode_steps(env, oracle):
+    """The bench workload itself: quantize the 2048-token prefill, then 128 x (append one token,
+    attend over everything cached).  Attention is checked against the oracle at steps
+    0, 1, 31, 64, 126, 127; the final caches must equal the oracle's bit for bit."""
+    nqkv, workloads = env
+    cfg = workloads.C2
+    dev = torch.device("cuda:0")
+    g = workloads.make_generator(cfg, dev)
+    B, H, D, S, n_dec, cap = cfg.B, cfg.H, cfg.D, cfg.S, cfg.decode_steps, cfg.cap_tokens
+    K, V = workloads.make_kv(cfg, dev, g, n_tokens=cap)
+    qs = [workloads.make_q(cfg, dev, g) for _ in range(n_dec)]
+    k, blk = cfg.bits, cfg.block
+    lv = nqkv.build_codebook(k)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    kc, ks = nqkv.alloc_cache(desc, dev)
+    vc, vs = nqkv.alloc_cache(desc, dev)
+    nqkv.quantize_kv_pair(desc, lv, K[:, :, :S], V[:, :, :S], kc, ks, vc, vs, 0)
+    outs = {}
+    check_at = {0, 1, 31, 64, 126, 127}
+    for i in range(n_dec):
+        pos = S + i
+        nqkv.quantize_kv_pair(desc, lv, K[:, :, pos:pos + 1], V[:, :, pos:pos + 1], kc, ks, vc, vs, pos)
+        o = nqkv.decode_attention(desc, lv, qs[i], kc, ks, vc, vs, pos + 1, 1.0)
+        if i in check_at:
+            outs[i] = o.clone()
+    torch.cuda.synchronize()
+    okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
+    ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
+    oracle.quantize_kv(bits(K), k, blk, lv, okc, oks, n_threads=THREADS)
+    oracle.quantize_kv(bits(V), k, blk, lv, ovc, ovs, n_threads=THREADS)
+    assert np.array_equal(bits(kc), okc) and np.array_equal(bits(ks), oks)
+    assert np.array_equal(bits(vc), ovc) and np.array_equal(bits(vs), ovs)
+    for i in sorted(check_at):
+        ref = oracle.decode_attention(bits(qs[i]), okc, oks, ovc, ovs, k, blk, lv, S + i + 1, 1.0, n_threads=THREADS)
+        assert attn_err(outs[i].cpu().numpy(), ref) <= ATTN_TOL, i
