@@ -8,8 +8,7 @@
 // the product path may call it, and it shares no code, header, table or constant
 // with the GPU library.
 //
-// Conventions (each is a reading of the paper where the paper is silent; the list
-// with reasons lives in the design document):
+// Conventions (each is a reading of the paper where the paper itself is silent):
 //   * codebook, variant 0: 2^k levels = medians of 2^k equal-probability bins of
 //     N(0,1), divided by the largest one, built for the positive half and mirrored
 //     (Sec. 1 "quantile points from a normal distribution"; Sec. 3.2);
