@@ -47,8 +47,9 @@ int check_strided(const nqkv_cache_desc* d, int64_t sb, int64_t sh, int64_t st, 
   if (sb < 0 || sh < 0 || st < 0) return NQKV_EINVAL;
   if ((sb % 8) || (sh % 8) || (st % 8)) return NQKV_EINVAL;   // every row 16-byte aligned
   if (n_tokens > 1 && st < d->D) return NQKV_EINVAL;
-  // offsets inside one (b,h) slab are formed in 32 bits of chunk index
+  // offsets inside one (b,h) slab are formed in 32 bits (chunk index, byte offset)
   if (n_tokens * (d->D / 8) >= ((int64_t)1 << 31) - 4096) return NQKV_EUNSUPPORTED;
+  if (n_tokens > 0 && ((n_tokens - 1) * st + d->D) * 2 >= ((int64_t)1 << 31)) return NQKV_EUNSUPPORTED;
   return NQKV_OK;
 }
 

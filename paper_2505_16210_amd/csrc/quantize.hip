@@ -2,6 +2,9 @@
 // (paper Sec. 3.2: I = quantize(X); Fig. 5: every token is cut into blocks and each block
 // is quantized on its own).  gfx950 only.
 //
+// Two grids: a whole-slab kernel for prefill-sized calls (scalar buffer descriptors, no
+// predication) and a flat kernel over all rows for calls with a few tokens per (b,h) (append).
+//
 // Work decomposition: one lane owns one 16-byte chunk = 8 consecutive fp16 of a token row,
 // so a 64-element block is shared by 8 neighbouring lanes (16 for a 128-element block) and
 // the block's max |x| is an all-reduce over those lanes done with DPP lane permutes -- no
@@ -193,11 +196,92 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantParams p)
   }
 }
 
+// Whole-slab variant (prefill): grid x = chunk tiles of one (b,h) slab, y = h, z = b + B * tensor.
+// Every address is a scalar buffer descriptor (source slab, code rows, scale rows of this (b,h))
+// plus a 32-bit per-lane byte offset, so no 64-bit address arithmetic runs in the vector ALU and
+// the ragged last tile needs no predication: chunks past the end read zeros, and their stores
+// -- like the stores of lanes that have nothing to write -- carry an offset beyond the
+// descriptor's range and are dropped by the hardware range check.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+constexpr int kBufferFlags = 0x00020000;       // raw buffer, 32-bit data format (gfx9 family)
+constexpr uint32_t kDropStore = 0xffffffffu;   // voffset outside every descriptor
+
+template <int KBITS, int D, int BLK, bool FAST, bool CONTIG>
+__global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantParams p) {
+  constexpr int CPR = D / 8;      // chunks per token row
+  constexpr int LPB = BLK / 8;    // lanes that share one block
+  constexpr int NB = D / BLK;
+  constexpr int kRowBytes = D * KBITS / 8;
+  __shared__ uint2 cells[FAST ? 128 : 1];   // 128 >= kCells: any 7-bit index stays inside
+  if (FAST) stage_cells(p, cells);
+
+  const uint32_t tensor = blockIdx.z >= (unsigned)p.B ? 1u : 0u;
+  const uint32_t b = blockIdx.z - (tensor ? (uint32_t)p.B : 0u), h = blockIdx.y;
+  const TensorPtrs tp = p.t[tensor];
+  const int64_t row0 = ((int64_t)b * p.H + h) * p.cap_tokens + p.tok_off;
+  const uint32_t n = (uint32_t)p.n_tokens;
+  const __amdgpu_buffer_rsrc_t src_r = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(tp.src) + (int64_t)b * p.stride_b + (int64_t)h * p.stride_h, 0,
+      (int)(((int64_t)(n - 1) * p.stride_t + D) * 2), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t code_r = __builtin_amdgcn_make_buffer_rsrc(
+      tp.codes + row0 * kRowBytes, 0, (int)(n * kRowBytes), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t scale_r = __builtin_amdgcn_make_buffer_rsrc(
+      tp.scales + row0 * NB, 0, (int)(n * NB * 2), kBufferFlags);
+  const uint32_t c0 = blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+  const uint32_t total = n * CPR;
+
+  uint4 w[kUnroll];
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t c = c0 + u * kThreads;
+    uint32_t voff;
+    if (CONTIG) {
+      voff = c * 16;                                           // rows back to back
+    } else {
+      voff = (c / CPR) * (uint32_t)(p.stride_t * 2) + (c % CPR) * 16;
+    }
+    if (c >= total) voff = kDropStore;                         // past the slab: reads zeros
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(src_r, voff, 0, 0);
+    w[u] = make_uint4(v.x, v.y, v.z, v.w);
+  }
+
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t c = c0 + u * kThreads;
+    // block scale: max |x| as fp16 bits (for non-negative finite fp16, value order == bit order)
+    const uint32_t M = 0x7fff7fffu;
+    const uint32_t a = pk_max_u16(pk_max_u16(w[u].x & M, w[u].y & M), pk_max_u16(w[u].z & M, w[u].w & M));
+    uint32_t s_bits = max(a & 0xffffu, a >> 16);
+    s_bits = max(s_bits, dpp<kQuadXor1>(s_bits));
+    s_bits = max(s_bits, dpp<kQuadXor2>(s_bits));
+    s_bits = max(s_bits, dpp<kRowHalfMirror>(s_bits));
+    if (LPB == 16) s_bits = max(s_bits, dpp<kRowMirror>(s_bits));
+
+    const uint32_t packed = encode_chunk<KBITS, FAST>(w[u], s_bits, p.levels, cells);
+    const bool live = c < total;
+    if (KBITS == 4) {
+      __builtin_amdgcn_raw_buffer_store_b32(packed, code_r, live ? c * 4 : kDropStore, 0, 0);
+    } else if (KBITS == 2) {
+      const uint32_t odd = dpp<kQuadOdd>(packed);
+      const bool writer = live && !(threadIdx.x & 1);
+      __builtin_amdgcn_raw_buffer_store_b32(packed | (odd << 16), code_r, writer ? c * 2 : kDropStore, 0, 0);
+    } else {  // KBITS == 3: four lanes hold 4 x 24 bits = three dwords
+      const uint32_t next = dpp<kQuadNext>(packed);
+      const uint32_t q = threadIdx.x & 3;
+      const uint32_t word = (packed >> (8 * q)) | (next << (24 - 8 * q));
+      const bool writer = live && q != 3;
+      __builtin_amdgcn_raw_buffer_store_b32(word, code_r, writer ? (c >> 2) * 12 + q * 4 : kDropStore, 0, 0);
+    }
+    const bool scale_writer = live && (c % LPB) == 0;
+    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)s_bits, scale_r, scale_writer ? (c / LPB) * 2 : kDropStore, 0, 0);
+  }
+}
+
 template <int KBITS, int D, int BLK>
 hipError_t launch_one(const QuantParams& p, hipStream_t stream) {
   constexpr int CPR = D / 8;
   const int64_t chunks_per_slab = p.n_tokens * CPR;
-  const bool flat = chunks_per_slab < 2 * kThreads;
+  const bool flat = chunks_per_slab < 2 * kThreads;     // few tokens per (b,h): one flat grid over all rows
   const bool fast = p.impl == 0;
   const int tile = kThreads * kUnroll;
   dim3 grid;
@@ -212,8 +296,11 @@ hipError_t launch_one(const QuantParams& p, hipStream_t stream) {
     if (fast) hipLaunchKernelGGL((quantize_kernel<KBITS, D, BLK, true, true>), grid, dim3(kThreads), 0, stream, p);
     else      hipLaunchKernelGGL((quantize_kernel<KBITS, D, BLK, false, true>), grid, dim3(kThreads), 0, stream, p);
   } else {
-    if (fast) hipLaunchKernelGGL((quantize_kernel<KBITS, D, BLK, true, false>), grid, dim3(kThreads), 0, stream, p);
-    else      hipLaunchKernelGGL((quantize_kernel<KBITS, D, BLK, false, false>), grid, dim3(kThreads), 0, stream, p);
+    const bool contig = p.stride_t == D;
+    if (fast && contig)       hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, true, true>), grid, dim3(kThreads), 0, stream, p);
+    else if (fast)            hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, true, false>), grid, dim3(kThreads), 0, stream, p);
+    else if (contig)          hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, false, true>), grid, dim3(kThreads), 0, stream, p);
+    else                      hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, false, false>), grid, dim3(kThreads), 0, stream, p);
   }
   return hipGetLastError();
 }
