@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--cold", type=int, default=1, help="1: rotate buffers to defeat the last-level cache")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch the step's 257 kernels one by one from Python instead of replaying a HIP graph")
+    ap.add_argument("--two-launch", action="store_true",
+                    help="decode iteration as two launches (quantizer append, then attention) instead of "
+                         "the fused single-launch step")
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="with --skip-step: also run a torch copy of this many MiB (counter calibration)")
     ap.add_argument("--skip-step", action="store_true",
@@ -78,6 +81,31 @@ def main():
         e1.record(stream)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters
+
+    def timed_graph(fn, n_calls, reps=6):
+        """average milliseconds per call of fn(i), i in [0, n_calls): the calls are captured into
+        one HIP graph and the replays timed, so the figure holds no host launch overhead (the
+        kernels here run 5-35 us, about what one launch from Python costs)"""
+        for i in range(min(n_calls, 4)):
+            fn(i)
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(gr, stream=side):
+                for i in range(n_calls):
+                    fn(i)
+        for _ in range(2):
+            gr.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            gr.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (reps * n_calls)
 
     if args.skip_step:
         kern = {}
@@ -141,25 +169,43 @@ def main():
         j = i % steps_dec
         nqkv.decode_attention(desc, lv, qs[j], kc, ks, vc, vs, S + j + 1, 1.0, out=out, workspace=ws)
 
+    def fused(i):
+        kc, ks, vc, vs = caches[i % R_CACHE]
+        j = i % steps_dec
+        kn, vn = new_views[j]
+        nqkv.decode_step(desc, lv, qs[j], kn, vn, kc, ks, vc, vs, S + j, 1.0, out=out, workspace=ws)
+
     def step(s):
         prefill(s)
         for i in range(steps_dec):
-            append(i)
-            attend(i)
+            if args.two_launch:
+                append(i)
+                attend(i)
+            else:
+                fused(i)
 
     # ------------------------------------------------------------------ per-kernel timings, C2
     it = args.kernel_iters
     kern = {}
-    t_pre = timed(prefill, it)
+    tk = timed if args.no_graph else (lambda fn, n, warm=0: timed_graph(fn, n))
+    t_pre = tk(prefill, it)
     qb = workloads.quantize_bytes_per_element(k, blk)
     kern["C2.quantize_prefill"] = kernel_entry(2 * B * H * S * D * qb, t_pre)
-    t_app = timed(append, steps_dec * 2)
+    t_app = tk(append, steps_dec * 2)
     kern["C2.quantize_append"] = kernel_entry(2 * B * H * D * qb, t_app)
-    t_att = timed(attend, steps_dec * 4, warm=steps_dec)
+    t_att = tk(attend, steps_dec * 4, warm=steps_dec)
     mean_seq = S + (steps_dec + 1) / 2.0
     dec_bytes = B * H * (mean_seq * workloads.decode_bytes_per_token_head(D, k, blk) + 4 * D) \
         + (2 * B * H * splits * (D + 2) * 4 if splits > 1 else 0)      # partials written and re-read
     kern["C2.decode_attention"] = kernel_entry(dec_bytes, t_att, splits=splits)
+    # fused step: the cached prefix is one token shorter, and the new token costs its fp16 rows
+    # in plus its codes and scales out
+    t_fused = tk(fused, steps_dec * 4, warm=steps_dec)
+    per_tok = workloads.decode_bytes_per_token_head(D, k, blk)
+    fused_bytes = dec_bytes - B * H * per_tok + B * H * (2 * D * 2 + per_tok)
+    kern["C2.decode_step_fused"] = kernel_entry(fused_bytes, t_fused, splits=splits)
+    if not args.two_launch:
+        dec_bytes, t_att = fused_bytes, t_fused          # the dominant kernel of the timed step
 
     # The step is 1 + 2 * 128 kernel launches of 5-35 us each: issued one by one from Python the
     # host cannot keep up, so the step is captured once into a HIP graph (kernel nodes only) and
@@ -208,7 +254,7 @@ def main():
     eff_bytes = 2 * (elems_quant + elems_attn)
     value = eff_bytes / (ms_per_step * 1e-3) / 1e9
 
-    roofline = {"kernel": "decode_kernel<4,64,64>", "bound": "hbm",
+    roofline = {"kernel": "decode_kernel<4,64,64,%s>" % ("false" if args.two_launch else "true"), "bound": "hbm",
                 "achieved": round(dec_bytes / (t_att * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(dec_bytes / (t_att * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                 "bytes_per_launch": int(dec_bytes), "avg_launch_us": round(t_att * 1e3, 2),
@@ -237,13 +283,13 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "C2 OPT-1.3B-shaped layer: B8 H32 D64, 4-bit block 64, quantize 2048-token "
-                               "prefill + 128 x (append 1 token + fused decode attention); "
-                               "%d cache copies rotated" % R_CACHE,
+                               "prefill + 128 x (append 1 token + fused decode attention, %s); "
+                               "%d cache copies rotated" % ("two launches" if args.two_launch else "one launch", R_CACHE),
                    "storage": "fp16 in/out, %d-bit codes, fp16 scales" % k},
         "decode_tokens_per_s_per_layer": round(tokens_per_s_layer, 1),
         "decode_step_us": round(t_decode_step * 1e3, 2),
         "host_ms_per_step": round(host_ms, 4),
-        "launch": "eager (Python, one call per kernel)" if args.no_graph else "HIP graph replay (257 kernel nodes per step)",
+        "launch": "eager (Python, one call per kernel)" if args.no_graph else "HIP graph replay (%d kernel nodes per step)" % (1 + steps_dec * (2 if args.two_launch else 1)),
         "roofline": roofline,
         "kernels": kern,
     }

@@ -12,6 +12,7 @@
  *   nqkv_dequantize_kv     indices -> fp16                           (Sec. 3.2, X' = dequantize(I))
  *   nqkv_decode_attention  softmax(q K'^T) V' read straight from the packed cache
  *                                                                    (Sec. 3.2 decoding phase)
+ *   nqkv_decode_step       append + attention of one decode step in one launch (Sec. 3.2)
  *
  * General rules
  *   - Every function returns NQKV_OK (0) or a negative NQKV_E* code.  Nothing throws,
@@ -185,6 +186,28 @@ int nqkv_decode_attention(const nqkv_cache_desc* desc, const float* levels,
                           int64_t seq_len, float softmax_scale, void* out,
                           void* workspace, size_t workspace_bytes, int num_splits,
                           void* hip_stream);
+
+/*
+ * One whole decode step of Sec. 3.2 in a single launch: quantize the new token's key and value
+ * (I_tK = quantize(t_K), I_tV = quantize(t_V)), append their indices at cache row `pos`
+ * (I <- Concat(I, I_t)), and attend over rows [0, pos] -- the appended token included.
+ * The cache afterwards holds exactly the bytes nqkv_quantize_kv_pair(n_tokens = 1,
+ * dst_token_offset = pos) would have written, and `out` is what nqkv_decode_attention(seq_len =
+ * pos + 1) would return up to rounding (the new token enters the softmax from registers).
+ *   k_new, v_new  device fp16, one row per (b,h): element (b,h,d) at
+ *                 b*new_stride_b + h*new_stride_h + d (strides in elements, multiples of 8)
+ *   pos           0 .. cap_tokens-1; rows [0, pos) must already be valid
+ *   workspace     as for nqkv_decode_attention, sized with
+ *                 nqkv_decode_workspace_bytes(desc, max(pos, 1), num_splits)
+ * Errors: as nqkv_decode_attention, plus NQKV_EINVAL for a null/misaligned k_new or v_new.
+ */
+int nqkv_decode_step(const nqkv_cache_desc* desc, const float* levels,
+                     const void* q, const void* k_new, const void* v_new,
+                     int64_t new_stride_b, int64_t new_stride_h,
+                     void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                     int64_t pos, float softmax_scale, void* out,
+                     void* workspace, size_t workspace_bytes, int num_splits,
+                     void* hip_stream);
 
 #ifdef __cplusplus
 }

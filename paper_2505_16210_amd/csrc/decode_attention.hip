@@ -38,6 +38,7 @@
 // (m, l, o[D]).  With split-K the workgroup that finishes an item's last partial (an integer
 // ticket per batch*head, no floating-point atomics) combines all of them in split order, so the
 // result does not depend on which workgroup that was.
+#include "code_search.h"
 #include "nqkv_internal.h"
 
 namespace nqkv {
@@ -324,7 +325,11 @@ __device__ __forceinline__ void reduce_groups(const float (&acc)[32], uint32_t l
 
 // ------------------------------------------------------------------ main kernel
 // grid: x = persistent workgroups; item i -> (bh = i / splits, split = i % splits)
-template <int KBITS, int D, int BLK>
+// FUSE: the whole decode step of the paper in one launch -- items cover the tokens already
+// cached, rows [0, pos); the last wave of each sequence's last item quantizes the new token's
+// key and value rows (same code search as the quantizer), stores their codes and scales at row
+// pos, and adds the token to its softmax straight from registers.
+template <int KBITS, int D, int BLK, bool FUSE>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) void decode_kernel(const DecodeParams p) {   // 128 VGPRs: two workgroups per CU
   constexpr int LPT = D / 32;             // lanes per token
   constexpr int TPR = 64 / LPT;           // tokens per wave load
@@ -335,6 +340,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   __shared__ float xw[kWaves][D];
   __shared__ float wave_m[kWaves], wave_l[kWaves];
   __shared__ uint32_t ticket_sh;
+  __shared__ uint2 cells[FUSE ? 128 : 1];
+  __shared__ uint32_t new_codes[FUSE ? 2 : 1][ROW];       // packed codes of the new token's K and V rows
+  __shared__ uint32_t new_scales[FUSE ? 2 : 1][NB];       // and their block scales (fp16 bits)
 
   const char* lut = reinterpret_cast<const char*>(smem);
   const uint32_t lane = threadIdx.x & 63;
@@ -358,6 +366,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   uint32_t bh = 0, sp = 0;
   int32_t n_tok = 0, base = 0;      // tokens in the item; this wave's current trip start (item-relative)
   __amdgpu_buffer_rsrc_t kc_r, vc_r, ks_r, vs_r;
+  __amdgpu_buffer_rsrc_t kn_r, vn_r;      // FUSE: the new token's rows, empty for waves that do not take it
+  uint32_t newx[4] = {0, 0, 0, 0};        // FUSE: this lane's 16-byte chunk of those rows
   auto set_item = [&](uint32_t item) {
     bh = item / (uint32_t)p.splits;
     sp = item - bh * (uint32_t)p.splits;
@@ -369,6 +379,25 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
     vc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.v_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
     ks_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.k_scales) + row0 * NB, 0, n_tok * (int)kScaleRowBytes, kBufferFlags);
     vs_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.v_scales) + row0 * NB, 0, n_tok * (int)kScaleRowBytes, kBufferFlags);
+    if (FUSE) {
+      const uint32_t b = bh / (uint32_t)p.H, h = bh - b * (uint32_t)p.H;
+      const int64_t off = (int64_t)b * p.new_stride_b + (int64_t)h * p.new_stride_h;
+      const int bytes = (sp == (uint32_t)p.splits - 1u && wave == kWaves - 1) ? D * 2 : 0;
+      kn_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.k_new) + off, 0, bytes, kBufferFlags);
+      vn_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.v_new) + off, 0, bytes, kBufferFlags);
+    }
+  };
+  // FUSE: one lane per 16-byte chunk -- lanes [0, D/8) take the key row, the next D/8 the value
+  // row.  The range check does the predication: a lane outside its row (and every lane of a wave
+  // whose descriptors are empty) reads zeros, so the two loads are issued unconditionally, like
+  // the trip loads, and sit in the same prefetch slot as the first K trip.
+  auto load_new = [&]() {
+    uint32_t a[4], c[4];
+    load_codes<4>(kn_r, lane * 16u, 0, a);
+    constexpr uint32_t CPR = D / 8;
+    load_codes<4>(vn_r, lane >= CPR ? (lane - CPR) * 16u : 0x40000000u, 0, c);     // far out of range, no wrap
+#pragma unroll
+    for (int i = 0; i < 4; ++i) newx[i] = a[i] | c[i];
   };
 
   // Loads of one trip starting at item-relative token tb (uniform).  The trip offset goes into
@@ -402,7 +431,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   set_item(item);
   load_trip(kc_r, ks_r, base, kw, ksc);
   load_q();
-  build_lut<KBITS>(p, smem);
+  if (FUSE) load_new();
+  if (FUSE) code_search::stage_cells(p.cell_thr, p.cell_below, cells);
+  build_lut<KBITS>(p, smem);          // ends with the barrier that also covers the cell table
   // Make the query registers "arrived" here, outside the trip loop: otherwise the wait for
   // them is re-imposed at the top of every trip (it is pending on the loop-entry path only), and
   // because the memory counter is positional that stalls each trip on its own fresh V loads.
@@ -418,6 +449,79 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
     for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
     float m_run = -INFINITY;   // wave-uniform, log2 domain
     float l_run = 0.0f;        // per lane; every lane of a token group adds the same p
+
+    if (FUSE && sp == (uint32_t)p.splits - 1u && wave == kWaves - 1) {
+      // ---- the token of this step: quantize, append, attend -- before this wave's share of
+      // the cached tokens, while the accumulators are not live yet.  One lane per 16-byte chunk
+      // (fetched by load_new), so the whole code search is one chunk deep.
+      constexpr uint32_t CPR = D / 8;         // chunks per row
+      constexpr uint32_t LPB = BLK / 8;       // lanes per quantization block (8 or 16: inside a DPP row)
+      // an opaque copy of the lane index: everything below is derived from it, so the compiler
+      // cannot hoist these address computations out of this block, where their registers would
+      // cost the streaming loop its occupancy
+      uint32_t ql = lane;
+      asm volatile("" : "+v"(ql));
+      const uint32_t t = ql / CPR, c = ql % CPR;          // tensor (0 key, 1 value), chunk in the row
+      const bool mine = t < 2;
+      const uint4 x = make_uint4(newx[0], newx[1], newx[2], newx[3]);    // zeros where !mine
+      const uint32_t M = 0x7fff7fffu;
+      const uint32_t a2 = code_search::pk_max_u16(code_search::pk_max_u16(x.x & M, x.y & M),
+                                                  code_search::pk_max_u16(x.z & M, x.w & M));
+      uint32_t s_bits = max(a2 & 0xffffu, a2 >> 16);
+      s_bits = max(s_bits, code_search::dpp<code_search::kQuadXor1>(s_bits));
+      s_bits = max(s_bits, code_search::dpp<code_search::kQuadXor2>(s_bits));
+      s_bits = max(s_bits, code_search::dpp<code_search::kRowHalfMirror>(s_bits));
+      if (LPB == 16) s_bits = max(s_bits, code_search::dpp<code_search::kRowMirror>(s_bits));
+      const uint32_t code = code_search::encode_chunk<KBITS, true>(x, s_bits, LevelTable{}, cells);
+      if (mine) {
+        // the LDS image of each row has the layout of a cache row: chunk c at byte c * KBITS
+        uint8_t* img = reinterpret_cast<uint8_t*>(&new_codes[t][0]) + c * KBITS;
+        if constexpr (KBITS == 4) {
+          *reinterpret_cast<uint32_t*>(img) = code;
+        } else if constexpr (KBITS == 2) {
+          *reinterpret_cast<uint16_t*>(img) = (uint16_t)code;
+        } else {
+          img[0] = (uint8_t)code; img[1] = (uint8_t)(code >> 8); img[2] = (uint8_t)(code >> 16);
+        }
+        if (c % LPB == 0) new_scales[t][c / LPB] = s_bits;
+      }
+      // written and read by different lanes of this one wave: LDS operations of a wave complete
+      // in order, the fence keeps the compiler from reordering them
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      uint32_t nk[KBITS], nv[KBITS];
+      uint32_t nks = 0, nvs = 0;
+#pragma unroll
+      for (int i = 0; i < KBITS; ++i) { nk[i] = 0; nv[i] = 0; }
+      if (ql < (uint32_t)LPT) {                 // token group 0: lane j owns 32 elements of each row
+        const int64_t row = (int64_t)bh * p.cap_tokens + p.pos;
+        uint32_t* kdst = reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(p.k_codes)) + (row * LPT + ql) * KBITS;
+        uint32_t* vdst = reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(p.v_codes)) + (row * LPT + ql) * KBITS;
+#pragma unroll
+        for (int i = 0; i < KBITS; ++i) {
+          nk[i] = new_codes[0][ql * KBITS + i];
+          nv[i] = new_codes[1][ql * KBITS + i];
+          kdst[i] = nk[i];
+          vdst[i] = nv[i];
+        }
+        nks = new_scales[0][(ql * 32) / BLK];
+        nvs = new_scales[1][(ql * 32) / BLK];
+        if ((ql * 32) % BLK == 0) {
+          const_cast<uint16_t*>(p.k_scales)[row * NB + (ql * 32) / BLK] = (uint16_t)nks;
+          const_cast<uint16_t*>(p.v_scales)[row * NB + (ql * 32) / BLK] = (uint16_t)nvs;
+        }
+      }
+      float part = k_dot<KBITS>(nk, q2, lut, lane_off);
+      part *= (float)__builtin_bit_cast(_Float16, (unsigned short)nks);
+      part += dpp_f<kQuadXor1>(part);
+      if (LPT == 4) part += dpp_f<kQuadXor2>(part);
+      const float z = (g == 0) ? part * p.scale_log2e : -INFINITY;
+      m_run = wave_max(z);                                   // finite: group 0 holds a real score
+      const float pn = __builtin_amdgcn_exp2f(z - m_run);    // 1 for the token's lanes, 0 elsewhere
+      l_run = pn;
+      v_axpy<KBITS>(nv, pn * (float)__builtin_bit_cast(_Float16, (unsigned short)nvs), acc, lut, lane_off);
+    }
 
     for (; base < n_tok; base += stride) {
       const bool full = base + CHUNK <= n_tok;
@@ -468,43 +572,51 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
       set_item(next_item);
       load_trip(kc_r, ks_r, base, kw, ksc);
       load_q();
+      if (FUSE) load_new();
     }
 
-    // ---- merge: token groups inside each wave, then the eight waves through LDS
+    // ---- merge: token groups inside each wave, then the eight waves through LDS.
+    // Everything here is addressed from an opaque copy of the thread index: derived from
+    // threadIdx.x directly, these item-invariant addresses would be hoisted out of the item loop
+    // and sit in registers through the streaming loop, which needs every one it can get.
+    uint32_t tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const uint32_t mlane = tid & 63;
     float red[2];
-    reduce_groups<LPT>(acc, lane, red);
+    reduce_groups<LPT>(acc, mlane, red);
     const float l_wave = wave_sum(l_run) * (1.0f / LPT);
     {
-      const uint32_t e = ((lane >> 5) & 1) * 16 + ((lane >> 4) & 1) * 8 + ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2;
+      const uint32_t mj = mlane % LPT;
+      const uint32_t e = ((mlane >> 5) & 1) * 16 + ((mlane >> 4) & 1) * 8 + ((mlane >> 3) & 1) * 4 + ((mlane >> 2) & 1) * 2;
       if (LPT == 4) {
-        xw[wave][j * 32 + e] = red[0];
-        xw[wave][j * 32 + e + 1] = red[1];
+        xw[wave][mj * 32 + e] = red[0];
+        xw[wave][mj * 32 + e + 1] = red[1];
       } else {
-        xw[wave][j * 32 + e + ((lane >> 1) & 1)] = red[0];
+        xw[wave][mj * 32 + e + ((mlane >> 1) & 1)] = red[0];
       }
-      if (lane == 0) { wave_m[wave] = m_run; wave_l[wave] = l_wave; }
+      if (mlane == 0) { wave_m[wave] = m_run; wave_l[wave] = l_wave; }
     }
     __syncthreads();
     float m_all = wave_m[0];
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) m_all = fmaxf(m_all, wave_m[w]);
     float l_all = 0.0f, o = 0.0f;
-    if (threadIdx.x < D) {
+    if (tid < D) {
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) {
         const float f = __builtin_amdgcn_exp2f(wave_m[w] - m_all);   // 0 for a wave that saw no token
         l_all += wave_l[w] * f;
-        o += xw[w][threadIdx.x] * f;
+        o += xw[w][tid] * f;
       }
       if (p.splits == 1) {
-        p.out[(int64_t)cur_bh * D + threadIdx.x] = __builtin_bit_cast(unsigned short, (_Float16)(o * p.inv_gamma / l_all));
+        p.out[(int64_t)cur_bh * D + tid] = __builtin_bit_cast(unsigned short, (_Float16)(o * p.inv_gamma / l_all));
       } else {
         // Partials travel between workgroups, possibly on different XCDs whose L2 caches are not
         // coherent with each other: write them through (agent-scope stores) rather than paying
         // for a whole-L2 write-back fence per item.
         uint32_t* ws = reinterpret_cast<uint32_t*>(p.partials + ((int64_t)cur_bh * p.splits + cur_sp) * (D + 2));
-        store_agent(ws + 2 + threadIdx.x, o);
-        if (threadIdx.x == 0) { store_agent(ws, m_all); store_agent(ws + 1, l_all); }
+        store_agent(ws + 2 + tid, o);
+        if (tid == 0) { store_agent(ws, m_all); store_agent(ws + 1, l_all); }
       }
     }
     if (p.splits > 1) {
@@ -513,10 +625,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
       // caches) and re-arms the ticket counter.
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
-      if (threadIdx.x == 0) ticket_sh = __hip_atomic_fetch_add(p.tickets + cur_bh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (tid == 0) ticket_sh = __hip_atomic_fetch_add(p.tickets + cur_bh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __syncthreads();
       if (ticket_sh == (uint32_t)p.splits - 1u) {
-        if (threadIdx.x < D) {
+        if (tid < D) {
           const uint32_t* ws = reinterpret_cast<const uint32_t*>(p.partials + (int64_t)cur_bh * p.splits * (D + 2));
           float mm = -INFINITY;
           for (int s2 = 0; s2 < p.splits; ++s2) mm = fmaxf(mm, load_agent(ws + s2 * (D + 2)));
@@ -524,11 +636,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
           for (int s2 = 0; s2 < p.splits; ++s2) {
             const float f = __builtin_amdgcn_exp2f(load_agent(ws + s2 * (D + 2)) - mm);
             ll += f * load_agent(ws + s2 * (D + 2) + 1);
-            oo += f * load_agent(ws + s2 * (D + 2) + 2 + threadIdx.x);
+            oo += f * load_agent(ws + s2 * (D + 2) + 2 + tid);
           }
-          p.out[(int64_t)cur_bh * D + threadIdx.x] = __builtin_bit_cast(unsigned short, (_Float16)(oo * p.inv_gamma / ll));
+          p.out[(int64_t)cur_bh * D + tid] = __builtin_bit_cast(unsigned short, (_Float16)(oo * p.inv_gamma / ll));
         }
-        if (threadIdx.x == 0) __hip_atomic_store(p.tickets + cur_bh, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) __hip_atomic_store(p.tickets + cur_bh, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
     settle_q();           // before the exit test, so that every path back to the loop head has it
@@ -539,17 +651,18 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
 }
 
 template <int KBITS, int D, int BLK>
-hipError_t launch_one(const DecodeParams& p, hipStream_t stream) {
+hipError_t launch_one(const DecodeParams& p, bool fuse, hipStream_t stream) {
   const int wgs = p.n_items < p.max_workgroups ? p.n_items : p.max_workgroups;
-  hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, p);
+  if (fuse) hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, true>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, p);
+  else      hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, false>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, p);
   return hipGetLastError();
 }
 
 template <int KBITS>
-hipError_t launch_k(const DecodeParams& p, int D, int blk, hipStream_t stream) {
-  if (D == 64 && blk == 64) return launch_one<KBITS, 64, 64>(p, stream);
-  if (D == 128 && blk == 64) return launch_one<KBITS, 128, 64>(p, stream);
-  if (D == 128 && blk == 128) return launch_one<KBITS, 128, 128>(p, stream);
+hipError_t launch_k(const DecodeParams& p, int D, int blk, bool fuse, hipStream_t stream) {
+  if (D == 64 && blk == 64) return launch_one<KBITS, 64, 64>(p, fuse, stream);
+  if (D == 128 && blk == 64) return launch_one<KBITS, 128, 64>(p, fuse, stream);
+  if (D == 128 && blk == 128) return launch_one<KBITS, 128, 128>(p, fuse, stream);
   return hipErrorInvalidValue;
 }
 
@@ -558,11 +671,11 @@ hipError_t launch_k(const DecodeParams& p, int D, int blk, hipStream_t stream) {
 int decode_chunk_tokens(int D) { return kRounds * (64 / (D / 32)); }
 int decode_waves_per_workgroup() { return kWaves; }
 
-hipError_t launch_decode_attention(const DecodeParams& p, int D, int k, int blk, hipStream_t stream) {
+hipError_t launch_decode_attention(const DecodeParams& p, int D, int k, int blk, bool fuse, hipStream_t stream) {
   switch (k) {
-    case 2: return launch_k<2>(p, D, blk, stream);
-    case 3: return launch_k<3>(p, D, blk, stream);
-    case 4: return launch_k<4>(p, D, blk, stream);
+    case 2: return launch_k<2>(p, D, blk, fuse, stream);
+    case 3: return launch_k<3>(p, D, blk, fuse, stream);
+    case 4: return launch_k<4>(p, D, blk, fuse, stream);
     default: return hipErrorInvalidValue;
   }
 }

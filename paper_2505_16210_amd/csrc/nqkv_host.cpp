@@ -328,30 +328,54 @@ int nqkv_decode_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, in
   return NQKV_OK;
 }
 
-int nqkv_decode_attention(const nqkv_cache_desc* desc, const float* levels,
-                          const void* q,
-                          const void* k_codes, const void* k_scales,
-                          const void* v_codes, const void* v_scales,
-                          int64_t seq_len, float softmax_scale, void* out,
-                          void* workspace, size_t workspace_bytes, int num_splits,
-                          void* hip_stream) {
+// Shared by nqkv_decode_attention (k_new == nullptr) and nqkv_decode_step.
+static int decode_impl(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                       const void* k_new, const void* v_new, int64_t new_stride_b, int64_t new_stride_h,
+                       const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                       int64_t seq_len, float softmax_scale, void* out,
+                       void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
   int rc = check_desc(desc);
   if (rc) return rc;
+  const bool fuse = k_new != nullptr;
   DecodeParams p;
   std::memset(&p, 0, sizeof(p));
   LevelTable checked;
   if ((rc = check_levels(levels, desc->k, &checked))) return rc;
+  if (seq_len < 1 || seq_len > desc->cap_tokens) return NQKV_EINVAL;
+  // the fused step streams the seq_len - 1 tokens already cached and takes the last one from
+  // k_new / v_new
+  const int64_t n_cached = fuse ? seq_len - 1 : seq_len;
   int splits = 1;
-  if ((rc = plan_splits(desc, seq_len, num_splits, &splits))) return rc;
+  if (n_cached >= 1) {
+    if ((rc = plan_splits(desc, n_cached, num_splits, &splits))) return rc;
+  } else if (num_splits < 0 || num_splits > 1) {
+    return NQKV_EINVAL;
+  }
   if (!std::isfinite(softmax_scale)) return NQKV_EINVAL;
   const void* ptrs[] = {q, k_codes, k_scales, v_codes, v_scales, out};
   for (const void* ptr : ptrs) {
     if (!ptr || !aligned16(ptr)) return NQKV_EINVAL;
   }
+  if (fuse) {
+    if (!v_new || !aligned16(k_new) || !aligned16(v_new)) return NQKV_EINVAL;
+    if (new_stride_b < 0 || new_stride_h < 0 || (new_stride_b % 8) || (new_stride_h % 8)) return NQKV_EINVAL;
+  }
   const size_t need = workspace_need(desc, splits);
   if (need > 0) {
     if (!workspace || !aligned16(workspace)) return NQKV_EINVAL;
     if (workspace_bytes < need) return NQKV_EWORKSPACE;
+  }
+  // one item's byte range is addressed with 32-bit offsets
+  if ((n_cached / splits + 1) * (int64_t)(desc->D * desc->k / 8) >= ((int64_t)1 << 31)) return NQKV_EUNSUPPORTED;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (fuse && !build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) {
+    // a table the in-kernel code search cannot take: append with the quantizer, then attend
+    rc = nqkv_quantize_kv_pair(desc, levels, k_new, v_new, new_stride_b, new_stride_h, desc->D, 1, seq_len - 1,
+                               const_cast<void*>(k_codes), const_cast<void*>(k_scales),
+                               const_cast<void*>(v_codes), const_cast<void*>(v_scales), hip_stream);
+    if (rc) return rc;
+    return decode_impl(desc, levels, q, nullptr, nullptr, 0, 0, k_codes, k_scales, v_codes, v_scales, seq_len,
+                       softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
   }
   p.q = static_cast<const uint16_t*>(q);
   p.k_codes = static_cast<const uint8_t*>(k_codes);
@@ -363,16 +387,45 @@ int nqkv_decode_attention(const nqkv_cache_desc* desc, const float* levels,
   p.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kTicketBytes);
   p.n_items = desc->B * desc->H * splits;
   p.splits = splits;
-  p.split_base = (int)(seq_len / splits);
-  p.split_rem = (int)(seq_len % splits);
+  p.split_base = (int)(n_cached / splits);
+  p.split_rem = (int)(n_cached % splits);
   p.max_workgroups = g_decode_grid_limit > 0 ? g_decode_grid_limit : max_decode_workgroups();
   p.cap_tokens = desc->cap_tokens;
   const LutChoice& lut = choose_lut_scale(checked.v, 1 << desc->k);
   std::memcpy(p.lut_levels, lut.bits, sizeof(uint16_t) * (1 << desc->k));
   p.inv_gamma = 1.0f / lut.gamma;
   p.scale_log2e = (float)((double)softmax_scale * 1.44269504088896340736 / (double)lut.gamma);
-  const hipError_t e = launch_decode_attention(p, desc->D, desc->k, desc->block, static_cast<hipStream_t>(hip_stream));
+  p.k_new = static_cast<const uint16_t*>(k_new);
+  p.v_new = static_cast<const uint16_t*>(v_new);
+  p.new_stride_b = new_stride_b;
+  p.new_stride_h = new_stride_h;
+  p.pos = seq_len - 1;
+  p.H = desc->H;
+  const hipError_t e = launch_decode_attention(p, desc->D, desc->k, desc->block, fuse, stream);
   return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
+}
+
+int nqkv_decode_attention(const nqkv_cache_desc* desc, const float* levels,
+                          const void* q,
+                          const void* k_codes, const void* k_scales,
+                          const void* v_codes, const void* v_scales,
+                          int64_t seq_len, float softmax_scale, void* out,
+                          void* workspace, size_t workspace_bytes, int num_splits,
+                          void* hip_stream) {
+  return decode_impl(desc, levels, q, nullptr, nullptr, 0, 0, k_codes, k_scales, v_codes, v_scales, seq_len,
+                     softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
+}
+
+int nqkv_decode_step(const nqkv_cache_desc* desc, const float* levels,
+                     const void* q, const void* k_new, const void* v_new,
+                     int64_t new_stride_b, int64_t new_stride_h,
+                     void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                     int64_t pos, float softmax_scale, void* out,
+                     void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
+  if (!k_new) return NQKV_EINVAL;
+  if (pos < 0 || (desc && pos >= desc->cap_tokens)) return NQKV_EINVAL;
+  return decode_impl(desc, levels, q, k_new, v_new, new_stride_b, new_stride_h, k_codes, k_scales, v_codes,
+                     v_scales, pos + 1, softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
 }
 
 }  // extern "C"

@@ -54,6 +54,15 @@ struct DecodeParams {
   float scale_log2e;         // softmax_scale * log2(e) / gamma
   float inv_gamma;           // 1 / gamma: undoes the table scaling on the value side
   uint16_t lut_levels[kMaxLevels];   // fp16 bits of gamma * level[i] (see choose_lut_scale)
+  // fused decode step only: the new token's fp16 key / value rows, element (b,h,d) at
+  // b * new_stride_b + h * new_stride_h + d; its cache row `pos`; the quantizer's cell table
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  int64_t new_stride_b, new_stride_h;
+  int64_t pos;
+  int H;
+  uint32_t cell_thr[kQuantCells];
+  uint32_t cell_below[kQuantCells];
 };
 
 // Bytes at the start of the split-K workspace that hold the ticket counters (one uint32 per
@@ -63,7 +72,8 @@ constexpr size_t kTicketBytes = 65536 * sizeof(uint32_t);
 // Each returns hipSuccess or the launch error.  D in {64,128}, k in {2,3,4}, blk in {64,128}.
 hipError_t launch_quantize(const QuantParams& p, int D, int k, int blk, hipStream_t stream);
 hipError_t launch_dequantize(const QuantParams& p, int D, int k, int blk, hipStream_t stream);
-hipError_t launch_decode_attention(const DecodeParams& p, int D, int k, int blk, hipStream_t stream);
+// fuse: also quantize and append the new token (p.k_new / p.v_new) and attend over it
+hipError_t launch_decode_attention(const DecodeParams& p, int D, int k, int blk, bool fuse, hipStream_t stream);
 
 // Tokens one wave of the attention kernel consumes per main-loop trip; split boundaries are
 // multiples of this.

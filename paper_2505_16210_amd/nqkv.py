@@ -20,7 +20,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_set_tuning", "nqkv_build_codebook",
            "nqkv_quantize_kv", "nqkv_quantize_kv_pair", "nqkv_dequantize_kv",
-           "nqkv_decode_workspace_bytes", "nqkv_decode_attention")
+           "nqkv_decode_workspace_bytes", "nqkv_decode_attention", "nqkv_decode_step")
 
 
 class CacheDesc(ctypes.Structure):
@@ -63,6 +63,9 @@ def _load() -> ctypes.CDLL:
     lib.nqkv_decode_attention.restype = i32
     lib.nqkv_decode_attention.argtypes = [dp, fp, vp, vp, vp, vp, vp, i64, c.c_float, vp, vp,
                                           c.c_size_t, i32, vp]
+    lib.nqkv_decode_step.restype = i32
+    lib.nqkv_decode_step.argtypes = [dp, fp, vp, vp, vp, i64, i64, vp, vp, vp, vp, i64, c.c_float, vp, vp,
+                                     c.c_size_t, i32, vp]
     return lib
 
 
@@ -191,4 +194,32 @@ def decode_attention(desc: CacheDesc, levels, q: torch.Tensor, k_codes, k_scales
                                    _dev_ptr(v_codes), _dev_ptr(v_scales), seq_len, float(softmax_scale),
                                    _dev_ptr(out), _dev_ptr(workspace), ws_bytes, num_splits, _stream(stream))
     _check(rc, "nqkv_decode_attention")
+    return out
+
+
+def decode_step(desc: CacheDesc, levels, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                k_codes, k_scales, v_codes, v_scales, pos: int, softmax_scale: float = 1.0,
+                out: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
+                num_splits: int = 0, stream=None) -> torch.Tensor:
+    """nqkv_decode_step: k_new, v_new fp16 [B,H,1,D] or [B,H,D] (D contiguous) -> out fp16 [B,H,D];
+    the caches gain row `pos`."""
+    lv, lvp = _levels_ptr(levels)
+    assert q.dtype == torch.float16 and q.is_contiguous()
+    if k_new.dim() == 4:
+        k_new, v_new = k_new[:, :, 0], v_new[:, :, 0]
+    assert k_new.dtype == torch.float16 and k_new.stride(2) == 1 and k_new.stride() == v_new.stride()
+    if out is None:
+        out = torch.empty_like(q)
+    ws_bytes = 0
+    if workspace is None:
+        need, _ = decode_workspace_bytes(desc, max(pos, 1), num_splits)
+        if need:
+            workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)
+    if workspace is not None:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    rc = lib.nqkv_decode_step(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_new), _dev_ptr(v_new),
+                              k_new.stride(0), k_new.stride(1), _dev_ptr(k_codes), _dev_ptr(k_scales),
+                              _dev_ptr(v_codes), _dev_ptr(v_scales), pos, float(softmax_scale), _dev_ptr(out),
+                              _dev_ptr(workspace), ws_bytes, num_splits, _stream(stream))
+    _check(rc, "nqkv_decode_step")
     return out

@@ -85,9 +85,11 @@ def test_c5_sweep_sampled_slabs(env, oracle, k, blk):
     torch.cuda.empty_cache()
 
 
-def test_c2_prefill_then_128_decode_steps(env, oracle):
+@pytest.mark.parametrize("fused", [False, True])
+def test_c2_prefill_then_128_decode_steps(env, oracle, fused):
     """The bench workload itself: quantize the 2048-token prefill, then 128 x (append one token,
-    attend over everything cached).  Attention is checked against the oracle at steps
+    attend over everything cached) -- as two launches per iteration, and as the single fused
+    launch bench.py times.  Attention is checked against the oracle at steps
     0, 1, 31, 64, 126, 127; the final caches must equal the oracle's bit for bit."""
     nqkv, workloads = env
     cfg = workloads.C2
@@ -106,8 +108,11 @@ def test_c2_prefill_then_128_decode_steps(env, oracle):
     check_at = {0, 1, 31, 64, 126, 127}
     for i in range(n_dec):
         pos = S + i
-        nqkv.quantize_kv_pair(desc, lv, K[:, :, pos:pos + 1], V[:, :, pos:pos + 1], kc, ks, vc, vs, pos)
-        o = nqkv.decode_attention(desc, lv, qs[i], kc, ks, vc, vs, pos + 1, 1.0)
+        if fused:
+            o = nqkv.decode_step(desc, lv, qs[i], K[:, :, pos:pos + 1], V[:, :, pos:pos + 1], kc, ks, vc, vs, pos, 1.0)
+        else:
+            nqkv.quantize_kv_pair(desc, lv, K[:, :, pos:pos + 1], V[:, :, pos:pos + 1], kc, ks, vc, vs, pos)
+            o = nqkv.decode_attention(desc, lv, qs[i], kc, ks, vc, vs, pos + 1, 1.0)
         if i in check_at:
             outs[i] = o.clone()
     torch.cuda.synchronize()

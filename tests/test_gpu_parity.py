@@ -306,3 +306,86 @@ def test_decode_steps_append_then_attend(nqkv, oracle):
         ref = oracle.decode_attention(h2n(q), okc, oks, ovc, ovs, k, blk, lv, pos + 1, 1.0)
         assert attn_err(h2n(out).view(np.float16), ref) <= ATTN_TOL
     assert np.array_equal(h2n(kc), okc) and np.array_equal(h2n(vs), ovs)
+
+
+# --------------------------------------------------------------------------- fused decode step
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("k,D,blk", COMBOS)
+def test_decode_step_fused_matches_oracle(nqkv, oracle, k, D, blk, variant):
+    """One launch per step: the new token's rows are quantized inside the attention kernel.
+    The cache rows it writes must equal the oracle's bit for bit (and therefore the separate
+    quantizer's), the output must meet the attention tolerance, and rows beyond the new token
+    must stay untouched -- for the first token of an empty cache, for prefixes shorter and longer
+    than one workgroup trip, and for every split count."""
+    B, H, S, cap = 2, 3, 1237, 1300
+    lv = nqkv.build_codebook(k, variant)
+    g = torch.Generator(device="cuda").manual_seed(1000 + 13 * k + D + blk + variant)
+    Kx = rand_kv((B, H, cap, D), 31 * k + D + blk + variant)
+    Vx = torch.randn(B, H, cap, D, device="cuda", generator=g).to(torch.float16)
+    # special rows for the in-kernel quantizer: an all-zero key row, a row of signed zeros and
+    # one huge value, a row of equal magnitudes
+    Kx[0, 1, 64] = 0.0
+    Vx[1, 2, 64] = -0.0
+    Vx[1, 2, 64, 3] = 65504.0
+    Kx[1, 0, 129] = Kx[1, 0, 129].abs().max() * torch.where(Kx[1, 0, 129] > 0, 1.0, -1.0).to(torch.float16)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    Kh, Vh = h2n(Kx), h2n(Vx)
+    for pos in (0, 1, 64, 129, 1000, S - 1):
+        kc, ks = nqkv.alloc_cache(desc)
+        vc, vs = nqkv.alloc_cache(desc)
+        okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
+        ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
+        oracle.quantize_kv(Kh[:, :, :pos + 1], k, blk, lv, okc, oks, n_threads=8)
+        oracle.quantize_kv(Vh[:, :, :pos + 1], k, blk, lv, ovc, ovs, n_threads=8)
+        q = (torch.randn(B, H, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+        ref = oracle.decode_attention(h2n(q), okc, oks, ovc, ovs, k, blk, lv, pos + 1, 0.9, n_threads=8)
+        for ns in (0, 1, 2, 7, 64):
+            if ns > max(pos, 1):
+                continue
+            kc.zero_(); ks.zero_(); vc.zero_(); vs.zero_()
+            if pos:
+                nqkv.quantize_kv_pair(desc, lv, Kx[:, :, :pos], Vx[:, :, :pos], kc, ks, vc, vs, 0)
+            out = nqkv.decode_step(desc, lv, q, Kx[:, :, pos:pos + 1], Vx[:, :, pos:pos + 1],
+                                   kc, ks, vc, vs, pos, 0.9, num_splits=ns)
+            torch.cuda.synchronize()
+            tag = (k, D, blk, variant, pos, ns)
+            assert np.array_equal(h2n(ks), oks) and np.array_equal(h2n(vs), ovs), tag
+            assert np.array_equal(h2n(kc), okc) and np.array_equal(h2n(vc), ovc), tag
+            err = attn_err(h2n(out).view(np.float16), ref)
+            assert err <= ATTN_TOL, tag + (err,)
+
+
+def test_decode_step_fused_loop_equals_two_launch_loop(nqkv, oracle):
+    """A run of fused steps against the append-then-attend pair of launches: identical cache
+    bytes after every step; outputs within tolerance of the oracle."""
+    k, D, blk = 4, 128, 64
+    B, H, S0, steps = 2, 8, 300, 16
+    cap = S0 + steps
+    lv = nqkv.build_codebook(k)
+    g = torch.Generator(device="cuda").manual_seed(19)
+    Kx = rand_kv((B, H, cap, D), 19)
+    Vx = torch.randn(B, H, cap, D, device="cuda", generator=g).to(torch.float16)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    caches = []
+    for _ in range(2):
+        kc, ks = nqkv.alloc_cache(desc)
+        vc, vs = nqkv.alloc_cache(desc)
+        nqkv.quantize_kv_pair(desc, lv, Kx[:, :, :S0], Vx[:, :, :S0], kc, ks, vc, vs, 0)
+        caches.append((kc, ks, vc, vs))
+    fused, plain = caches
+    for i in range(steps):
+        pos = S0 + i
+        q = (torch.randn(B, H, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+        # the new rows as a [B,H,D] tensor with padded strides
+        kn = torch.zeros(B, H, D + 8, device="cuda", dtype=torch.float16)[:, :, :D]
+        vn = torch.zeros(B, H, D + 8, device="cuda", dtype=torch.float16)[:, :, :D]
+        kn.copy_(Kx[:, :, pos]); vn.copy_(Vx[:, :, pos])
+        a = nqkv.decode_step(desc, lv, q, kn, vn, *fused, pos, 1.0)
+        nqkv.quantize_kv_pair(desc, lv, Kx[:, :, pos:pos + 1], Vx[:, :, pos:pos + 1], *plain, pos)
+        b = nqkv.decode_attention(desc, lv, q, *plain, pos + 1, 1.0)
+        torch.cuda.synchronize()
+        for x, y in zip(fused, plain):
+            assert torch.equal(x, y), i
+        ref = oracle.decode_attention(h2n(q), *[h2n(t) for t in plain], k, blk, lv, pos + 1, 1.0, n_threads=8)
+        assert attn_err(h2n(a).view(np.float16), ref) <= ATTN_TOL
+        assert attn_err(h2n(b).view(np.float16), ref) <= ATTN_TOL

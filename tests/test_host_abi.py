@@ -155,6 +155,33 @@ def test_decode_argument_errors(nqkv):
     assert call(levels=None) == nqkv.EINVAL
 
 
+def test_decode_step_argument_errors(nqkv):
+    lv, lvp = _levels(nqkv)
+    d = nqkv.make_desc(1, 32, 128, 4, 64, 32768)
+    f = nqkv.lib.nqkv_decode_step
+
+    def call(q=FAKE, kn=FAKE, vn=FAKE, sb=4096, sh=128, kc=FAKE, ks=FAKE, vc=FAKE, vs=FAKE, pos=32767,
+             scale=1.0, out=FAKE, ws=FAKE, ws_bytes=1 << 30, ns=0, desc=d, levels=lvp):
+        return f(ctypes.byref(desc), levels, q, kn, vn, sb, sh, kc, ks, vc, vs, pos, scale, out, ws, ws_bytes,
+                 ns, None)
+
+    assert call(kn=None) == nqkv.EINVAL
+    assert call(vn=None) == nqkv.EINVAL
+    assert call(kn=FAKE + 2) == nqkv.EINVAL                      # rows are read 16 bytes at a time
+    assert call(sb=4100) == nqkv.EINVAL
+    assert call(sh=-128) == nqkv.EINVAL
+    assert call(pos=-1) == nqkv.EINVAL
+    assert call(pos=32768) == nqkv.EINVAL                        # no room for the new row
+    assert call(q=None) == nqkv.EINVAL
+    assert call(kc=None) == nqkv.EINVAL
+    assert call(scale=float("nan")) == nqkv.EINVAL
+    assert call(ns=8, ws=None) == nqkv.EINVAL
+    assert call(ns=8, ws_bytes=100) == nqkv.EWORKSPACE
+    assert call(pos=0, ns=2) == nqkv.EINVAL                      # nothing cached: nothing to cut
+    assert call(pos=5, ns=6) == nqkv.EINVAL                      # more pieces than cached tokens
+    assert call(levels=None) == nqkv.EINVAL
+
+
 def test_tuning_knobs(nqkv):
     assert nqkv.lib.nqkv_set_tuning(0, 2) == nqkv.EINVAL
     assert nqkv.lib.nqkv_set_tuning(9, 0) == nqkv.EINVAL
