@@ -428,12 +428,23 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   // The first item's K loads and query slice go out before anything else, so HBM latency
   // overlaps the table build.
   uint32_t item = blockIdx.x;
+  // FUSE: lane l fetches entry l of the code-search cell table.  These are vector loads from the
+  // kernel arguments; they go out first so that waiting for them (the memory counter is
+  // positional) never means waiting for the cache prefetches behind them.
+  uint32_t cell_thr = 0, cell_below = 0;
+  if (FUSE) { cell_thr = p.cell_thr[lane]; cell_below = p.cell_below[lane]; }
   set_item(item);
   load_trip(kc_r, ks_r, base, kw, ksc);
   load_q();
   if (FUSE) load_new();
-  if (FUSE) code_search::stage_cells(p.cell_thr, p.cell_below, cells);
-  build_lut<KBITS>(p, smem);          // ends with the barrier that also covers the cell table
+  build_lut<KBITS>(p, smem);          // ends with a barrier
+  if (FUSE && wave == kWaves - 1) {
+    // only this wave searches codes: it stages the table for itself, no barrier needed (LDS
+    // operations of one wave complete in order)
+    cells[lane] = make_uint2(cell_thr, cell_below);
+    if (lane == 0) cells[code_search::kCells - 1] = make_uint2(p.cell_thr[code_search::kCells - 1], p.cell_below[code_search::kCells - 1]);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  }
   // Make the query registers "arrived" here, outside the trip loop: otherwise the wait for
   // them is re-imposed at the top of every trip (it is pending on the loop-entry path only), and
   // because the memory counter is positional that stalls each trip on its own fresh V loads.
@@ -459,6 +470,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
       // an opaque copy of the lane index: everything below is derived from it, so the compiler
       // cannot hoist these address computations out of this block, where their registers would
       // cost the streaming loop its occupancy
+      __builtin_amdgcn_s_setprio(3);           // one wave's serial chain: do not queue behind the streaming waves
       uint32_t ql = lane;
       asm volatile("" : "+v"(ql));
       const uint32_t t = ql / CPR, c = ql % CPR;          // tensor (0 key, 1 value), chunk in the row
@@ -495,22 +507,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
 #pragma unroll
       for (int i = 0; i < KBITS; ++i) { nk[i] = 0; nv[i] = 0; }
       if (ql < (uint32_t)LPT) {                 // token group 0: lane j owns 32 elements of each row
-        const int64_t row = (int64_t)bh * p.cap_tokens + p.pos;
-        uint32_t* kdst = reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(p.k_codes)) + (row * LPT + ql) * KBITS;
-        uint32_t* vdst = reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(p.v_codes)) + (row * LPT + ql) * KBITS;
 #pragma unroll
         for (int i = 0; i < KBITS; ++i) {
           nk[i] = new_codes[0][ql * KBITS + i];
           nv[i] = new_codes[1][ql * KBITS + i];
-          kdst[i] = nk[i];
-          vdst[i] = nv[i];
         }
         nks = new_scales[0][(ql * 32) / BLK];
         nvs = new_scales[1][(ql * 32) / BLK];
-        if ((ql * 32) % BLK == 0) {
-          const_cast<uint16_t*>(p.k_scales)[row * NB + (ql * 32) / BLK] = (uint16_t)nks;
-          const_cast<uint16_t*>(p.v_scales)[row * NB + (ql * 32) / BLK] = (uint16_t)nvs;
-        }
       }
       float part = k_dot<KBITS>(nk, q2, lut, lane_off);
       part *= (float)__builtin_bit_cast(_Float16, (unsigned short)nks);
@@ -521,6 +524,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
       const float pn = __builtin_amdgcn_exp2f(z - m_run);    // 1 for the token's lanes, 0 elsewhere
       l_run = pn;
       v_axpy<KBITS>(nv, pn * (float)__builtin_bit_cast(_Float16, (unsigned short)nvs), acc, lut, lane_off);
+      __builtin_amdgcn_s_setprio(0);
     }
 
     for (; base < n_tok; base += stride) {
@@ -597,6 +601,20 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
       if (mlane == 0) { wave_m[wave] = m_run; wave_l[wave] = l_wave; }
     }
     __syncthreads();
+    if (FUSE && cur_sp == (uint32_t)p.splits - 1u) {
+      // Append: the LDS images of the new token's rows go to cache row pos.  Done here rather
+      // than where they are produced because stores share the loads' in-order memory counter:
+      // issued ahead of the streaming loop, their acknowledgements would hold up its first trip.
+      const int64_t row = (int64_t)cur_bh * p.cap_tokens + p.pos;
+      if (tid < 2u * ROW) {
+        const uint32_t t = tid / ROW, w = tid % ROW;
+        uint32_t* dst = reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(t ? p.v_codes : p.k_codes)) + row * ROW + w;
+        *dst = new_codes[t][w];
+      } else if (tid < 2u * ROW + 2u * NB) {
+        const uint32_t t = (tid - 2u * ROW) / NB, w = (tid - 2u * ROW) % NB;
+        const_cast<uint16_t*>(t ? p.v_scales : p.k_scales)[row * NB + w] = (uint16_t)new_scales[t][w];
+      }
+    }
     float m_all = wave_m[0];
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) m_all = fmaxf(m_all, wave_m[w]);
