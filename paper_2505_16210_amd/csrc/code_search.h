@@ -44,9 +44,13 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t h) {
 }
 
 // The cell table is built on the host (build_cell_table) and arrives in the kernel arguments;
-// each workgroup copies it into LDS once.  The caller provides the barrier.
-__device__ __forceinline__ void stage_cells(const uint32_t* thr, const uint32_t* below, uint2* cells) {
-  if (threadIdx.x < kCells) cells[threadIdx.x] = make_uint2(thr[threadIdx.x], below[threadIdx.x]);
+// each workgroup copies it into LDS once: thread i fetches entry i early, stores it later.  The
+// caller provides the barrier.
+__device__ __forceinline__ uint2 fetch_cell(const uint32_t* thr, const uint32_t* below) {
+  return threadIdx.x < kCells ? make_uint2(thr[threadIdx.x], below[threadIdx.x]) : make_uint2(0, 0);
+}
+__device__ __forceinline__ void put_cell(const uint2& cell, uint2* cells) {
+  if (threadIdx.x < kCells) cells[threadIdx.x] = cell;
 }
 
 // Codes of the 8 fp16 values in w against scale bits s_bits, packed LSB-first, KBITS each.

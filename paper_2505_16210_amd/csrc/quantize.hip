@@ -44,10 +44,10 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantParams p)
   constexpr int LPB = BLK / 8;    // lanes that share one block
   constexpr int NB = D / BLK;
   __shared__ uint2 cells[FAST ? 128 : 1];   // 128 >= kCells: any 7-bit index stays inside
-  if (FAST) {
-    stage_cells(p.cell_thr, p.cell_below, cells);
-    __syncthreads();
-  }
+  // The cell table comes from the kernel arguments by vector loads.  They are issued first and
+  // consumed after the source loads have gone out, so that their latency overlaps the source's
+  // (the memory counter is positional: waiting for an early load does not wait for later ones).
+  const uint2 my_cell = FAST ? fetch_cell(p.cell_thr, p.cell_below) : make_uint2(0, 0);
 
   const int tensor = FLAT ? (int)blockIdx.z : (int)(blockIdx.z >= (unsigned)p.B);
   const TensorPtrs tp = p.t[tensor];
@@ -83,6 +83,11 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantParams p)
                             (int64_t)t * p.stride_t + part * 8;
       w[u] = *reinterpret_cast<const uint4*>(src);
     }
+  }
+
+  if (FAST) {
+    put_cell(my_cell, cells);
+    __syncthreads();
   }
 
 #pragma unroll
@@ -136,10 +141,10 @@ __global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantPara
   constexpr int NB = D / BLK;
   constexpr int kRowBytes = D * KBITS / 8;
   __shared__ uint2 cells[FAST ? 128 : 1];   // 128 >= kCells: any 7-bit index stays inside
-  if (FAST) {
-    stage_cells(p.cell_thr, p.cell_below, cells);
-    __syncthreads();
-  }
+  // The cell table comes from the kernel arguments by vector loads.  They are issued first and
+  // consumed after the source loads have gone out, so that their latency overlaps the source's
+  // (the memory counter is positional: waiting for an early load does not wait for later ones).
+  const uint2 my_cell = FAST ? fetch_cell(p.cell_thr, p.cell_below) : make_uint2(0, 0);
 
   const uint32_t tensor = blockIdx.z >= (unsigned)p.B ? 1u : 0u;
   const uint32_t b = blockIdx.z - (tensor ? (uint32_t)p.B : 0u), h = blockIdx.y;
@@ -169,6 +174,11 @@ __global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantPara
     if (c >= total) voff = kDropStore;                         // past the slab: reads zeros
     const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(src_r, voff, 0, 0);
     w[u] = make_uint4(v.x, v.y, v.z, v.w);
+  }
+
+  if (FAST) {
+    put_cell(my_cell, cells);
+    __syncthreads();
   }
 
 #pragma unroll
