@@ -325,11 +325,14 @@ __device__ __forceinline__ void reduce_groups(const float (&acc)[32], uint32_t l
 
 // ------------------------------------------------------------------ main kernel
 // grid: x = persistent workgroups; item i -> (bh = i / splits, split = i % splits)
+// SPLIT: sequences are cut into p.splits > 1 items whose partial results are combined by the
+// workgroup that finishes last; without it (p.splits == 1) that code and the item -> (sequence,
+// split) division are compiled out.
 // FUSE: the whole decode step of the paper in one launch -- items cover the tokens already
 // cached, rows [0, pos); the last wave of each sequence's last item quantizes the new token's
 // key and value rows (same code search as the quantizer), stores their codes and scales at row
 // pos, and adds the token to its softmax straight from registers.
-template <int KBITS, int D, int BLK, bool FUSE>
+template <int KBITS, int D, int BLK, bool FUSE, bool SPLIT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) void decode_kernel(const DecodeParams p) {   // 128 VGPRs: two workgroups per CU
   constexpr int LPT = D / 32;             // lanes per token
   constexpr int TPR = 64 / LPT;           // tokens per wave load
@@ -369,8 +372,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   __amdgpu_buffer_rsrc_t kn_r, vn_r;      // FUSE: the new token's rows, empty for waves that do not take it
   uint32_t newx[4] = {0, 0, 0, 0};        // FUSE: this lane's 16-byte chunk of those rows
   auto set_item = [&](uint32_t item) {
-    bh = item / (uint32_t)p.splits;
-    sp = item - bh * (uint32_t)p.splits;
+    if (SPLIT) {
+      bh = item / (uint32_t)p.splits;
+      sp = item - bh * (uint32_t)p.splits;
+    } else {
+      bh = item; sp = 0;
+    }
     const int64_t t0 = (int64_t)sp * p.split_base + min((int32_t)sp, p.split_rem);
     n_tok = p.split_base + ((int32_t)sp < p.split_rem ? 1 : 0);
     base = (int32_t)wave * CHUNK;
@@ -382,7 +389,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
     if (FUSE) {
       const uint32_t b = bh / (uint32_t)p.H, h = bh - b * (uint32_t)p.H;
       const int64_t off = (int64_t)b * p.new_stride_b + (int64_t)h * p.new_stride_h;
-      const int bytes = (sp == (uint32_t)p.splits - 1u && wave == kWaves - 1) ? D * 2 : 0;
+      const int bytes = ((!SPLIT || sp == (uint32_t)p.splits - 1u) && wave == kWaves - 1) ? D * 2 : 0;
       kn_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.k_new) + off, 0, bytes, kBufferFlags);
       vn_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.v_new) + off, 0, bytes, kBufferFlags);
     }
@@ -461,7 +468,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
     float m_run = -INFINITY;   // wave-uniform, log2 domain
     float l_run = 0.0f;        // per lane; every lane of a token group adds the same p
 
-    if (FUSE && sp == (uint32_t)p.splits - 1u && wave == kWaves - 1) {
+    if (FUSE && (!SPLIT || sp == (uint32_t)p.splits - 1u) && wave == kWaves - 1) {
       // ---- the token of this step: quantize, append, attend -- before this wave's share of
       // the cached tokens, while the accumulators are not live yet.  One lane per 16-byte chunk
       // (fetched by load_new), so the whole code search is one chunk deep.
@@ -601,7 +608,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
       if (mlane == 0) { wave_m[wave] = m_run; wave_l[wave] = l_wave; }
     }
     __syncthreads();
-    if (FUSE && cur_sp == (uint32_t)p.splits - 1u) {
+    if (FUSE && (!SPLIT || cur_sp == (uint32_t)p.splits - 1u)) {
       // Append: the LDS images of the new token's rows go to cache row pos.  Done here rather
       // than where they are produced because stores share the loads' in-order memory counter:
       // issued ahead of the streaming loop, their acknowledgements would hold up its first trip.
@@ -626,7 +633,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
         l_all += wave_l[w] * f;
         o += xw[w][tid] * f;
       }
-      if (p.splits == 1) {
+      if (!SPLIT) {
         p.out[(int64_t)cur_bh * D + tid] = __builtin_bit_cast(unsigned short, (_Float16)(o * p.inv_gamma / l_all));
       } else {
         // Partials travel between workgroups, possibly on different XCDs whose L2 caches are not
@@ -637,7 +644,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
         if (tid == 0) { store_agent(ws, m_all); store_agent(ws + 1, l_all); }
       }
     }
-    if (p.splits > 1) {
+    if (SPLIT) {
       // Once every store above is acknowledged, take a ticket; the workgroup holding the last
       // ticket of this (b,h) combines all partials in split order (reading them past the
       // caches) and re-arms the ticket counter.
@@ -645,18 +652,51 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
       __syncthreads();
       if (tid == 0) ticket_sh = __hip_atomic_fetch_add(p.tickets + cur_bh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __syncthreads();
-      if (ticket_sh == (uint32_t)p.splits - 1u) {
-        if (tid < D) {
-          const uint32_t* ws = reinterpret_cast<const uint32_t*>(p.partials + (int64_t)cur_bh * p.splits * (D + 2));
-          float mm = -INFINITY;
-          for (int s2 = 0; s2 < p.splits; ++s2) mm = fmaxf(mm, load_agent(ws + s2 * (D + 2)));
-          float oo = 0.0f, ll = 0.0f;
-          for (int s2 = 0; s2 < p.splits; ++s2) {
-            const float f = __builtin_amdgcn_exp2f(load_agent(ws + s2 * (D + 2)) - mm);
-            ll += f * load_agent(ws + s2 * (D + 2) + 1);
-            oo += f * load_agent(ws + s2 * (D + 2) + 2 + tid);
+      if (ticket_sh == (uint32_t)p.splits - 1u) {           // uniform over the workgroup
+        // All 512 threads combine: thread (grp, d) folds the partials of splits grp, grp + G, ...
+        // for output element d, four splits per trip so that their loads (which bypass the
+        // caches, a full memory round trip each) are in flight together; the G group results
+        // then merge through LDS exactly like the eight waves above.  The order of the folds is
+        // fixed by this layout, not by which workgroup arrives last: equal inputs, equal bits.
+        constexpr uint32_t G = kThreads / D, U = 4;
+        const uint32_t grp = tid / D, d = tid % D;
+        const uint32_t* ws = reinterpret_cast<const uint32_t*>(p.partials + (int64_t)cur_bh * p.splits * (D + 2));
+        float mm = -INFINITY, ll = 0.0f, oo = 0.0f;
+        for (uint32_t s0 = grp; s0 < (uint32_t)p.splits; s0 += G * U) {
+          float ms[U], ls[U], os[U];
+#pragma unroll
+          for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t s2 = min(s0 + u * G, (uint32_t)p.splits - 1u);      // clamped: always a valid record
+            const uint32_t* rec = ws + s2 * (D + 2);
+            ms[u] = load_agent(rec);
+            ls[u] = load_agent(rec + 1);
+            os[u] = load_agent(rec + 2 + d);
           }
-          p.out[(int64_t)cur_bh * D + tid] = __builtin_bit_cast(unsigned short, (_Float16)(oo * p.inv_gamma / ll));
+#pragma unroll
+          for (uint32_t u = 0; u < U; ++u) {
+            const float m_s = (s0 + u * G < (uint32_t)p.splits) ? ms[u] : -INFINITY;   // a clamped duplicate weighs 0
+            const float m_new = fmaxf(mm, m_s);                 // finite from the first fold on
+            const float f_old = __builtin_amdgcn_exp2f(mm - m_new), f_s = __builtin_amdgcn_exp2f(m_s - m_new);
+            ll = ll * f_old + ls[u] * f_s;
+            oo = oo * f_old + os[u] * f_s;
+            mm = m_new;
+          }
+        }
+        xw[grp][d] = oo;
+        if (d == 0) { wave_m[grp] = mm; wave_l[grp] = ll; }
+        __syncthreads();
+        if (tid < D) {
+          float m_fin = wave_m[0];
+#pragma unroll
+          for (uint32_t g2 = 1; g2 < G; ++g2) m_fin = fmaxf(m_fin, wave_m[g2]);
+          float l_fin = 0.0f, o_fin = 0.0f;
+#pragma unroll
+          for (uint32_t g2 = 0; g2 < G; ++g2) {
+            const float f = __builtin_amdgcn_exp2f(wave_m[g2] - m_fin);       // 0 for a group without splits
+            l_fin += wave_l[g2] * f;
+            o_fin += xw[g2][tid] * f;
+          }
+          p.out[(int64_t)cur_bh * D + tid] = __builtin_bit_cast(unsigned short, (_Float16)(o_fin * p.inv_gamma / l_fin));
         }
         if (tid == 0) __hip_atomic_store(p.tickets + cur_bh, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
@@ -671,8 +711,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
 template <int KBITS, int D, int BLK>
 hipError_t launch_one(const DecodeParams& p, bool fuse, hipStream_t stream) {
   const int wgs = p.n_items < p.max_workgroups ? p.n_items : p.max_workgroups;
-  if (fuse) hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, true>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, p);
-  else      hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, false>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, p);
+  const dim3 grid((unsigned)wgs), block(kThreads);
+  const bool split = p.splits > 1;
+  if (fuse && split)       hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, true, true>), grid, block, 0, stream, p);
+  else if (fuse)           hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, true, false>), grid, block, 0, stream, p);
+  else if (split)          hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, false, true>), grid, block, 0, stream, p);
+  else                     hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, false, false>), grid, block, 0, stream, p);
   return hipGetLastError();
 }
 
