@@ -254,15 +254,17 @@ def main():
     eff_bytes = 2 * (elems_quant + elems_attn)
     value = eff_bytes / (ms_per_step * 1e-3) / 1e9
 
+    traffic_ratio = 1.0032 if args.two_launch else 1.0064
     roofline = {"kernel": "decode_kernel<4,64,64,%s>" % ("false" if args.two_launch else "true"), "bound": "hbm",
                 "achieved": round(dec_bytes / (t_att * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(dec_bytes / (t_att * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                 "bytes_per_launch": int(dec_bytes), "avg_launch_us": round(t_att * 1e3, 2),
                 # HBM bytes of one launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a 1 GiB copy
-                # kernel: x2.000 / x1.000), measured at 2048 cached tokens: 1.0035 x algorithmic
-                # (profiles/hbm_traffic_counters_quantize_decode.txt)
-                "traffic": int(round(dec_bytes * 1.0035)),
-                "traffic_source": "rocprofv3 pmc, separate run; ratio measured/algorithmic = 1.0035"}
+                # kernel: x2.000 / x1.000), measured at 2048 tokens: 1.0064 x algorithmic for the fused
+                # step, 1.0032 x for attention alone
+                # (profiles/hbm_traffic_counters_c2_quantize_decode_fused_step.txt)
+                "traffic": int(round(dec_bytes * traffic_ratio)),
+                "traffic_source": "rocprofv3 pmc, separate run; ratio measured/algorithmic = %.4f" % traffic_ratio}
 
     # free the C2 buffers before the big configurations
     del srcs, caches, Knew, Vnew, qs, new_views
@@ -307,7 +309,7 @@ def kernel_entry(nbytes, ms, **extra):
 
 
 def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, timed, iters, cold):
-    """quantize (K and V in one launch) and one fused decode attention at full size."""
+    """quantize (K and V in one launch), decode attention, and the fused decode step at full size."""
     B, H, D, S = base.B, base.H, base.D, base.S
     fp16_bytes = 2 * B * H * S * D * 2
     # rotate so that copies x working set >= 1 GiB (sources) / packed caches likewise
@@ -327,6 +329,7 @@ def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, time
             vc, vs = nqkv.alloc_cache(desc, dev)
             caches.append((kc, ks, vc, vs))
         ws_bytes, splits = nqkv.decode_workspace_bytes(desc, S, 0)
+        ws_bytes = max(ws_bytes, nqkv.decode_workspace_bytes(desc, S - 1, 0)[0])     # the fused step plans over S - 1
         ws = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
 
         def quant(i):
@@ -338,17 +341,28 @@ def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, time
             kc, ks, vc, vs = caches[i % r_cache]
             nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, 1.0, out=out, workspace=ws, stream=stream)
 
+        def step_fused(i):
+            # the decode step over the same cache: rows [0, S-1) are read, row S-1 is the new token
+            kc, ks, vc, vs = caches[i % r_cache]
+            ksrc, vsrc = srcs[i % r_src]
+            nqkv.decode_step(desc, lv, q, ksrc[:, :, S - 1:S], vsrc[:, :, S - 1:S], kc, ks, vc, vs, S - 1, 1.0,
+                             out=out, workspace=ws, stream=stream)
+
         for r in range(r_cache):
             quant(r)
         n_it = max(5, min(iters, int(2000.0 / max(1.0, fp16_bytes / 1e9 * 0.4))))
         t_q = timed(quant, n_it, warm=max(2, r_cache))
         t_a = timed(attend, n_it * 2, warm=max(2, r_cache))
+        t_f = timed(step_fused, n_it * 2, warm=max(2, r_cache))
         tag = "%s.k%d.b%d" % (base.name.split("-")[0], kb, bl)
         qbytes = 2 * B * H * S * D * workloads.quantize_bytes_per_element(kb, bl)
         dbytes = packed + B * H * 4 * D + (2 * B * H * splits * (D + 2) * 4 if splits > 1 else 0)
         kern[tag + ".quantize"] = kernel_entry(qbytes, t_q, src_copies=r_src)
         kern[tag + ".decode_attention"] = kernel_entry(dbytes, t_a, splits=splits, cache_copies=r_cache,
                                                        tokens_per_s_per_layer=round(B / (t_a * 1e-3), 1))
+        per_tok = workloads.decode_bytes_per_token_head(D, kb, bl)
+        kern[tag + ".decode_step_fused"] = kernel_entry(dbytes - B * H * per_tok + B * H * (2 * D * 2 + per_tok), t_f,
+                                                        splits=nqkv.decode_workspace_bytes(desc, S - 1, 0)[1])
         del caches, ws
         torch.cuda.empty_cache()
 
