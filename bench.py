@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--two-launch", action="store_true",
                     help="decode iteration as two launches (quantizer append, then attention) instead of "
                          "the fused single-launch step")
+    ap.add_argument("--no-paper-flow", action="store_true",
+                    help="skip the paper's own decode flow (dequantize the whole cache, then unfused attention)")
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="with --skip-step: also run a torch copy of this many MiB (counter calibration)")
     ap.add_argument("--skip-step", action="store_true",
@@ -107,6 +109,14 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / (reps * n_calls)
 
+    def read_stream_ceiling():
+        """GB/s of a plain 128-bit read stream over 2 GiB (the library's probe kernel): what this
+        box's memory system delivers to the simplest reader, quoted beside the 8 TB/s peak"""
+        buf = torch.empty(1 << 29, dtype=torch.int32, device=dev).fill_(1)
+        sums = torch.empty(nqkv.PROBE_WORKGROUPS, dtype=torch.int32, device=dev)
+        ms = timed(lambda i: nqkv.probe_read_stream(buf, sums), 10)
+        return buf.numel() * 4 / (ms * 1e-3) / 1e9
+
     if args.skip_step:
         kern = {}
         if args.calib_copy:
@@ -124,7 +134,8 @@ def main():
             variants = [(base.bits, base.block)]
             if name == "C5" and args.sweep:
                 variants = [(kb, bl) for kb in (4, 3, 2) for bl in (64, 128)]
-            bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, timed, args.kernel_iters, args.cold)
+            bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, timed, args.kernel_iters, args.cold,
+                         not args.no_paper_flow)
         print(json.dumps({"kernels": kern}))
         return
 
@@ -271,12 +282,19 @@ def main():
     torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ larger configurations
-    for name in [c for c in args.configs.split(",") if c and c != "C2"]:
+    for name in [c for c in args.configs.split(",") if c]:
         base = workloads.CONFIGS[name]
         variants = [(base.bits, base.block)]
         if name == "C5" and args.sweep:
             variants = [(kb, bl) for kb in (4, 3, 2) for bl in (64, 128)]
-        bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, timed, it, args.cold)
+        bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, timed, it, args.cold, not args.no_paper_flow,
+                     timed_kernels=tk if name == "C2" else None)
+
+    stream_gbps = read_stream_ceiling()
+    for e in kern.values():
+        e["frac_of_read_stream"] = round(e["GBps"] / stream_gbps, 4)
+    roofline["read_stream_GBps"] = round(stream_gbps, 1)
+    roofline["frac_of_read_stream"] = round(roofline["achieved"] / stream_gbps, 4)
 
     result = {
         "metric": "effective KV GB/s (quantize + fused decode attn) & decode tokens/s/layer",
@@ -308,7 +326,8 @@ def kernel_entry(nbytes, ms, **extra):
     return e
 
 
-def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, timed, iters, cold):
+def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, timed, iters, cold, paper_flow_on=True,
+                 timed_kernels=None):
     """quantize (K and V in one launch), decode attention, and the fused decode step at full size."""
     B, H, D, S = base.B, base.H, base.D, base.S
     fp16_bytes = 2 * B * H * S * D * 2
@@ -335,31 +354,54 @@ def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, time
         def quant(i):
             ksrc, vsrc = srcs[i % r_src]
             kc, ks, vc, vs = caches[i % r_cache]
-            nqkv.quantize_kv_pair(desc, lv, ksrc, vsrc, kc, ks, vc, vs, 0, stream=stream)
+            nqkv.quantize_kv_pair(desc, lv, ksrc, vsrc, kc, ks, vc, vs, 0)
 
         def attend(i):
             kc, ks, vc, vs = caches[i % r_cache]
-            nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, 1.0, out=out, workspace=ws, stream=stream)
+            nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, 1.0, out=out, workspace=ws)
 
         def step_fused(i):
             # the decode step over the same cache: rows [0, S-1) are read, row S-1 is the new token
             kc, ks, vc, vs = caches[i % r_cache]
             ksrc, vsrc = srcs[i % r_src]
             nqkv.decode_step(desc, lv, q, ksrc[:, :, S - 1:S], vsrc[:, :, S - 1:S], kc, ks, vc, vs, S - 1, 1.0,
-                             out=out, workspace=ws, stream=stream)
+                             out=out, workspace=ws)
+
+        def paper_flow(i):
+            # the decode flow as the paper runs it: restore the whole cache to fp16, then attention
+            # as two batched matrix products around a softmax (library GEMMs; fp32 softmax)
+            kc, ks, vc, vs = caches[i % r_cache]
+            nqkv.dequantize_kv(desc, lv, kc, ks, 0, S, out=k_full)
+            nqkv.dequantize_kv(desc, lv, vc, vs, 0, S, out=v_full)
+            torch.matmul(q.unsqueeze(2), k_full.transpose(-1, -2), out=scores)
+            torch.softmax(scores.float(), dim=-1, out=probs32)
+            probs16.copy_(probs32)
+            torch.matmul(probs16, v_full, out=out_pf)
 
         for r in range(r_cache):
             quant(r)
         n_it = max(5, min(iters, int(2000.0 / max(1.0, fp16_bytes / 1e9 * 0.4))))
-        t_q = timed(quant, n_it, warm=max(2, r_cache))
-        t_a = timed(attend, n_it * 2, warm=max(2, r_cache))
-        t_f = timed(step_fused, n_it * 2, warm=max(2, r_cache))
+        tk = timed_kernels or timed       # short kernels: timed through graph replays, without launch gaps
+        t_q = tk(quant, n_it, warm=max(2, r_cache))
+        t_a = tk(attend, n_it * 2, warm=max(2, r_cache))
+        t_f = tk(step_fused, n_it * 2, warm=max(2, r_cache))
         tag = "%s.k%d.b%d" % (base.name.split("-")[0], kb, bl)
         qbytes = 2 * B * H * S * D * workloads.quantize_bytes_per_element(kb, bl)
         dbytes = packed + B * H * 4 * D + (2 * B * H * splits * (D + 2) * 4 if splits > 1 else 0)
         kern[tag + ".quantize"] = kernel_entry(qbytes, t_q, src_copies=r_src)
         kern[tag + ".decode_attention"] = kernel_entry(dbytes, t_a, splits=splits, cache_copies=r_cache,
                                                        tokens_per_s_per_layer=round(B / (t_a * 1e-3), 1))
+        if paper_flow_on and fp16_bytes <= (8 << 30):
+            k_full = torch.empty(B, H, S, D, dtype=torch.float16, device=dev)
+            v_full = torch.empty_like(k_full)
+            scores = torch.empty(B, H, 1, S, dtype=torch.float16, device=dev)
+            probs32 = torch.empty(B, H, 1, S, dtype=torch.float32, device=dev)
+            probs16 = torch.empty_like(scores)
+            out_pf = torch.empty(B, H, 1, D, dtype=torch.float16, device=dev)
+            t_p = timed(paper_flow, max(3, n_it // 2), warm=2)
+            # bytes this flow moves: packed cache in, fp16 cache out, fp16 cache back in
+            kern[tag + ".paper_flow_decode"] = kernel_entry(packed + 2 * fp16_bytes, t_p, fused_speedup=round(t_p / t_a, 2))
+            del k_full, v_full, scores, probs32, probs16, out_pf
         per_tok = workloads.decode_bytes_per_token_head(D, kb, bl)
         kern[tag + ".decode_step_fused"] = kernel_entry(dbytes - B * H * per_tok + B * H * (2 * D * 2 + per_tok), t_f,
                                                         splits=nqkv.decode_workspace_bytes(desc, S - 1, 0)[1])

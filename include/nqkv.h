@@ -209,6 +209,17 @@ int nqkv_decode_step(const nqkv_cache_desc* desc, const float* levels,
                      void* workspace, size_t workspace_bytes, int num_splits,
                      void* hip_stream);
 
+/*
+ * Measurement helper, not part of the method: reads `bytes` (a multiple of 16) of device memory
+ * at `src` once, with plain 128-bit loads, and writes one 32-bit xor checksum per workgroup to
+ * `checksums` (device, NQKV_PROBE_WORKGROUPS uint32).  Timed by a benchmark it gives the read
+ * bandwidth this machine delivers to the simplest possible kernel, the yardstick beside the
+ * published peak; the xor of all checksums equals the xor of all 32-bit words of the buffer.
+ * Errors: NQKV_EINVAL for null / misaligned pointers or bytes % 16 != 0.
+ */
+#define NQKV_PROBE_WORKGROUPS 4096
+int nqkv_probe_read_stream(const void* src, size_t bytes, void* checksums, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

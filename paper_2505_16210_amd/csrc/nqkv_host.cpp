@@ -428,4 +428,11 @@ int nqkv_decode_step(const nqkv_cache_desc* desc, const float* levels,
                      v_scales, pos + 1, softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
 }
 
+int nqkv_probe_read_stream(const void* src, size_t bytes, void* checksums, void* hip_stream) {
+  if (!src || !checksums || !aligned16(src) || !aligned16(checksums) || (bytes % 16) != 0) return NQKV_EINVAL;
+  const hipError_t e = launch_read_stream(src, bytes, static_cast<uint32_t*>(checksums), NQKV_PROBE_WORKGROUPS,
+                                          static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
+}
+
 }  // extern "C"

@@ -75,6 +75,10 @@ hipError_t launch_dequantize(const QuantParams& p, int D, int k, int blk, hipStr
 // fuse: also quantize and append the new token (p.k_new / p.v_new) and attend over it
 hipError_t launch_decode_attention(const DecodeParams& p, int D, int k, int blk, bool fuse, hipStream_t stream);
 
+// Measurement helper: xor checksum per workgroup of a plain 128-bit read stream over `bytes`
+// (a multiple of 16) of device memory.
+hipError_t launch_read_stream(const void* src, uint64_t bytes, uint32_t* checksums, int workgroups, hipStream_t stream);
+
 // Tokens one wave of the attention kernel consumes per main-loop trip; split boundaries are
 // multiples of this.
 int decode_chunk_tokens(int D);

@@ -20,7 +20,8 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_set_tuning", "nqkv_build_codebook",
            "nqkv_quantize_kv", "nqkv_quantize_kv_pair", "nqkv_dequantize_kv",
-           "nqkv_decode_workspace_bytes", "nqkv_decode_attention", "nqkv_decode_step")
+           "nqkv_decode_workspace_bytes", "nqkv_decode_attention", "nqkv_decode_step",
+           "nqkv_probe_read_stream")
 
 
 class CacheDesc(ctypes.Structure):
@@ -66,6 +67,8 @@ def _load() -> ctypes.CDLL:
     lib.nqkv_decode_step.restype = i32
     lib.nqkv_decode_step.argtypes = [dp, fp, vp, vp, vp, i64, i64, vp, vp, vp, vp, i64, c.c_float, vp, vp,
                                      c.c_size_t, i32, vp]
+    lib.nqkv_probe_read_stream.restype = i32
+    lib.nqkv_probe_read_stream.argtypes = [vp, c.c_size_t, vp, vp]
     return lib
 
 
@@ -223,3 +226,18 @@ def decode_step(desc: CacheDesc, levels, q: torch.Tensor, k_new: torch.Tensor, v
                               _dev_ptr(workspace), ws_bytes, num_splits, _stream(stream))
     _check(rc, "nqkv_decode_step")
     return out
+
+
+PROBE_WORKGROUPS = 4096
+
+
+def probe_read_stream(src: torch.Tensor, checksums: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """nqkv_probe_read_stream: one plain read pass over `src` (contiguous, bytes % 16 == 0) ->
+    int32 [PROBE_WORKGROUPS] xor checksums (device)."""
+    assert src.is_contiguous()
+    if checksums is None:
+        checksums = torch.empty(PROBE_WORKGROUPS, dtype=torch.int32, device=src.device)
+    rc = lib.nqkv_probe_read_stream(_dev_ptr(src), src.numel() * src.element_size(), _dev_ptr(checksums),
+                                    _stream(stream))
+    _check(rc, "nqkv_probe_read_stream")
+    return checksums

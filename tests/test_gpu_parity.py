@@ -389,3 +389,38 @@ def test_decode_step_fused_loop_equals_two_launch_loop(nqkv, oracle):
         ref = oracle.decode_attention(h2n(q), *[h2n(t) for t in plain], k, blk, lv, pos + 1, 1.0, n_threads=8)
         assert attn_err(h2n(a).view(np.float16), ref) <= ATTN_TOL
         assert attn_err(h2n(b).view(np.float16), ref) <= ATTN_TOL
+
+
+# --------------------------------------------------------------------------- measurement helper
+@pytest.mark.parametrize("n_bytes", [16, 16 * 1000 + 16, 64 << 20])
+def test_probe_read_stream_reads_every_word_once(nqkv, n_bytes):
+    g = torch.Generator(device="cuda").manual_seed(n_bytes % 1000)
+    x = torch.randint(-2**31, 2**31 - 1, (n_bytes // 4,), device="cuda", dtype=torch.int32, generator=g)
+    sums = nqkv.probe_read_stream(x)
+    torch.cuda.synchronize()
+    got = np.bitwise_xor.reduce(sums.cpu().numpy().view(np.uint32))
+    want = np.bitwise_xor.reduce(x.cpu().numpy().view(np.uint32))
+    assert got == want
+
+
+# --------------------------------------------------------------------------- the paper's own flow
+@pytest.mark.parametrize("k,D,blk", [(4, 64, 64), (4, 128, 128), (3, 128, 64), (2, 64, 64)])
+def test_paper_flow_dequantize_then_unfused_attention(nqkv, oracle, k, D, blk):
+    """Sec. 3.2 decoding phase as the paper runs it -- dequantize the whole cache to fp16, then
+    softmax(q K'^T) V' as separate operations -- built from nqkv_dequantize_kv and library
+    matrix products.  It is the baseline bench.py times against the fused kernel, so it has to
+    compute the same thing: same tolerance against the oracle, and agreement with the fused
+    kernel."""
+    B, H, S = 2, 4, 777
+    lv, desc, q, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, S, S, seed=3 * k + D)
+    k_full = nqkv.dequantize_kv(desc, lv, kc, ks, 0, S)
+    v_full = nqkv.dequantize_kv(desc, lv, vc, vs, 0, S)
+    scores = torch.matmul(q.unsqueeze(2), k_full.transpose(-1, -2)).float() * 0.9
+    probs = torch.softmax(scores, dim=-1).half()
+    out_pf = torch.matmul(probs, v_full)[:, :, 0]
+    out_fused = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, 0.9)
+    torch.cuda.synchronize()
+    ref = oracle.decode_attention(*[h2n(t) for t in (q, kc, ks, vc, vs)], k, blk, lv, S, 0.9, n_threads=8)
+    # fp16 scores and fp16 probabilities cost the unfused flow precision the fused kernel keeps
+    assert attn_err(h2n(out_pf).view(np.float16), ref) <= 2.5 * ATTN_TOL
+    assert attn_err(h2n(out_fused).view(np.float16), ref) <= ATTN_TOL

@@ -182,6 +182,14 @@ def test_decode_step_argument_errors(nqkv):
     assert call(levels=None) == nqkv.EINVAL
 
 
+def test_probe_argument_errors(nqkv):
+    f = nqkv.lib.nqkv_probe_read_stream
+    assert f(None, 1024, FAKE, None) == nqkv.EINVAL
+    assert f(FAKE, 1024, None, None) == nqkv.EINVAL
+    assert f(FAKE + 4, 1024, FAKE, None) == nqkv.EINVAL
+    assert f(FAKE, 1000, FAKE, None) == nqkv.EINVAL              # whole 16-byte vectors only
+
+
 def test_tuning_knobs(nqkv):
     assert nqkv.lib.nqkv_set_tuning(0, 2) == nqkv.EINVAL
     assert nqkv.lib.nqkv_set_tuning(9, 0) == nqkv.EINVAL
