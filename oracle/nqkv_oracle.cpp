@@ -286,6 +286,51 @@ int oracle_quantize_kv(const uint16_t* src, int64_t sb, int64_t sh, int64_t ss,
   return 0;
 }
 
+// Blocks over the token's hidden vector (Fig. 5: "each token ... divided into blocks" of a fixed
+// size; Sec. 4.1: block size 256).  The hidden vector of one token is its H heads of D elements
+// side by side, h-major; a block is `blk_hidden` consecutive elements of it, a multiple of D, so
+// it covers blk_hidden / D whole heads.  Each block is quantized on its own exactly like any
+// other block (oracle_quantize_block).  The cache keeps its per-head layout: codes uint8
+// [B, H, cap_tokens, D*k/8] and ONE scale per token-head, fp16 bits [B, H, cap_tokens, 1] -- the
+// block's scale written once for every head the block covers -- so that dequantization and
+// attention read it as a cache of block size D.
+//   src  fp16 bits, element (b,h,t,d) at b*sb + h*sh + t*ss + d  (token-major [B,S,H*D]: sh = D, ss = H*D)
+// Returns 0, or -1 on a bad argument.
+int oracle_quantize_kv_hidden(const uint16_t* src, int64_t sb, int64_t sh, int64_t ss,
+                              int B, int H, int D, int64_t n_tokens,
+                              int k, int blk_hidden, const float* levels32,
+                              int64_t cap_tokens, int64_t dst_off,
+                              uint8_t* codes, uint16_t* scales, int n_threads) {
+  if (k < 1 || k > 8 || (D * k) % 8 != 0) return -1;
+  if (blk_hidden < D || blk_hidden % D != 0 || ((int64_t)H * D) % blk_hidden != 0) return -1;
+  if (dst_off < 0 || n_tokens < 0 || dst_off + n_tokens > cap_tokens) return -1;
+  const int heads_per_block = blk_hidden / D;
+  const int blocks_per_token = H / heads_per_block;
+  const int64_t row_bytes = (int64_t)D * k / 8;
+  run_parallel((int64_t)B * n_tokens, n_threads, [&](int64_t bt) {
+    const int64_t b = bt / n_tokens, t = bt % n_tokens;
+    std::vector<uint16_t> x((size_t)blk_hidden);
+    std::vector<uint8_t> c((size_t)blk_hidden);
+    for (int j = 0; j < blocks_per_token; ++j) {
+      // gather the block: heads j*heads_per_block .. +heads_per_block-1 of this token
+      for (int g = 0; g < heads_per_block; ++g) {
+        const int h = j * heads_per_block + g;
+        const uint16_t* row = src + b * sb + (int64_t)h * sh + t * ss;
+        for (int d = 0; d < D; ++d) x[(size_t)g * D + d] = row[d];
+      }
+      uint16_t scale = 0;
+      oracle_quantize_block(x.data(), blk_hidden, k, levels32, c.data(), &scale);
+      for (int g = 0; g < heads_per_block; ++g) {
+        const int h = j * heads_per_block + g;
+        const int64_t row = ((int64_t)b * H + h) * cap_tokens + dst_off + t;
+        oracle_pack_bits(c.data() + (size_t)g * D, D, k, codes + row * row_bytes);
+        scales[row] = scale;
+      }
+    }
+  });
+  return 0;
+}
+
 // Dequantize tokens [off, off+n_tokens) of a cache to fp16 (Fig. 5 caption; Sec. 3.2
 // X' = dequantize(I)):  out = fp16_rne( fl32( level[code] * float(scale) ) ).
 //   dst fp16 bits, logical [B, H, n_tokens, D], strides sb, sh, ss.

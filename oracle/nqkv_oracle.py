@@ -62,6 +62,10 @@ def _load():
                                                c.c_int, c.c_int, c.c_int, c.c_int64,
                                                c.c_int, c.c_int, p, c.c_int64, c.c_int64,
                                                p, p, c.c_int]
+            lib.oracle_quantize_kv_hidden.restype = c.c_int
+            lib.oracle_quantize_kv_hidden.argtypes = [p, c.c_int64, c.c_int64, c.c_int64,
+                                                      c.c_int, c.c_int, c.c_int, c.c_int64,
+                                                      c.c_int, c.c_int, p, c.c_int64, c.c_int64, p, p, c.c_int]
             lib.oracle_dequantize_kv.restype = c.c_int
             lib.oracle_dequantize_kv.argtypes = [p, p, c.c_int, c.c_int, c.c_int, c.c_int, c.c_int, p,
                                                  c.c_int64, c.c_int64, c.c_int64,
@@ -164,6 +168,28 @@ def quantize_kv(src, k: int, blk: int, levels32, codes: np.ndarray, scales: np.n
                                     cap, dst_off, _ptr(codes), _ptr(scales), n_threads)
     if rc != 0:
         raise ValueError("oracle_quantize_kv: bad argument")
+
+
+def quantize_kv_hidden(src, k: int, blk_hidden: int, levels32, codes: np.ndarray, scales: np.ndarray,
+                       dst_off: int = 0, n_threads: int = 1) -> None:
+    """Blocks of blk_hidden consecutive elements of the token's hidden vector (its H heads side by
+    side).  src fp16 [B,H,n,D] as a view with any B/H/token strides (token-major storage is the
+    view x.reshape(B,n,H,D).transpose(1,2)) -> rows [dst_off, dst_off+n) of a cache with one
+    scale per token-head (scales [B,H,cap,1])."""
+    src = _as_u16(src)
+    B, H, n, D = src.shape
+    assert src.strides[3] == 2
+    sb, sh, ss = (s // 2 for s in src.strides[:3])
+    lv = np.ascontiguousarray(levels32, np.float32)
+    assert lv.size == 1 << k
+    assert codes.flags.c_contiguous and scales.flags.c_contiguous
+    assert codes.shape[:2] == (B, H) and codes.shape[3] == D * k // 8
+    cap = codes.shape[2]
+    assert scales.shape == (B, H, cap, 1)
+    rc = _load().oracle_quantize_kv_hidden(_ptr(src), sb, sh, ss, B, H, D, n, k, blk_hidden, _ptr(lv),
+                                           cap, dst_off, _ptr(codes), _ptr(scales), n_threads)
+    if rc != 0:
+        raise ValueError("oracle_quantize_kv_hidden: bad argument")
 
 
 def dequantize_kv(codes: np.ndarray, scales: np.ndarray, k: int, blk: int, levels32,

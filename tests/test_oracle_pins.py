@@ -281,6 +281,97 @@ def test_quantize_kv_strided_source_and_layout(oracle):
     assert np.array_equal(c1, c2) and np.array_equal(s1, s2)
 
 
+# ----------------------------------------------------------------------------- blocks over the hidden vector
+def test_hidden_blocks_reduce_to_per_head_blocks_when_block_is_one_head(oracle):
+    """Fig. 5's own numbers: hidden size 24, block 6 -> 4 blocks per token.  With the hidden vector
+    seen as 4 heads of 6, a block is one head, and the result must be the per-head quantizer's."""
+    k = 4
+    _, l32, _ = oracle.codebook(k)
+    X = RNG.standard_normal((2, 4, 50, 6)).astype(np.float16)          # [B,H,S,D]
+    c1, s1 = oracle.new_cache(2, 4, 6, k, 6, 60)
+    c2, s2 = oracle.new_cache(2, 4, 6, k, 6, 60)
+    oracle.quantize_kv(X, k, 6, l32, c1, s1, dst_off=7)
+    oracle.quantize_kv_hidden(X, k, 6, l32, c2, s2, dst_off=7, n_threads=2)
+    assert np.array_equal(c1, c2) and np.array_equal(s1, s2)
+
+
+@pytest.mark.parametrize("k,D,blk_hidden", [(4, 64, 256), (3, 128, 256), (2, 64, 128), (4, 8, 32)])
+def test_hidden_blocks_against_numpy_brute_force(oracle, k, D, blk_hidden):
+    """Scale = max |x| over the blk_hidden consecutive hidden elements (numpy), written once per
+    covered head; code = nearest level of x / scale in fp64 wherever that is not a near-tie."""
+    _, l32, _ = oracle.codebook(k)
+    B, H, S = 2, 2 * blk_hidden // D, 9
+    tok_major = (RNG.standard_normal((B, S, H * D)) * np.exp(RNG.normal(0, 1, (B, S, 1)))).astype(np.float16)
+    view = tok_major.reshape(B, S, H, D).transpose(0, 2, 1, 3)           # [B,H,S,D] view of token-major storage
+    codes, scales = oracle.new_cache(B, H, D, k, D, S + 3)
+    oracle.quantize_kv_hidden(view, k, blk_hidden, l32, codes, scales, dst_off=3)
+    assert not codes[:, :, :3].any() and not scales[:, :, :3].any()      # rows before the offset untouched
+    lev = l32.astype(np.float64)
+    g = blk_hidden // D
+    near_ties = 0
+    for b in range(B):
+        for t in range(S):
+            hid = tok_major[b, t].astype(np.float64)
+            for j in range(H * D // blk_hidden):
+                blk = hid[j * blk_hidden:(j + 1) * blk_hidden]
+                s = np.abs(blk).max()
+                want_scale = np.float16(s).view(np.uint16)
+                for gg in range(g):
+                    h = j * g + gg
+                    assert scales[b, h, 3 + t, 0] == want_scale
+                    got = oracle.unpack_bits(codes[b, h, 3 + t], D, k)
+                    r = blk[gg * D:(gg + 1) * D] / s
+                    dist = np.abs(r[:, None] - lev[None, :])
+                    order = np.sort(dist, axis=1)
+                    clear = (order[:, 1] - order[:, 0]) > 2e-6
+                    near_ties += int((~clear).sum())
+                    assert np.array_equal(got[clear], dist.argmin(1)[clear])
+    assert near_ties <= 2
+
+
+def test_hidden_blocks_cover_exactly_their_heads_and_honour_strides(oracle):
+    k, D, H, S, blk_hidden = 4, 64, 8, 6, 256
+    _, l32, _ = oracle.codebook(k)
+    X = RNG.standard_normal((1, H, S, D)).astype(np.float16)
+    c0, s0 = oracle.new_cache(1, H, D, k, D, S)
+    oracle.quantize_kv_hidden(X, k, blk_hidden, l32, c0, s0)
+    # the four heads of a block share their scale, the two blocks do not
+    assert (s0[0, 0:4] == s0[0, 0:1]).all() and (s0[0, 4:8] == s0[0, 4:5]).all()
+    assert (s0[0, 0] != s0[0, 4]).any()
+    # an outlier in head 5 rescales heads 4..7 of that token only
+    Y = X.copy()
+    Y[0, 5, 2, 17] = np.float16(300.0)
+    c1, s1 = oracle.new_cache(1, H, D, k, D, S)
+    oracle.quantize_kv_hidden(Y, k, blk_hidden, l32, c1, s1)
+    changed = (s1 != s0)[0, :, :, 0]
+    want = np.zeros((H, S), bool)
+    want[4:8, 2] = True
+    assert np.array_equal(changed, want)
+    assert s1[0, 4, 2, 0] == np.float16(300.0).view(np.uint16)
+    assert np.array_equal(c1[0, :4], c0[0, :4])
+    # swapping two heads of one block swaps their code rows and nothing else
+    Z = X.copy()
+    Z[0, [1, 2]] = X[0, [2, 1]]
+    c2, s2 = oracle.new_cache(1, H, D, k, D, S)
+    oracle.quantize_kv_hidden(Z, k, blk_hidden, l32, c2, s2)
+    assert np.array_equal(s2, s0)
+    assert np.array_equal(c2[0, 1], c0[0, 2]) and np.array_equal(c2[0, 2], c0[0, 1])
+    assert np.array_equal(c2[0, [0, 3, 4, 5, 6, 7]], c0[0, [0, 3, 4, 5, 6, 7]])
+    # token-major storage presented as a strided view gives the same cache as a contiguous copy
+    tm = np.ascontiguousarray(X.transpose(0, 2, 1, 3))                   # [B,S,H,D]
+    c3, s3 = oracle.new_cache(1, H, D, k, D, S)
+    oracle.quantize_kv_hidden(tm.transpose(0, 2, 1, 3), k, blk_hidden, l32, c3, s3, n_threads=3)
+    assert np.array_equal(c3, c0) and np.array_equal(s3, s0)
+    # round trip through the ordinary dequantizer (block size D, the duplicated scale)
+    back = oracle.dequantize_kv(c0, s0, k, D, l32, 0, S).view(np.float16).astype(np.float64)
+    sc = s0.view(np.float16).astype(np.float64)
+    assert (np.abs(back - X.astype(np.float64)) <= sc * (HALF_GAP[k] + 2.0 ** -10) + 1e-12).all()
+    # bad geometry is refused
+    for bad in (32, 96, 192, 1024):
+        with pytest.raises(ValueError):
+            oracle.quantize_kv_hidden(X, k, bad, l32, c0, s0)
+
+
 # ----------------------------------------------------------------------------- dequantize
 @pytest.mark.parametrize("k", [2, 3, 4])
 def test_dequantize_exhaustive_over_scales(oracle, k):
