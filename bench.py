@@ -402,6 +402,22 @@ def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, time
             # bytes this flow moves: packed cache in, fp16 cache out, fp16 cache back in
             kern[tag + ".paper_flow_decode"] = kernel_entry(packed + 2 * fp16_bytes, t_p, fused_speedup=round(t_p / t_a, 2))
             del k_full, v_full, scores, probs32, probs16, out_pf
+        if (H * D) % 256 == 0:
+            # the paper's own block geometry: 256 consecutive elements of the token's hidden vector,
+            # read from token-major storage (the same bytes viewed as [B,S,H,D]); one scale per head
+            desc_h = nqkv.make_desc(B, H, D, kb, D, S)
+            caches_h = [nqkv.alloc_cache(desc_h, dev) + nqkv.alloc_cache(desc_h, dev) for _ in range(r_cache)]
+
+            def quant_hidden(i):
+                ksrc, vsrc = srcs[i % r_src]
+                kc, ks, vc, vs = caches_h[i % r_cache]
+                nqkv.quantize_kv_hidden(desc_h, lv, ksrc.view(B, S, H, D).transpose(1, 2),
+                                        vsrc.view(B, S, H, D).transpose(1, 2), kc, ks, vc, vs, 0, 256)
+
+            t_h = tk(quant_hidden, n_it, warm=max(2, r_cache))
+            kern[tag.rsplit(".", 1)[0] + ".hidden256.quantize"] = kernel_entry(
+                2 * B * H * S * D * workloads.quantize_bytes_per_element(kb, D), t_h, src_copies=r_src)
+            del caches_h
         per_tok = workloads.decode_bytes_per_token_head(D, kb, bl)
         kern[tag + ".decode_step_fused"] = kernel_entry(dbytes - B * H * per_tok + B * H * (2 * D * 2 + per_tok), t_f,
                                                         splits=nqkv.decode_workspace_bytes(desc, S - 1, 0)[1])

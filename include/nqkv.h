@@ -13,6 +13,8 @@
  *   nqkv_decode_attention  softmax(q K'^T) V' read straight from the packed cache
  *                                                                    (Sec. 3.2 decoding phase)
  *   nqkv_decode_step       append + attention of one decode step in one launch (Sec. 3.2)
+ *   nqkv_quantize_kv_hidden  blocks over the token's hidden vector, token-major source
+ *                                                                    (Fig. 5, Sec. 4.1)
  *
  * General rules
  *   - Every function returns NQKV_OK (0) or a negative NQKV_E* code.  Nothing throws,
@@ -72,6 +74,8 @@ int nqkv_version(void);
  * its tolerance), only which kernel variant or launch shape is used.
  *   knob 0  quantizer: 0 = cell-table code search (default), 1 = plain scan of all thresholds
  *   knob 1  decode attention: workgroups aimed for when num_splits == 0 (0 = default)
+ *   knob 2  decode attention: upper limit of the persistent grid in workgroups (0 = default:
+ *           two per compute unit)
  * Returns NQKV_EINVAL for an unknown knob or value.
  */
 int nqkv_set_tuning(int knob, int value);
@@ -208,6 +212,31 @@ int nqkv_decode_step(const nqkv_cache_desc* desc, const float* levels,
                      int64_t pos, float softmax_scale, void* out,
                      void* workspace, size_t workspace_bytes, int num_splits,
                      void* hip_stream);
+
+/*
+ * Quantization with blocks over the token's hidden vector (Fig. 5: "each token ... divided into
+ * blocks" of a fixed size; Sec. 4.1: block size 256).  The hidden vector of a token is its H
+ * heads of D elements side by side; a block is `block_hidden` consecutive elements of it and so
+ * covers block_hidden / D whole heads.  Each block is quantized exactly like the blocks of
+ * nqkv_quantize_kv (same scale, code and packing rules).  The cache keeps the per-head layout of
+ * the other calls with ONE scale per token-head -- desc->block must equal desc->D -- and the
+ * block's scale is stored once for every head the block covers, so nqkv_dequantize_kv,
+ * nqkv_decode_attention and nqkv_decode_step read the result as it is.
+ *   k_src, v_src  device fp16, element (b,h,t,d) at b*stride_b + h*stride_h + t*stride_t + d;
+ *                 the projection's own token-major layout [B, S, H*D] is stride_h = D,
+ *                 stride_t = H*D (strides in elements, multiples of 8).  v_* may all be NULL.
+ *   block_hidden  128 or 256, a multiple of D that divides H*D; or D itself (then the same
+ *                 as nqkv_quantize_kv_pair)
+ * Errors: as nqkv_quantize_kv, plus NQKV_EINVAL for desc->block != desc->D or a block_hidden
+ * that does not fit the head geometry, NQKV_EUNSUPPORTED for other block sizes or a batch row
+ * whose source or cache extent reaches 2 GiB.
+ */
+int nqkv_quantize_kv_hidden(const nqkv_cache_desc* desc, const float* levels,
+                            const void* k_src, const void* v_src,
+                            int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                            int64_t n_tokens, int64_t dst_token_offset, int block_hidden,
+                            void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                            void* hip_stream);
 
 /*
  * Measurement helper, not part of the method: reads `bytes` (a multiple of 16) of device memory

@@ -286,6 +286,59 @@ int nqkv_quantize_kv(const nqkv_cache_desc* desc, const float* levels,
                                dst_token_offset, codes, scales, nullptr, nullptr, hip_stream);
 }
 
+int nqkv_quantize_kv_hidden(const nqkv_cache_desc* desc, const float* levels,
+                            const void* k_src, const void* v_src,
+                            int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                            int64_t n_tokens, int64_t dst_token_offset, int block_hidden,
+                            void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                            void* hip_stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (desc->block != desc->D) return NQKV_EINVAL;                 // the cache holds one scale per token-head
+  if (block_hidden == desc->D)                                      // a block is one head: the ordinary quantizer
+    return nqkv_quantize_kv_pair(desc, levels, k_src, v_src, stride_b, stride_h, stride_t, n_tokens,
+                                 dst_token_offset, k_codes, k_scales, v_codes, v_scales, hip_stream);
+  if (block_hidden != 128 && block_hidden != 256) return NQKV_EUNSUPPORTED;
+  if (block_hidden % desc->D != 0 || ((int64_t)desc->H * desc->D) % block_hidden != 0) return NQKV_EINVAL;
+  QuantParams p;
+  std::memset(&p, 0, sizeof(p));
+  if ((rc = check_levels(levels, desc->k, &p.levels))) return rc;
+  if ((rc = check_range(desc, dst_token_offset, n_tokens))) return rc;
+  if ((rc = check_strided(desc, stride_b, stride_h, stride_t, n_tokens))) return rc;
+  if (desc->H > 1 && stride_h < desc->D) return NQKV_EINVAL;
+  if (n_tokens == 0) return NQKV_OK;
+  // offsets inside one batch row are formed in 32 bits: source extent, cache extent, chunk count
+  const int64_t src_extent = (((int64_t)desc->H - 1) * stride_h + (n_tokens - 1) * stride_t + desc->D) * 2;
+  const int64_t cache_extent = (int64_t)desc->H * desc->cap_tokens * (desc->D * desc->k / 8);
+  const int64_t chunks = n_tokens * desc->H * (desc->D / 8);
+  if (src_extent >= ((int64_t)1 << 31) || cache_extent >= ((int64_t)1 << 31) || chunks >= ((int64_t)1 << 31) - 8192)
+    return NQKV_EUNSUPPORTED;
+  const bool pair = v_src || v_codes || v_scales;
+  if (!k_src || !k_codes || !k_scales || !aligned16(k_src) || !aligned16(k_codes) || !aligned16(k_scales))
+    return NQKV_EINVAL;
+  if (pair && (!v_src || !v_codes || !v_scales || !aligned16(v_src) || !aligned16(v_codes) || !aligned16(v_scales)))
+    return NQKV_EINVAL;
+  if (desc->B > 65535) return NQKV_EUNSUPPORTED;
+  p.t[0].src = static_cast<const uint16_t*>(k_src);
+  p.t[0].codes = static_cast<uint8_t*>(k_codes);
+  p.t[0].scales = static_cast<uint16_t*>(k_scales);
+  p.t[1].src = static_cast<const uint16_t*>(v_src);
+  p.t[1].codes = static_cast<uint8_t*>(v_codes);
+  p.t[1].scales = static_cast<uint16_t*>(v_scales);
+  p.n_tensors = pair ? 2 : 1;
+  p.B = desc->B;
+  p.H = desc->H;
+  p.stride_b = stride_b;
+  p.stride_h = stride_h;
+  p.stride_t = stride_t;
+  p.n_tokens = n_tokens;
+  p.tok_off = dst_token_offset;
+  p.cap_tokens = desc->cap_tokens;
+  p.impl = (g_quantize_impl == 0 && build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) ? 0 : 1;
+  const hipError_t e = launch_quantize_hidden(p, desc->D, desc->k, block_hidden, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
+}
+
 int nqkv_dequantize_kv(const nqkv_cache_desc* desc, const float* levels,
                        const void* codes, const void* scales,
                        int64_t token_offset, int64_t n_tokens,

@@ -72,6 +72,8 @@ constexpr size_t kTicketBytes = 65536 * sizeof(uint32_t);
 // Each returns hipSuccess or the launch error.  D in {64,128}, k in {2,3,4}, blk in {64,128}.
 hipError_t launch_quantize(const QuantParams& p, int D, int k, int blk, hipStream_t stream);
 hipError_t launch_dequantize(const QuantParams& p, int D, int k, int blk, hipStream_t stream);
+// blocks of blk_hidden (128 or 256) consecutive elements of the token's hidden vector; cache with one scale per token-head
+hipError_t launch_quantize_hidden(const QuantParams& p, int D, int k, int blk_hidden, hipStream_t stream);
 // fuse: also quantize and append the new token (p.k_new / p.v_new) and attend over it
 hipError_t launch_decode_attention(const DecodeParams& p, int D, int k, int blk, bool fuse, hipStream_t stream);
 

@@ -213,6 +213,112 @@ __global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantPara
   }
 }
 
+// Blocks over the token's hidden vector (the paper's own geometry: a block is a fixed number of
+// consecutive elements of the token's H*D hidden vector, 256 in its experiments), for caches
+// that keep one scale per token-head.  grid: x = token tiles, y = b * blocks-per-token + block,
+// z = tensor.  A workgroup takes ONE block position (LPB = 16 or 32 chunk lanes, i.e. 2 or 4
+// heads of 64, 1 or 2 of 128) for a run of consecutive tokens: the half wave (or quarter) that
+// holds a block reads its 256 or 512 contiguous source bytes, and for each head the code rows
+// of consecutive tokens -- adjacent in the cache -- are written by the same workgroup in one
+// run.  The block's max |x| is all-reduced with DPP inside 16-lane rows plus one ds_swizzle
+// across the two rows of a half wave.  The source may be token-major ([B,S,H*D]: stride_h = D)
+// or any other strided view; the block's scale goes to every head it covers.
+template <int KBITS, int D, int LPB, bool FAST>
+__global__ __launch_bounds__(kThreads) void quantize_hidden_kernel(const QuantParams p) {
+  constexpr uint32_t CPH = D / 8;              // chunks per head row
+  constexpr uint32_t HPB = LPB / CPH;          // heads per block
+  constexpr uint32_t TOK = kThreads / LPB;     // tokens per pass of the workgroup
+  constexpr uint32_t kRowBytes = D * KBITS / 8;
+  __shared__ uint2 cells[FAST ? 128 : 1];
+  const uint2 my_cell = FAST ? fetch_cell(p.cell_thr, p.cell_below) : make_uint2(0, 0);
+
+  const uint32_t H = (uint32_t)p.H, n = (uint32_t)p.n_tokens;
+  const uint32_t blocks_per_token = H / HPB;
+  const uint32_t b = blockIdx.y / blocks_per_token, blk = blockIdx.y - b * blocks_per_token;
+  const TensorPtrs tp = p.t[blockIdx.z];
+  const int64_t bh0 = (int64_t)b * H;
+  const __amdgpu_buffer_rsrc_t src_r = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(tp.src) + (int64_t)b * p.stride_b, 0,
+      (int)((((int64_t)H - 1) * p.stride_h + ((int64_t)n - 1) * p.stride_t + D) * 2), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t code_r = __builtin_amdgcn_make_buffer_rsrc(
+      tp.codes + bh0 * p.cap_tokens * kRowBytes, 0, (int)((int64_t)H * p.cap_tokens * kRowBytes), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t scale_r = __builtin_amdgcn_make_buffer_rsrc(
+      tp.scales + bh0 * p.cap_tokens, 0, (int)((int64_t)H * p.cap_tokens * 2), kBufferFlags);
+
+  const uint32_t cib = threadIdx.x % LPB;                    // chunk inside the block
+  const uint32_t head = blk * HPB + cib / CPH, part = cib % CPH;
+  const uint32_t t_first = blockIdx.x * (TOK * kUnroll) + threadIdx.x / LPB;
+  const uint32_t src_lane = head * (uint32_t)(p.stride_h * 2) + part * 16;
+  const uint32_t row_lane = head * (uint32_t)p.cap_tokens + (uint32_t)p.tok_off;   // row inside the batch row's cache
+
+  uint4 w[kUnroll];
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t t = t_first + u * TOK;
+    const uint32_t voff = t < n ? src_lane + t * (uint32_t)(p.stride_t * 2) : kDropStore;   // past the end: reads zeros
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(src_r, voff, 0, 0);
+    w[u] = make_uint4(v.x, v.y, v.z, v.w);
+  }
+
+  if (FAST) {
+    put_cell(my_cell, cells);
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t t = t_first + u * TOK;
+    const bool live = t < n;
+    const uint32_t M = 0x7fff7fffu;
+    const uint32_t a = pk_max_u16(pk_max_u16(w[u].x & M, w[u].y & M), pk_max_u16(w[u].z & M, w[u].w & M));
+    uint32_t s_bits = max(a & 0xffffu, a >> 16);
+    s_bits = max(s_bits, dpp<kQuadXor1>(s_bits));
+    s_bits = max(s_bits, dpp<kQuadXor2>(s_bits));
+    s_bits = max(s_bits, dpp<kRowHalfMirror>(s_bits));
+    s_bits = max(s_bits, dpp<kRowMirror>(s_bits));
+    if (LPB == 32) s_bits = max(s_bits, (uint32_t)__builtin_amdgcn_ds_swizzle((int)s_bits, 0x401F));   // lane ^ 16
+
+    const uint32_t packed = encode_chunk<KBITS, FAST>(w[u], s_bits, p.levels, cells);
+    const uint32_t row = row_lane + t;
+    if (KBITS == 4) {
+      __builtin_amdgcn_raw_buffer_store_b32(packed, code_r, live ? row * kRowBytes + part * 4 : kDropStore, 0, 0);
+    } else if (KBITS == 2) {
+      const uint32_t odd = dpp<kQuadOdd>(packed);
+      const bool writer = live && !(threadIdx.x & 1);
+      __builtin_amdgcn_raw_buffer_store_b32(packed | (odd << 16), code_r, writer ? row * kRowBytes + part * 2 : kDropStore, 0, 0);
+    } else {  // KBITS == 3: four lanes hold 4 x 24 bits = three dwords
+      const uint32_t next = dpp<kQuadNext>(packed);
+      const uint32_t q4 = threadIdx.x & 3;
+      const uint32_t word = (packed >> (8 * q4)) | (next << (24 - 8 * q4));
+      const bool writer = live && q4 != 3;
+      __builtin_amdgcn_raw_buffer_store_b32(word, code_r, writer ? row * kRowBytes + (part >> 2) * 12 + q4 * 4 : kDropStore, 0, 0);
+    }
+    const bool scale_writer = live && part == 0;             // once per covered head
+    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)s_bits, scale_r, scale_writer ? row * 2 : kDropStore, 0, 0);
+  }
+}
+
+template <int KBITS, int D>
+hipError_t launch_hidden_one(const QuantParams& p, int lanes_per_block, hipStream_t stream) {
+  const int heads_per_block = lanes_per_block / (D / 8);
+  const int tokens_per_wg = (kThreads / lanes_per_block) * kUnroll;
+  const dim3 grid((unsigned)((p.n_tokens + tokens_per_wg - 1) / tokens_per_wg),
+                  (unsigned)(p.B * (p.H / heads_per_block)), (unsigned)p.n_tensors);
+  const bool fast = p.impl == 0;
+  if (lanes_per_block == 32) {
+    if (fast) hipLaunchKernelGGL((quantize_hidden_kernel<KBITS, D, 32, true>), grid, dim3(kThreads), 0, stream, p);
+    else      hipLaunchKernelGGL((quantize_hidden_kernel<KBITS, D, 32, false>), grid, dim3(kThreads), 0, stream, p);
+  } else {
+    if constexpr (D == 64) {
+      if (fast) hipLaunchKernelGGL((quantize_hidden_kernel<KBITS, D, 16, true>), grid, dim3(kThreads), 0, stream, p);
+      else      hipLaunchKernelGGL((quantize_hidden_kernel<KBITS, D, 16, false>), grid, dim3(kThreads), 0, stream, p);
+    } else {
+      return hipErrorInvalidValue;      // a 128-element block is one head of 128: the ordinary quantizer
+    }
+  }
+  return hipGetLastError();
+}
+
 template <int KBITS, int D, int BLK>
 hipError_t launch_one(const QuantParams& p, hipStream_t stream) {
   constexpr int CPR = D / 8;
@@ -275,6 +381,25 @@ bool build_cell_table(const float* levels, int k, uint32_t* thr_bits, uint32_t* 
     below[c] = n_below;
   }
   return true;
+}
+
+hipError_t launch_quantize_hidden(const QuantParams& p, int D, int k, int blk_hidden, hipStream_t stream) {
+  const int lpb = blk_hidden / 8;
+  if (lpb != 16 && lpb != 32) return hipErrorInvalidValue;
+  if (D == 64) {
+    switch (k) {
+      case 2: return launch_hidden_one<2, 64>(p, lpb, stream);
+      case 3: return launch_hidden_one<3, 64>(p, lpb, stream);
+      case 4: return launch_hidden_one<4, 64>(p, lpb, stream);
+    }
+  } else if (D == 128) {
+    switch (k) {
+      case 2: return launch_hidden_one<2, 128>(p, lpb, stream);
+      case 3: return launch_hidden_one<3, 128>(p, lpb, stream);
+      case 4: return launch_hidden_one<4, 128>(p, lpb, stream);
+    }
+  }
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_quantize(const QuantParams& p, int D, int k, int blk, hipStream_t stream) {

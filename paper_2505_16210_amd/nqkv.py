@@ -21,7 +21,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_set_tuning", "nqkv_build_codebook",
            "nqkv_quantize_kv", "nqkv_quantize_kv_pair", "nqkv_dequantize_kv",
            "nqkv_decode_workspace_bytes", "nqkv_decode_attention", "nqkv_decode_step",
-           "nqkv_probe_read_stream")
+           "nqkv_probe_read_stream", "nqkv_quantize_kv_hidden")
 
 
 class CacheDesc(ctypes.Structure):
@@ -67,6 +67,8 @@ def _load() -> ctypes.CDLL:
     lib.nqkv_decode_step.restype = i32
     lib.nqkv_decode_step.argtypes = [dp, fp, vp, vp, vp, i64, i64, vp, vp, vp, vp, i64, c.c_float, vp, vp,
                                      c.c_size_t, i32, vp]
+    lib.nqkv_quantize_kv_hidden.restype = i32
+    lib.nqkv_quantize_kv_hidden.argtypes = [dp, fp, vp, vp, i64, i64, i64, i64, i64, i32, vp, vp, vp, vp, vp]
     lib.nqkv_probe_read_stream.restype = i32
     lib.nqkv_probe_read_stream.argtypes = [vp, c.c_size_t, vp, vp]
     return lib
@@ -153,6 +155,22 @@ def quantize_kv_pair(desc: CacheDesc, levels, k_src: torch.Tensor, v_src: torch.
                                    k_src.shape[2], dst_token_offset, _dev_ptr(k_codes), _dev_ptr(k_scales),
                                    _dev_ptr(v_codes), _dev_ptr(v_scales), _stream(stream))
     _check(rc, "nqkv_quantize_kv_pair")
+
+
+def quantize_kv_hidden(desc: CacheDesc, levels, k_src: torch.Tensor, v_src, k_codes, k_scales, v_codes, v_scales,
+                       dst_token_offset: int = 0, block_hidden: int = 256, stream=None) -> None:
+    """nqkv_quantize_kv_hidden: k_src (and v_src or None) fp16 [B,H,n,D] views, e.g. token-major
+    storage x.view(B,n,H,D).transpose(1,2); the cache has one scale per token-head."""
+    lv, lvp = _levels_ptr(levels)
+    assert k_src.dtype == torch.float16 and k_src.dim() == 4 and (k_src.numel() == 0 or k_src.stride(3) == 1)
+    if v_src is not None:
+        assert v_src.dtype == torch.float16 and v_src.shape == k_src.shape and v_src.stride() == k_src.stride()
+    sb, sh, st = _src_strides(k_src)
+    rc = lib.nqkv_quantize_kv_hidden(ctypes.byref(desc), lvp, _dev_ptr(k_src), _dev_ptr(v_src), sb, sh, st,
+                                     k_src.shape[2], dst_token_offset, block_hidden,
+                                     _dev_ptr(k_codes), _dev_ptr(k_scales), _dev_ptr(v_codes), _dev_ptr(v_scales),
+                                     _stream(stream))
+    _check(rc, "nqkv_quantize_kv_hidden")
 
 
 def dequantize_kv(desc: CacheDesc, levels, codes, scales, token_offset: int, n_tokens: int,

@@ -424,3 +424,64 @@ def test_paper_flow_dequantize_then_unfused_attention(nqkv, oracle, k, D, blk):
     # fp16 scores and fp16 probabilities cost the unfused flow precision the fused kernel keeps
     assert attn_err(h2n(out_pf).view(np.float16), ref) <= 2.5 * ATTN_TOL
     assert attn_err(h2n(out_fused).view(np.float16), ref) <= ATTN_TOL
+
+
+# --------------------------------------------------------------------------- blocks over the hidden vector
+@pytest.mark.parametrize("impl", [0, 1])
+@pytest.mark.parametrize("k,D,H,blk_hidden", [(4, 64, 8, 256), (4, 128, 6, 256), (3, 64, 12, 256), (3, 128, 4, 256),
+                                               (2, 64, 8, 256), (2, 128, 2, 256), (4, 64, 6, 128), (3, 64, 2, 128)])
+def test_quantize_hidden_blocks_bit_exact(nqkv, oracle, k, D, H, blk_hidden, impl):
+    """Token-major source ([B,S,H*D], the projection's layout), blocks of 128 / 256 hidden elements
+    spanning heads, K and V in one launch, append offset, a token count that ends mid-tile."""
+    B, n, cap, off = 2, 333, 400, 41
+    lv = nqkv.build_codebook(k)
+    g = torch.Generator(device="cuda").manual_seed(7 * k + D + H)
+    tok_scale = torch.exp(torch.randn(B, n, 1, 1, device="cuda", generator=g))
+    Kt = (torch.randn(B, n, H, D, device="cuda", generator=g) * tok_scale).to(torch.float16)     # token-major storage
+    Vt = torch.randn(B, n, H, D, device="cuda", generator=g).to(torch.float16)
+    Kt[0, 5] = 0.0                                       # an all-zero token: zero blocks
+    Kt[1, 7, 1, 3] = 65504.0                             # the largest fp16 in one head of a block
+    Kv, Vv = Kt.transpose(1, 2), Vt.transpose(1, 2)      # [B,H,n,D] views
+    desc = nqkv.make_desc(B, H, D, k, D, cap)
+    kc, ks = nqkv.alloc_cache(desc)
+    vc, vs = nqkv.alloc_cache(desc)
+    nqkv.set_tuning(0, impl)
+    try:
+        nqkv.quantize_kv_hidden(desc, lv, Kv, Vv, kc, ks, vc, vs, off, blk_hidden)
+        torch.cuda.synchronize()
+    finally:
+        nqkv.set_tuning(0, 0)
+    for src, codes, scales in ((Kv, kc, ks), (Vv, vc, vs)):
+        rc, rs = oracle.new_cache(B, H, D, k, D, cap)
+        oracle.quantize_kv_hidden(h2n(src), k, blk_hidden, lv, rc, rs, dst_off=off, n_threads=8)
+        assert np.array_equal(h2n(scales), rs)
+        assert np.array_equal(h2n(codes), rc)
+
+
+def test_quantize_hidden_head_major_source_single_tensor_then_attention(nqkv, oracle):
+    """The same quantizer on a head-major source, one tensor per call; the cache it writes is an
+    ordinary one-scale-per-head cache: dequantize bit-exact, attention and the fused step (which
+    appends a per-head block) within tolerance against the oracle."""
+    k, D, H, B, S = 4, 64, 8, 2, 600
+    lv = nqkv.build_codebook(k)
+    Kx = rand_kv((B, H, S, D), 91)
+    g = torch.Generator(device="cuda").manual_seed(92)
+    Vx = torch.randn(B, H, S, D, device="cuda", generator=g).to(torch.float16)
+    q = (torch.randn(B, H, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+    desc = nqkv.make_desc(B, H, D, k, D, S + 1)
+    kc, ks = nqkv.alloc_cache(desc)
+    vc, vs = nqkv.alloc_cache(desc)
+    nqkv.quantize_kv_hidden(desc, lv, Kx, None, kc, ks, None, None, 0, 256)
+    nqkv.quantize_kv_hidden(desc, lv, Vx, None, vc, vs, None, None, 0, 256)
+    okc, oks = oracle.new_cache(B, H, D, k, D, S + 1)
+    ovc, ovs = oracle.new_cache(B, H, D, k, D, S + 1)
+    oracle.quantize_kv_hidden(h2n(Kx), k, 256, lv, okc, oks, n_threads=8)
+    oracle.quantize_kv_hidden(h2n(Vx), k, 256, lv, ovc, ovs, n_threads=8)
+    torch.cuda.synchronize()
+    assert np.array_equal(h2n(kc), okc) and np.array_equal(h2n(ks), oks)
+    assert np.array_equal(h2n(vc), ovc) and np.array_equal(h2n(vs), ovs)
+    back = nqkv.dequantize_kv(desc, lv, kc, ks, 0, S)
+    assert np.array_equal(h2n(back), oracle.dequantize_kv(okc, oks, k, D, lv, 0, S, n_threads=8))
+    out = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, 1.0)
+    ref = oracle.decode_attention(h2n(q), okc, oks, ovc, ovs, k, D, lv, S, 1.0, n_threads=8)
+    assert attn_err(h2n(out).view(np.float16), ref) <= ATTN_TOL

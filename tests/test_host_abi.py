@@ -182,6 +182,32 @@ def test_decode_step_argument_errors(nqkv):
     assert call(levels=None) == nqkv.EINVAL
 
 
+def test_quantize_hidden_argument_errors(nqkv):
+    lv, lvp = _levels(nqkv)
+    f = nqkv.lib.nqkv_quantize_kv_hidden
+
+    def call(desc, sb=32 * 100 * 64, sh=64, st=32 * 64, n=100, off=0, blk=256, ks=FAKE, kc=FAKE, ksc=FAKE,
+             vs=None, vc=None, vsc=None, levels=lvp):
+        return f(ctypes.byref(desc), levels, ks, vs, sb, sh, st, n, off, blk, kc, ksc, vc, vsc, None)
+
+    d = nqkv.make_desc(2, 32, 64, 4, 64, 128)                     # one scale per token-head
+    assert call(d, n=0) == nqkv.OK                                 # nothing to do
+    assert call(nqkv.make_desc(2, 32, 128, 4, 64, 128)) == nqkv.EINVAL      # two scales per token-head
+    assert call(d, blk=512) == nqkv.EUNSUPPORTED
+    assert call(d, blk=64, ks=None) == nqkv.EINVAL                 # one head per block: the ordinary call's checks
+    assert call(nqkv.make_desc(2, 3, 64, 4, 64, 128)) == nqkv.EINVAL        # 3 heads of 64: 192 is not a multiple of 256
+    assert call(nqkv.make_desc(2, 3, 128, 4, 128, 128), blk=256) == nqkv.EINVAL
+    assert call(d, sh=32) == nqkv.EINVAL                           # heads would overlap
+    assert call(d, st=2052) == nqkv.EINVAL                         # rows must stay 16-byte aligned
+    assert call(d, ks=None) == nqkv.EINVAL
+    assert call(d, kc=FAKE + 8) == nqkv.EINVAL
+    assert call(d, vs=FAKE) == nqkv.EINVAL                         # half a pair
+    assert call(d, n=100, off=29) == nqkv.EINVAL                   # past the capacity
+    assert call(d, levels=None) == nqkv.EINVAL
+    big = nqkv.make_desc(1, 32, 128, 4, 128, 1 << 20)              # 2 GiB of codes per batch row
+    assert call(big, sh=128, st=32 * 128, sb=0, n=1) == nqkv.EUNSUPPORTED
+
+
 def test_probe_argument_errors(nqkv):
     f = nqkv.lib.nqkv_probe_read_stream
     assert f(None, 1024, FAKE, None) == nqkv.EINVAL
