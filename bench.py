@@ -402,6 +402,22 @@ def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, time
             # bytes this flow moves: packed cache in, fp16 cache out, fp16 cache back in
             kern[tag + ".paper_flow_decode"] = kernel_entry(packed + 2 * fp16_bytes, t_p, fused_speedup=round(t_p / t_a, 2))
             del k_full, v_full, scores, probs32, probs16, out_pf
+        if B >= 8:
+            # a length mix (continuous batching): sequence lengths spread evenly over [S/8, S], in a
+            # seeded random order over the batch
+            lens_host = torch.linspace(S / 8, S, B).round().to(torch.int32)
+            lens_host = lens_host[torch.randperm(B, generator=torch.Generator().manual_seed(0))]
+            lens_dev = lens_host.to(dev)
+
+            def attend_varlen(i):
+                kc, ks, vc, vs = caches[i % r_cache]
+                nqkv.decode_attention_varlen(desc, lv, q, kc, ks, vc, vs, lens_dev, S, 1.0, out=out, workspace=ws)
+
+            t_v = tk(attend_varlen, n_it * 2, warm=max(2, r_cache))
+            vbytes = int(lens_host.sum()) * H * workloads.decode_bytes_per_token_head(D, kb, bl) + B * H * 4 * D \
+                + (2 * B * H * splits * (D + 2) * 4 if splits > 1 else 0)
+            kern[tag + ".decode_attention_varlen"] = kernel_entry(vbytes, t_v, splits=splits,
+                                                                  lengths="%d..%d evenly spread" % (S // 8, S))
         if (H * D) % 256 == 0:
             # the paper's own block geometry: 256 consecutive elements of the token's hidden vector,
             # read from token-major storage (the same bytes viewed as [B,S,H,D]); one scale per head

@@ -13,6 +13,7 @@
  *   nqkv_decode_attention  softmax(q K'^T) V' read straight from the packed cache
  *                                                                    (Sec. 3.2 decoding phase)
  *   nqkv_decode_step       append + attention of one decode step in one launch (Sec. 3.2)
+ *   nqkv_decode_attention_varlen / nqkv_decode_step_varlen  the same for per-sequence lengths
  *   nqkv_quantize_kv_hidden  blocks over the token's hidden vector, token-major source
  *                                                                    (Fig. 5, Sec. 4.1)
  *
@@ -212,6 +213,33 @@ int nqkv_decode_step(const nqkv_cache_desc* desc, const float* levels,
                      int64_t pos, float softmax_scale, void* out,
                      void* workspace, size_t workspace_bytes, int num_splits,
                      void* hip_stream);
+
+/*
+ * The two decode calls for a batch whose sequences differ in length (continuous batching): the
+ * number of cached tokens of sequence b comes from device memory instead of an argument.
+ *   seq_lens  device int32 [B], 4-byte aligned: tokens of sequence b to attend over, 1..max_seq_len
+ *   pos       device int32 [B]: cached rows of sequence b = the row its new token is appended at,
+ *             0..max_pos
+ *   max_seq_len / max_pos  host upper bound of the array's values (<= cap_tokens, < cap_tokens):
+ *             the split count and the workspace are planned for it, as by
+ *             nqkv_decode_workspace_bytes(desc, max_seq_len, ...) / (desc, max(max_pos, 1), ...)
+ * The arrays are read by the kernel only; values outside the stated range are clamped into it
+ * (no out-of-bounds access), the result for such a sequence is then unspecified.  Everything
+ * else is as for nqkv_decode_attention / nqkv_decode_step, which these equal when all entries
+ * are the same.  Errors: as those, plus NQKV_EINVAL for a null / misaligned array, and
+ * NQKV_EUNSUPPORTED from nqkv_decode_step_varlen for a table the in-kernel quantizer cannot take.
+ */
+int nqkv_decode_attention_varlen(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                                 const void* k_codes, const void* k_scales,
+                                 const void* v_codes, const void* v_scales,
+                                 const int32_t* seq_lens, int64_t max_seq_len, float softmax_scale, void* out,
+                                 void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream);
+int nqkv_decode_step_varlen(const nqkv_cache_desc* desc, const float* levels,
+                            const void* q, const void* k_new, const void* v_new,
+                            int64_t new_stride_b, int64_t new_stride_h,
+                            void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                            const int32_t* pos, int64_t max_pos, float softmax_scale, void* out,
+                            void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream);
 
 /*
  * Quantization with blocks over the token's hidden vector (Fig. 5: "each token ... divided into

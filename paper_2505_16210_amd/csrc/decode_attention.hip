@@ -46,6 +46,12 @@ namespace {
 
 constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
+// Running maximum of a wave that has seen no token yet: a finite number below every real score
+// instead of -inf, so that an item without any token (a split beyond the end of a short
+// sequence) comes out as (m, l = 0, o = 0) -- exp2(m - m) = 1 times zero sums -- where -inf
+// would make exp2(-inf - -inf) = NaN.  Real scores lift the maximum on their first trip and
+// exp2(kNoScore - score) is exactly 0.
+constexpr float kNoScore = -1.0e30f;
 constexpr int kRounds = 4;               // wave loads of K (and of V) in flight per trip
 constexpr int kLutWords = 16384;         // 64 KiB: 256 rows of 256 bytes (k = 4, 2); k = 3 uses 2048
 
@@ -328,11 +334,14 @@ __device__ __forceinline__ void reduce_groups(const float (&acc)[32], uint32_t l
 // SPLIT: sequences are cut into p.splits > 1 items whose partial results are combined by the
 // workgroup that finishes last; without it (p.splits == 1) that code and the item -> (sequence,
 // split) division are compiled out.
+// VARLEN: every sequence of the batch has its own number of cached tokens, read from device
+// memory (p.seq_lens[b], clamped to [0, p.max_len]); the split geometry is laid out for
+// p.max_len and each item keeps the part of its range that lies inside its sequence.
 // FUSE: the whole decode step of the paper in one launch -- items cover the tokens already
 // cached, rows [0, pos); the last wave of each sequence's last item quantizes the new token's
 // key and value rows (same code search as the quantizer), stores their codes and scales at row
 // pos, and adds the token to its softmax straight from registers.
-template <int KBITS, int D, int BLK, bool FUSE, bool SPLIT>
+template <int KBITS, int D, int BLK, bool FUSE, bool SPLIT, bool VARLEN>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) void decode_kernel(const DecodeParams p) {   // 128 VGPRs: two workgroups per CU
   constexpr int LPT = D / 32;             // lanes per token
   constexpr int TPR = 64 / LPT;           // tokens per wave load
@@ -368,6 +377,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   const uint32_t scale_voff = g * kScaleRowBytes + ((j * 32) / BLK) * 2;
   uint32_t bh = 0, sp = 0;
   int32_t n_tok = 0, base = 0;      // tokens in the item; this wave's current trip start (item-relative)
+  int64_t pos = 0;                  // FUSE and VARLEN: the sequence's own row for the new token (else p.pos)
   __amdgpu_buffer_rsrc_t kc_r, vc_r, ks_r, vs_r;
   __amdgpu_buffer_rsrc_t kn_r, vn_r;      // FUSE: the new token's rows, empty for waves that do not take it
   uint32_t newx[4] = {0, 0, 0, 0};        // FUSE: this lane's 16-byte chunk of those rows
@@ -380,6 +390,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
     }
     const int64_t t0 = (int64_t)sp * p.split_base + min((int32_t)sp, p.split_rem);
     n_tok = p.split_base + ((int32_t)sp < p.split_rem ? 1 : 0);
+    uint32_t b = 0, h = 0;
+    if (VARLEN) {
+      b = bh / (uint32_t)p.H; h = bh - b * (uint32_t)p.H;
+      const int32_t len = min(max(p.seq_lens[b], 0), p.max_len);     // whatever the array holds, stay inside the cache
+      n_tok = min(n_tok, max(len - (int32_t)t0, 0));
+      pos = len;
+    }
     base = (int32_t)wave * CHUNK;
     const int64_t row0 = (int64_t)bh * p.cap_tokens + t0;
     kc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.k_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
@@ -387,7 +404,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
     ks_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.k_scales) + row0 * NB, 0, n_tok * (int)kScaleRowBytes, kBufferFlags);
     vs_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.v_scales) + row0 * NB, 0, n_tok * (int)kScaleRowBytes, kBufferFlags);
     if (FUSE) {
-      const uint32_t b = bh / (uint32_t)p.H, h = bh - b * (uint32_t)p.H;
+      if (!VARLEN) { b = bh / (uint32_t)p.H; h = bh - b * (uint32_t)p.H; }
       const int64_t off = (int64_t)b * p.new_stride_b + (int64_t)h * p.new_stride_h;
       const int bytes = ((!SPLIT || sp == (uint32_t)p.splits - 1u) && wave == kWaves - 1) ? D * 2 : 0;
       kn_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.k_new) + off, 0, bytes, kBufferFlags);
@@ -465,7 +482,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
     float acc[32];
 #pragma unroll
     for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
-    float m_run = -INFINITY;   // wave-uniform, log2 domain
+    float m_run = kNoScore;    // wave-uniform, log2 domain
     float l_run = 0.0f;        // per lane; every lane of a token group adds the same p
 
     if (FUSE && (!SPLIT || sp == (uint32_t)p.splits - 1u) && wave == kWaves - 1) {
@@ -577,6 +594,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
     // ---- this item is streamed; remember where its result goes, then start the next item's
     // first K loads so that they fly during the merge
     const uint32_t cur_bh = bh, cur_sp = sp;
+    const int64_t cur_pos = pos;
     const uint32_t next_item = item + gridDim.x;
     const bool more = next_item < (uint32_t)p.n_items;
     if (more) {
@@ -612,7 +630,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
       // Append: the LDS images of the new token's rows go to cache row pos.  Done here rather
       // than where they are produced because stores share the loads' in-order memory counter:
       // issued ahead of the streaming loop, their acknowledgements would hold up its first trip.
-      const int64_t row = (int64_t)cur_bh * p.cap_tokens + p.pos;
+      const int64_t row = (int64_t)cur_bh * p.cap_tokens + (VARLEN ? cur_pos : p.pos);
       if (tid < 2u * ROW) {
         const uint32_t t = tid / ROW, w = tid % ROW;
         uint32_t* dst = reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(t ? p.v_codes : p.k_codes)) + row * ROW + w;
@@ -675,7 +693,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
 #pragma unroll
           for (uint32_t u = 0; u < U; ++u) {
             const float m_s = (s0 + u * G < (uint32_t)p.splits) ? ms[u] : -INFINITY;   // a clamped duplicate weighs 0
-            const float m_new = fmaxf(mm, m_s);                 // finite from the first fold on
+            const float m_new = fmaxf(mm, m_s);                 // finite: every stored m is (kNoScore at least)
             const float f_old = __builtin_amdgcn_exp2f(mm - m_new), f_s = __builtin_amdgcn_exp2f(m_s - m_new);
             ll = ll * f_old + ls[u] * f_s;
             oo = oo * f_old + os[u] * f_s;
@@ -708,16 +726,21 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   }
 }
 
-template <int KBITS, int D, int BLK>
-hipError_t launch_one(const DecodeParams& p, bool fuse, hipStream_t stream) {
+template <int KBITS, int D, int BLK, bool VARLEN>
+hipError_t launch_var(const DecodeParams& p, bool fuse, hipStream_t stream) {
   const int wgs = p.n_items < p.max_workgroups ? p.n_items : p.max_workgroups;
   const dim3 grid((unsigned)wgs), block(kThreads);
   const bool split = p.splits > 1;
-  if (fuse && split)       hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, true, true>), grid, block, 0, stream, p);
-  else if (fuse)           hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, true, false>), grid, block, 0, stream, p);
-  else if (split)          hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, false, true>), grid, block, 0, stream, p);
-  else                     hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, false, false>), grid, block, 0, stream, p);
+  if (fuse && split)       hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, true, true, VARLEN>), grid, block, 0, stream, p);
+  else if (fuse)           hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, true, false, VARLEN>), grid, block, 0, stream, p);
+  else if (split)          hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, false, true, VARLEN>), grid, block, 0, stream, p);
+  else                     hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, false, false, VARLEN>), grid, block, 0, stream, p);
   return hipGetLastError();
+}
+
+template <int KBITS, int D, int BLK>
+hipError_t launch_one(const DecodeParams& p, bool fuse, hipStream_t stream) {
+  return p.seq_lens ? launch_var<KBITS, D, BLK, true>(p, fuse, stream) : launch_var<KBITS, D, BLK, false>(p, fuse, stream);
 }
 
 template <int KBITS>

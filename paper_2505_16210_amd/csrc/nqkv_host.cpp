@@ -384,6 +384,7 @@ int nqkv_decode_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, in
 // Shared by nqkv_decode_attention (k_new == nullptr) and nqkv_decode_step.
 static int decode_impl(const nqkv_cache_desc* desc, const float* levels, const void* q,
                        const void* k_new, const void* v_new, int64_t new_stride_b, int64_t new_stride_h,
+                       const int32_t* lens,
                        const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
                        int64_t seq_len, float softmax_scale, void* out,
                        void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
@@ -423,11 +424,12 @@ static int decode_impl(const nqkv_cache_desc* desc, const float* levels, const v
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (fuse && !build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) {
     // a table the in-kernel code search cannot take: append with the quantizer, then attend
+    if (lens) return NQKV_EUNSUPPORTED;        // (the quantizer appends at one row for the whole batch)
     rc = nqkv_quantize_kv_pair(desc, levels, k_new, v_new, new_stride_b, new_stride_h, desc->D, 1, seq_len - 1,
                                const_cast<void*>(k_codes), const_cast<void*>(k_scales),
                                const_cast<void*>(v_codes), const_cast<void*>(v_scales), hip_stream);
     if (rc) return rc;
-    return decode_impl(desc, levels, q, nullptr, nullptr, 0, 0, k_codes, k_scales, v_codes, v_scales, seq_len,
+    return decode_impl(desc, levels, q, nullptr, nullptr, 0, 0, nullptr, k_codes, k_scales, v_codes, v_scales, seq_len,
                        softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
   }
   p.q = static_cast<const uint16_t*>(q);
@@ -454,6 +456,8 @@ static int decode_impl(const nqkv_cache_desc* desc, const float* levels, const v
   p.new_stride_h = new_stride_h;
   p.pos = seq_len - 1;
   p.H = desc->H;
+  p.seq_lens = lens;                                    // fused: lens[b] = cached rows = the new token's row
+  p.max_len = (int)n_cached;
   const hipError_t e = launch_decode_attention(p, desc->D, desc->k, desc->block, fuse, stream);
   return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
 }
@@ -465,7 +469,7 @@ int nqkv_decode_attention(const nqkv_cache_desc* desc, const float* levels,
                           int64_t seq_len, float softmax_scale, void* out,
                           void* workspace, size_t workspace_bytes, int num_splits,
                           void* hip_stream) {
-  return decode_impl(desc, levels, q, nullptr, nullptr, 0, 0, k_codes, k_scales, v_codes, v_scales, seq_len,
+  return decode_impl(desc, levels, q, nullptr, nullptr, 0, 0, nullptr, k_codes, k_scales, v_codes, v_scales, seq_len,
                      softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
 }
 
@@ -477,8 +481,31 @@ int nqkv_decode_step(const nqkv_cache_desc* desc, const float* levels,
                      void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
   if (!k_new) return NQKV_EINVAL;
   if (pos < 0 || (desc && pos >= desc->cap_tokens)) return NQKV_EINVAL;
-  return decode_impl(desc, levels, q, k_new, v_new, new_stride_b, new_stride_h, k_codes, k_scales, v_codes,
+  return decode_impl(desc, levels, q, k_new, v_new, new_stride_b, new_stride_h, nullptr, k_codes, k_scales, v_codes,
                      v_scales, pos + 1, softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
+}
+
+int nqkv_decode_attention_varlen(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                                 const void* k_codes, const void* k_scales,
+                                 const void* v_codes, const void* v_scales,
+                                 const int32_t* seq_lens, int64_t max_seq_len, float softmax_scale, void* out,
+                                 void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
+  if (!seq_lens || (reinterpret_cast<uintptr_t>(seq_lens) & 3u)) return NQKV_EINVAL;
+  return decode_impl(desc, levels, q, nullptr, nullptr, 0, 0, seq_lens, k_codes, k_scales, v_codes, v_scales,
+                     max_seq_len, softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
+}
+
+int nqkv_decode_step_varlen(const nqkv_cache_desc* desc, const float* levels,
+                            const void* q, const void* k_new, const void* v_new,
+                            int64_t new_stride_b, int64_t new_stride_h,
+                            void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                            const int32_t* pos, int64_t max_pos, float softmax_scale, void* out,
+                            void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
+  if (!k_new) return NQKV_EINVAL;
+  if (!pos || (reinterpret_cast<uintptr_t>(pos) & 3u)) return NQKV_EINVAL;
+  if (max_pos < 0 || (desc && max_pos >= desc->cap_tokens)) return NQKV_EINVAL;
+  return decode_impl(desc, levels, q, k_new, v_new, new_stride_b, new_stride_h, pos, k_codes, k_scales, v_codes,
+                     v_scales, max_pos + 1, softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
 }
 
 int nqkv_probe_read_stream(const void* src, size_t bytes, void* checksums, void* hip_stream) {

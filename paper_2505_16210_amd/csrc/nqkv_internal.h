@@ -61,6 +61,10 @@ struct DecodeParams {
   int64_t new_stride_b, new_stride_h;
   int64_t pos;
   int H;
+  // per-sequence lengths (NULL: every sequence has the same): cached tokens of sequence b, and
+  // the length the split geometry is laid out for
+  const int32_t* seq_lens;
+  int max_len;
   uint32_t cell_thr[kQuantCells];
   uint32_t cell_below[kQuantCells];
 };

@@ -21,7 +21,8 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_set_tuning", "nqkv_build_codebook",
            "nqkv_quantize_kv", "nqkv_quantize_kv_pair", "nqkv_dequantize_kv",
            "nqkv_decode_workspace_bytes", "nqkv_decode_attention", "nqkv_decode_step",
-           "nqkv_probe_read_stream", "nqkv_quantize_kv_hidden")
+           "nqkv_probe_read_stream", "nqkv_quantize_kv_hidden",
+           "nqkv_decode_attention_varlen", "nqkv_decode_step_varlen")
 
 
 class CacheDesc(ctypes.Structure):
@@ -67,6 +68,12 @@ def _load() -> ctypes.CDLL:
     lib.nqkv_decode_step.restype = i32
     lib.nqkv_decode_step.argtypes = [dp, fp, vp, vp, vp, i64, i64, vp, vp, vp, vp, i64, c.c_float, vp, vp,
                                      c.c_size_t, i32, vp]
+    lib.nqkv_decode_attention_varlen.restype = i32
+    lib.nqkv_decode_attention_varlen.argtypes = [dp, fp, vp, vp, vp, vp, vp, vp, i64, c.c_float, vp, vp,
+                                                 c.c_size_t, i32, vp]
+    lib.nqkv_decode_step_varlen.restype = i32
+    lib.nqkv_decode_step_varlen.argtypes = [dp, fp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp, i64, c.c_float, vp, vp,
+                                            c.c_size_t, i32, vp]
     lib.nqkv_quantize_kv_hidden.restype = i32
     lib.nqkv_quantize_kv_hidden.argtypes = [dp, fp, vp, vp, i64, i64, i64, i64, i64, i32, vp, vp, vp, vp, vp]
     lib.nqkv_probe_read_stream.restype = i32
@@ -243,6 +250,64 @@ def decode_step(desc: CacheDesc, levels, q: torch.Tensor, k_new: torch.Tensor, v
                               _dev_ptr(v_codes), _dev_ptr(v_scales), pos, float(softmax_scale), _dev_ptr(out),
                               _dev_ptr(workspace), ws_bytes, num_splits, _stream(stream))
     _check(rc, "nqkv_decode_step")
+    return out
+
+
+def _lens_arg(lens: torch.Tensor, B: int):
+    assert lens.dtype == torch.int32 and lens.is_contiguous() and lens.numel() == B and lens.is_cuda
+    return _dev_ptr(lens)
+
+
+def decode_attention_varlen(desc: CacheDesc, levels, q: torch.Tensor, k_codes, k_scales, v_codes, v_scales,
+                            seq_lens: torch.Tensor, max_seq_len: int, softmax_scale: float = 1.0,
+                            out: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
+                            num_splits: int = 0, stream=None) -> torch.Tensor:
+    """nqkv_decode_attention_varlen: seq_lens int32 [B] on the device, max_seq_len its host upper bound."""
+    lv, lvp = _levels_ptr(levels)
+    assert q.dtype == torch.float16 and q.is_contiguous()
+    if out is None:
+        out = torch.empty_like(q)
+    ws_bytes = 0
+    if workspace is None:
+        need, _ = decode_workspace_bytes(desc, max_seq_len, num_splits)
+        if need:
+            workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)
+    if workspace is not None:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    rc = lib.nqkv_decode_attention_varlen(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_codes), _dev_ptr(k_scales),
+                                          _dev_ptr(v_codes), _dev_ptr(v_scales), _lens_arg(seq_lens, desc.B),
+                                          max_seq_len, float(softmax_scale), _dev_ptr(out), _dev_ptr(workspace),
+                                          ws_bytes, num_splits, _stream(stream))
+    _check(rc, "nqkv_decode_attention_varlen")
+    return out
+
+
+def decode_step_varlen(desc: CacheDesc, levels, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                       k_codes, k_scales, v_codes, v_scales, pos: torch.Tensor, max_pos: int,
+                       softmax_scale: float = 1.0, out: torch.Tensor | None = None,
+                       workspace: torch.Tensor | None = None, num_splits: int = 0, stream=None) -> torch.Tensor:
+    """nqkv_decode_step_varlen: pos int32 [B] on the device (cached rows of each sequence), max_pos its
+    host upper bound; the caches gain row pos[b] of every sequence b."""
+    lv, lvp = _levels_ptr(levels)
+    assert q.dtype == torch.float16 and q.is_contiguous()
+    if k_new.dim() == 4:
+        k_new, v_new = k_new[:, :, 0], v_new[:, :, 0]
+    assert k_new.dtype == torch.float16 and k_new.stride(2) == 1 and k_new.stride() == v_new.stride()
+    if out is None:
+        out = torch.empty_like(q)
+    ws_bytes = 0
+    if workspace is None:
+        need, _ = decode_workspace_bytes(desc, max(max_pos, 1), num_splits)
+        if need:
+            workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)
+    if workspace is not None:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    rc = lib.nqkv_decode_step_varlen(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_new), _dev_ptr(v_new),
+                                     k_new.stride(0), k_new.stride(1), _dev_ptr(k_codes), _dev_ptr(k_scales),
+                                     _dev_ptr(v_codes), _dev_ptr(v_scales), _lens_arg(pos, desc.B), max_pos,
+                                     float(softmax_scale), _dev_ptr(out), _dev_ptr(workspace), ws_bytes, num_splits,
+                                     _stream(stream))
+    _check(rc, "nqkv_decode_step_varlen")
     return out
 
 

@@ -485,3 +485,84 @@ def test_quantize_hidden_head_major_source_single_tensor_then_attention(nqkv, or
     out = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, 1.0)
     ref = oracle.decode_attention(h2n(q), okc, oks, ovc, ovs, k, D, lv, S, 1.0, n_threads=8)
     assert attn_err(h2n(out).view(np.float16), ref) <= ATTN_TOL
+
+
+# --------------------------------------------------------------------------- per-sequence lengths
+@pytest.mark.parametrize("k,D,blk", [(4, 64, 64), (4, 128, 64), (3, 128, 128), (2, 64, 64)])
+def test_decode_varlen_matches_oracle_per_sequence(nqkv, oracle, k, D, blk):
+    """A batch whose sequences have their own lengths (1 token, a ragged tail, less than one
+    split's share, the full cache): every sequence must equal the oracle run on it alone, for
+    every split count, and the fixed-length call when all lengths agree."""
+    B, H, S, cap = 5, 3, 1500, 1536
+    lv, desc, q, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, S, cap, seed=17 * k + D + blk)
+    kc[:, :, S:] = 0xFF                                          # rows beyond the longest sequence: poison
+    ks[:, :, S:] = 60000.0
+    vs[:, :, S:] = 60000.0
+    hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+    lens = [1, 65, 700, 1237, S]
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    refs = [oracle.decode_attention(*[a[b:b + 1] for a in hk], k, blk, lv, lens[b], 0.9, n_threads=4) for b in range(B)]
+    ref = np.concatenate(refs, 0)
+    for ns in (0, 1, 2, 7, 64):
+        out = nqkv.decode_attention_varlen(desc, lv, q, kc, ks, vc, vs, lens_dev, S, 0.9, num_splits=ns)
+        torch.cuda.synchronize()
+        err = attn_err(h2n(out).view(np.float16), ref)
+        assert err <= ATTN_TOL, (k, D, blk, ns, err)
+    same = torch.full((B,), 1000, dtype=torch.int32, device="cuda")
+    for ns in (1, 5):
+        a = nqkv.decode_attention_varlen(desc, lv, q, kc, ks, vc, vs, same, 1000, 0.9, num_splits=ns)
+        b_ = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, 1000, 0.9, num_splits=ns)
+        assert torch.equal(a, b_)
+    # values outside [.., max_seq_len] are clamped: no fault, sequences inside the range unaffected
+    wild = torch.tensor([1, 65, -5, 10 ** 9, S], dtype=torch.int32, device="cuda")
+    out = nqkv.decode_attention_varlen(desc, lv, q, kc, ks, vc, vs, wild, S, 0.9)
+    torch.cuda.synchronize()
+    o = h2n(out).view(np.float16)
+    for b in (0, 1, 4):
+        assert attn_err(o[b:b + 1], ref[b:b + 1]) <= ATTN_TOL
+
+
+@pytest.mark.parametrize("k,D,blk", [(4, 64, 64), (3, 128, 64), (2, 128, 128)])
+def test_decode_step_varlen_appends_at_each_sequences_own_row(nqkv, oracle, k, D, blk):
+    """Continuous batching: every sequence appends its new token at its own row and attends over
+    its own history.  Cache rows bit-exact (and nothing else touched), outputs within tolerance,
+    for several steps in a row and several split counts."""
+    B, H, cap = 4, 3, 1400
+    lv = nqkv.build_codebook(k)
+    g = torch.Generator(device="cuda").manual_seed(5 * k + D)
+    Kx = rand_kv((B, H, cap, D), 123 + k)
+    Vx = torch.randn(B, H, cap, D, device="cuda", generator=g).to(torch.float16)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    kc, ks = nqkv.alloc_cache(desc)
+    vc, vs = nqkv.alloc_cache(desc)
+    start = [0, 63, 640, 1290]
+    okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
+    ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
+    Kh, Vh = h2n(Kx), h2n(Vx)
+    for b in range(B):
+        if start[b]:
+            nqkv.quantize_kv_pair(nqkv.make_desc(1, H, D, k, blk, cap), lv, Kx[b:b + 1, :, :start[b]],
+                                  Vx[b:b + 1, :, :start[b]], kc[b:b + 1], ks[b:b + 1], vc[b:b + 1], vs[b:b + 1], 0)
+            oracle.quantize_kv(Kh[b:b + 1, :, :start[b]], k, blk, lv, okc[b:b + 1], oks[b:b + 1])
+            oracle.quantize_kv(Vh[b:b + 1, :, :start[b]], k, blk, lv, ovc[b:b + 1], ovs[b:b + 1])
+    for step, ns in enumerate((0, 1, 3, 16, 0)):
+        pos = [s0 + step for s0 in start]
+        if ns > max(max(pos), 1):
+            continue
+        pos_dev = torch.tensor(pos, dtype=torch.int32, device="cuda")
+        q = (torch.randn(B, H, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+        kn = torch.stack([Kx[b, :, pos[b]] for b in range(B)])          # [B,H,D]
+        vn = torch.stack([Vx[b, :, pos[b]] for b in range(B)])
+        out = nqkv.decode_step_varlen(desc, lv, q, kn, vn, kc, ks, vc, vs, pos_dev, max(pos), 1.0, num_splits=ns)
+        torch.cuda.synchronize()
+        refs = []
+        for b in range(B):
+            sl = slice(b, b + 1)
+            oracle.quantize_kv(Kh[sl, :, pos[b]:pos[b] + 1], k, blk, lv, okc[sl], oks[sl], dst_off=pos[b])
+            oracle.quantize_kv(Vh[sl, :, pos[b]:pos[b] + 1], k, blk, lv, ovc[sl], ovs[sl], dst_off=pos[b])
+            refs.append(oracle.decode_attention(h2n(q)[sl], okc[sl], oks[sl], ovc[sl], ovs[sl], k, blk, lv,
+                                                pos[b] + 1, 1.0, n_threads=4))
+        assert np.array_equal(h2n(kc), okc) and np.array_equal(h2n(ks), oks), (step, ns)
+        assert np.array_equal(h2n(vc), ovc) and np.array_equal(h2n(vs), ovs), (step, ns)
+        err = attn_err(h2n(out).view(np.float16), np.concatenate(refs, 0))
+        assert err <= ATTN_TOL, (step, ns, err)

@@ -182,6 +182,32 @@ def test_decode_step_argument_errors(nqkv):
     assert call(levels=None) == nqkv.EINVAL
 
 
+def test_varlen_argument_errors(nqkv):
+    lv, lvp = _levels(nqkv)
+    d = nqkv.make_desc(4, 8, 128, 4, 64, 4096)
+    fa, fs = nqkv.lib.nqkv_decode_attention_varlen, nqkv.lib.nqkv_decode_step_varlen
+
+    def att(lens=FAKE, mx=4096, q=FAKE, ws=FAKE, ns=0, ws_bytes=1 << 30):
+        return fa(ctypes.byref(d), lvp, q, FAKE, FAKE, FAKE, FAKE, lens, mx, 1.0, FAKE, ws, ws_bytes, ns, None)
+
+    def step(pos=FAKE, mx=4095, kn=FAKE, ns=0):
+        return fs(ctypes.byref(d), lvp, FAKE, kn, FAKE, 1024, 128, FAKE, FAKE, FAKE, FAKE, pos, mx, 1.0, FAKE, FAKE,
+                  1 << 30, ns, None)
+
+    assert att(lens=None) == nqkv.EINVAL
+    assert att(lens=FAKE + 2) == nqkv.EINVAL                     # int32 alignment
+    assert att(mx=0) == nqkv.EINVAL
+    assert att(mx=4097) == nqkv.EINVAL                           # bound above the capacity
+    assert att(q=None) == nqkv.EINVAL
+    assert att(ns=4, ws=None) == nqkv.EINVAL
+    assert att(ns=4, ws_bytes=64) == nqkv.EWORKSPACE
+    assert step(pos=None) == nqkv.EINVAL
+    assert step(mx=4096) == nqkv.EINVAL                          # no row left for the new token
+    assert step(mx=-1) == nqkv.EINVAL
+    assert step(kn=None) == nqkv.EINVAL
+    assert step(mx=0, ns=2) == nqkv.EINVAL
+
+
 def test_quantize_hidden_argument_errors(nqkv):
     lv, lvp = _levels(nqkv)
     f = nqkv.lib.nqkv_quantize_kv_hidden
