@@ -318,7 +318,7 @@ int nqkv_quantize_kv_hidden(const nqkv_cache_desc* desc, const float* levels,
     return NQKV_EINVAL;
   if (pair && (!v_src || !v_codes || !v_scales || !aligned16(v_src) || !aligned16(v_codes) || !aligned16(v_scales)))
     return NQKV_EINVAL;
-  if (desc->B > 65535) return NQKV_EUNSUPPORTED;
+  if ((n_tokens + 31) / 32 > 65535 || (int64_t)desc->B * 2 > 65535) return NQKV_EUNSUPPORTED;   // 16-bit grid dimensions
   p.t[0].src = static_cast<const uint16_t*>(k_src);
   p.t[0].codes = static_cast<uint8_t*>(k_codes);
   p.t[0].scales = static_cast<uint16_t*>(k_scales);

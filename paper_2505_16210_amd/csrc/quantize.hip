@@ -215,8 +215,8 @@ __global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantPara
 
 // Blocks over the token's hidden vector (the paper's own geometry: a block is a fixed number of
 // consecutive elements of the token's H*D hidden vector, 256 in its experiments), for caches
-// that keep one scale per token-head.  grid: x = token tiles, y = b * blocks-per-token + block,
-// z = tensor.  A workgroup takes ONE block position (LPB = 16 or 32 chunk lanes, i.e. 2 or 4
+// that keep one scale per token-head.  grid: x = block position in the token, y = token tiles,
+// z = b + B * tensor.  A workgroup takes ONE block position (LPB = 16 or 32 chunk lanes, i.e. 2 or 4
 // heads of 64, 1 or 2 of 128) for a run of consecutive tokens: the half wave (or quarter) that
 // holds a block reads its 256 or 512 contiguous source bytes, and for each head the code rows
 // of consecutive tokens -- adjacent in the cache -- are written by the same workgroup in one
@@ -233,9 +233,10 @@ __global__ __launch_bounds__(kThreads) void quantize_hidden_kernel(const QuantPa
   const uint2 my_cell = FAST ? fetch_cell(p.cell_thr, p.cell_below) : make_uint2(0, 0);
 
   const uint32_t H = (uint32_t)p.H, n = (uint32_t)p.n_tokens;
-  const uint32_t blocks_per_token = H / HPB;
-  const uint32_t b = blockIdx.y / blocks_per_token, blk = blockIdx.y - b * blocks_per_token;
-  const TensorPtrs tp = p.t[blockIdx.z];
+  const uint32_t blk = blockIdx.x;
+  const uint32_t tensor = blockIdx.z >= (unsigned)p.B ? 1u : 0u;
+  const uint32_t b = blockIdx.z - (tensor ? (uint32_t)p.B : 0u);
+  const TensorPtrs tp = p.t[tensor];
   const int64_t bh0 = (int64_t)b * H;
   const __amdgpu_buffer_rsrc_t src_r = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint16_t*>(tp.src) + (int64_t)b * p.stride_b, 0,
@@ -247,9 +248,8 @@ __global__ __launch_bounds__(kThreads) void quantize_hidden_kernel(const QuantPa
 
   const uint32_t cib = threadIdx.x % LPB;                    // chunk inside the block
   const uint32_t head = blk * HPB + cib / CPH, part = cib % CPH;
-  const uint32_t t_first = blockIdx.x * (TOK * kUnroll) + threadIdx.x / LPB;
+  const uint32_t t_first = blockIdx.y * (TOK * kUnroll) + threadIdx.x / LPB;
   const uint32_t src_lane = head * (uint32_t)(p.stride_h * 2) + part * 16;
-  const uint32_t row_lane = head * (uint32_t)p.cap_tokens + (uint32_t)p.tok_off;   // row inside the batch row's cache
 
   uint4 w[kUnroll];
 #pragma unroll
@@ -265,10 +265,18 @@ __global__ __launch_bounds__(kThreads) void quantize_hidden_kernel(const QuantPa
     __syncthreads();
   }
 
+  // Codes and scales are assembled in LDS as the tile's image of the cache -- per covered head,
+  // the rows of the tile's consecutive tokens, which are contiguous in the cache -- and leave
+  // from there as fully coalesced dword stores.  (Stored straight from the lanes that produce
+  // them, every store instruction scatters eight pieces of 32-64 bytes.)
+  constexpr uint32_t TILE_TOK = TOK * kUnroll;                // tokens per workgroup
+  constexpr uint32_t kHeadDwords = TILE_TOK * kRowBytes / 4;   // one head's rows of the tile
+  constexpr uint32_t kHeadPitch = kHeadDwords + 8;             // LDS pitch: heads land on different banks
+  __shared__ uint32_t stage[HPB * kHeadPitch];
+  __shared__ uint16_t stage_scale[HPB * TILE_TOK];
+  const uint32_t h_local = cib / CPH, t_local0 = threadIdx.x / LPB;
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
-    const uint32_t t = t_first + u * TOK;
-    const bool live = t < n;
     const uint32_t M = 0x7fff7fffu;
     const uint32_t a = pk_max_u16(pk_max_u16(w[u].x & M, w[u].y & M), pk_max_u16(w[u].z & M, w[u].w & M));
     uint32_t s_bits = max(a & 0xffffu, a >> 16);
@@ -279,22 +287,38 @@ __global__ __launch_bounds__(kThreads) void quantize_hidden_kernel(const QuantPa
     if (LPB == 32) s_bits = max(s_bits, (uint32_t)__builtin_amdgcn_ds_swizzle((int)s_bits, 0x401F));   // lane ^ 16
 
     const uint32_t packed = encode_chunk<KBITS, FAST>(w[u], s_bits, p.levels, cells);
-    const uint32_t row = row_lane + t;
+    const uint32_t t_local = t_local0 + u * TOK;
+    uint32_t* row = stage + h_local * kHeadPitch + t_local * (kRowBytes / 4);
     if (KBITS == 4) {
-      __builtin_amdgcn_raw_buffer_store_b32(packed, code_r, live ? row * kRowBytes + part * 4 : kDropStore, 0, 0);
+      row[part] = packed;
     } else if (KBITS == 2) {
       const uint32_t odd = dpp<kQuadOdd>(packed);
-      const bool writer = live && !(threadIdx.x & 1);
-      __builtin_amdgcn_raw_buffer_store_b32(packed | (odd << 16), code_r, writer ? row * kRowBytes + part * 2 : kDropStore, 0, 0);
+      if (!(threadIdx.x & 1)) row[part >> 1] = packed | (odd << 16);
     } else {  // KBITS == 3: four lanes hold 4 x 24 bits = three dwords
       const uint32_t next = dpp<kQuadNext>(packed);
       const uint32_t q4 = threadIdx.x & 3;
       const uint32_t word = (packed >> (8 * q4)) | (next << (24 - 8 * q4));
-      const bool writer = live && q4 != 3;
-      __builtin_amdgcn_raw_buffer_store_b32(word, code_r, writer ? row * kRowBytes + (part >> 2) * 12 + q4 * 4 : kDropStore, 0, 0);
+      if (q4 != 3) row[(part >> 2) * 3 + q4] = word;
     }
-    const bool scale_writer = live && part == 0;             // once per covered head
-    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)s_bits, scale_r, scale_writer ? row * 2 : kDropStore, 0, 0);
+    if (part == 0) stage_scale[h_local * TILE_TOK + t_local] = (uint16_t)s_bits;   // once per covered head
+  }
+  __syncthreads();
+
+  const uint32_t tile_t0 = blockIdx.y * TILE_TOK;
+  const uint32_t row0 = (blk * HPB) * (uint32_t)p.cap_tokens + (uint32_t)p.tok_off + tile_t0;   // head 0 of the block, first token
+#pragma unroll
+  for (uint32_t i0 = 0; i0 < HPB * kHeadDwords; i0 += kThreads) {
+    const uint32_t i = i0 + threadIdx.x;
+    const uint32_t hl = i / kHeadDwords, off = i % kHeadDwords;          // head of the block, dword inside its rows
+    const bool live = tile_t0 + off / (kRowBytes / 4) < n;
+    const uint32_t voff = (row0 + hl * (uint32_t)p.cap_tokens) * kRowBytes + off * 4;
+    __builtin_amdgcn_raw_buffer_store_b32(stage[hl * kHeadPitch + off], code_r, live ? voff : kDropStore, 0, 0);
+  }
+  if (threadIdx.x < HPB * TILE_TOK) {
+    const uint32_t hl = threadIdx.x / TILE_TOK, tl = threadIdx.x % TILE_TOK;
+    const bool live = tile_t0 + tl < n;
+    __builtin_amdgcn_raw_buffer_store_b16(stage_scale[threadIdx.x], scale_r,
+                                          live ? (row0 + hl * (uint32_t)p.cap_tokens + tl) * 2 : kDropStore, 0, 0);
   }
 }
 
@@ -302,8 +326,10 @@ template <int KBITS, int D>
 hipError_t launch_hidden_one(const QuantParams& p, int lanes_per_block, hipStream_t stream) {
   const int heads_per_block = lanes_per_block / (D / 8);
   const int tokens_per_wg = (kThreads / lanes_per_block) * kUnroll;
-  const dim3 grid((unsigned)((p.n_tokens + tokens_per_wg - 1) / tokens_per_wg),
-                  (unsigned)(p.B * (p.H / heads_per_block)), (unsigned)p.n_tensors);
+  // x = block position (fastest), so that workgroups running side by side read one token row
+  // end to end rather than one 256- or 512-byte stripe of many rows
+  const dim3 grid((unsigned)(p.H / heads_per_block),
+                  (unsigned)((p.n_tokens + tokens_per_wg - 1) / tokens_per_wg), (unsigned)(p.B * p.n_tensors));
   const bool fast = p.impl == 0;
   if (lanes_per_block == 32) {
     if (fast) hipLaunchKernelGGL((quantize_hidden_kernel<KBITS, D, 32, true>), grid, dim3(kThreads), 0, stream, p);
