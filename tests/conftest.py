@@ -17,3 +17,17 @@ def oracle():
     from oracle import nqkv_oracle
     nqkv_oracle.build()
     return nqkv_oracle
+
+
+def load_golden(filename: str) -> dict:
+    """tests/golden/<filename>: 'name = v [v ...]' lines ('#' comments) -> {name: float | [float, ...]}."""
+    out = {}
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", filename)) as f:
+        for line in f:
+            line = line.split("#", 1)[0].strip()
+            if not line:
+                continue
+            name, val = (t.strip() for t in line.split("=", 1))
+            nums = [float(v) for v in val.split()]
+            out[name] = nums[0] if len(nums) == 1 else nums
+    return out

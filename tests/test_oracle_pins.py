@@ -9,7 +9,11 @@ import numpy as np
 import pytest
 from scipy import integrate, stats
 
+from conftest import load_golden
+
 RNG = np.random.default_rng(20250516)
+CLOSED_FORM = load_golden("closed_form_constants.txt")     # scipy-only closed forms (see its generator)
+PAPER = load_golden("paper_worked_examples.txt")           # numbers the paper prints
 
 
 # ----------------------------------------------------------------------------- fp16 conversion
@@ -42,13 +46,8 @@ def test_float_to_half_rne_against_numpy(oracle):
 # ----------------------------------------------------------------------------- codebook
 # Normalised positive halves of the symmetric normal-quantile table, from the closed form
 # Phi^-1((i+1/2)/L) / Phi^-1(1 - 1/(2L))  (paper Sec. 1: levels are quantile points of N(0,1)).
-POS_HALF = {
-    2: [0.2769935547, 1.0],
-    3: [0.1025412802, 0.3186036540, 0.5782769563, 1.0],
-    4: [0.0420953837, 0.1273409842, 0.2159463057, 0.3109047375,
-        0.4168188534, 0.5422090999, 0.7075687706, 1.0],
-}
-RAW_MAX = {2: 1.1503493804, 3: 1.5341205444, 4: 1.8627318674}
+POS_HALF = {k: CLOSED_FORM["positive_half_k%d" % k] for k in (2, 3, 4)}
+RAW_MAX = {k: CLOSED_FORM["raw_max_k%d" % k] for k in (2, 3, 4)}
 
 
 @pytest.mark.parametrize("k", range(1, 9))
@@ -225,7 +224,7 @@ def test_roundtrip_bound_idempotence_and_end_levels(oracle, k, blk):
     assert np.array_equal(codes2, codes) and np.array_equal(scales2, scales)
 
 
-HALF_GAP = {2: 0.3615032, 3: 0.2108615, 4: 0.1462156}
+HALF_GAP = {k: CLOSED_FORM["half_largest_gap_k%d" % k] for k in (2, 3, 4)}
 
 
 @pytest.mark.parametrize("k", [2, 3, 4])
@@ -416,7 +415,7 @@ def _absmax_block_mse(levels, n):
 
 def test_fixed_scale_distortion_closed_form_constants():
     """Unit-variance Gaussian, raw (unnormalised) quantile levels, fixed scale: the textbook cell sum."""
-    expect = {2: 0.1448734, 3: 0.0571638, 4: 0.0231705}
+    expect = {k: CLOSED_FORM["fixed_scale_distortion_k%d" % k] for k in (2, 3, 4)}
     for k, want in expect.items():
         L = 1 << k
         c = stats.norm.ppf((np.arange(L) + 0.5) / L)
@@ -428,11 +427,10 @@ def test_fixed_scale_distortion_closed_form_constants():
         assert abs(total - want) < 2e-7
 
 
-@pytest.mark.parametrize("k,blk,want", [(4, 64, 0.0083966), (4, 128, 0.0090472),
-                                        (3, 64, 0.0365532), (3, 128, 0.0410924),
-                                        (2, 64, 0.2161548), (2, 128, 0.2490737)])
-def test_empirical_mse_matches_expected_distortion(oracle, k, blk, want):
+@pytest.mark.parametrize("k,blk", [(4, 64), (4, 128), (3, 64), (3, 128), (2, 64), (2, 128)])
+def test_empirical_mse_matches_expected_distortion(oracle, k, blk):
     """Oracle round-trip MSE on N(0,1) data equals the semi-analytic absmax-block distortion."""
+    want = CLOSED_FORM["absmax_block_mse_k%d_n%d" % (k, blk)]
     l64, l32, _ = oracle.codebook(k)
     model = _absmax_block_mse(l64, blk)
     assert abs(model - want) / want < 2e-4          # the integral reproduces the tabulated constant
@@ -538,9 +536,29 @@ def test_decode_attention_is_attention_over_dequantized_values(oracle, k, blk, D
 def test_paper_kv_bytes_example():
     """Sec. 1: OPT-175B (96 layers, hidden 12288), batch 64, sequence 8192, fp16 -> about 2.3 TB."""
     from paper_2505_16210_amd import workloads
-    nbytes = workloads.fp16_kv_bytes(96, 12288, 64, 8192)
-    assert nbytes == 2 * 96 * 12288 * 2 * 64 * 8192
-    assert abs(nbytes / 2 ** 40 - 2.25) < 0.01 and abs(nbytes / 1e12 - 2.3) < 0.2
+    layers, hidden = int(PAPER["kv_example_layers"]), int(PAPER["kv_example_hidden"])
+    batch, seq = int(PAPER["kv_example_batch"]), int(PAPER["kv_example_seq_len"])
+    nbytes = workloads.fp16_kv_bytes(layers, hidden, batch, seq)
+    assert nbytes == 2 * layers * hidden * int(PAPER["kv_example_bytes_per_value"]) * batch * seq
+    # "2.3TB" as printed: 2.25 TiB, 2.47e12 bytes -- within rounding of the former
+    assert abs(nbytes / 2 ** 40 - PAPER["kv_example_terabytes"]) < 0.06
+
+
+def test_paper_fig5_block_geometry(oracle):
+    """Fig. 5 caption: hidden size 24, 1024 tokens, block size 6 -> 4 blocks per token, 1024 x 4 blocks;
+    Sec. 4.1: the experiments use 4 bits and blocks of 256."""
+    hidden, tokens, blk = int(PAPER["fig5_hidden"]), int(PAPER["fig5_tokens"]), int(PAPER["fig5_block"])
+    codes, scales = oracle.new_cache(1, 1, hidden, int(PAPER["experiments_bits"]), blk, tokens)
+    assert scales.shape[-1] == PAPER["fig5_blocks_per_token"] and scales.size == PAPER["fig5_blocks_total"]
+    # a 256-element block of the experiments' geometry covers 4 heads of 64 or 2 of 128
+    c2, s2 = oracle.new_cache(1, 8, 64, 4, 64, 3)
+    x = RNG.standard_normal((1, 8, 3, 64)).astype(np.float16)
+    oracle.quantize_kv_hidden(x, 4, int(PAPER["experiments_block"]), oracle.codebook(4)[1], c2, s2)
+    assert (s2[0, 0:4] == s2[0, 0:1]).all() and (s2[0, 4:8] == s2[0, 4:5]).all()
+
+
+def test_algorithmic_byte_counts():
+    from paper_2505_16210_amd import workloads
     assert workloads.quantize_bytes_per_element(4, 64) == 2.53125
     assert workloads.decode_bytes_per_token_head(64, 4, 64) == 68
     assert workloads.decode_bytes_per_token_head(128, 4, 64) == 136
