@@ -6,8 +6,8 @@
 //
 // Mapping.  The grid is persistent: at most two eight-wave workgroups per compute unit, each
 // building the look-up table once and then walking over work items (batch*head, split) with the
-// grid as stride; an item's token range is streamed once.  A lane owns 32 consecutive head-dim elements of a token (4*k bytes of
-// codes, one block scale), so LPT = D/32 adjacent lanes hold one token and a wave load covers
+// grid as stride; an item's token range is streamed once.  A lane owns 32 consecutive head-dim
+// elements of a token (4*k bytes of codes, one block scale), so LPT = D/32 adjacent lanes hold one token and a wave load covers
 // 64/LPT tokens with one fully coalesced request (1 KiB at k = 4).  Four such loads of K and
 // four of V are in flight per wave; the first trip's loads are issued before the look-up table
 // is built and the next trip's K loads before the current trip's V arithmetic.
@@ -36,8 +36,12 @@
 // reduce-scatter over lanes (v_permlane32_swap / v_permlane16_swap / DPP / ds_swizzle), the eight
 // waves meet in 4 KiB of LDS, and the workgroup writes fp16 output or an fp32 partial
 // (m, l, o[D]).  With split-K the workgroup that finishes an item's last partial (an integer
-// ticket per batch*head, no floating-point atomics) combines all of them in split order, so the
-// result does not depend on which workgroup that was.
+// ticket per batch*head, no floating-point atomics) combines all of them in an order fixed by
+// its thread layout, so the result does not depend on which workgroup that was.
+//
+// Variants (template parameters of the one kernel): SPLIT as above; FUSE, the whole decode step
+// of Sec. 3.2 in one launch -- the new token's rows are quantized in the kernel, appended to the
+// cache and attended over; VARLEN, a length per sequence read from device memory.
 #include "code_search.h"
 #include "nqkv_internal.h"
 
@@ -247,11 +251,11 @@ __device__ __forceinline__ void v_axpy(const uint32_t (&w)[KBITS], float wgt, fl
 
 // ------------------------------------------------------------------ HBM loads
 // All cache reads are raw buffer loads: a scalar descriptor per item (base = first token of the
-// item's range, num_records = bytes of the range), one per-lane byte offset in a VGPR and the
-// trip/round offset in a scalar register.  That keeps addresses out of the vector ALU and out
-// of vector registers.  Only voffset (not the scalar offset) takes part in the hardware range
-// check, so trip offsets are added into voffset: lanes past the end of the range then read
-// zeros -- code 0, scale 0 -- and never touch memory outside the range.
+// item's range, num_records = bytes of the range), one per-lane byte offset in a VGPR, and the
+// four round offsets of a trip as instruction immediates.  That keeps 64-bit addresses out of
+// the vector ALU and out of vector registers.  Only voffset (not a scalar offset) takes part in
+// the hardware range check, so the trip's offset is added into voffset: lanes past the end of
+// the range then read zeros -- code 0, scale 0 -- and never touch memory outside the range.
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x3_t __attribute__((ext_vector_type(3)));
 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
