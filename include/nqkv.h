@@ -256,8 +256,8 @@ int nqkv_decode_step_varlen(const nqkv_cache_desc* desc, const float* levels,
  *   block_hidden  128 or 256, a multiple of D that divides H*D; or D itself (then the same
  *                 as nqkv_quantize_kv_pair)
  * Errors: as nqkv_quantize_kv, plus NQKV_EINVAL for desc->block != desc->D or a block_hidden
- * that does not fit the head geometry, NQKV_EUNSUPPORTED for other block sizes or a batch row
- * whose source or cache extent reaches 2 GiB.
+ * that does not fit the head geometry, NQKV_EUNSUPPORTED for other block sizes, for a batch row
+ * whose source or cache extent reaches 2 GiB, or for more than 2 097 120 tokens in one call.
  */
 int nqkv_quantize_kv_hidden(const nqkv_cache_desc* desc, const float* levels,
                             const void* k_src, const void* v_src,

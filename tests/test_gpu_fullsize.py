@@ -125,3 +125,82 @@ def test_c2_prefill_then_128_decode_steps(env, oracle, fused):
     for i in sorted(check_at):
         ref = oracle.decode_attention(bits(qs[i]), okc, oks, ovc, ovs, k, blk, lv, S + i + 1, 1.0, n_threads=THREADS)
         assert attn_err(outs[i].cpu().numpy(), ref) <= ATTN_TOL, i
+
+
+def test_largest_slab_the_library_accepts(env, oracle):
+    """Maximum size: one (batch, head) slab just under the 2 GiB the 32-bit lane offsets can address
+    (D 128: 2^23 - 1 tokens, 1.07 G elements per tensor), one token more being refused.  The GPU
+    quantizes K and V whole; the oracle (given the same fp16 bits) quantizes them in 16 token
+    windows on 16 threads; codes, scales and a 64-way split-K attention over all 8.4 M tokens
+    are compared in full."""
+    import concurrent.futures
+    nqkv, workloads = env
+    dev = torch.device("cuda:0")
+    D, k, blk = 128, 4, 64
+    n = (1 << 23) - 1
+    lv = nqkv.build_codebook(k)
+    desc = nqkv.make_desc(1, 1, D, k, blk, n + 1)
+    g = torch.Generator(device=dev).manual_seed(123)
+    K = torch.empty(1, 1, n + 1, D, dtype=torch.float16, device=dev)
+    V = torch.empty_like(K)
+    step = 1 << 20
+    for t0 in range(0, n + 1, step):                       # fp32 noise in slices, cast to fp16
+        t1 = min(t0 + step, n + 1)
+        K[0, 0, t0:t1] = (torch.randn(t1 - t0, D, device=dev, generator=g) *
+                          torch.exp(0.5 * torch.randn(1, D, device=dev, generator=g))).to(torch.float16)
+        V[0, 0, t0:t1] = torch.randn(t1 - t0, D, device=dev, generator=g).to(torch.float16)
+    q = (torch.randn(1, 1, D, device=dev, generator=g) / 128 ** 0.5).to(torch.float16)
+    kc, ks = nqkv.alloc_cache(desc, dev)
+    vc, vs = nqkv.alloc_cache(desc, dev)
+    with pytest.raises(nqkv.NqkvError) as e:               # 2^23 tokens: one past the limit
+        nqkv.quantize_kv_pair(desc, lv, K, V, kc, ks, vc, vs, 0)
+    assert e.value.status == nqkv.EUNSUPPORTED
+    nqkv.quantize_kv_pair(desc, lv, K[:, :, :n], V[:, :, :n], kc, ks, vc, vs, 0)
+    out = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, n, 1.0, num_splits=64)
+    torch.cuda.synchronize()
+    Kh, Vh = bits(K), bits(V)
+    okc, oks = oracle.new_cache(1, 1, D, k, blk, n + 1)
+    ovc, ovs = oracle.new_cache(1, 1, D, k, blk, n + 1)
+    edges = np.linspace(0, n, THREADS + 1).astype(np.int64)
+
+    def window(i):
+        a, b = int(edges[i]), int(edges[i + 1])
+        oracle.quantize_kv(Kh[:, :, a:b], k, blk, lv, okc, oks, dst_off=a)
+        oracle.quantize_kv(Vh[:, :, a:b], k, blk, lv, ovc, ovs, dst_off=a)
+
+    with concurrent.futures.ThreadPoolExecutor(THREADS) as pool:
+        list(pool.map(window, range(THREADS)))
+    assert np.array_equal(bits(ks), oks) and np.array_equal(bits(vs), ovs)
+    assert np.array_equal(bits(kc), okc) and np.array_equal(bits(vc), ovc)
+    ref = oracle.decode_attention(bits(q), okc, oks, ovc, ovs, k, blk, lv, n, 1.0, n_threads=1)
+    assert attn_err(out.cpu().numpy(), ref) <= ATTN_TOL
+
+
+def test_largest_batch_row_of_the_hidden_block_quantizer(env, oracle):
+    """Maximum size of nqkv_quantize_kv_hidden: one batch row of token-major source just under
+    2 GiB (16 heads of 64: 2^20 - 1 tokens, 1.07 G elements), compared in full; one token more
+    is refused."""
+    nqkv, workloads = env
+    dev = torch.device("cuda:0")
+    H, D, k = 16, 64, 4
+    n = (1 << 20) - 1
+    lv = nqkv.build_codebook(k)
+    desc = nqkv.make_desc(1, H, D, k, D, n + 1)
+    g = torch.Generator(device=dev).manual_seed(321)
+    X = torch.empty(1, n + 1, H, D, dtype=torch.float16, device=dev)      # token-major storage
+    step = 1 << 18
+    for t0 in range(0, n + 1, step):
+        t1 = min(t0 + step, n + 1)
+        X[0, t0:t1] = (torch.randn(t1 - t0, H, D, device=dev, generator=g) *
+                       torch.exp(torch.randn(t1 - t0, 1, 1, device=dev, generator=g))).to(torch.float16)
+    view = X.transpose(1, 2)                                               # [1,H,n+1,D]
+    kc, ks = nqkv.alloc_cache(desc, dev)
+    with pytest.raises(nqkv.NqkvError) as e:
+        nqkv.quantize_kv_hidden(desc, lv, view, None, kc, ks, None, None, 0, 256)
+    assert e.value.status == nqkv.EUNSUPPORTED
+    nqkv.quantize_kv_hidden(desc, lv, view[:, :, :n], None, kc, ks, None, None, 0, 256)
+    torch.cuda.synchronize()
+    okc, oks = oracle.new_cache(1, H, D, k, D, n + 1)
+    oracle.quantize_kv_hidden(bits(X).transpose(0, 2, 1, 3)[:, :, :n], k, 256, lv, okc, oks, n_threads=THREADS)
+    assert np.array_equal(bits(ks), oks)
+    assert np.array_equal(bits(kc), okc)
