@@ -14,6 +14,7 @@
  *                                                                    (Sec. 3.2 decoding phase)
  *   nqkv_decode_step       append + attention of one decode step in one launch (Sec. 3.2)
  *   nqkv_decode_attention_varlen / nqkv_decode_step_varlen  the same for per-sequence lengths
+ *   nqkv_decode_attention_paged / nqkv_decode_step_paged  the same over a paged cache
  *   nqkv_quantize_kv_hidden  blocks over the token's hidden vector, token-major source
  *                                                                    (Fig. 5, Sec. 4.1)
  *
@@ -240,6 +241,38 @@ int nqkv_decode_step_varlen(const nqkv_cache_desc* desc, const float* levels,
                             void* k_codes, void* k_scales, void* v_codes, void* v_scales,
                             const int32_t* pos, int64_t max_pos, float softmax_scale, void* out,
                             void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream);
+
+/*
+ * The two decode calls over a PAGED cache.  The pool is num_pages pages; a page holds P =
+ * desc->cap_tokens tokens of all H heads in the layout of a one-sequence cache -- codes uint8
+ * [num_pages][H][P][D*k/8], scales fp16 [num_pages][H][P][D/block] -- so a page can be filled
+ * with nqkv_quantize_kv on a desc with B = 1 and pointers offset to the page.  Logical page j of
+ * sequence b (its tokens j*P .. j*P+P-1) is page block_table[b*table_stride + j].
+ *   block_table  device int32, 4-byte aligned; entries of pages that hold tokens (and, for the
+ *                step, the page of row pos[b]) must be valid page numbers; entries are clamped
+ *                into [0, num_pages) before use, so no value can cause an out-of-bounds access
+ *   seq_lens / pos, max_seq_len / max_pos   as for the _varlen calls (max_* bound by
+ *                table_stride * P instead of the capacity)
+ *   workspace    sized with nqkv_decode_paged_workspace_bytes(desc, max_seq_len or
+ *                max(max_pos, 1), ...): one partial result per logical page (at most 1024 pages
+ *                per sequence: NQKV_EUNSUPPORTED beyond); may be NULL when that size is 0
+ * Results: as nqkv_decode_attention_varlen / nqkv_decode_step_varlen on the same tokens laid
+ * out contiguously, up to the rounding of a different split.
+ */
+int nqkv_decode_paged_workspace_bytes(const nqkv_cache_desc* desc, int64_t max_tokens,
+                                      size_t* bytes_out, int* pages_out);
+int nqkv_decode_attention_paged(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                                const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                                const int32_t* block_table, int64_t table_stride, int64_t num_pages,
+                                const int32_t* seq_lens, int64_t max_seq_len, float softmax_scale, void* out,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+int nqkv_decode_step_paged(const nqkv_cache_desc* desc, const float* levels,
+                           const void* q, const void* k_new, const void* v_new,
+                           int64_t new_stride_b, int64_t new_stride_h,
+                           void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                           const int32_t* block_table, int64_t table_stride, int64_t num_pages,
+                           const int32_t* pos, int64_t max_pos, float softmax_scale, void* out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Quantization with blocks over the token's hidden vector (Fig. 5: "each token ... divided into

@@ -341,6 +341,7 @@ __device__ __forceinline__ void reduce_groups(const float (&acc)[32], uint32_t l
 // VARLEN: every sequence of the batch has its own number of cached tokens, read from device
 // memory (p.seq_lens[b], clamped to [0, p.max_len]); the split geometry is laid out for
 // p.max_len and each item keeps the part of its range that lies inside its sequence.
+// With p.block_table set (VARLEN kernels only) the cache is paged: see set_item.
 // FUSE: the whole decode step of the paper in one launch -- items cover the tokens already
 // cached, rows [0, pos); the last wave of each sequence's last item quantizes the new token's
 // key and value rows (same code search as the quantizer), stores their codes and scales at row
@@ -352,13 +353,28 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   constexpr int CHUNK = kRounds * TPR;    // tokens per wave trip
   constexpr int NB = D / BLK;
   constexpr int ROW = LPT * KBITS;        // dwords of codes per token
-  __shared__ __attribute__((aligned(16))) uint32_t smem[kLutWords];
-  __shared__ float xw[kWaves][D];
-  __shared__ float wave_m[kWaves], wave_l[kWaves];
-  __shared__ uint32_t ticket_sh;
-  __shared__ uint2 cells[FUSE ? 128 : 1];
-  __shared__ uint32_t new_codes[FUSE ? 2 : 1][ROW];       // packed codes of the new token's K and V rows
-  __shared__ uint32_t new_scales[FUSE ? 2 : 1][NB];       // and their block scales (fp16 bits)
+  // One LDS object, the small arrays first: everything but the table then lies below 64 KiB,
+  // within reach of the 16-bit offset field of the LDS instructions.  (As separate variables the
+  // compiler put the table first, and every fixed address above 64 KiB cost a register that
+  // stayed live around the whole item loop.)
+  struct Lds {
+    float xw[kWaves][D];                            // per-wave partial outputs
+    float wave_m[kWaves], wave_l[kWaves];
+    uint32_t ticket;
+    uint2 cells[FUSE ? 128 : 1];                    // FUSE: code-search cell table
+    uint32_t new_codes[FUSE ? 2 : 1][ROW];          // packed codes of the new token's K and V rows
+    uint32_t new_scales[FUSE ? 2 : 1][NB];          // and their block scales (fp16 bits)
+    __attribute__((aligned(256))) uint32_t lut[kLutWords];
+  };
+  __shared__ Lds lds;
+  uint32_t* const smem = lds.lut;
+  auto& xw = lds.xw;
+  auto& wave_m = lds.wave_m;
+  auto& wave_l = lds.wave_l;
+  uint32_t& ticket_sh = lds.ticket;
+  auto& cells = lds.cells;
+  auto& new_codes = lds.new_codes;
+  auto& new_scales = lds.new_scales;
 
   const char* lut = reinterpret_cast<const char*>(smem);
   const uint32_t lane = threadIdx.x & 63;
@@ -395,14 +411,21 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
     const int64_t t0 = (int64_t)sp * p.split_base + min((int32_t)sp, p.split_rem);
     n_tok = p.split_base + ((int32_t)sp < p.split_rem ? 1 : 0);
     uint32_t b = 0, h = 0;
+    int64_t row0 = (int64_t)bh * p.cap_tokens + t0;
     if (VARLEN) {
       b = bh / (uint32_t)p.H; h = bh - b * (uint32_t)p.H;
       const int32_t len = min(max(p.seq_lens[b], 0), p.max_len);     // whatever the array holds, stay inside the cache
       n_tok = min(n_tok, max(len - (int32_t)t0, 0));
       pos = len;
+      if (p.block_table) {
+        // paged cache: the item is logical page sp of its sequence (the host lays the splits
+        // out as pages: split_base = tokens per page); its rows are page block_table[b][sp] of
+        // the pool, pages being [H][tokens per page] rows each
+        const int32_t phys = min(max(p.block_table[(int64_t)b * p.table_stride + sp], 0), p.num_pages - 1);
+        row0 = ((int64_t)phys * p.H + h) * p.split_base;
+      }
     }
     base = (int32_t)wave * CHUNK;
-    const int64_t row0 = (int64_t)bh * p.cap_tokens + t0;
     kc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.k_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
     vc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.v_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
     ks_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.k_scales) + row0 * NB, 0, n_tok * (int)kScaleRowBytes, kBufferFlags);
@@ -634,7 +657,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
       // Append: the LDS images of the new token's rows go to cache row pos.  Done here rather
       // than where they are produced because stores share the loads' in-order memory counter:
       // issued ahead of the streaming loop, their acknowledgements would hold up its first trip.
-      const int64_t row = (int64_t)cur_bh * p.cap_tokens + (VARLEN ? cur_pos : p.pos);
+      int64_t row = (int64_t)cur_bh * p.cap_tokens + (VARLEN ? cur_pos : p.pos);
+      if (VARLEN && p.block_table) {                  // paged: the row's page comes from the table
+        const uint32_t cb = cur_bh / (uint32_t)p.H, ch = cur_bh - cb * (uint32_t)p.H;
+        const int32_t lp = (int32_t)(cur_pos / p.split_base);
+        const int32_t phys = min(max(p.block_table[(int64_t)cb * p.table_stride + lp], 0), p.num_pages - 1);
+        row = ((int64_t)phys * p.H + ch) * p.split_base + (cur_pos - (int64_t)lp * p.split_base);
+      }
       if (tid < 2u * ROW) {
         const uint32_t t = tid / ROW, w = tid % ROW;
         uint32_t* dst = reinterpret_cast<uint32_t*>(const_cast<uint8_t*>(t ? p.v_codes : p.k_codes)) + row * ROW + w;

@@ -4,6 +4,7 @@
 #include "../../include/nqkv.h"
 #include "nqkv_internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 
@@ -506,6 +507,120 @@ int nqkv_decode_step_varlen(const nqkv_cache_desc* desc, const float* levels,
   if (max_pos < 0 || (desc && max_pos >= desc->cap_tokens)) return NQKV_EINVAL;
   return decode_impl(desc, levels, q, k_new, v_new, new_stride_b, new_stride_h, pos, k_codes, k_scales, v_codes,
                      v_scales, max_pos + 1, softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
+}
+
+// Paged cache: the pool holds num_pages pages of [H][P] rows (P = desc->cap_tokens tokens per
+// page); logical page j of sequence b is page block_table[b * table_stride + j].  One work item
+// per logical page; their partial results are combined like split-K partials.
+static int paged_pages(const nqkv_cache_desc* desc, int64_t n_cached) {
+  const int64_t P = desc->cap_tokens;
+  const int64_t pages = n_cached <= 0 ? 1 : (n_cached + P - 1) / P;
+  return pages > 1024 ? -1 : (int)pages;
+}
+
+int nqkv_decode_paged_workspace_bytes(const nqkv_cache_desc* desc, int64_t max_tokens, size_t* bytes_out, int* pages_out) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!bytes_out || max_tokens < 1) return NQKV_EINVAL;
+  const int pages = paged_pages(desc, max_tokens);
+  if (pages < 0) return NQKV_EUNSUPPORTED;
+  *bytes_out = workspace_need(desc, pages);
+  if (pages_out) *pages_out = pages;
+  return NQKV_OK;
+}
+
+static int decode_paged_impl(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                             const void* k_new, const void* v_new, int64_t new_stride_b, int64_t new_stride_h,
+                             const int32_t* lens, const int32_t* block_table, int64_t table_stride, int64_t num_pages,
+                             const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                             int64_t n_cached, float softmax_scale, void* out,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  const bool fuse = k_new != nullptr;
+  DecodeParams p;
+  std::memset(&p, 0, sizeof(p));
+  LevelTable checked;
+  if ((rc = check_levels(levels, desc->k, &checked))) return rc;
+  const int64_t P = desc->cap_tokens;
+  if (n_cached < (fuse ? 0 : 1)) return NQKV_EINVAL;
+  if (!lens || (reinterpret_cast<uintptr_t>(lens) & 3u) || !block_table || (reinterpret_cast<uintptr_t>(block_table) & 3u))
+    return NQKV_EINVAL;
+  if (num_pages < 1 || num_pages > ((int64_t)1 << 31) - 1) return NQKV_EINVAL;
+  const int pages = paged_pages(desc, n_cached);
+  if (pages < 0) return NQKV_EUNSUPPORTED;
+  // table columns the kernel may look at: the pages of the cached tokens, and the page of the new row
+  const int64_t cols = fuse ? std::max<int64_t>(pages, n_cached / P + 1) : pages;
+  if (table_stride < cols || table_stride > ((int64_t)1 << 31) - 1) return NQKV_EINVAL;
+  if (n_cached > ((int64_t)1 << 31) - 1 || P * (int64_t)(desc->D * desc->k / 8) >= ((int64_t)1 << 31)) return NQKV_EUNSUPPORTED;
+  if (!std::isfinite(softmax_scale)) return NQKV_EINVAL;
+  const void* ptrs[] = {q, k_codes, k_scales, v_codes, v_scales, out};
+  for (const void* ptr : ptrs) {
+    if (!ptr || !aligned16(ptr)) return NQKV_EINVAL;
+  }
+  if (fuse) {
+    if (!v_new || !aligned16(k_new) || !aligned16(v_new)) return NQKV_EINVAL;
+    if (new_stride_b < 0 || new_stride_h < 0 || (new_stride_b % 8) || (new_stride_h % 8)) return NQKV_EINVAL;
+    if (!build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) return NQKV_EUNSUPPORTED;
+  }
+  const size_t need = workspace_need(desc, pages);
+  if (need > 0) {
+    if (!workspace || !aligned16(workspace)) return NQKV_EINVAL;
+    if (workspace_bytes < need) return NQKV_EWORKSPACE;
+  }
+  p.q = static_cast<const uint16_t*>(q);
+  p.k_codes = static_cast<const uint8_t*>(k_codes);
+  p.k_scales = static_cast<const uint16_t*>(k_scales);
+  p.v_codes = static_cast<const uint8_t*>(v_codes);
+  p.v_scales = static_cast<const uint16_t*>(v_scales);
+  p.out = static_cast<uint16_t*>(out);
+  p.tickets = static_cast<uint32_t*>(workspace);
+  p.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kTicketBytes);
+  p.n_items = desc->B * desc->H * pages;
+  p.splits = pages;
+  p.split_base = (int)P;                               // item j of a sequence = its logical page j
+  p.split_rem = 0;
+  p.max_workgroups = g_decode_grid_limit > 0 ? g_decode_grid_limit : max_decode_workgroups();
+  p.cap_tokens = P;
+  const LutChoice& lut = choose_lut_scale(checked.v, 1 << desc->k);
+  std::memcpy(p.lut_levels, lut.bits, sizeof(uint16_t) * (1 << desc->k));
+  p.inv_gamma = 1.0f / lut.gamma;
+  p.scale_log2e = (float)((double)softmax_scale * 1.44269504088896340736 / (double)lut.gamma);
+  p.k_new = static_cast<const uint16_t*>(k_new);
+  p.v_new = static_cast<const uint16_t*>(v_new);
+  p.new_stride_b = new_stride_b;
+  p.new_stride_h = new_stride_h;
+  p.H = desc->H;
+  p.seq_lens = lens;
+  p.max_len = (int)n_cached;
+  p.block_table = block_table;
+  p.table_stride = (int)table_stride;
+  p.num_pages = (int)num_pages;
+  const hipError_t e = launch_decode_attention(p, desc->D, desc->k, desc->block, fuse, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
+}
+
+int nqkv_decode_attention_paged(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                                const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                                const int32_t* block_table, int64_t table_stride, int64_t num_pages,
+                                const int32_t* seq_lens, int64_t max_seq_len, float softmax_scale, void* out,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return decode_paged_impl(desc, levels, q, nullptr, nullptr, 0, 0, seq_lens, block_table, table_stride, num_pages,
+                           k_codes, k_scales, v_codes, v_scales, max_seq_len, softmax_scale, out, workspace,
+                           workspace_bytes, hip_stream);
+}
+
+int nqkv_decode_step_paged(const nqkv_cache_desc* desc, const float* levels,
+                           const void* q, const void* k_new, const void* v_new,
+                           int64_t new_stride_b, int64_t new_stride_h,
+                           void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                           const int32_t* block_table, int64_t table_stride, int64_t num_pages,
+                           const int32_t* pos, int64_t max_pos, float softmax_scale, void* out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!k_new) return NQKV_EINVAL;
+  return decode_paged_impl(desc, levels, q, k_new, v_new, new_stride_b, new_stride_h, pos, block_table, table_stride,
+                           num_pages, k_codes, k_scales, v_codes, v_scales, max_pos, softmax_scale, out, workspace,
+                           workspace_bytes, hip_stream);
 }
 
 int nqkv_probe_read_stream(const void* src, size_t bytes, void* checksums, void* hip_stream) {

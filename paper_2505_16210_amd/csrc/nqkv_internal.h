@@ -65,6 +65,12 @@ struct DecodeParams {
   // the length the split geometry is laid out for
   const int32_t* seq_lens;
   int max_len;
+  // paged cache (NULL: contiguous [B][H][cap_tokens] rows): physical page of logical page j of
+  // sequence b at block_table[b * table_stride + j]; the pool holds num_pages pages of
+  // [H][split_base] rows; one item per logical page
+  const int32_t* block_table;
+  int table_stride;
+  int num_pages;
   uint32_t cell_thr[kQuantCells];
   uint32_t cell_below[kQuantCells];
 };

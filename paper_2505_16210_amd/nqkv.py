@@ -22,7 +22,8 @@ EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_set_tuning", "nqkv_build_codeb
            "nqkv_quantize_kv", "nqkv_quantize_kv_pair", "nqkv_dequantize_kv",
            "nqkv_decode_workspace_bytes", "nqkv_decode_attention", "nqkv_decode_step",
            "nqkv_probe_read_stream", "nqkv_quantize_kv_hidden",
-           "nqkv_decode_attention_varlen", "nqkv_decode_step_varlen")
+           "nqkv_decode_attention_varlen", "nqkv_decode_step_varlen",
+           "nqkv_decode_paged_workspace_bytes", "nqkv_decode_attention_paged", "nqkv_decode_step_paged")
 
 
 class CacheDesc(ctypes.Structure):
@@ -74,6 +75,14 @@ def _load() -> ctypes.CDLL:
     lib.nqkv_decode_step_varlen.restype = i32
     lib.nqkv_decode_step_varlen.argtypes = [dp, fp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp, i64, c.c_float, vp, vp,
                                             c.c_size_t, i32, vp]
+    lib.nqkv_decode_paged_workspace_bytes.restype = i32
+    lib.nqkv_decode_paged_workspace_bytes.argtypes = [dp, i64, c.POINTER(c.c_size_t), c.POINTER(i32)]
+    lib.nqkv_decode_attention_paged.restype = i32
+    lib.nqkv_decode_attention_paged.argtypes = [dp, fp, vp, vp, vp, vp, vp, vp, i64, i64, vp, i64, c.c_float, vp, vp,
+                                                c.c_size_t, vp]
+    lib.nqkv_decode_step_paged.restype = i32
+    lib.nqkv_decode_step_paged.argtypes = [dp, fp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp, i64, i64, vp, i64,
+                                           c.c_float, vp, vp, c.c_size_t, vp]
     lib.nqkv_quantize_kv_hidden.restype = i32
     lib.nqkv_quantize_kv_hidden.argtypes = [dp, fp, vp, vp, i64, i64, i64, i64, i64, i32, vp, vp, vp, vp, vp]
     lib.nqkv_probe_read_stream.restype = i32
@@ -308,6 +317,76 @@ def decode_step_varlen(desc: CacheDesc, levels, q: torch.Tensor, k_new: torch.Te
                                      float(softmax_scale), _dev_ptr(out), _dev_ptr(workspace), ws_bytes, num_splits,
                                      _stream(stream))
     _check(rc, "nqkv_decode_step_varlen")
+    return out
+
+
+def alloc_paged_pool(desc: CacheDesc, num_pages: int, device="cuda"):
+    """Pool of pages for the paged calls (desc.cap_tokens = tokens per page):
+    (codes uint8 [num_pages,H,P,D*k/8], scales fp16 [num_pages,H,P,D/block])."""
+    P = desc.cap_tokens
+    codes = torch.zeros(num_pages, desc.H, P, desc.D * desc.k // 8, dtype=torch.uint8, device=device)
+    scales = torch.zeros(num_pages, desc.H, P, desc.D // desc.block, dtype=torch.float16, device=device)
+    return codes, scales
+
+
+def decode_paged_workspace_bytes(desc: CacheDesc, max_tokens: int):
+    """nqkv_decode_paged_workspace_bytes -> (bytes, pages per sequence)."""
+    nbytes = ctypes.c_size_t(0)
+    pages = ctypes.c_int(0)
+    rc = lib.nqkv_decode_paged_workspace_bytes(ctypes.byref(desc), max_tokens, ctypes.byref(nbytes), ctypes.byref(pages))
+    _check(rc, "nqkv_decode_paged_workspace_bytes")
+    return int(nbytes.value), int(pages.value)
+
+
+def _table_arg(block_table: torch.Tensor, B: int):
+    assert block_table.dtype == torch.int32 and block_table.dim() == 2 and block_table.shape[0] == B
+    assert block_table.is_cuda and block_table.stride(1) == 1
+    return _dev_ptr(block_table), block_table.stride(0)
+
+
+def decode_attention_paged(desc: CacheDesc, levels, q, k_codes, k_scales, v_codes, v_scales,
+                           block_table: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int,
+                           softmax_scale: float = 1.0, out=None, workspace=None, stream=None) -> torch.Tensor:
+    """nqkv_decode_attention_paged: pools [num_pages,H,P,*], block_table int32 [B,max_pages] (device)."""
+    lv, lvp = _levels_ptr(levels)
+    assert q.dtype == torch.float16 and q.is_contiguous()
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        need, _ = decode_paged_workspace_bytes(desc, max_seq_len)
+        workspace = torch.zeros(need, dtype=torch.uint8, device=q.device) if need else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    tp, ts = _table_arg(block_table, desc.B)
+    rc = lib.nqkv_decode_attention_paged(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_codes), _dev_ptr(k_scales),
+                                         _dev_ptr(v_codes), _dev_ptr(v_scales), tp, ts, k_codes.shape[0],
+                                         _lens_arg(seq_lens, desc.B), max_seq_len, float(softmax_scale), _dev_ptr(out),
+                                         _dev_ptr(workspace), ws_bytes, _stream(stream))
+    _check(rc, "nqkv_decode_attention_paged")
+    return out
+
+
+def decode_step_paged(desc: CacheDesc, levels, q, k_new, v_new, k_codes, k_scales, v_codes, v_scales,
+                      block_table: torch.Tensor, pos: torch.Tensor, max_pos: int, softmax_scale: float = 1.0,
+                      out=None, workspace=None, stream=None) -> torch.Tensor:
+    """nqkv_decode_step_paged: appends row pos[b] of every sequence into its page and attends."""
+    lv, lvp = _levels_ptr(levels)
+    assert q.dtype == torch.float16 and q.is_contiguous()
+    if k_new.dim() == 4:
+        k_new, v_new = k_new[:, :, 0], v_new[:, :, 0]
+    assert k_new.dtype == torch.float16 and k_new.stride(2) == 1 and k_new.stride() == v_new.stride()
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        need, _ = decode_paged_workspace_bytes(desc, max(max_pos, 1))
+        workspace = torch.zeros(need, dtype=torch.uint8, device=q.device) if need else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    tp, ts = _table_arg(block_table, desc.B)
+    rc = lib.nqkv_decode_step_paged(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_new), _dev_ptr(v_new),
+                                    k_new.stride(0), k_new.stride(1), _dev_ptr(k_codes), _dev_ptr(k_scales),
+                                    _dev_ptr(v_codes), _dev_ptr(v_scales), tp, ts, k_codes.shape[0],
+                                    _lens_arg(pos, desc.B), max_pos, float(softmax_scale), _dev_ptr(out),
+                                    _dev_ptr(workspace), ws_bytes, _stream(stream))
+    _check(rc, "nqkv_decode_step_paged")
     return out
 
 

@@ -566,3 +566,118 @@ def test_decode_step_varlen_appends_at_each_sequences_own_row(nqkv, oracle, k, D
         assert np.array_equal(h2n(vc), ovc) and np.array_equal(h2n(vs), ovs), (step, ns)
         err = attn_err(h2n(out).view(np.float16), np.concatenate(refs, 0))
         assert err <= ATTN_TOL, (step, ns, err)
+
+
+# --------------------------------------------------------------------------- paged cache
+def _scatter_to_pages(contig, table, P):
+    """contiguous cache tensor [B,H,cap,X] -> pool [num_pages,H,P,X] following block_table [B,pages]."""
+    B, H, cap, X = contig.shape
+    n_pages_seq = cap // P
+    num_pages = int(table.max().item()) + 1
+    pool = torch.zeros(num_pages, H, P, X, dtype=contig.dtype, device=contig.device)
+    for b in range(B):
+        for j in range(n_pages_seq):
+            pool[table[b, j]] = contig[b, :, j * P:(j + 1) * P]
+    return pool
+
+
+@pytest.mark.parametrize("k,D,blk,P", [(4, 64, 64, 128), (4, 128, 64, 256), (3, 128, 128, 64), (2, 64, 64, 512)])
+def test_decode_attention_paged_matches_oracle(nqkv, oracle, k, D, blk, P):
+    """The cache of every sequence scattered over a shuffled pool of pages (with unused pages in
+    between): attention must equal the oracle's on the contiguous cache, sequence by sequence,
+    and the contiguous per-sequence-length call up to rounding."""
+    B, H, cap = 4, 3, 1536
+    lv, desc, q, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, cap, cap, seed=41 * k + D + P)
+    n_pages_seq = cap // P
+    perm = torch.randperm(2 * B * n_pages_seq, generator=torch.Generator().manual_seed(P))[:B * n_pages_seq]
+    table = perm.reshape(B, n_pages_seq).to(torch.int32).cuda()
+    pools = [_scatter_to_pages(t, table, P) for t in (kc, ks, vc, vs)]
+    lens = [1, P, P + 1, cap]
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    # table entries of pages a sequence does not reach: garbage must be harmless
+    wild = table.clone()
+    for b in range(B):
+        used = -(-lens[b] // P)
+        wild[b, used:] = torch.tensor([-7, 10 ** 9] * n_pages_seq, dtype=torch.int32)[:n_pages_seq - used].cuda()
+    pdesc = nqkv.make_desc(B, H, D, k, blk, P)
+    hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+    ref = np.concatenate([oracle.decode_attention(*[a[b:b + 1] for a in hk], k, blk, lv, lens[b], 0.9, n_threads=4)
+                          for b in range(B)], 0)
+    for tb in (table, wild):
+        out = nqkv.decode_attention_paged(pdesc, lv, q, *pools, tb, lens_dev, max(lens), 0.9)
+        torch.cuda.synchronize()
+        assert attn_err(h2n(out).view(np.float16), ref) <= ATTN_TOL
+    contig = nqkv.decode_attention_varlen(desc, lv, q, kc, ks, vc, vs, lens_dev, cap, 0.9)
+    d = (out.float() - contig.float()).abs().amax(-1) / contig.float().abs().amax(-1)
+    assert d.max().item() <= 2e-3
+    # a shorter bound: fewer pages per sequence in play, longer sequences clamped to it
+    short = torch.tensor([1, P, P + 1, 2 * P], dtype=torch.int32, device="cuda")
+    out2 = nqkv.decode_attention_paged(pdesc, lv, q, *pools, table, short, 2 * P, 0.9)
+    ref2 = oracle.decode_attention(*[a[3:4] for a in hk], k, blk, lv, 2 * P, 0.9, n_threads=4)
+    torch.cuda.synchronize()
+    assert attn_err(h2n(out2).view(np.float16)[3:4], ref2) <= ATTN_TOL
+    assert attn_err(h2n(out2).view(np.float16)[:3], ref[:3]) <= ATTN_TOL
+
+
+@pytest.mark.parametrize("k,D,blk,P", [(4, 64, 64, 128), (3, 128, 64, 64), (2, 128, 128, 256)])
+def test_decode_step_paged_appends_into_pages(nqkv, oracle, k, D, blk, P):
+    """Fused step over a paged cache: sequences at different positions (an empty one, one whose
+    new row opens a fresh page, one in the middle of a page); pages filled with nqkv_quantize_kv
+    through a one-sequence view of the page.  After every step the pool, gathered back, must equal
+    the oracle's contiguous cache bit for bit and the outputs stay within tolerance."""
+    B, H, n_pages_seq = 4, 3, 6
+    cap = n_pages_seq * P
+    lv = nqkv.build_codebook(k)
+    g = torch.Generator(device="cuda").manual_seed(9 * k + D + P)
+    Kx = rand_kv((B, H, cap, D), 77 + k)
+    Vx = torch.randn(B, H, cap, D, device="cuda", generator=g).to(torch.float16)
+    perm = torch.randperm(B * n_pages_seq + 5, generator=torch.Generator().manual_seed(D + P))[:B * n_pages_seq]
+    table = perm.reshape(B, n_pages_seq).to(torch.int32).cuda()
+    pdesc = nqkv.make_desc(B, H, D, k, blk, P)
+    num_pages = B * n_pages_seq + 5
+    kcp, ksp = nqkv.alloc_paged_pool(pdesc, num_pages)
+    vcp, vsp = nqkv.alloc_paged_pool(pdesc, num_pages)
+    start = [0, 2 * P, 3 * P - 1, 4 * P + 17]
+    page_desc = nqkv.make_desc(1, H, D, k, blk, P)
+    okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
+    ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
+    Kh, Vh = h2n(Kx), h2n(Vx)
+    for b in range(B):                      # prefill page by page through the ordinary quantizer
+        for j in range(-(-start[b] // P)):
+            t0, t1 = j * P, min((j + 1) * P, start[b])
+            pg = int(table[b, j])
+            nqkv.quantize_kv_pair(page_desc, lv, Kx[b:b + 1, :, t0:t1], Vx[b:b + 1, :, t0:t1],
+                                  kcp[pg:pg + 1], ksp[pg:pg + 1], vcp[pg:pg + 1], vsp[pg:pg + 1], 0)
+        if start[b]:
+            oracle.quantize_kv(Kh[b:b + 1, :, :start[b]], k, blk, lv, okc[b:b + 1], oks[b:b + 1])
+            oracle.quantize_kv(Vh[b:b + 1, :, :start[b]], k, blk, lv, ovc[b:b + 1], ovs[b:b + 1])
+
+    def gather(pool, n_rows):
+        out = np.zeros((B, H, cap, pool.shape[-1]), h2n(pool).dtype)
+        hp = h2n(pool)
+        for b in range(B):
+            for j in range(n_pages_seq):
+                out[b, :, j * P:(j + 1) * P] = hp[int(table[b, j])]
+            out[b, :, n_rows[b]:] = 0           # rows beyond the sequence: whatever the pool holds
+        return out
+
+    for step in range(3):
+        pos = [s0 + step for s0 in start]
+        pos_dev = torch.tensor(pos, dtype=torch.int32, device="cuda")
+        q = (torch.randn(B, H, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+        kn = torch.stack([Kx[b, :, pos[b]] for b in range(B)])
+        vn = torch.stack([Vx[b, :, pos[b]] for b in range(B)])
+        out = nqkv.decode_step_paged(pdesc, lv, q, kn, vn, kcp, ksp, vcp, vsp, table, pos_dev, max(pos), 1.0)
+        torch.cuda.synchronize()
+        refs = []
+        for b in range(B):
+            sl = slice(b, b + 1)
+            oracle.quantize_kv(Kh[sl, :, pos[b]:pos[b] + 1], k, blk, lv, okc[sl], oks[sl], dst_off=pos[b])
+            oracle.quantize_kv(Vh[sl, :, pos[b]:pos[b] + 1], k, blk, lv, ovc[sl], ovs[sl], dst_off=pos[b])
+            refs.append(oracle.decode_attention(h2n(q)[sl], okc[sl], oks[sl], ovc[sl], ovs[sl], k, blk, lv,
+                                                pos[b] + 1, 1.0, n_threads=4))
+        rows = [p_ + 1 for p_ in pos]
+        assert np.array_equal(gather(kcp, rows), okc) and np.array_equal(gather(ksp, rows), oks), step
+        assert np.array_equal(gather(vcp, rows), ovc) and np.array_equal(gather(vsp, rows), ovs), step
+        err = attn_err(h2n(out).view(np.float16), np.concatenate(refs, 0))
+        assert err <= ATTN_TOL, (step, err)

@@ -208,6 +208,39 @@ def test_varlen_argument_errors(nqkv):
     assert step(mx=0, ns=2) == nqkv.EINVAL
 
 
+def test_paged_argument_errors(nqkv):
+    lv, lvp = _levels(nqkv)
+    d = nqkv.make_desc(4, 8, 128, 4, 64, 256)                     # pages of 256 tokens
+    assert nqkv.decode_paged_workspace_bytes(d, 256) == (0, 1)
+    assert nqkv.decode_paged_workspace_bytes(d, 257) == (262144 + 4 * 8 * 2 * 130 * 4, 2)
+    with pytest.raises(nqkv.NqkvError) as e:
+        nqkv.decode_paged_workspace_bytes(d, 256 * 1024 + 1)      # more than 1024 pages per sequence
+    assert e.value.status == nqkv.EUNSUPPORTED
+    fa, fs = nqkv.lib.nqkv_decode_attention_paged, nqkv.lib.nqkv_decode_step_paged
+
+    def att(table=FAKE, stride=16, pages=100, lens=FAKE, mx=4096, ws=FAKE, ws_bytes=1 << 30, q=FAKE):
+        return fa(ctypes.byref(d), lvp, q, FAKE, FAKE, FAKE, FAKE, table, stride, pages, lens, mx, 1.0, FAKE, ws,
+                  ws_bytes, None)
+
+    def step(table=FAKE, stride=17, pages=100, pos=FAKE, mx=4096, kn=FAKE):
+        return fs(ctypes.byref(d), lvp, FAKE, kn, FAKE, 1024, 128, FAKE, FAKE, FAKE, FAKE, table, stride, pages, pos, mx,
+                  1.0, FAKE, FAKE, 1 << 30, None)
+
+    assert att(table=None) == nqkv.EINVAL
+    assert att(table=FAKE + 2) == nqkv.EINVAL
+    assert att(lens=None) == nqkv.EINVAL
+    assert att(stride=15) == nqkv.EINVAL                          # 4096 tokens need 16 table columns
+    assert att(pages=0) == nqkv.EINVAL
+    assert att(mx=0) == nqkv.EINVAL
+    assert att(ws=None) == nqkv.EINVAL
+    assert att(ws_bytes=1000) == nqkv.EWORKSPACE
+    assert att(q=None) == nqkv.EINVAL
+    assert step(stride=16) == nqkv.EINVAL                         # row 4096 opens page 16: 17 columns
+    assert step(kn=None) == nqkv.EINVAL
+    assert step(pos=None) == nqkv.EINVAL
+    assert step(mx=-1) == nqkv.EINVAL
+
+
 def test_quantize_hidden_argument_errors(nqkv):
     lv, lvp = _levels(nqkv)
     f = nqkv.lib.nqkv_quantize_kv_hidden
