@@ -418,6 +418,34 @@ def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, time
                 + (2 * B * H * splits * (D + 2) * 4 if splits > 1 else 0)
             kern[tag + ".decode_attention_varlen"] = kernel_entry(vbytes, t_v, splits=splits,
                                                                   lengths="%d..%d evenly spread" % (S // 8, S))
+        if B >= 8 and packed <= (1 << 30) and S % 256 == 0:
+            # the same cache as a shuffled pool of 256-token pages behind a block table
+            P = 256
+            n_pg = S // P
+            perm = torch.randperm(B * n_pg, generator=torch.Generator().manual_seed(1)).to(dev)
+            table = perm.reshape(B, n_pg).to(torch.int32)
+            inv = torch.empty_like(perm)
+            inv[perm] = torch.arange(B * n_pg, device=dev)
+
+            def to_pool(t):      # [B,H,S,X] -> [B*n_pg,H,P,X], logical page (b, j) stored at page table[b, j]
+                X = t.shape[-1]
+                pages = t.reshape(B, H, n_pg, P, X).permute(0, 2, 1, 3, 4).reshape(B * n_pg, H, P, X)
+                return pages.index_select(0, inv).contiguous()
+
+            pools = [tuple(to_pool(t) for t in c) for c in caches]
+            pdesc = nqkv.make_desc(B, H, D, kb, bl, P)
+            pws_bytes, p_items = nqkv.decode_paged_workspace_bytes(pdesc, S)
+            pws = torch.zeros(max(pws_bytes, 16), dtype=torch.uint8, device=dev)
+            full = torch.full((B,), S, dtype=torch.int32, device=dev)
+
+            def attend_paged(i):
+                nqkv.decode_attention_paged(pdesc, lv, q, *pools[i % r_cache], table, full, S, 1.0, out=out, workspace=pws)
+
+            t_pg = tk(attend_paged, n_it * 2, warm=max(2, r_cache))
+            kern[tag + ".decode_attention_paged"] = kernel_entry(
+                packed + B * H * 4 * D + (2 * B * H * p_items * (D + 2) * 4 if p_items > 1 else 0), t_pg,
+                page_tokens=P, pages_per_sequence=n_pg, items_per_sequence=p_items)
+            del pools, pws
         if (H * D) % 256 == 0:
             # the paper's own block geometry: 256 consecutive elements of the token's hidden vector,
             # read from token-major storage (the same bytes viewed as [B,S,H,D]); one scale per head

@@ -244,23 +244,26 @@ int nqkv_decode_step_varlen(const nqkv_cache_desc* desc, const float* levels,
 
 /*
  * The two decode calls over a PAGED cache.  The pool is num_pages pages; a page holds P =
- * desc->cap_tokens tokens of all H heads in the layout of a one-sequence cache -- codes uint8
- * [num_pages][H][P][D*k/8], scales fp16 [num_pages][H][P][D/block] -- so a page can be filled
- * with nqkv_quantize_kv on a desc with B = 1 and pointers offset to the page.  Logical page j of
- * sequence b (its tokens j*P .. j*P+P-1) is page block_table[b*table_stride + j].
+ * desc->cap_tokens tokens (a power of two, at least 128) of all H heads in the layout of a
+ * one-sequence cache -- codes uint8 [num_pages][H][P][D*k/8], scales fp16
+ * [num_pages][H][P][D/block] -- so a page can be filled with nqkv_quantize_kv on a desc with
+ * B = 1 and pointers offset to the page.  Logical page j of sequence b (its tokens j*P ..
+ * j*P+P-1) is page block_table[b*table_stride + j].
  *   block_table  device int32, 4-byte aligned; entries of pages that hold tokens (and, for the
- *                step, the page of row pos[b]) must be valid page numbers; entries are clamped
- *                into [0, num_pages) before use, so no value can cause an out-of-bounds access
+ *                step, the page of row pos[b]) must be valid page numbers; indices and entries
+ *                are clamped into the table and the pool before use, so no value can cause an
+ *                out-of-bounds access
  *   seq_lens / pos, max_seq_len / max_pos   as for the _varlen calls (max_* bound by
  *                table_stride * P instead of the capacity)
  *   workspace    sized with nqkv_decode_paged_workspace_bytes(desc, max_seq_len or
- *                max(max_pos, 1), ...): one partial result per logical page (at most 1024 pages
- *                per sequence: NQKV_EUNSUPPORTED beyond); may be NULL when that size is 0
+ *                max(max_pos, 1), ...), which also reports into how many work items (runs of
+ *                whole pages) a sequence is cut; may be NULL when that size is 0
  * Results: as nqkv_decode_attention_varlen / nqkv_decode_step_varlen on the same tokens laid
  * out contiguously, up to the rounding of a different split.
+ * Errors: as those, plus NQKV_EUNSUPPORTED for a page size that is not a power of two >= 128.
  */
 int nqkv_decode_paged_workspace_bytes(const nqkv_cache_desc* desc, int64_t max_tokens,
-                                      size_t* bytes_out, int* pages_out);
+                                      size_t* bytes_out, int* items_out);
 int nqkv_decode_attention_paged(const nqkv_cache_desc* desc, const float* levels, const void* q,
                                 const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
                                 const int32_t* block_table, int64_t table_stride, int64_t num_pages,

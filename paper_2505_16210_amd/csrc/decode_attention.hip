@@ -249,6 +249,17 @@ __device__ __forceinline__ void v_axpy(const uint32_t (&w)[KBITS], float wgt, fl
   }
 }
 
+// ------------------------------------------------------------------ scalar reads
+// One 32-bit word from a wave-uniform address of read-only device memory (sequence lengths, the
+// block table), as a scalar load.  Left to the compiler such a read becomes a vector load
+// whose result -- and every address and buffer descriptor derived from it -- lives in vector
+// registers and has to be made uniform again before each use.
+__device__ __forceinline__ int32_t scalar_read(const int32_t* uniform_ptr) {
+  int32_t v;
+  asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(uniform_ptr) : "memory");
+  return v;
+}
+
 // ------------------------------------------------------------------ HBM loads
 // All cache reads are raw buffer loads: a scalar descriptor per item (base = first token of the
 // item's range, num_records = bytes of the range), one per-lane byte offset in a VGPR, and the
@@ -341,12 +352,13 @@ __device__ __forceinline__ void reduce_groups(const float (&acc)[32], uint32_t l
 // VARLEN: every sequence of the batch has its own number of cached tokens, read from device
 // memory (p.seq_lens[b], clamped to [0, p.max_len]); the split geometry is laid out for
 // p.max_len and each item keeps the part of its range that lies inside its sequence.
-// With p.block_table set (VARLEN kernels only) the cache is paged: see set_item.
+// PAGED (with VARLEN): the cache is a pool of pages behind a block table; token ranges stay
+// logical and every trip translates its start token to a page (see page_rows).
 // FUSE: the whole decode step of the paper in one launch -- items cover the tokens already
 // cached, rows [0, pos); the last wave of each sequence's last item quantizes the new token's
 // key and value rows (same code search as the quantizer), stores their codes and scales at row
 // pos, and adds the token to its softmax straight from registers.
-template <int KBITS, int D, int BLK, bool FUSE, bool SPLIT, bool VARLEN>
+template <int KBITS, int D, int BLK, bool FUSE, bool SPLIT, bool VARLEN, bool PAGED>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) void decode_kernel(const DecodeParams p) {   // 128 VGPRs: two workgroups per CU
   constexpr int LPT = D / 32;             // lanes per token
   constexpr int TPR = 64 / LPT;           // tokens per wave load
@@ -399,6 +411,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   int32_t n_tok = 0, base = 0;      // tokens in the item; this wave's current trip start (item-relative)
   int64_t pos = 0;                  // FUSE and VARLEN: the sequence's own row for the new token (else p.pos)
   __amdgpu_buffer_rsrc_t kc_r, vc_r, ks_r, vs_r;
+  // PAGED: the item's sequence, head and first token (logical), and the pool rows / row count
+  // of the trip whose K loads were issued last (its V loads follow at the top of the trip)
+  uint32_t item_b = 0, item_h = 0;
+  int32_t item_t0 = 0, trip_left = 0;
+  int64_t trip_rows = 0;
   __amdgpu_buffer_rsrc_t kn_r, vn_r;      // FUSE: the new token's rows, empty for waves that do not take it
   uint32_t newx[4] = {0, 0, 0, 0};        // FUSE: this lane's 16-byte chunk of those rows
   auto set_item = [&](uint32_t item) {
@@ -414,16 +431,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
     int64_t row0 = (int64_t)bh * p.cap_tokens + t0;
     if (VARLEN) {
       b = bh / (uint32_t)p.H; h = bh - b * (uint32_t)p.H;
-      const int32_t len = min(max(p.seq_lens[b], 0), p.max_len);     // whatever the array holds, stay inside the cache
+      const int32_t len = min(max(scalar_read(p.seq_lens + b), 0), p.max_len);     // whatever the array holds, stay inside the cache
       n_tok = min(n_tok, max(len - (int32_t)t0, 0));
       pos = len;
-      if (p.block_table) {
-        // paged cache: the item is logical page sp of its sequence (the host lays the splits
-        // out as pages: split_base = tokens per page); its rows are page block_table[b][sp] of
-        // the pool, pages being [H][tokens per page] rows each
-        const int32_t phys = min(max(p.block_table[(int64_t)b * p.table_stride + sp], 0), p.num_pages - 1);
-        row0 = ((int64_t)phys * p.H + h) * p.split_base;
-      }
+      if (PAGED) { item_b = b; item_h = h; item_t0 = (int32_t)t0; }
     }
     base = (int32_t)wave * CHUNK;
     kc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.k_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
@@ -467,6 +478,40 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
       sc[r] = __builtin_amdgcn_raw_buffer_load_b16(scales, sv + r * TPR * kScaleRowBytes, 0, 0);
     }
   };
+  // PAGED: pool rows of the trip that starts at item-relative token tb.  Items start at multiples
+  // of the page size and trips at multiples of CHUNK, which divides it, so a trip never straddles
+  // two pages.  Table index and entry are clamped: nothing the table holds (and no trip past the
+  // end of the sequence, whose row count is 0) can address memory outside the pool.
+  auto page_rows = [&](int32_t tb) {
+    const int32_t tok = item_t0 + tb;
+    const int32_t lp = min(tok >> p.page_shift, p.table_stride - 1);
+    const int32_t phys = min(max(scalar_read(p.block_table + ((int64_t)item_b * p.table_stride + lp)), 0), p.num_pages - 1);
+    trip_rows = ((((int64_t)phys * p.H + item_h)) << p.page_shift) + (tok & ((1 << p.page_shift) - 1));
+    // (the clamp selects as a vector instruction; without the readfirstlane the descriptors built
+    // from it would count as non-uniform and every load would run in a make-uniform loop)
+    trip_left = __builtin_amdgcn_readfirstlane(min(max(n_tok - tb, 0), CHUNK));
+  };
+  auto load_rows = [&](const uint8_t* codes, const uint16_t* scales,
+                       uint32_t (&w)[kRounds][KBITS], uint16_t (&sc)[kRounds]) {
+    const __amdgpu_buffer_rsrc_t cr = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(codes) + trip_rows * kRowBytes, 0, trip_left * (int)kRowBytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t sr = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(scales) + trip_rows * NB, 0, trip_left * (int)kScaleRowBytes, kBufferFlags);
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+      load_codes<KBITS>(cr, code_voff + r * TPR * kRowBytes, 0, w[r]);
+      sc[r] = __builtin_amdgcn_raw_buffer_load_b16(sr, scale_voff + r * TPR * kScaleRowBytes, 0, 0);
+    }
+  };
+  // K loads of the trip at tb; V loads of the trip whose K loads went out last
+  auto load_k = [&](int32_t tb) {
+    if constexpr (PAGED) { page_rows(tb); load_rows(p.k_codes, p.k_scales, kw, ksc); }
+    else load_trip(kc_r, ks_r, tb, kw, ksc);
+  };
+  auto load_v = [&](int32_t tb) {
+    if constexpr (PAGED) load_rows(p.v_codes, p.v_scales, vw, vsc);
+    else load_trip(vc_r, vs_r, tb, vw, vsc);
+  };
   auto load_q = [&]() {
     const uint4* qp = reinterpret_cast<const uint4*>(p.q + (int64_t)bh * D + j * 32);
 #pragma unroll
@@ -485,7 +530,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   uint32_t cell_thr = 0, cell_below = 0;
   if (FUSE) { cell_thr = p.cell_thr[lane]; cell_below = p.cell_below[lane]; }
   set_item(item);
-  load_trip(kc_r, ks_r, base, kw, ksc);
+  load_k(base);
   load_q();
   if (FUSE) load_new();
   build_lut<KBITS>(p, smem);          // ends with a barrier
@@ -580,7 +625,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
 
     for (; base < n_tok; base += stride) {
       const bool full = base + CHUNK <= n_tok;
-      load_trip(vc_r, vs_r, base, vw, vsc);
+      load_v(base);
 
       // scores of this trip's tokens (log2 domain)
       float z[kRounds];
@@ -609,7 +654,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
         l_run += pw[r];
       }
 
-      load_trip(kc_r, ks_r, base + stride, kw, ksc);     // past the end on the last trip: reads zeros
+      load_k(base + stride);     // past the end on the last trip: reads zeros
 
 #pragma unroll
       for (int r = 0; r < kRounds; ++r) {
@@ -626,7 +671,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
     const bool more = next_item < (uint32_t)p.n_items;
     if (more) {
       set_item(next_item);
-      load_trip(kc_r, ks_r, base, kw, ksc);
+      load_k(base);
       load_q();
       if (FUSE) load_new();
     }
@@ -658,11 +703,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
       // than where they are produced because stores share the loads' in-order memory counter:
       // issued ahead of the streaming loop, their acknowledgements would hold up its first trip.
       int64_t row = (int64_t)cur_bh * p.cap_tokens + (VARLEN ? cur_pos : p.pos);
-      if (VARLEN && p.block_table) {                  // paged: the row's page comes from the table
+      if (PAGED) {                                    // the row's page comes from the table
         const uint32_t cb = cur_bh / (uint32_t)p.H, ch = cur_bh - cb * (uint32_t)p.H;
-        const int32_t lp = (int32_t)(cur_pos / p.split_base);
-        const int32_t phys = min(max(p.block_table[(int64_t)cb * p.table_stride + lp], 0), p.num_pages - 1);
-        row = ((int64_t)phys * p.H + ch) * p.split_base + (cur_pos - (int64_t)lp * p.split_base);
+        const int32_t lp = min((int32_t)(cur_pos >> p.page_shift), p.table_stride - 1);
+        const int32_t phys = min(max(scalar_read(p.block_table + ((int64_t)cb * p.table_stride + lp)), 0), p.num_pages - 1);
+        row = ((((int64_t)phys * p.H + ch)) << p.page_shift) + (cur_pos & ((1 << p.page_shift) - 1));
       }
       if (tid < 2u * ROW) {
         const uint32_t t = tid / ROW, w = tid % ROW;
@@ -759,21 +804,23 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   }
 }
 
-template <int KBITS, int D, int BLK, bool VARLEN>
+template <int KBITS, int D, int BLK, bool VARLEN, bool PAGED>
 hipError_t launch_var(const DecodeParams& p, bool fuse, hipStream_t stream) {
   const int wgs = p.n_items < p.max_workgroups ? p.n_items : p.max_workgroups;
   const dim3 grid((unsigned)wgs), block(kThreads);
   const bool split = p.splits > 1;
-  if (fuse && split)       hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, true, true, VARLEN>), grid, block, 0, stream, p);
-  else if (fuse)           hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, true, false, VARLEN>), grid, block, 0, stream, p);
-  else if (split)          hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, false, true, VARLEN>), grid, block, 0, stream, p);
-  else                     hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, false, false, VARLEN>), grid, block, 0, stream, p);
+  if (fuse && split)       hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, true, true, VARLEN, PAGED>), grid, block, 0, stream, p);
+  else if (fuse)           hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, true, false, VARLEN, PAGED>), grid, block, 0, stream, p);
+  else if (split)          hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, false, true, VARLEN, PAGED>), grid, block, 0, stream, p);
+  else                     hipLaunchKernelGGL((decode_kernel<KBITS, D, BLK, false, false, VARLEN, PAGED>), grid, block, 0, stream, p);
   return hipGetLastError();
 }
 
 template <int KBITS, int D, int BLK>
 hipError_t launch_one(const DecodeParams& p, bool fuse, hipStream_t stream) {
-  return p.seq_lens ? launch_var<KBITS, D, BLK, true>(p, fuse, stream) : launch_var<KBITS, D, BLK, false>(p, fuse, stream);
+  if (p.block_table) return launch_var<KBITS, D, BLK, true, true>(p, fuse, stream);
+  return p.seq_lens ? launch_var<KBITS, D, BLK, true, false>(p, fuse, stream)
+                    : launch_var<KBITS, D, BLK, false, false>(p, fuse, stream);
 }
 
 template <int KBITS>

@@ -510,22 +510,42 @@ int nqkv_decode_step_varlen(const nqkv_cache_desc* desc, const float* levels,
 }
 
 // Paged cache: the pool holds num_pages pages of [H][P] rows (P = desc->cap_tokens tokens per
-// page); logical page j of sequence b is page block_table[b * table_stride + j].  One work item
-// per logical page; their partial results are combined like split-K partials.
-static int paged_pages(const nqkv_cache_desc* desc, int64_t n_cached) {
+// page, a power of two >= 128 so that no wave trip straddles two pages); logical page j of
+// sequence b is page block_table[b * table_stride + j].  A sequence is cut into work items of
+// whole pages, as many items as the contiguous calls would use splits.
+struct PagedPlan {
+  int page_shift;
+  int items;             // work items per sequence
+  int64_t item_tokens;   // tokens per item: a multiple of the page size
+};
+
+static int plan_paged(const nqkv_cache_desc* desc, int64_t n_cached, PagedPlan* plan) {
   const int64_t P = desc->cap_tokens;
+  if (P < 128 || (P & (P - 1)) != 0 || P > ((int64_t)1 << 24)) return NQKV_EUNSUPPORTED;
+  int shift = 0;
+  while (((int64_t)1 << shift) < P) ++shift;
   const int64_t pages = n_cached <= 0 ? 1 : (n_cached + P - 1) / P;
-  return pages > 1024 ? -1 : (int)pages;
+  const int64_t bh = (int64_t)desc->B * desc->H;
+  const int64_t target = g_decode_target_wgs > 0 ? g_decode_target_wgs : 256;
+  int64_t want = target / bh;
+  if (want > pages) want = pages;
+  if (want > 1024) want = 1024;
+  if (want < 1) want = 1;
+  const int64_t pages_per_item = (pages + want - 1) / want;
+  plan->page_shift = shift;
+  plan->items = (int)((pages + pages_per_item - 1) / pages_per_item);
+  plan->item_tokens = pages_per_item * P;
+  return NQKV_OK;
 }
 
-int nqkv_decode_paged_workspace_bytes(const nqkv_cache_desc* desc, int64_t max_tokens, size_t* bytes_out, int* pages_out) {
+int nqkv_decode_paged_workspace_bytes(const nqkv_cache_desc* desc, int64_t max_tokens, size_t* bytes_out, int* items_out) {
   int rc = check_desc(desc);
   if (rc) return rc;
   if (!bytes_out || max_tokens < 1) return NQKV_EINVAL;
-  const int pages = paged_pages(desc, max_tokens);
-  if (pages < 0) return NQKV_EUNSUPPORTED;
-  *bytes_out = workspace_need(desc, pages);
-  if (pages_out) *pages_out = pages;
+  PagedPlan plan;
+  if ((rc = plan_paged(desc, max_tokens, &plan))) return rc;
+  *bytes_out = workspace_need(desc, plan.items);
+  if (items_out) *items_out = plan.items;
   return NQKV_OK;
 }
 
@@ -547,12 +567,13 @@ static int decode_paged_impl(const nqkv_cache_desc* desc, const float* levels, c
   if (!lens || (reinterpret_cast<uintptr_t>(lens) & 3u) || !block_table || (reinterpret_cast<uintptr_t>(block_table) & 3u))
     return NQKV_EINVAL;
   if (num_pages < 1 || num_pages > ((int64_t)1 << 31) - 1) return NQKV_EINVAL;
-  const int pages = paged_pages(desc, n_cached);
-  if (pages < 0) return NQKV_EUNSUPPORTED;
+  PagedPlan plan;
+  if ((rc = plan_paged(desc, n_cached, &plan))) return rc;
   // table columns the kernel may look at: the pages of the cached tokens, and the page of the new row
-  const int64_t cols = fuse ? std::max<int64_t>(pages, n_cached / P + 1) : pages;
+  const int64_t cached_pages = n_cached <= 0 ? 0 : (n_cached + P - 1) / P;
+  const int64_t cols = std::max<int64_t>(1, fuse ? std::max<int64_t>(cached_pages, n_cached / P + 1) : cached_pages);
   if (table_stride < cols || table_stride > ((int64_t)1 << 31) - 1) return NQKV_EINVAL;
-  if (n_cached > ((int64_t)1 << 31) - 1 || P * (int64_t)(desc->D * desc->k / 8) >= ((int64_t)1 << 31)) return NQKV_EUNSUPPORTED;
+  if (n_cached + plan.item_tokens > ((int64_t)1 << 31) - 1) return NQKV_EUNSUPPORTED;
   if (!std::isfinite(softmax_scale)) return NQKV_EINVAL;
   const void* ptrs[] = {q, k_codes, k_scales, v_codes, v_scales, out};
   for (const void* ptr : ptrs) {
@@ -563,7 +584,7 @@ static int decode_paged_impl(const nqkv_cache_desc* desc, const float* levels, c
     if (new_stride_b < 0 || new_stride_h < 0 || (new_stride_b % 8) || (new_stride_h % 8)) return NQKV_EINVAL;
     if (!build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) return NQKV_EUNSUPPORTED;
   }
-  const size_t need = workspace_need(desc, pages);
+  const size_t need = workspace_need(desc, plan.items);
   if (need > 0) {
     if (!workspace || !aligned16(workspace)) return NQKV_EINVAL;
     if (workspace_bytes < need) return NQKV_EWORKSPACE;
@@ -576,9 +597,9 @@ static int decode_paged_impl(const nqkv_cache_desc* desc, const float* levels, c
   p.out = static_cast<uint16_t*>(out);
   p.tickets = static_cast<uint32_t*>(workspace);
   p.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kTicketBytes);
-  p.n_items = desc->B * desc->H * pages;
-  p.splits = pages;
-  p.split_base = (int)P;                               // item j of a sequence = its logical page j
+  p.n_items = desc->B * desc->H * plan.items;
+  p.splits = plan.items;
+  p.split_base = (int)plan.item_tokens;                // items are runs of whole pages
   p.split_rem = 0;
   p.max_workgroups = g_decode_grid_limit > 0 ? g_decode_grid_limit : max_decode_workgroups();
   p.cap_tokens = P;
@@ -596,6 +617,7 @@ static int decode_paged_impl(const nqkv_cache_desc* desc, const float* levels, c
   p.block_table = block_table;
   p.table_stride = (int)table_stride;
   p.num_pages = (int)num_pages;
+  p.page_shift = plan.page_shift;
   const hipError_t e = launch_decode_attention(p, desc->D, desc->k, desc->block, fuse, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
 }

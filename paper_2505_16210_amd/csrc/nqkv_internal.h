@@ -67,10 +67,11 @@ struct DecodeParams {
   int max_len;
   // paged cache (NULL: contiguous [B][H][cap_tokens] rows): physical page of logical page j of
   // sequence b at block_table[b * table_stride + j]; the pool holds num_pages pages of
-  // [H][split_base] rows; one item per logical page
+  // [H][1 << page_shift] rows; items cover split_base tokens, a multiple of the page size
   const int32_t* block_table;
   int table_stride;
   int num_pages;
+  int page_shift;
   uint32_t cell_thr[kQuantCells];
   uint32_t cell_below[kQuantCells];
 };

@@ -581,7 +581,7 @@ def _scatter_to_pages(contig, table, P):
     return pool
 
 
-@pytest.mark.parametrize("k,D,blk,P", [(4, 64, 64, 128), (4, 128, 64, 256), (3, 128, 128, 64), (2, 64, 64, 512)])
+@pytest.mark.parametrize("k,D,blk,P", [(4, 64, 64, 128), (4, 128, 64, 256), (3, 128, 128, 128), (2, 64, 64, 512)])
 def test_decode_attention_paged_matches_oracle(nqkv, oracle, k, D, blk, P):
     """The cache of every sequence scattered over a shuffled pool of pages (with unused pages in
     between): attention must equal the oracle's on the contiguous cache, sequence by sequence,
@@ -619,7 +619,7 @@ def test_decode_attention_paged_matches_oracle(nqkv, oracle, k, D, blk, P):
     assert attn_err(h2n(out2).view(np.float16)[:3], ref[:3]) <= ATTN_TOL
 
 
-@pytest.mark.parametrize("k,D,blk,P", [(4, 64, 64, 128), (3, 128, 64, 64), (2, 128, 128, 256)])
+@pytest.mark.parametrize("k,D,blk,P", [(4, 64, 64, 128), (3, 128, 64, 128), (2, 128, 128, 256)])
 def test_decode_step_paged_appends_into_pages(nqkv, oracle, k, D, blk, P):
     """Fused step over a paged cache: sequences at different positions (an empty one, one whose
     new row opens a fresh page, one in the middle of a page); pages filled with nqkv_quantize_kv

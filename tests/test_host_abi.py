@@ -213,9 +213,11 @@ def test_paged_argument_errors(nqkv):
     d = nqkv.make_desc(4, 8, 128, 4, 64, 256)                     # pages of 256 tokens
     assert nqkv.decode_paged_workspace_bytes(d, 256) == (0, 1)
     assert nqkv.decode_paged_workspace_bytes(d, 257) == (262144 + 4 * 8 * 2 * 130 * 4, 2)
-    with pytest.raises(nqkv.NqkvError) as e:
-        nqkv.decode_paged_workspace_bytes(d, 256 * 1024 + 1)      # more than 1024 pages per sequence
-    assert e.value.status == nqkv.EUNSUPPORTED
+    assert nqkv.decode_paged_workspace_bytes(d, 256 * 1024 + 1)[1] == 8        # 1025 pages in 8 runs of whole pages
+    for bad_page in (64, 192, 1000):                               # not a power of two >= 128
+        with pytest.raises(nqkv.NqkvError) as e:
+            nqkv.decode_paged_workspace_bytes(nqkv.make_desc(4, 8, 128, 4, 64, bad_page), 4096)
+        assert e.value.status == nqkv.EUNSUPPORTED
     fa, fs = nqkv.lib.nqkv_decode_attention_paged, nqkv.lib.nqkv_decode_step_paged
 
     def att(table=FAKE, stride=16, pages=100, lens=FAKE, mx=4096, ws=FAKE, ws_bytes=1 << 30, q=FAKE):
