@@ -441,6 +441,12 @@ def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, time
             def attend_paged(i):
                 nqkv.decode_attention_paged(pdesc, lv, q, *pools[i % r_cache], table, full, S, 1.0, out=out, workspace=pws)
 
+            def quant_paged(i):
+                ksrc, vsrc = srcs[i % r_src]
+                nqkv.quantize_kv_paged(pdesc, lv, ksrc, vsrc, *pools[i % r_cache], table, 0)
+
+            t_qp = tk(quant_paged, n_it, warm=max(2, r_cache))
+            kern[tag + ".quantize_paged"] = kernel_entry(qbytes, t_qp, page_tokens=P)
             t_pg = tk(attend_paged, n_it * 2, warm=max(2, r_cache))
             kern[tag + ".decode_attention_paged"] = kernel_entry(
                 packed + B * H * 4 * D + (2 * B * H * p_items * (D + 2) * 4 if p_items > 1 else 0), t_pg,

@@ -243,11 +243,11 @@ int nqkv_decode_step_varlen(const nqkv_cache_desc* desc, const float* levels,
                             void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream);
 
 /*
- * The two decode calls over a PAGED cache.  The pool is num_pages pages; a page holds P =
+ * The decode calls, and the quantizer, over a PAGED cache.  The pool is num_pages pages; a page holds P =
  * desc->cap_tokens tokens (a power of two, at least 128) of all H heads in the layout of a
  * one-sequence cache -- codes uint8 [num_pages][H][P][D*k/8], scales fp16
- * [num_pages][H][P][D/block] -- so a page can be filled with nqkv_quantize_kv on a desc with
- * B = 1 and pointers offset to the page.  Logical page j of sequence b (its tokens j*P ..
+ * [num_pages][H][P][D/block] (so a page can also be filled with nqkv_quantize_kv on a desc
+ * with B = 1 and pointers offset to the page).  Logical page j of sequence b (its tokens j*P ..
  * j*P+P-1) is page block_table[b*table_stride + j].
  *   block_table  device int32, 4-byte aligned; entries of pages that hold tokens (and, for the
  *                step, the page of row pos[b]) must be valid page numbers; indices and entries
@@ -262,6 +262,22 @@ int nqkv_decode_step_varlen(const nqkv_cache_desc* desc, const float* levels,
  * out contiguously, up to the rounding of a different split.
  * Errors: as those, plus NQKV_EUNSUPPORTED for a page size that is not a power of two >= 128.
  */
+/*
+ * nqkv_quantize_kv_pair into a paged cache (layout and block table as described above): tokens
+ * [dst_token_offset, dst_token_offset + n_tokens) of EVERY sequence of the batch go to the pages
+ * its row of the block table names -- prefill (offset 0) or a multi-token append.  The pages
+ * touched must be valid entries; n_tokens is the same for all sequences (call per sequence, with
+ * B = 1 and the sequence's table row, for ragged prompts).  v_* may all be NULL.
+ * Errors: as nqkv_quantize_kv, plus NQKV_EINVAL for a null / misaligned table or rows beyond
+ * table_stride * P, NQKV_EUNSUPPORTED for a page size that is not a power of two >= 128.
+ */
+int nqkv_quantize_kv_paged(const nqkv_cache_desc* desc, const float* levels,
+                           const void* k_src, const void* v_src,
+                           int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                           int64_t n_tokens, int64_t dst_token_offset,
+                           const int32_t* block_table, int64_t table_stride, int64_t num_pages,
+                           void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                           void* hip_stream);
 int nqkv_decode_paged_workspace_bytes(const nqkv_cache_desc* desc, int64_t max_tokens,
                                       size_t* bytes_out, int* items_out);
 int nqkv_decode_attention_paged(const nqkv_cache_desc* desc, const float* levels, const void* q,

@@ -44,6 +44,7 @@
 // cache and attended over; VARLEN, a length per sequence read from device memory.
 #include "code_search.h"
 #include "nqkv_internal.h"
+#include "scalar_read.h"
 
 namespace nqkv {
 namespace {
@@ -247,17 +248,6 @@ __device__ __forceinline__ void v_axpy(const uint32_t (&w)[KBITS], float wgt, fl
       acc[2 * pr + 1] = __builtin_fmaf((float)h.y, wgt, acc[2 * pr + 1]);
     }
   }
-}
-
-// ------------------------------------------------------------------ scalar reads
-// One 32-bit word from a wave-uniform address of read-only device memory (sequence lengths, the
-// block table), as a scalar load.  Left to the compiler such a read becomes a vector load
-// whose result -- and every address and buffer descriptor derived from it -- lives in vector
-// registers and has to be made uniform again before each use.
-__device__ __forceinline__ int32_t scalar_read(const int32_t* uniform_ptr) {
-  int32_t v;
-  asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(uniform_ptr) : "memory");
-  return v;
 }
 
 // ------------------------------------------------------------------ HBM loads

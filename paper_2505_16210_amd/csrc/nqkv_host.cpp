@@ -622,6 +622,59 @@ static int decode_paged_impl(const nqkv_cache_desc* desc, const float* levels, c
   return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
 }
 
+int nqkv_quantize_kv_paged(const nqkv_cache_desc* desc, const float* levels,
+                           const void* k_src, const void* v_src,
+                           int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                           int64_t n_tokens, int64_t dst_token_offset,
+                           const int32_t* block_table, int64_t table_stride, int64_t num_pages,
+                           void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                           void* hip_stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  QuantParams p;
+  std::memset(&p, 0, sizeof(p));
+  if ((rc = check_levels(levels, desc->k, &p.levels))) return rc;
+  PagedPlan plan;
+  if ((rc = plan_paged(desc, 1, &plan))) return rc;                // page size check
+  const int64_t P = desc->cap_tokens;
+  if (n_tokens < 0 || dst_token_offset < 0) return NQKV_EINVAL;
+  if (!block_table || (reinterpret_cast<uintptr_t>(block_table) & 3u)) return NQKV_EINVAL;
+  if (num_pages < 1 || num_pages > ((int64_t)1 << 31) - 1) return NQKV_EINVAL;
+  if (table_stride < 1 || table_stride > ((int64_t)1 << 31) - 1) return NQKV_EINVAL;
+  if (dst_token_offset + n_tokens > table_stride * P) return NQKV_EINVAL;        // rows beyond the table
+  if ((rc = check_strided(desc, stride_b, stride_h, stride_t, n_tokens))) return rc;
+  if (dst_token_offset + n_tokens >= ((int64_t)1 << 31) / (desc->D / 8)) return NQKV_EUNSUPPORTED;   // 32-bit chunk indices
+  if (n_tokens == 0) return NQKV_OK;
+  const bool pair = v_src || v_codes || v_scales;
+  if (!k_src || !k_codes || !k_scales || !aligned16(k_src) || !aligned16(k_codes) || !aligned16(k_scales))
+    return NQKV_EINVAL;
+  if (pair && (!v_src || !v_codes || !v_scales || !aligned16(v_src) || !aligned16(v_codes) || !aligned16(v_scales)))
+    return NQKV_EINVAL;
+  if ((int64_t)desc->B * 2 > 65535) return NQKV_EUNSUPPORTED;
+  p.t[0].src = static_cast<const uint16_t*>(k_src);
+  p.t[0].codes = static_cast<uint8_t*>(k_codes);
+  p.t[0].scales = static_cast<uint16_t*>(k_scales);
+  p.t[1].src = static_cast<const uint16_t*>(v_src);
+  p.t[1].codes = static_cast<uint8_t*>(v_codes);
+  p.t[1].scales = static_cast<uint16_t*>(v_scales);
+  p.n_tensors = pair ? 2 : 1;
+  p.B = desc->B;
+  p.H = desc->H;
+  p.stride_b = stride_b;
+  p.stride_h = stride_h;
+  p.stride_t = stride_t;
+  p.n_tokens = n_tokens;
+  p.tok_off = dst_token_offset;
+  p.cap_tokens = P;
+  p.impl = (g_quantize_impl == 0 && build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) ? 0 : 1;
+  p.block_table = block_table;
+  p.table_stride = (int)table_stride;
+  p.num_pages = (int)num_pages;
+  p.page_shift = plan.page_shift;
+  const hipError_t e = launch_quantize_paged(p, desc->D, desc->k, desc->block, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
+}
+
 int nqkv_decode_attention_paged(const nqkv_cache_desc* desc, const float* levels, const void* q,
                                 const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
                                 const int32_t* block_table, int64_t table_stride, int64_t num_pages,

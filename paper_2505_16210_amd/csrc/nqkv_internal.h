@@ -33,6 +33,12 @@ struct QuantParams {
   int64_t cap_tokens;
   LevelTable levels;
   int impl;              // 0 = cell-table quantizer, 1 = plain threshold scan
+  // paged destination (NULL: contiguous [B][H][cap_tokens] rows): page of logical page j of
+  // sequence b at block_table[b * table_stride + j], pages of [H][1 << page_shift] rows
+  const int32_t* block_table;
+  int table_stride;
+  int num_pages;
+  int page_shift;
   uint32_t cell_thr[kQuantCells];    // impl 0: fp32 bits of the threshold that may lie in the cell
   uint32_t cell_below[kQuantCells];  //         thresholds certainly below the cell
 };
@@ -84,6 +90,8 @@ constexpr size_t kTicketBytes = 65536 * sizeof(uint32_t);
 hipError_t launch_quantize(const QuantParams& p, int D, int k, int blk, hipStream_t stream);
 hipError_t launch_dequantize(const QuantParams& p, int D, int k, int blk, hipStream_t stream);
 // blocks of blk_hidden (128 or 256) consecutive elements of the token's hidden vector; cache with one scale per token-head
+// rows [tok_off, tok_off + n_tokens) of every sequence into the pages its block table names
+hipError_t launch_quantize_paged(const QuantParams& p, int D, int k, int blk, hipStream_t stream);
 hipError_t launch_quantize_hidden(const QuantParams& p, int D, int k, int blk_hidden, hipStream_t stream);
 // fuse: also quantize and append the new token (p.k_new / p.v_new) and attend over it
 hipError_t launch_decode_attention(const DecodeParams& p, int D, int k, int blk, bool fuse, hipStream_t stream);

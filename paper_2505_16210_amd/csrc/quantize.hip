@@ -24,6 +24,7 @@
 // it is within the cell widened by a margin larger than any error u can carry; a table for
 // which some widened cell would hold two thresholds is routed to the plain scan instead.
 #include "code_search.h"
+#include "scalar_read.h"
 #include "nqkv_internal.h"
 
 #include <cstring>
@@ -134,7 +135,7 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kBufferFlags = 0x00020000;       // raw buffer, 32-bit data format (gfx9 family)
 constexpr uint32_t kDropStore = 0xffffffffu;   // voffset outside every descriptor
 
-template <int KBITS, int D, int BLK, bool FAST, bool CONTIG>
+template <int KBITS, int D, int BLK, bool FAST, bool CONTIG, bool PAGED = false>
 __global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantParams p) {
   constexpr int CPR = D / 8;      // chunks per token row
   constexpr int LPB = BLK / 8;    // lanes that share one block
@@ -149,16 +150,32 @@ __global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantPara
   const uint32_t tensor = blockIdx.z >= (unsigned)p.B ? 1u : 0u;
   const uint32_t b = blockIdx.z - (tensor ? (uint32_t)p.B : 0u), h = blockIdx.y;
   const TensorPtrs tp = p.t[tensor];
-  const int64_t row0 = ((int64_t)b * p.H + h) * p.cap_tokens + p.tok_off;
   const uint32_t n = (uint32_t)p.n_tokens;
+  // PAGED: tiles are laid over ABSOLUTE token positions (tile T = tokens [T * kTileTok, ...)), so
+  // that a tile -- 64 or 128 tokens, which divides the page size -- lies inside one page
+  // whatever tok_off is; the tile's destination is that page's rows of head h.
+  constexpr uint32_t kTileTok = kThreads * kUnroll / CPR;
+  const uint32_t abs_tok0 = PAGED ? ((uint32_t)p.tok_off / kTileTok + blockIdx.x) * kTileTok : 0u;
+  int64_t row0 = ((int64_t)b * p.H + h) * p.cap_tokens + p.tok_off;
+  if (PAGED) {
+    const int32_t lp = min((int32_t)(abs_tok0 >> p.page_shift), p.table_stride - 1);
+    const int32_t phys = min(max(scalar_read(p.block_table + ((int64_t)b * p.table_stride + lp)), 0), p.num_pages - 1);
+    row0 = ((((int64_t)phys * p.H + h)) << p.page_shift) + (abs_tok0 & ((1u << p.page_shift) - 1u));
+  }
+  const uint32_t dst_rows = PAGED ? kTileTok : n;
   const __amdgpu_buffer_rsrc_t src_r = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint16_t*>(tp.src) + (int64_t)b * p.stride_b + (int64_t)h * p.stride_h, 0,
       (int)(((int64_t)(n - 1) * p.stride_t + D) * 2), kBufferFlags);
   const __amdgpu_buffer_rsrc_t code_r = __builtin_amdgcn_make_buffer_rsrc(
-      tp.codes + row0 * kRowBytes, 0, (int)(n * kRowBytes), kBufferFlags);
+      tp.codes + row0 * kRowBytes, 0, (int)(dst_rows * kRowBytes), kBufferFlags);
   const __amdgpu_buffer_rsrc_t scale_r = __builtin_amdgcn_make_buffer_rsrc(
-      tp.scales + row0 * NB, 0, (int)(n * NB * 2), kBufferFlags);
-  const uint32_t c0 = blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+      tp.scales + row0 * NB, 0, (int)(dst_rows * NB * 2), kBufferFlags);
+  // c0: this lane's first SOURCE chunk.  PAGED: absolute chunk minus the chunks before tok_off;
+  // for lanes of the first tile that lie before tok_off this wraps to a huge number: past the
+  // end, like the tail.  d0: the same lane's chunk inside the destination descriptor.
+  const uint32_t c0 = PAGED ? abs_tok0 * CPR + threadIdx.x - (uint32_t)p.tok_off * CPR
+                            : blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+  const uint32_t d0 = PAGED ? threadIdx.x : c0;
   const uint32_t total = n * CPR;
 
   uint4 w[kUnroll];
@@ -195,21 +212,22 @@ __global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantPara
 
     const uint32_t packed = encode_chunk<KBITS, FAST>(w[u], s_bits, p.levels, cells);
     const bool live = c < total;
+    const uint32_t dc = d0 + u * kThreads;               // chunk inside the destination descriptor
     if (KBITS == 4) {
-      __builtin_amdgcn_raw_buffer_store_b32(packed, code_r, live ? c * 4 : kDropStore, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b32(packed, code_r, live ? dc * 4 : kDropStore, 0, 0);
     } else if (KBITS == 2) {
       const uint32_t odd = dpp<kQuadOdd>(packed);
       const bool writer = live && !(threadIdx.x & 1);
-      __builtin_amdgcn_raw_buffer_store_b32(packed | (odd << 16), code_r, writer ? c * 2 : kDropStore, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b32(packed | (odd << 16), code_r, writer ? dc * 2 : kDropStore, 0, 0);
     } else {  // KBITS == 3: four lanes hold 4 x 24 bits = three dwords
       const uint32_t next = dpp<kQuadNext>(packed);
       const uint32_t q = threadIdx.x & 3;
       const uint32_t word = (packed >> (8 * q)) | (next << (24 - 8 * q));
       const bool writer = live && q != 3;
-      __builtin_amdgcn_raw_buffer_store_b32(word, code_r, writer ? (c >> 2) * 12 + q * 4 : kDropStore, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b32(word, code_r, writer ? (dc >> 2) * 12 + q * 4 : kDropStore, 0, 0);
     }
-    const bool scale_writer = live && (c % LPB) == 0;
-    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)s_bits, scale_r, scale_writer ? (c / LPB) * 2 : kDropStore, 0, 0);
+    const bool scale_writer = live && (dc % LPB) == 0;
+    __builtin_amdgcn_raw_buffer_store_b16((unsigned short)s_bits, scale_r, scale_writer ? (dc / LPB) * 2 : kDropStore, 0, 0);
   }
 }
 
@@ -407,6 +425,38 @@ bool build_cell_table(const float* levels, int k, uint32_t* thr_bits, uint32_t* 
     below[c] = n_below;
   }
   return true;
+}
+
+namespace {
+template <int KBITS, int D, int BLK>
+hipError_t launch_paged_one(const QuantParams& p, hipStream_t stream) {
+  constexpr int kTileTok = kThreads * kUnroll / (D / 8);
+  const int64_t first = p.tok_off / kTileTok, last = (p.tok_off + p.n_tokens - 1) / kTileTok;
+  const dim3 grid((unsigned)(last - first + 1), (unsigned)p.H, (unsigned)(p.B * p.n_tensors));
+  const bool fast = p.impl == 0, contig = p.stride_t == D;
+  if (fast && contig)       hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, true, true, true>), grid, dim3(kThreads), 0, stream, p);
+  else if (fast)            hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, true, false, true>), grid, dim3(kThreads), 0, stream, p);
+  else if (contig)          hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, false, true, true>), grid, dim3(kThreads), 0, stream, p);
+  else                      hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, false, false, true>), grid, dim3(kThreads), 0, stream, p);
+  return hipGetLastError();
+}
+
+template <int KBITS>
+hipError_t launch_paged_k(const QuantParams& p, int D, int blk, hipStream_t stream) {
+  if (D == 64 && blk == 64) return launch_paged_one<KBITS, 64, 64>(p, stream);
+  if (D == 128 && blk == 64) return launch_paged_one<KBITS, 128, 64>(p, stream);
+  if (D == 128 && blk == 128) return launch_paged_one<KBITS, 128, 128>(p, stream);
+  return hipErrorInvalidValue;
+}
+}  // namespace
+
+hipError_t launch_quantize_paged(const QuantParams& p, int D, int k, int blk, hipStream_t stream) {
+  switch (k) {
+    case 2: return launch_paged_k<2>(p, D, blk, stream);
+    case 3: return launch_paged_k<3>(p, D, blk, stream);
+    case 4: return launch_paged_k<4>(p, D, blk, stream);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 hipError_t launch_quantize_hidden(const QuantParams& p, int D, int k, int blk_hidden, hipStream_t stream) {

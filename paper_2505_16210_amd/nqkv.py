@@ -23,7 +23,8 @@ EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_set_tuning", "nqkv_build_codeb
            "nqkv_decode_workspace_bytes", "nqkv_decode_attention", "nqkv_decode_step",
            "nqkv_probe_read_stream", "nqkv_quantize_kv_hidden",
            "nqkv_decode_attention_varlen", "nqkv_decode_step_varlen",
-           "nqkv_decode_paged_workspace_bytes", "nqkv_decode_attention_paged", "nqkv_decode_step_paged")
+           "nqkv_decode_paged_workspace_bytes", "nqkv_decode_attention_paged", "nqkv_decode_step_paged",
+           "nqkv_quantize_kv_paged")
 
 
 class CacheDesc(ctypes.Structure):
@@ -75,6 +76,8 @@ def _load() -> ctypes.CDLL:
     lib.nqkv_decode_step_varlen.restype = i32
     lib.nqkv_decode_step_varlen.argtypes = [dp, fp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp, i64, c.c_float, vp, vp,
                                             c.c_size_t, i32, vp]
+    lib.nqkv_quantize_kv_paged.restype = i32
+    lib.nqkv_quantize_kv_paged.argtypes = [dp, fp, vp, vp, i64, i64, i64, i64, i64, vp, i64, i64, vp, vp, vp, vp, vp]
     lib.nqkv_decode_paged_workspace_bytes.restype = i32
     lib.nqkv_decode_paged_workspace_bytes.argtypes = [dp, i64, c.POINTER(c.c_size_t), c.POINTER(i32)]
     lib.nqkv_decode_attention_paged.restype = i32
@@ -342,6 +345,22 @@ def _table_arg(block_table: torch.Tensor, B: int):
     assert block_table.dtype == torch.int32 and block_table.dim() == 2 and block_table.shape[0] == B
     assert block_table.is_cuda and block_table.stride(1) == 1
     return _dev_ptr(block_table), block_table.stride(0)
+
+
+def quantize_kv_paged(desc: CacheDesc, levels, k_src: torch.Tensor, v_src, k_codes, k_scales, v_codes, v_scales,
+                      block_table: torch.Tensor, dst_token_offset: int = 0, stream=None) -> None:
+    """nqkv_quantize_kv_paged: k_src (and v_src or None) fp16 [B,H,n,D] -> rows [off, off+n) of every
+    sequence, in the pages its block-table row names."""
+    lv, lvp = _levels_ptr(levels)
+    sb, sh, st = _src_strides(k_src)
+    if v_src is not None:
+        assert v_src.shape == k_src.shape and v_src.stride() == k_src.stride()
+    tp, ts = _table_arg(block_table, desc.B)
+    rc = lib.nqkv_quantize_kv_paged(ctypes.byref(desc), lvp, _dev_ptr(k_src), _dev_ptr(v_src), sb, sh, st,
+                                    k_src.shape[2], dst_token_offset, tp, ts, k_codes.shape[0],
+                                    _dev_ptr(k_codes), _dev_ptr(k_scales), _dev_ptr(v_codes), _dev_ptr(v_scales),
+                                    _stream(stream))
+    _check(rc, "nqkv_quantize_kv_paged")
 
 
 def decode_attention_paged(desc: CacheDesc, levels, q, k_codes, k_scales, v_codes, v_scales,

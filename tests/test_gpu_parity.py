@@ -681,3 +681,54 @@ def test_decode_step_paged_appends_into_pages(nqkv, oracle, k, D, blk, P):
         assert np.array_equal(gather(vcp, rows), ovc) and np.array_equal(gather(vsp, rows), ovs), step
         err = attn_err(h2n(out).view(np.float16), np.concatenate(refs, 0))
         assert err <= ATTN_TOL, (step, err)
+
+
+@pytest.mark.parametrize("impl", [0, 1])
+@pytest.mark.parametrize("k,D,blk,P", [(4, 64, 64, 128), (4, 128, 64, 256), (3, 64, 64, 256), (3, 128, 128, 128),
+                                        (2, 128, 64, 128), (2, 64, 64, 512)])
+def test_quantize_paged_bit_exact(nqkv, oracle, k, D, blk, P, impl):
+    """The paged quantizer: a prefill from offset 0 that ends in the middle of a page, then an
+    append that starts there and crosses page boundaries, K and V in one launch, from a strided
+    (token-major) source.  The pool, gathered back through the block table, must equal the
+    oracle's contiguous cache bit for bit, and pages no sequence owns stay untouched."""
+    B, H, n_pages_seq = 3, 2, 4
+    cap = n_pages_seq * P
+    n1, n2 = P + P // 2 + 3, P + 29                       # prefill, then append across a boundary
+    lv = nqkv.build_codebook(k)
+    g = torch.Generator(device="cuda").manual_seed(3 * k + D + P)
+    Kt = (torch.randn(B, cap, H, D, device="cuda", generator=g) *
+          torch.exp(torch.randn(B, cap, 1, 1, device="cuda", generator=g))).to(torch.float16)
+    Vt = torch.randn(B, cap, H, D, device="cuda", generator=g).to(torch.float16)
+    Kv, Vv = Kt.transpose(1, 2), Vt.transpose(1, 2)       # [B,H,cap,D] views of token-major storage
+    num_pages = B * n_pages_seq + 3
+    perm = torch.randperm(num_pages, generator=torch.Generator().manual_seed(P + k))[:B * n_pages_seq]
+    table = perm.reshape(B, n_pages_seq).to(torch.int32).cuda()
+    pdesc = nqkv.make_desc(B, H, D, k, blk, P)
+    kcp, ksp = nqkv.alloc_paged_pool(pdesc, num_pages)
+    vcp, vsp = nqkv.alloc_paged_pool(pdesc, num_pages)
+    for t in (kcp, vcp):
+        t.fill_(0xAB)                                      # untouched rows must keep this
+    nqkv.set_tuning(0, impl)
+    try:
+        nqkv.quantize_kv_paged(pdesc, lv, Kv[:, :, :n1], Vv[:, :, :n1], kcp, ksp, vcp, vsp, table, 0)
+        nqkv.quantize_kv_paged(pdesc, lv, Kv[:, :, n1:n1 + n2], Vv[:, :, n1:n1 + n2], kcp, ksp, vcp, vsp, table, n1)
+        torch.cuda.synchronize()
+    finally:
+        nqkv.set_tuning(0, 0)
+    n = n1 + n2
+    okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
+    ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
+    oracle.quantize_kv(h2n(Kv[:, :, :n]), k, blk, lv, okc, oks, n_threads=8)
+    oracle.quantize_kv(h2n(Vv[:, :, :n]), k, blk, lv, ovc, ovs, n_threads=8)
+    tb = table.cpu().numpy()
+    for pool, ref, fill in ((kcp, okc, 0xAB), (ksp, oks, 0), (vcp, ovc, 0xAB), (vsp, ovs, 0)):
+        hp = h2n(pool)
+        for b in range(B):
+            for j in range(n_pages_seq):
+                rows = max(0, min(P, n - j * P))
+                assert np.array_equal(hp[tb[b, j], :, :rows], ref[b, :, j * P:j * P + rows]), (b, j)
+                assert (hp[tb[b, j], :, rows:] == fill).all(), (b, j)        # rows past the sequence: untouched
+        owned = set(tb.reshape(-1).tolist())
+        for pg in range(num_pages):
+            if pg not in owned:
+                assert (hp[pg] == fill).all(), pg

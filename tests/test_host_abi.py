@@ -243,6 +243,29 @@ def test_paged_argument_errors(nqkv):
     assert step(mx=-1) == nqkv.EINVAL
 
 
+def test_quantize_paged_argument_errors(nqkv):
+    lv, lvp = _levels(nqkv)
+    d = nqkv.make_desc(2, 8, 64, 4, 64, 256)                      # pages of 256 tokens
+    f = nqkv.lib.nqkv_quantize_kv_paged
+
+    def call(desc=d, n=300, off=0, table=FAKE, stride=4, pages=50, ks=FAKE, kc=FAKE, ksc=FAKE, vs=None, vc=None,
+             vsc=None, st=64):
+        return f(ctypes.byref(desc), lvp, ks, vs, 8 * 300 * 64, 300 * 64, st, n, off, table, stride, pages,
+                 kc, ksc, vc, vsc, None)
+
+    assert call(n=0) == nqkv.OK
+    assert call(table=None) == nqkv.EINVAL
+    assert call(table=FAKE + 1) == nqkv.EINVAL
+    assert call(pages=0) == nqkv.EINVAL
+    assert call(stride=1) == nqkv.EINVAL                          # 300 tokens need two table columns
+    assert call(off=800) == nqkv.EINVAL                           # 800 + 300 tokens: beyond four pages
+    assert call(off=-1) == nqkv.EINVAL
+    assert call(ks=None) == nqkv.EINVAL
+    assert call(vs=FAKE) == nqkv.EINVAL
+    assert call(st=60) == nqkv.EINVAL
+    assert call(desc=nqkv.make_desc(2, 8, 64, 4, 64, 100)) == nqkv.EUNSUPPORTED   # page size not a power of two
+
+
 def test_quantize_hidden_argument_errors(nqkv):
     lv, lvp = _levels(nqkv)
     f = nqkv.lib.nqkv_quantize_kv_hidden
