@@ -265,13 +265,13 @@ def main():
     eff_bytes = 2 * (elems_quant + elems_attn)
     value = eff_bytes / (ms_per_step * 1e-3) / 1e9
 
-    traffic_ratio = 1.0032 if args.two_launch else 1.0064
+    traffic_ratio = 1.0032 if args.two_launch else 1.0062
     roofline = {"kernel": "decode_kernel<4,64,64,%s>" % ("false" if args.two_launch else "true"), "bound": "hbm",
                 "achieved": round(dec_bytes / (t_att * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(dec_bytes / (t_att * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                 "bytes_per_launch": int(dec_bytes), "avg_launch_us": round(t_att * 1e3, 2),
                 # HBM bytes of one launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a 1 GiB copy
-                # kernel: x2.000 / x1.000), measured at 2048 tokens: 1.0064 x algorithmic for the fused
+                # kernel: x2.000 / x1.000), measured at 2048 tokens: 1.0062 x algorithmic for the fused
                 # step, 1.0032 x for attention alone
                 # (profiles/hbm_traffic_counters_c2_quantize_decode_fused_step.txt)
                 "traffic": int(round(dec_bytes * traffic_ratio)),

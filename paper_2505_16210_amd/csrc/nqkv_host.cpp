@@ -382,6 +382,35 @@ int nqkv_decode_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, in
   return NQKV_OK;
 }
 
+// The part of DecodeParams every decode entry point fills the same way.
+static void fill_decode_common(DecodeParams* p, const nqkv_cache_desc* desc, const LevelTable& checked,
+                               const void* q, const void* k_new, const void* v_new,
+                               int64_t new_stride_b, int64_t new_stride_h,
+                               const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                               float softmax_scale, void* out, void* workspace, int items_per_sequence) {
+  p->q = static_cast<const uint16_t*>(q);
+  p->k_codes = static_cast<const uint8_t*>(k_codes);
+  p->k_scales = static_cast<const uint16_t*>(k_scales);
+  p->v_codes = static_cast<const uint8_t*>(v_codes);
+  p->v_scales = static_cast<const uint16_t*>(v_scales);
+  p->out = static_cast<uint16_t*>(out);
+  p->tickets = static_cast<uint32_t*>(workspace);
+  p->partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kTicketBytes);
+  p->n_items = desc->B * desc->H * items_per_sequence;
+  p->splits = items_per_sequence;
+  p->max_workgroups = g_decode_grid_limit > 0 ? g_decode_grid_limit : max_decode_workgroups();
+  p->cap_tokens = desc->cap_tokens;
+  const LutChoice& lut = choose_lut_scale(checked.v, 1 << desc->k);
+  std::memcpy(p->lut_levels, lut.bits, sizeof(uint16_t) * (1 << desc->k));
+  p->inv_gamma = 1.0f / lut.gamma;
+  p->scale_log2e = (float)((double)softmax_scale * 1.44269504088896340736 / (double)lut.gamma);
+  p->k_new = static_cast<const uint16_t*>(k_new);
+  p->v_new = static_cast<const uint16_t*>(v_new);
+  p->new_stride_b = new_stride_b;
+  p->new_stride_h = new_stride_h;
+  p->H = desc->H;
+}
+
 // Shared by nqkv_decode_attention (k_new == nullptr) and nqkv_decode_step.
 static int decode_impl(const nqkv_cache_desc* desc, const float* levels, const void* q,
                        const void* k_new, const void* v_new, int64_t new_stride_b, int64_t new_stride_h,
@@ -433,30 +462,11 @@ static int decode_impl(const nqkv_cache_desc* desc, const float* levels, const v
     return decode_impl(desc, levels, q, nullptr, nullptr, 0, 0, nullptr, k_codes, k_scales, v_codes, v_scales, seq_len,
                        softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
   }
-  p.q = static_cast<const uint16_t*>(q);
-  p.k_codes = static_cast<const uint8_t*>(k_codes);
-  p.k_scales = static_cast<const uint16_t*>(k_scales);
-  p.v_codes = static_cast<const uint8_t*>(v_codes);
-  p.v_scales = static_cast<const uint16_t*>(v_scales);
-  p.out = static_cast<uint16_t*>(out);
-  p.tickets = static_cast<uint32_t*>(workspace);
-  p.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kTicketBytes);
-  p.n_items = desc->B * desc->H * splits;
-  p.splits = splits;
+  fill_decode_common(&p, desc, checked, q, k_new, v_new, new_stride_b, new_stride_h, k_codes, k_scales, v_codes, v_scales,
+                     softmax_scale, out, workspace, splits);
   p.split_base = (int)(n_cached / splits);
   p.split_rem = (int)(n_cached % splits);
-  p.max_workgroups = g_decode_grid_limit > 0 ? g_decode_grid_limit : max_decode_workgroups();
-  p.cap_tokens = desc->cap_tokens;
-  const LutChoice& lut = choose_lut_scale(checked.v, 1 << desc->k);
-  std::memcpy(p.lut_levels, lut.bits, sizeof(uint16_t) * (1 << desc->k));
-  p.inv_gamma = 1.0f / lut.gamma;
-  p.scale_log2e = (float)((double)softmax_scale * 1.44269504088896340736 / (double)lut.gamma);
-  p.k_new = static_cast<const uint16_t*>(k_new);
-  p.v_new = static_cast<const uint16_t*>(v_new);
-  p.new_stride_b = new_stride_b;
-  p.new_stride_h = new_stride_h;
   p.pos = seq_len - 1;
-  p.H = desc->H;
   p.seq_lens = lens;                                    // fused: lens[b] = cached rows = the new token's row
   p.max_len = (int)n_cached;
   const hipError_t e = launch_decode_attention(p, desc->D, desc->k, desc->block, fuse, stream);
@@ -589,29 +599,10 @@ static int decode_paged_impl(const nqkv_cache_desc* desc, const float* levels, c
     if (!workspace || !aligned16(workspace)) return NQKV_EINVAL;
     if (workspace_bytes < need) return NQKV_EWORKSPACE;
   }
-  p.q = static_cast<const uint16_t*>(q);
-  p.k_codes = static_cast<const uint8_t*>(k_codes);
-  p.k_scales = static_cast<const uint16_t*>(k_scales);
-  p.v_codes = static_cast<const uint8_t*>(v_codes);
-  p.v_scales = static_cast<const uint16_t*>(v_scales);
-  p.out = static_cast<uint16_t*>(out);
-  p.tickets = static_cast<uint32_t*>(workspace);
-  p.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kTicketBytes);
-  p.n_items = desc->B * desc->H * plan.items;
-  p.splits = plan.items;
+  fill_decode_common(&p, desc, checked, q, k_new, v_new, new_stride_b, new_stride_h, k_codes, k_scales, v_codes, v_scales,
+                     softmax_scale, out, workspace, plan.items);
   p.split_base = (int)plan.item_tokens;                // items are runs of whole pages
   p.split_rem = 0;
-  p.max_workgroups = g_decode_grid_limit > 0 ? g_decode_grid_limit : max_decode_workgroups();
-  p.cap_tokens = P;
-  const LutChoice& lut = choose_lut_scale(checked.v, 1 << desc->k);
-  std::memcpy(p.lut_levels, lut.bits, sizeof(uint16_t) * (1 << desc->k));
-  p.inv_gamma = 1.0f / lut.gamma;
-  p.scale_log2e = (float)((double)softmax_scale * 1.44269504088896340736 / (double)lut.gamma);
-  p.k_new = static_cast<const uint16_t*>(k_new);
-  p.v_new = static_cast<const uint16_t*>(v_new);
-  p.new_stride_b = new_stride_b;
-  p.new_stride_h = new_stride_h;
-  p.H = desc->H;
   p.seq_lens = lens;
   p.max_len = (int)n_cached;
   p.block_table = block_table;
