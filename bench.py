@@ -215,6 +215,12 @@ def main():
     per_tok = workloads.decode_bytes_per_token_head(D, k, blk)
     fused_bytes = dec_bytes - B * H * per_tok + B * H * (2 * D * 2 + per_tok)
     kern["C2.decode_step_fused"] = kernel_entry(fused_bytes, t_fused, splits=splits)
+    if args.cold:
+        # labelled cache-warm: the same launch over ONE cache copy, which the 256 MB last-level cache keeps
+        t_warm = tk(lambda i: nqkv.decode_step(desc, lv, qs[i % steps_dec], *new_views[i % steps_dec], *caches[0],
+                                               S + (i % steps_dec), 1.0, out=out, workspace=ws), steps_dec * 2)
+        kern["C2.decode_step_fused.cache_warm"] = kernel_entry(fused_bytes, t_warm, splits=splits,
+                                                                note="one cache copy, served from the last-level cache")
     if not args.two_launch:
         dec_bytes, t_att = fused_bytes, t_fused          # the dominant kernel of the timed step
 
@@ -248,13 +254,18 @@ def main():
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_host0 = time.perf_counter()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]     # per-step marks: median, min
     e0.record(stream)
+    marks[0].record(stream)
     for s in range(args.steps):
         run_step(args.warmup + s)
+        marks[s + 1].record(stream)
     e1.record(stream)
     torch.cuda.synchronize()
     host_ms = (time.perf_counter() - t_host0) * 1e3 / args.steps
     ms_per_step = e0.elapsed_time(e1) / args.steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    ms_median, ms_min = per_step[len(per_step) // 2], per_step[0]
 
     # decode-step time as it runs inside the step (graph: no launch gaps)
     t_decode_step = max(ms_per_step - t_pre, 0.0) / steps_dec
@@ -300,7 +311,8 @@ def main():
         "metric": "effective KV GB/s (quantize + fused decode attn) & decode tokens/s/layer",
         "value": round(value, 1), "unit": "GB/s (fp16-equivalent KV bytes processed per second)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": round(ms_per_step, 4), "ms_per_step_median": round(ms_median, 4),
+        "ms_per_step_min": round(ms_min, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "C2 OPT-1.3B-shaped layer: B8 H32 D64, 4-bit block 64, quantize 2048-token "
                                "prefill + 128 x (append 1 token + fused decode attention, %s); "
