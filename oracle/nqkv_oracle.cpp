@@ -429,4 +429,36 @@ int oracle_decode_attention(const uint16_t* q,
   return 0;
 }
 
+// Decode attention for q_len new queries per (batch, head) (several tokens appended in one step:
+// Sec. 1, the cache is append-only and new keys/values go to its end; Sec. 3.2 decoding-phase
+// equations applied to each new token in turn).  The queries belong to the LAST q_len tokens of
+// the first seq_len cached tokens, so query i sees what a one-token step at that position would:
+// tokens [0, seq_len - q_len + 1 + i).  fp64 attention over the exact dequantized values.
+//   q    fp16 bits [B, H, q_len, D] contiguous;  out double [B, H, q_len, D];  caches as above
+int oracle_decode_attention_multi(const uint16_t* q,
+                                  const uint8_t* k_codes, const uint16_t* k_scales,
+                                  const uint8_t* v_codes, const uint16_t* v_scales,
+                                  int B, int H, int D, int k, int blk, const float* levels32,
+                                  int64_t cap_tokens, int64_t seq_len, int q_len, float softmax_scale,
+                                  double* out, int n_threads) {
+  if (k < 1 || k > 8 || blk < 1 || D % blk != 0 || (D * k) % 8 != 0) return -1;
+  if (q_len < 1 || seq_len < q_len || seq_len > cap_tokens) return -1;
+  const int nb = D / blk;
+  const int64_t row_bytes = (int64_t)D * k / 8;
+  run_parallel((int64_t)B * H, n_threads, [&](int64_t bh) {
+    std::vector<double> qd(D), Kx((size_t)seq_len * D), Vx((size_t)seq_len * D);
+    oracle_dequantize_slab_f64(k_codes + bh * cap_tokens * row_bytes, k_scales + bh * cap_tokens * nb,
+                               D, k, blk, levels32, seq_len, Kx.data());
+    oracle_dequantize_slab_f64(v_codes + bh * cap_tokens * row_bytes, v_scales + bh * cap_tokens * nb,
+                               D, k, blk, levels32, seq_len, Vx.data());
+    for (int i = 0; i < q_len; ++i) {
+      const int64_t visible = seq_len - q_len + 1 + i;
+      for (int d = 0; d < D; ++d) qd[d] = (double)half_bits_to_float(q[(bh * q_len + i) * D + d]);
+      oracle_attention_f64(qd.data(), Kx.data(), Vx.data(), visible, D, (double)softmax_scale,
+                           out + (bh * q_len + i) * D);
+    }
+  });
+  return 0;
+}
+
 }  // extern "C"

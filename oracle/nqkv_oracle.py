@@ -75,6 +75,10 @@ def _load():
             lib.oracle_dequantize_slab_f64.restype = None
             lib.oracle_dequantize_slab_f64.argtypes = [p, p, c.c_int, c.c_int, c.c_int, p, c.c_int64, p]
             lib.oracle_decode_attention.restype = c.c_int
+            lib.oracle_decode_attention_multi.argtypes = [p, p, p, p, p, c.c_int, c.c_int, c.c_int, c.c_int,
+                                                          c.c_int, p, c.c_int64, c.c_int64, c.c_int,
+                                                          c.c_float, p, c.c_int]
+            lib.oracle_decode_attention_multi.restype = c.c_int
             lib.oracle_decode_attention.argtypes = [p, p, p, p, p, c.c_int, c.c_int, c.c_int, c.c_int,
                                                     c.c_int, p, c.c_int64, c.c_int64, c.c_float,
                                                     p, c.c_int]
@@ -249,4 +253,25 @@ def decode_attention(q, k_codes, k_scales, v_codes, v_scales, k: int, blk: int, 
                                          float(softmax_scale), _ptr(out), n_threads)
     if rc != 0:
         raise ValueError("oracle_decode_attention: bad argument")
+    return out
+
+
+def decode_attention_multi(q, k_codes, k_scales, v_codes, v_scales, k: int, blk: int, levels32,
+                           seq_len: int, softmax_scale: float = 1.0, n_threads: int = 1) -> np.ndarray:
+    """q fp16 [B,H,Q,D], the queries of the last Q of the first seq_len cached tokens -> fp64 [B,H,Q,D]."""
+    q = np.ascontiguousarray(_as_u16(q))
+    B, H, Q, D = q.shape
+    cap = k_codes.shape[2]
+    for a in (k_codes, k_scales, v_codes, v_scales):
+        assert a.flags.c_contiguous
+    assert k_codes.shape == v_codes.shape == (B, H, cap, D * k // 8)
+    assert k_scales.shape == v_scales.shape == (B, H, cap, D // blk)
+    lv = np.ascontiguousarray(levels32, np.float32)
+    out = np.zeros((B, H, Q, D), np.float64)
+    rc = _load().oracle_decode_attention_multi(_ptr(q), _ptr(k_codes), _ptr(_as_u16(k_scales)),
+                                               _ptr(v_codes), _ptr(_as_u16(v_scales)),
+                                               B, H, D, k, blk, _ptr(lv), cap, seq_len, Q,
+                                               float(softmax_scale), _ptr(out), n_threads)
+    if rc != 0:
+        raise ValueError("oracle_decode_attention_multi: bad argument")
     return out

@@ -532,6 +532,64 @@ def test_decode_attention_is_attention_over_dequantized_values(oracle, k, blk, D
             assert np.allclose(got[b, h], ref, rtol=1e-11, atol=1e-13)
 
 
+@pytest.mark.parametrize("k,blk,D,Q", [(4, 64, 64, 4), (4, 64, 128, 7), (3, 64, 128, 2), (2, 128, 128, 16)])
+def test_decode_attention_multi_is_causal_attention(oracle, k, blk, D, Q):
+    """Several new tokens in one step: query i is the query of cached token S-Q+i and sees tokens
+    [0, S-Q+1+i).  Pinned against (a) the masked-matrix form of causal softmax attention over values
+    decoded independently in numpy, (b) the one-query function at each position, (c) what changing a
+    hidden / a visible cache row does."""
+    B, H, S, cap = 2, 2, 45, 50
+    _, l32, _ = oracle.codebook(k)
+    Kx = (RNG.standard_normal((B, H, cap, D)) * 1.5).astype(np.float16)
+    Vx = RNG.standard_normal((B, H, cap, D)).astype(np.float16)
+    q = (RNG.standard_normal((B, H, Q, D)) / math.sqrt(D)).astype(np.float16)
+    kc, ks = oracle.new_cache(B, H, D, k, blk, cap)
+    vc, vs = oracle.new_cache(B, H, D, k, blk, cap)
+    oracle.quantize_kv(Kx, k, blk, l32, kc, ks)
+    oracle.quantize_kv(Vx, k, blk, l32, vc, vs)
+    sigma = 0.8
+    got = oracle.decode_attention_multi(q, kc, ks, vc, vs, k, blk, l32, S, sigma, n_threads=2)
+    assert got.shape == (B, H, Q, D)
+
+    def decode_numpy(codes, scales):
+        bits = np.unpackbits(codes, axis=-1, bitorder="little").reshape(B, H, cap, D, k)
+        c = (bits.astype(np.int64) << np.arange(k)).sum(-1)
+        s = np.repeat(scales.view(np.float16).astype(np.float64), blk, axis=-1)
+        return l32.astype(np.float64)[c] * s
+
+    # (a) whole score matrix, lower-triangular mask aligned to the END of the sequence
+    Kd, Vd = decode_numpy(kc, ks)[:, :, :S], decode_numpy(vc, vs)[:, :, :S]
+    z = float(np.float32(sigma)) * np.einsum("bhqd,bhtd->bhqt", q.astype(np.float64), Kd)
+    tok = np.arange(S)[None, :]
+    qpos = (S - Q + np.arange(Q))[:, None]
+    z = np.where(tok <= qpos, z, -np.inf)
+    w = np.exp(z - z.max(-1, keepdims=True))
+    ref = np.einsum("bhqt,bhtd->bhqd", w / w.sum(-1, keepdims=True), Vd)
+    assert np.allclose(got, ref, rtol=1e-11, atol=1e-13)
+    # (b) row i == the one-query step at sequence length S-Q+1+i
+    for i in range(Q):
+        one = oracle.decode_attention(np.ascontiguousarray(q[:, :, i]), kc, ks, vc, vs, k, blk, l32, S - Q + 1 + i, sigma)
+        assert np.allclose(got[:, :, i], one, rtol=1e-13, atol=1e-15)
+    # (c) a row only later queries may see: rewriting row S-Q+j changes queries >= j and no earlier one
+    if Q >= 2:
+        j = Q // 2
+        kc2, vc2 = kc.copy(), vc.copy()
+        kc2[:, :, S - Q + j] ^= 0x5A
+        vc2[:, :, S - Q + j] ^= 0xA5
+        got2 = oracle.decode_attention_multi(q, kc2, ks, vc2, vs, k, blk, l32, S, sigma)
+        assert np.array_equal(got2[:, :, :j], got[:, :, :j])
+        for i in range(j, Q):
+            assert not np.allclose(got2[:, :, i], got[:, :, i], rtol=1e-9, atol=0)
+    # rows beyond seq_len never matter; q_len = 1 is the one-query function
+    kc3 = kc.copy(); kc3[:, :, S:] = 0xFF
+    assert np.array_equal(oracle.decode_attention_multi(q, kc3, ks, vc, vs, k, blk, l32, S, sigma), got)
+    q1 = np.ascontiguousarray(q[:, :, :1])
+    assert np.array_equal(oracle.decode_attention_multi(q1, kc, ks, vc, vs, k, blk, l32, S, sigma)[:, :, 0],
+                          oracle.decode_attention(np.ascontiguousarray(q1[:, :, 0]), kc, ks, vc, vs, k, blk, l32, S, sigma))
+    with pytest.raises(ValueError):
+        oracle.decode_attention_multi(q, kc, ks, vc, vs, k, blk, l32, Q - 1, sigma)      # fewer tokens than queries
+
+
 # ----------------------------------------------------------------------------- byte accounting
 def test_paper_kv_bytes_example():
     """Sec. 1: OPT-175B (96 layers, hidden 12288), batch 64, sequence 8192, fp16 -> about 2.3 TB."""
