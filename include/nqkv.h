@@ -17,6 +17,7 @@
  *   nqkv_decode_attention_paged / nqkv_decode_step_paged  the same over a paged cache
  *   nqkv_quantize_kv_hidden  blocks over the token's hidden vector, token-major source
  *                                                                    (Fig. 5, Sec. 4.1)
+ *   nqkv_decode_attention_multi  several new tokens' queries in one step (Sec. 1, Sec. 3.2)
  *
  * General rules
  *   - Every function returns NQKV_OK (0) or a negative NQKV_E* code.  Nothing throws,
@@ -317,6 +318,31 @@ int nqkv_quantize_kv_hidden(const nqkv_cache_desc* desc, const float* levels,
                             int64_t n_tokens, int64_t dst_token_offset, int block_hidden,
                             void* k_codes, void* k_scales, void* v_codes, void* v_scales,
                             void* hip_stream);
+
+/*
+ * Attention for a step that appended SEVERAL tokens (Sec. 1: new keys and values go to the end of
+ * the append-only cache; Sec. 3.2 decoding-phase equations, once per new token): the q_len
+ * queries of a (batch, head) belong to the LAST q_len of the first seq_len cached tokens, and
+ * query i attends over tokens [0, seq_len - q_len + 1 + i) -- what nqkv_decode_attention would
+ * give it at that sequence length.  The new tokens must already be in the cache
+ * (nqkv_quantize_kv_pair with n_tokens = q_len appends them).  The products run on the matrix
+ * cores (fp16 inputs, fp32 accumulation); weights times the value scale are rounded to fp16, so
+ * value scales below 2^-14 lose precision.  Tolerance as for nqkv_decode_attention.
+ *   q, out     device fp16 [B][H][q_len][D] contiguous
+ *   q_len      1..16
+ *   workspace  nqkv_decode_multi_workspace_bytes(desc, seq_len, q_len, num_splits, ...) bytes
+ *              (partial results only: no zero-fill needed); may be NULL when that is 0
+ * Errors: NQKV_EINVAL for null / misaligned pointers, q_len < 1, seq_len outside
+ * [q_len, cap_tokens], num_splits above the number of 32-token pieces of the sequence;
+ * NQKV_EUNSUPPORTED for q_len > 16, k other than 4, or an odd cap_tokens * (D / block);
+ * NQKV_EWORKSPACE for a short workspace.
+ */
+int nqkv_decode_multi_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, int q_len, int num_splits,
+                                      size_t* bytes_out, int* splits_out);
+int nqkv_decode_attention_multi(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                                const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                                int64_t seq_len, int q_len, float softmax_scale, void* out,
+                                void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream);
 
 /*
  * Measurement helper, not part of the method: reads `bytes` (a multiple of 16) of device memory

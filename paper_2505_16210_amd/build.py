@@ -21,6 +21,7 @@ SOURCES = [
     ("quantize.hip", ["-ffp-contract=off"]),
     ("dequantize.hip", ["-ffp-contract=off"]),
     ("decode_attention.hip", []),
+    ("decode_multi.hip", []),
     ("stream_probe.hip", []),
 ]
 

@@ -1,0 +1,380 @@
+// Dequantize-fused attention of SEVERAL new queries per sequence over the packed cache: the
+// decoding-phase equations of paper Sec. 3.2 (A = Softmax(t_Q X_K'^T), t_O = A X_V') for the
+// case where a step appends q_len > 1 tokens to the append-only cache (Sec. 1) and each of them
+// needs its output -- query i sees the cache up to and including its own token.
+//
+// With up to 16 query rows per head the two products are real (if skinny) matrix products, so
+// they run on the matrix cores: v_mfma_f32_16x16x16_f16, fp32 accumulate.  The table look-up that
+// turns codes into fp16 levels is the same byte-indexed LDS table as in the one-query kernel and
+// costs the same per cached element whatever q_len is; the arithmetic that the one-query kernel
+// spends vector instructions on (dot products, weighted sums) moves to the matrix pipe.
+//
+// Operand layouts of the 16x16x16 instruction (lane l, i16 = l % 16, gq = l / 16):
+//   A[row i16][k = 4 gq + 0..3],  B[k = 4 gq + 0..3][col i16],  C/D[row 4 gq + 0..3][col i16].
+//
+// Scores.   C1[token][query] = sum_d K[token][d] q[query][d]:  A = levels of a 16-token tile of
+//   K (row = token i16), B = q^T.  The contraction index of one instruction is 16 head-dim
+//   elements of one 64-element chunk, element  64 c + 16 gq + 4 s + e  for step s, so a lane
+//   needs 8 contiguous code bytes per chunk (one 64-bit load) and the chunk lies inside one
+//   quantization block; the block scale of the token multiplies C1 afterwards, in fp32.
+// Softmax.  A lane holds scores of tokens 4 gq + r (r = 0..3) of the tile for query i16: the
+//   running maximum and sum are per lane (= per query), reduced over gq with lane swaps.
+// Output.   O^T[d][query] = sum_token V[token][d] P[token][query]:  B = P^T is exactly the layout
+//   C1 came out in (k = token 4 gq + r, col = query), converted to fp16 after multiplying in
+//   the token's V block scale.  A = V^T needs, per lane, one head-dim element of four tokens; a
+//   look-up yields two adjacent elements of ONE token, so four look-ups (tokens 4 gq + 0..3, the
+//   same code byte) are re-paired with v_perm_b32 into the operands of two instructions (even
+//   and odd element).  Rows of one instruction are the 16 code bytes  4 (i16 % 8) + G + 2 (i16 / 8)
+//   (G = 0, 1) of a 32-byte chunk, so that they too stay inside one quantization block.
+//
+// Work split: one workgroup of eight waves per (sequence, split); waves take 32-token trips
+// round-robin; per-wave results (m, l per query, O) meet in LDS in the space of the look-up
+// table, which is no longer needed then; with splits > 1 a second small kernel combines the
+// partial results in split order.
+#include "decode_common.h"
+#include "nqkv_internal.h"
+
+namespace nqkv {
+namespace {
+
+constexpr int kWaves = 8;
+constexpr int kThreads = 64 * kWaves;
+constexpr int kTile = 16;                // tokens per matrix tile
+constexpr int kTilesPerTrip = 2;
+constexpr int kTrip = kTile * kTilesPerTrip;
+constexpr int kMaxQ = 16;
+
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float4_t mfma16(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, float4_t c) {
+  const u32x2_t a = {a0, a1}, b = {b0, b1};
+  return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4_t, a), __builtin_bit_cast(half4_t, b), c, 0, 0, 0);
+}
+
+// All-reduce over the four 16-lane rows of a wave (lane bits 4 and 5): v_permlane32_swap exchanges
+// lanes 32..63 of its first operand with lanes 0..31 of its second, v_permlane16_swap the odd rows
+// of the first with the even rows of the second; fed two copies of x, the two results hold the
+// two halves side by side.  (Inline assembly for the reason given in the one-query kernel; the
+// s_nop covers the wait states after a VALU write of the operands.)
+template <class Op>
+__device__ __forceinline__ float allreduce_rows(float x, Op op) {
+  float a = x, b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  x = op(a, b);
+  a = x; b = x;
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  return op(a, b);
+}
+
+__device__ __forceinline__ float half_lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w & 0xffffu)); }
+__device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w >> 16)); }
+__device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
+  const half2_t h = {(_Float16)lo, (_Float16)hi};      // round to nearest even
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+template <int D, int BLK>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128)))
+void decode_multi_kernel(const MultiParams p) {
+  constexpr int KBITS = 4;
+  constexpr int NC = D / 64;                 // 64-element chunks of a row
+  constexpr int NB = D / BLK;                // quantization blocks of a row
+  constexpr int CPB = BLK / 64;              // chunks per block
+  constexpr uint32_t kRowBytes = D * KBITS / 8, kChunkBytes = 8 * KBITS, kScaleRowBytes = NB * 2;
+  constexpr int SW = NB * 2;                 // dwords of scales of four tokens
+  constexpr int XS = D + 1;                  // padded row of the merge buffer
+  struct Lds {
+    float wm[kWaves][kMaxQ], wl[kWaves][kMaxQ];
+    union {
+      __attribute__((aligned(256))) uint32_t lut[kLutWords];
+      float xo[kWaves][kMaxQ][XS];           // per-wave outputs, after the table's last use
+    };
+  };
+  __shared__ Lds lds;
+  const char* lut = reinterpret_cast<const char*>(lds.lut);
+
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t i16 = lane & 15, gq = lane >> 4;
+  const uint32_t lane_off = lane << 2;
+  // V side: the two code bytes of its dword this lane looks up (see the row mapping above)
+  const uint32_t vsel0 = 0x0c0c0000u | ((4u + 2u * (i16 >> 3)) << 8);
+  const uint32_t vsel1 = vsel0 + 0x100u;
+
+  // ---- item geometry
+  const uint32_t item = blockIdx.x;
+  const uint32_t bh = item / (uint32_t)p.splits, sp = item - bh * (uint32_t)p.splits;
+  // splits are whole 32-token trips (so that every four-token scale load is dword aligned)
+  const int32_t u0 = (int32_t)sp * p.split_base + min((int32_t)sp, p.split_rem);
+  const int32_t t0 = u0 * kTrip;
+  const int32_t n_tok = min((p.split_base + ((int32_t)sp < p.split_rem ? 1 : 0)) * kTrip, p.seq_len - t0);
+  const int64_t row0 = (int64_t)bh * p.cap_tokens + t0;
+  // item-relative token limit of this lane's query: query i sees tokens [0, seq_len - q_len + 1 + i)
+  const int32_t qi = min((int32_t)i16, p.q_len - 1);
+  const int32_t lim = min(n_tok, p.seq_len - p.q_len + 1 + qi - t0);
+  const int32_t lim_first = p.seq_len - p.q_len + 1 - t0;           // query 0's, uniform
+
+  // Scale ranges end on a dword: with one 2-byte scale per token and an odd token count the last
+  // dword also holds the scale of the row after the item (the host makes sure that row exists);
+  // tokens past the item are masked below, whatever their scales hold.
+  const int scale_bytes = (n_tok * (int)kScaleRowBytes + 3) & ~3;
+  const __amdgpu_buffer_rsrc_t kc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.k_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
+  const __amdgpu_buffer_rsrc_t vc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.v_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
+  const __amdgpu_buffer_rsrc_t ks_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.k_scales) + row0 * NB, 0, scale_bytes, kBufferFlags);
+  const __amdgpu_buffer_rsrc_t vs_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.v_scales) + row0 * NB, 0, scale_bytes, kBufferFlags);
+  const __amdgpu_buffer_rsrc_t q_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.q) + (int64_t)bh * p.q_len * D, 0, p.q_len * D * 2, kBufferFlags);
+
+  // per-lane byte offsets inside a tile (the trip and tile offsets are added to them: only the
+  // vector offset takes part in the hardware range check, and rows past the item read zeros)
+  const uint32_t k_voff = i16 * kRowBytes + gq * 8u;                       // + c * kChunkBytes
+  const uint32_t v_voff = (4u * gq) * kRowBytes + (i16 & 7u) * 4u;         // + e * kRowBytes + c * kChunkBytes
+  const uint32_t s_voff = (4u * gq) * kScaleRowBytes;
+
+  uint32_t kw[kTilesPerTrip][NC][2], vw[kTilesPerTrip][NC][4];
+  uint32_t ksr[kTilesPerTrip][SW], vsr[kTilesPerTrip][SW];
+
+  auto load_scales = [&](__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t (&s)[SW]) {
+    if constexpr (NB == 1) {
+      const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, 0, 0);
+      s[0] = v.x; s[1] = v.y;
+    } else {
+      const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, 0, 0);
+      s[0] = v.x; s[1] = v.y; s[2] = v.z; s[3] = v.w;
+    }
+  };
+  auto load_k = [&](int32_t tb) {
+#pragma unroll
+    for (int u = 0; u < kTilesPerTrip; ++u) {
+      const uint32_t tok = (uint32_t)tb + u * kTile;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(kc_r, k_voff + tok * kRowBytes + c * kChunkBytes, 0, 0);
+        kw[u][c][0] = v.x; kw[u][c][1] = v.y;
+      }
+      load_scales(ks_r, s_voff + tok * kScaleRowBytes, ksr[u]);
+    }
+  };
+  auto load_v = [&](int32_t tb) {
+#pragma unroll
+    for (int u = 0; u < kTilesPerTrip; ++u) {
+      const uint32_t tok = (uint32_t)tb + u * kTile;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          vw[u][c][e] = __builtin_amdgcn_raw_buffer_load_b32(vc_r, v_voff + (tok + e) * kRowBytes + c * kChunkBytes, 0, 0);
+      }
+      load_scales(vs_r, s_voff + tok * kScaleRowBytes, vsr[u]);
+    }
+  };
+  // scale of token 4 gq + r, block b, from the four-token scale words
+  auto scale_of = [&](const uint32_t (&s)[SW], int r, int b) {
+    const int idx = r * NB + b;
+    return (idx & 1) ? half_hi(s[idx >> 1]) : half_lo(s[idx >> 1]);
+  };
+
+  int32_t base = (int32_t)wave * kTrip;
+  load_k(base);
+  // the query operand: q[query i16][64 c + 16 gq + 4 s + 0..3] for c, s -- 32 bytes per chunk;
+  // rows beyond q_len read zeros
+  uint32_t qb[NC][4][2];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+#pragma unroll
+    for (int hlf = 0; hlf < 2; ++hlf) {
+      const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(q_r, (i16 * D + 64u * c + 16u * gq + 8u * hlf) * 2u, 0, 0);
+      qb[c][2 * hlf][0] = v.x; qb[c][2 * hlf][1] = v.y; qb[c][2 * hlf + 1][0] = v.z; qb[c][2 * hlf + 1][1] = v.w;
+    }
+  }
+  build_lut<KBITS>(p, lds.lut);          // ends with a barrier
+
+  float4_t acc[NC][2][2];                // [chunk][G][even, odd element]
+#pragma unroll
+  for (int c = 0; c < NC; ++c)
+#pragma unroll
+    for (int G = 0; G < 2; ++G) { acc[c][G][0] = float4_t{0, 0, 0, 0}; acc[c][G][1] = float4_t{0, 0, 0, 0}; }
+  float m_run = kNoScore;                // this lane's query, log2 domain; equal over gq
+  float l_run = 0.0f;                    // over this lane's own tokens only
+
+  constexpr int32_t stride = kWaves * kTrip;
+  for (; base < n_tok; base += stride) {
+    load_v(base);
+
+    // ---- scores of the trip's two tiles
+    float z[kTilesPerTrip][4];
+    bool full_tile[kTilesPerTrip];
+#pragma unroll
+    for (int u = 0; u < kTilesPerTrip; ++u) {
+      float4_t c1[NB];
+#pragma unroll
+      for (int b = 0; b < NB; ++b) c1[b] = float4_t{0, 0, 0, 0};
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const uint32_t w0 = kw[u][c][0], w1 = kw[u][c][1];
+        const uint32_t a[8] = {row_addr<0>(w0, lane_off), row_addr<1>(w0, lane_off), row_addr<2>(w0, lane_off), row_addr<3>(w0, lane_off),
+                               row_addr<0>(w1, lane_off), row_addr<1>(w1, lane_off), row_addr<2>(w1, lane_off), row_addr<3>(w1, lane_off)};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const uint32_t x0 = *reinterpret_cast<const uint32_t*>(lut + a[2 * s]);
+          const uint32_t x1 = *reinterpret_cast<const uint32_t*>(lut + a[2 * s + 1]);
+          c1[c / CPB] = mfma16(x0, x1, qb[c][s][0], qb[c][s][1], c1[c / CPB]);
+        }
+      }
+      const bool full = base + (u + 1) * kTile <= min(n_tok, lim_first);      // uniform
+      full_tile[u] = full;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float v = 0.0f;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) v = __builtin_fmaf(c1[b][r], scale_of(ksr[u], r, b), v);
+        const bool visible = full || (base + u * kTile + (int32_t)(4u * gq) + r < lim);
+        z[u][r] = visible ? v * p.scale_log2e : -INFINITY;
+      }
+    }
+    float m_trip = fmaxf(fmaxf(fmaxf(z[0][0], z[0][1]), fmaxf(z[0][2], z[0][3])),
+                         fmaxf(fmaxf(z[1][0], z[1][1]), fmaxf(z[1][2], z[1][3])));
+    m_trip = allreduce_rows(m_trip, [](float a, float b) { return fmaxf(a, b); });
+    const float m_new = fmaxf(m_run, m_trip);
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {       // uniform: some query's maximum grew
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int G = 0; G < 2; ++G) { acc[c][G][0] *= alpha; acc[c][G][1] *= alpha; }
+      l_run *= alpha;
+      m_run = m_new;
+    }
+    float pw[kTilesPerTrip][4];
+#pragma unroll
+    for (int u = 0; u < kTilesPerTrip; ++u)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        pw[u][r] = __builtin_amdgcn_exp2f(z[u][r] - m_run);
+        l_run += pw[u][r];
+      }
+
+    load_k(base + stride);      // past the end on the last trip: reads zeros
+
+    // ---- weighted values
+#pragma unroll
+    for (int u = 0; u < kTilesPerTrip; ++u) {
+      uint32_t b2[NB][2];       // P^T of the tile times the V block scale, fp16
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        float wv[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          wv[r] = pw[u][r] * scale_of(vsr[u], r, b);
+          // a token past the item has weight 0, but its scale may be anything (0 * NaN): select
+          if (!full_tile[u]) wv[r] = (base + u * kTile + (int32_t)(4u * gq) + r < n_tok) ? wv[r] : 0.0f;
+        }
+        b2[b][0] = pack_half2(wv[0], wv[1]);
+        b2[b][1] = pack_half2(wv[2], wv[3]);
+      }
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+#pragma unroll
+        for (int G = 0; G < 2; ++G) {
+          uint32_t h[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const uint32_t addr = __builtin_amdgcn_perm(vw[u][c][e], lane_off, G ? vsel1 : vsel0);
+            h[e] = *reinterpret_cast<const uint32_t*>(lut + addr);
+          }
+          // {h[e].lo} over the four tokens -> even element's operand, {h[e].hi} -> odd element's
+          const uint32_t e0 = __builtin_amdgcn_perm(h[1], h[0], 0x05040100u), e1 = __builtin_amdgcn_perm(h[3], h[2], 0x05040100u);
+          const uint32_t o0 = __builtin_amdgcn_perm(h[1], h[0], 0x07060302u), o1 = __builtin_amdgcn_perm(h[3], h[2], 0x07060302u);
+          acc[c][G][0] = mfma16(e0, e1, b2[c / CPB][0], b2[c / CPB][1], acc[c][G][0]);
+          acc[c][G][1] = mfma16(o0, o1, b2[c / CPB][0], b2[c / CPB][1], acc[c][G][1]);
+        }
+      }
+    }
+  }
+
+  // ---- merge the eight waves.  The table is dead once every wave is here.
+  const float l_wave = allreduce_rows(l_run, [](float a, float b) { return a + b; });
+  __syncthreads();
+  if ((int32_t)i16 < p.q_len) {
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int G = 0; G < 2; ++G)
+#pragma unroll
+        for (int par = 0; par < 2; ++par)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const uint32_t row = 4u * gq + r;                       // the instruction's output row
+            const uint32_t d = 64u * c + 8u * (row & 7u) + 2u * (G + 2u * (row >> 3)) + par;
+            lds.xo[wave][i16][d] = acc[c][G][par][r];
+          }
+    if (gq == 0) { lds.wm[wave][i16] = m_run; lds.wl[wave][i16] = l_wave; }
+  }
+  __syncthreads();
+  const int32_t n_out = p.q_len * D;
+  for (int32_t idx = (int32_t)threadIdx.x; idx < n_out; idx += kThreads) {
+    const int32_t qy = idx / D, d = idx % D;
+    float m_all = lds.wm[0][qy];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) m_all = fmaxf(m_all, lds.wm[w][qy]);
+    float l_all = 0.0f, o = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float f = __builtin_amdgcn_exp2f(lds.wm[w][qy] - m_all);     // 0 for a wave without visible tokens
+      l_all += lds.wl[w][qy] * f;
+      o += lds.xo[w][qy][d] * f;
+    }
+    if (p.splits == 1) {
+      p.out[((int64_t)bh * p.q_len + qy) * D + d] = __builtin_bit_cast(unsigned short, (_Float16)(o * p.inv_gamma / l_all));
+    } else {
+      float* rec = p.partials + (((int64_t)bh * p.splits + sp) * p.q_len + qy) * (D + 2);
+      rec[2 + d] = o;
+      if (d == 0) { rec[0] = m_all; rec[1] = l_all; }
+    }
+  }
+}
+
+// splits > 1: fold the partial results of one (sequence, query) in split order; one thread per
+// output element.  (A split whose tokens the query cannot see has l = 0 and the sentinel maximum.)
+template <int D>
+__global__ __launch_bounds__(D) void combine_multi_kernel(const MultiParams p) {
+  const int64_t bq = blockIdx.x;                     // (b*H + h) * q_len + query
+  const int64_t bh = bq / p.q_len, qy = bq % p.q_len;
+  const int d = threadIdx.x;
+  float mm = kNoScore, ll = 0.0f, oo = 0.0f;
+  for (int s = 0; s < p.splits; ++s) {
+    const float* rec = p.partials + ((bh * p.splits + s) * p.q_len + qy) * (D + 2);
+    const float m_s = rec[0], l_s = rec[1], o_s = rec[2 + d];
+    const float m_new = fmaxf(mm, m_s);
+    const float f_old = __builtin_amdgcn_exp2f(mm - m_new), f_s = __builtin_amdgcn_exp2f(m_s - m_new);
+    ll = ll * f_old + l_s * f_s;
+    oo = oo * f_old + o_s * f_s;
+    mm = m_new;
+  }
+  p.out[bq * D + d] = __builtin_bit_cast(unsigned short, (_Float16)(oo * p.inv_gamma / ll));
+}
+
+template <int D, int BLK>
+hipError_t launch_dims(const MultiParams& p, int B_H, hipStream_t stream) {
+  hipLaunchKernelGGL((decode_multi_kernel<D, BLK>), dim3((unsigned)p.n_items), dim3(kThreads), 0, stream, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || p.splits == 1) return e;
+  hipLaunchKernelGGL((combine_multi_kernel<D>), dim3((unsigned)(B_H * p.q_len)), dim3(D), 0, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+int decode_multi_trip_tokens() { return kTrip; }
+int decode_multi_item_tokens() { return kWaves * kTrip; }
+
+hipError_t launch_decode_attention_multi(const MultiParams& p, int D, int k, int blk, hipStream_t stream) {
+  if (k != 4 || p.q_len < 1 || p.q_len > kMaxQ || p.splits < 1 || p.n_items % p.splits) return hipErrorInvalidValue;
+  const int bh = p.n_items / p.splits;
+  if (D == 64 && blk == 64) return launch_dims<64, 64>(p, bh, stream);
+  if (D == 128 && blk == 64) return launch_dims<128, 64>(p, bh, stream);
+  if (D == 128 && blk == 128) return launch_dims<128, 128>(p, bh, stream);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace nqkv

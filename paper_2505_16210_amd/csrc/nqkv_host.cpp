@@ -179,6 +179,35 @@ int plan_splits(const nqkv_cache_desc* d, int64_t seq_len, int num_splits, int* 
   return NQKV_OK;
 }
 
+// Cut of a sequence for the several-queries kernel, in whole 32-token trips.  One workgroup per
+// piece, each building its own look-up table, so pieces are kept at one sweep of the eight waves
+// (256 tokens) or longer; the cut aims at two workgroups per compute unit.
+int plan_multi(const nqkv_cache_desc* d, int64_t seq_len, int q_len, int num_splits, int* splits) {
+  if (q_len < 1 || q_len > 16) return q_len < 1 ? NQKV_EINVAL : NQKV_EUNSUPPORTED;
+  if (seq_len < q_len || seq_len > d->cap_tokens || seq_len >= ((int64_t)1 << 31) - 64) return NQKV_EINVAL;
+  if (num_splits < 0 || num_splits > 1024) return NQKV_EINVAL;
+  const int64_t trips = (seq_len + decode_multi_trip_tokens() - 1) / decode_multi_trip_tokens();
+  if (num_splits > 0) {
+    if ((int64_t)num_splits > trips) return NQKV_EINVAL;
+    *splits = num_splits;
+    return NQKV_OK;
+  }
+  const int64_t bh = (int64_t)d->B * d->H;
+  const int64_t target = g_decode_target_wgs > 0 ? g_decode_target_wgs : (int64_t)max_decode_workgroups();
+  int64_t want = target / bh;
+  const int64_t longest = seq_len / decode_multi_item_tokens();
+  if (want > longest) want = longest;
+  if (want > 1024) want = 1024;
+  if (want < 1) want = 1;
+  *splits = (int)want;
+  return NQKV_OK;
+}
+
+size_t multi_workspace_need(const nqkv_cache_desc* d, int q_len, int splits) {
+  if (splits <= 1) return 0;
+  return (size_t)d->B * d->H * splits * q_len * (d->D + 2) * sizeof(float);
+}
+
 }  // namespace
 
 extern "C" {
@@ -687,6 +716,69 @@ int nqkv_decode_step_paged(const nqkv_cache_desc* desc, const float* levels,
   return decode_paged_impl(desc, levels, q, k_new, v_new, new_stride_b, new_stride_h, pos, block_table, table_stride,
                            num_pages, k_codes, k_scales, v_codes, v_scales, max_pos, softmax_scale, out, workspace,
                            workspace_bytes, hip_stream);
+}
+
+int nqkv_decode_multi_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, int q_len, int num_splits,
+                                      size_t* bytes_out, int* splits_out) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!bytes_out) return NQKV_EINVAL;
+  int splits = 1;
+  if ((rc = plan_multi(desc, seq_len, q_len, num_splits, &splits))) return rc;
+  *bytes_out = multi_workspace_need(desc, q_len, splits);
+  if (splits_out) *splits_out = splits;
+  return NQKV_OK;
+}
+
+int nqkv_decode_attention_multi(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                                const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                                int64_t seq_len, int q_len, float softmax_scale, void* out,
+                                void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  LevelTable checked;
+  if ((rc = check_levels(levels, desc->k, &checked))) return rc;
+  int splits = 1;
+  if ((rc = plan_multi(desc, seq_len, q_len, num_splits, &splits))) return rc;
+  if (!std::isfinite(softmax_scale)) return NQKV_EINVAL;
+  const void* ptrs[] = {q, k_codes, k_scales, v_codes, v_scales, out};
+  for (const void* ptr : ptrs) {
+    if (!ptr || !aligned16(ptr)) return NQKV_EINVAL;
+  }
+  if (desc->k != 4) return NQKV_EUNSUPPORTED;
+  // four-token scale loads need dword-aligned rows
+  if ((desc->cap_tokens * (desc->D / desc->block)) % 2) return NQKV_EUNSUPPORTED;
+  const size_t need = multi_workspace_need(desc, q_len, splits);
+  if (need > 0) {
+    if (!workspace || !aligned16(workspace)) return NQKV_EINVAL;
+    if (workspace_bytes < need) return NQKV_EWORKSPACE;
+  }
+  const int64_t trip = decode_multi_trip_tokens();
+  const int64_t trips = (seq_len + trip - 1) / trip;
+  // one piece's byte range is addressed with 32-bit offsets
+  if ((trips / splits + 1) * trip * (int64_t)(desc->D * desc->k / 8) >= ((int64_t)1 << 31)) return NQKV_EUNSUPPORTED;
+  MultiParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.q = static_cast<const uint16_t*>(q);
+  p.k_codes = static_cast<const uint8_t*>(k_codes);
+  p.k_scales = static_cast<const uint16_t*>(k_scales);
+  p.v_codes = static_cast<const uint8_t*>(v_codes);
+  p.v_scales = static_cast<const uint16_t*>(v_scales);
+  p.out = static_cast<uint16_t*>(out);
+  p.partials = static_cast<float*>(workspace);
+  p.n_items = desc->B * desc->H * splits;
+  p.splits = splits;
+  p.split_base = (int)(trips / splits);
+  p.split_rem = (int)(trips % splits);
+  p.seq_len = (int)seq_len;
+  p.q_len = q_len;
+  p.cap_tokens = desc->cap_tokens;
+  const LutChoice& lut = choose_lut_scale(checked.v, 1 << desc->k);
+  std::memcpy(p.lut_levels, lut.bits, sizeof(uint16_t) * (1 << desc->k));
+  p.inv_gamma = 1.0f / lut.gamma;
+  p.scale_log2e = (float)((double)softmax_scale * 1.44269504088896340736 / (double)lut.gamma);
+  const hipError_t e = launch_decode_attention_multi(p, desc->D, desc->k, desc->block, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
 }
 
 int nqkv_probe_read_stream(const void* src, size_t bytes, void* checksums, void* hip_stream) {

@@ -82,6 +82,25 @@ struct DecodeParams {
   uint32_t cell_below[kQuantCells];
 };
 
+// Attention of several new queries per sequence (the last q_len cached tokens' queries).
+struct MultiParams {
+  const uint16_t* q;         // [B*H][q_len][D] fp16
+  const uint8_t* k_codes;
+  const uint16_t* k_scales;
+  const uint8_t* v_codes;
+  const uint16_t* v_scales;
+  uint16_t* out;             // [B*H][q_len][D] fp16
+  float* partials;           // splits > 1: [B*H][splits][q_len][D+2] fp32 (m, l, o[D])
+  int n_items;               // B*H*splits
+  int splits;
+  int split_base, split_rem; // in 32-token trips: ceil(seq_len / 32) = splits * split_base + split_rem
+  int seq_len, q_len;
+  int64_t cap_tokens;
+  float scale_log2e;         // softmax_scale * log2(e) / gamma
+  float inv_gamma;
+  uint16_t lut_levels[kMaxLevels];
+};
+
 // Bytes at the start of the split-K workspace that hold the ticket counters (one uint32 per
 // (b,h), room for the largest supported B*H), before the partial results.
 constexpr size_t kTicketBytes = 65536 * sizeof(uint32_t);
@@ -95,6 +114,11 @@ hipError_t launch_quantize_paged(const QuantParams& p, int D, int k, int blk, hi
 hipError_t launch_quantize_hidden(const QuantParams& p, int D, int k, int blk_hidden, hipStream_t stream);
 // fuse: also quantize and append the new token (p.k_new / p.v_new) and attend over it
 hipError_t launch_decode_attention(const DecodeParams& p, int D, int k, int blk, bool fuse, hipStream_t stream);
+
+// q_len in [1, 16]; k = 4 only
+hipError_t launch_decode_attention_multi(const MultiParams& p, int D, int k, int blk, hipStream_t stream);
+int decode_multi_trip_tokens();    // split boundaries of that kernel are multiples of this
+int decode_multi_item_tokens();    // tokens one workgroup of it consumes per sweep of its waves
 
 // Measurement helper: xor checksum per workgroup of a plain 128-bit read stream over `bytes`
 // (a multiple of 16) of device memory.

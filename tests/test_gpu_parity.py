@@ -732,3 +732,87 @@ def test_quantize_paged_bit_exact(nqkv, oracle, k, D, blk, P, impl):
         for pg in range(num_pages):
             if pg not in owned:
                 assert (hp[pg] == fill).all(), pg
+
+
+# --------------------------------------------------------------------------- several queries per step
+def _multi_err(out: torch.Tensor, ref: np.ndarray) -> float:
+    """worst relative error over (batch, head, query) rows."""
+    o = h2n(out).view(np.float16)
+    assert np.isfinite(o.astype(np.float32)).all()
+    return attn_err(o.reshape(1, -1, o.shape[-1]), ref.reshape(1, -1, ref.shape[-1]))
+
+
+@pytest.mark.parametrize("k,D,blk", [(4, 64, 64), (4, 128, 64), (4, 128, 128)])
+def test_decode_attention_multi_matches_oracle(nqkv, oracle, k, D, blk):
+    """q_len queries of the last q_len cached tokens, each over its own causal prefix; lengths
+    that end inside a 16-token tile, on a tile and on a 32-token piece; every split count."""
+    B, H, S, cap = 2, 3, 1237, 1300
+    lv, desc, _, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, S, cap, seed=13 * k + D + blk)
+    kc[:, :, S:] = 0xFF                    # rows beyond S must not matter, whatever they hold
+    ks[:, :, S:] = 60000.0
+    vs[:, :, S:] = float("nan")
+    g = torch.Generator(device="cuda").manual_seed(3)
+    hk = [h2n(t) for t in (kc, ks, vc, vs)]
+    for Q in (1, 2, 5, 16):
+        q = (torch.randn(B, H, Q, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+        for seq in (Q, 33, 64, 257, 1000, S):
+            if seq < Q:
+                continue
+            ref = oracle.decode_attention_multi(h2n(q), hk[0], hk[1], hk[2], hk[3], k, blk, lv, seq, 0.9, n_threads=8)
+            for ns in (0, 1, 2, 7, 39):
+                if ns > (seq + 31) // 32:
+                    continue
+                out = nqkv.decode_attention_multi(desc, lv, q, kc, ks, vc, vs, seq, 0.9, num_splits=ns)
+                torch.cuda.synchronize()
+                err = _multi_err(out, ref)
+                assert err <= ATTN_TOL, (k, D, blk, Q, seq, ns, err)
+
+
+def test_decode_multi_step_append_then_attend(nqkv, oracle):
+    """A step that appends several tokens: quantize them into the cache (one call), then attend
+    with their queries -- against the oracle doing the same, and against the one-query kernel at
+    each position; equal arguments give equal bits."""
+    k, D, blk = 4, 128, 64
+    B, H, S0, Q, cap = 2, 4, 700, 6, 1024
+    lv, desc, _, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, S0, cap, seed=21)
+    g = torch.Generator(device="cuda").manual_seed(22)
+    k_new = rand_kv((B, H, Q, D), seed=23)
+    v_new = torch.randn(B, H, Q, D, device="cuda", generator=g).to(torch.float16)
+    q = (torch.randn(B, H, Q, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+    nqkv.quantize_kv_pair(desc, lv, k_new, v_new, kc, ks, vc, vs, S0)
+    out = nqkv.decode_attention_multi(desc, lv, q, kc, ks, vc, vs, S0 + Q, 0.7)
+    again = nqkv.decode_attention_multi(desc, lv, q, kc, ks, vc, vs, S0 + Q, 0.7)
+    torch.cuda.synchronize()
+    assert torch.equal(out, again)
+    hk = [h2n(t) for t in (kc, ks, vc, vs)]
+    ref = oracle.decode_attention_multi(h2n(q), hk[0], hk[1], hk[2], hk[3], k, blk, lv, S0 + Q, 0.7, n_threads=8)
+    assert _multi_err(out, ref) <= ATTN_TOL
+    for i in range(Q):
+        one = nqkv.decode_attention(desc, lv, q[:, :, i].contiguous(), kc, ks, vc, vs, S0 + i + 1, 0.7)
+        torch.cuda.synchronize()
+        d = (out[:, :, i].float() - one.float()).abs().amax(-1) / one.float().abs().amax(-1)
+        assert d.max().item() <= 2 * ATTN_TOL
+
+
+def test_decode_attention_multi_peaked_flat_and_tiny_value_scales(nqkv, oracle):
+    """Softmax extremes, and value rows whose block scale is small: the weights times that scale
+    are rounded to fp16 inside the kernel."""
+    k, D, blk = 4, 64, 64
+    B, H, S, Q = 1, 4, 900, 4
+    lv = nqkv.build_codebook(k)
+    g = torch.Generator(device="cuda").manual_seed(31)
+    Kx = rand_kv((B, H, S, D), seed=32)
+    Vx = (torch.randn(B, H, S, D, device="cuda", generator=g) * 1e-3).to(torch.float16)
+    q = (torch.randn(B, H, Q, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+    desc = nqkv.make_desc(B, H, D, k, blk, S)
+    kc, ks = nqkv.alloc_cache(desc)
+    vc, vs = nqkv.alloc_cache(desc)
+    nqkv.quantize_kv_pair(desc, lv, Kx, Vx, kc, ks, vc, vs, 0)
+    torch.cuda.synchronize()
+    hk = [h2n(t) for t in (kc, ks, vc, vs)]
+    for scale in (8.0, 1.0, 1e-3, 0.0):
+        ref = oracle.decode_attention_multi(h2n(q), hk[0], hk[1], hk[2], hk[3], k, blk, lv, S, scale, n_threads=4)
+        for ns in (1, 3):
+            out = nqkv.decode_attention_multi(desc, lv, q, kc, ks, vc, vs, S, scale, num_splits=ns)
+            torch.cuda.synchronize()
+            assert _multi_err(out, ref) <= ATTN_TOL, (scale, ns)

@@ -182,6 +182,43 @@ def test_decode_step_argument_errors(nqkv):
     assert call(levels=None) == nqkv.EINVAL
 
 
+def test_decode_multi_argument_errors_and_planning(nqkv):
+    lv, lvp = _levels(nqkv)
+    d = nqkv.make_desc(1, 32, 128, 4, 64, 32768)
+    f = nqkv.lib.nqkv_decode_attention_multi
+
+    def call(q=FAKE, kc=FAKE, ks=FAKE, vc=FAKE, vs=FAKE, seq=32768, q_len=4, scale=1.0, out=FAKE, ws=FAKE,
+             ws_bytes=1 << 30, ns=0, desc=d, levels=lvp):
+        return f(ctypes.byref(desc), levels, q, kc, ks, vc, vs, seq, q_len, scale, out, ws, ws_bytes, ns, None)
+
+    assert call(q=None) == nqkv.EINVAL
+    assert call(out=None) == nqkv.EINVAL
+    assert call(ks=FAKE + 2) == nqkv.EINVAL
+    assert call(q_len=0) == nqkv.EINVAL
+    assert call(q_len=17) == nqkv.EUNSUPPORTED
+    assert call(seq=3) == nqkv.EINVAL                            # fewer cached tokens than queries
+    assert call(seq=32769) == nqkv.EINVAL
+    assert call(scale=float("nan")) == nqkv.EINVAL
+    assert call(ns=8, ws=None) == nqkv.EINVAL
+    assert call(ns=8, ws_bytes=100) == nqkv.EWORKSPACE
+    assert call(ns=1025) == nqkv.EINVAL
+    assert call(seq=100, ns=5) == nqkv.EINVAL                    # 100 tokens are four 32-token pieces
+    assert call(levels=None) == nqkv.EINVAL
+    assert call(desc=nqkv.make_desc(1, 32, 128, 3, 64, 32768), levels=_levels(nqkv, 3)[1]) == nqkv.EUNSUPPORTED
+    assert call(desc=nqkv.make_desc(1, 32, 128, 4, 128, 32767), seq=100) == nqkv.EUNSUPPORTED   # odd scale rows
+    # workspace: partial results only, [B*H][splits][q_len][D+2] floats
+    assert nqkv.decode_multi_workspace_bytes(d, 32768, 4, 1) == (0, 1)
+    assert nqkv.decode_multi_workspace_bytes(d, 32768, 4, 7) == (32 * 7 * 4 * 130 * 4, 7)
+    nbytes, splits = nqkv.decode_multi_workspace_bytes(d, 32768, 16, 0)
+    assert splits > 1 and nbytes == 32 * splits * 16 * 130 * 4
+    assert nqkv.decode_multi_workspace_bytes(d, 40, 8, 0) == (0, 1)
+    for seq, ql, ns in ((0, 1, 0), (7, 8, 0), (32769, 1, 0), (64, 1, 3), (64, 1, -1)):
+        with pytest.raises(nqkv.NqkvError) as e:
+            nqkv.decode_multi_workspace_bytes(d, seq, ql, ns)
+        assert e.value.status == nqkv.EINVAL
+    assert nqkv.lib.nqkv_decode_multi_workspace_bytes(ctypes.byref(d), 100, 2, 0, None, None) == nqkv.EINVAL
+
+
 def test_varlen_argument_errors(nqkv):
     lv, lvp = _levels(nqkv)
     d = nqkv.make_desc(4, 8, 128, 4, 64, 4096)
