@@ -464,6 +464,26 @@ def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, time
                 packed + B * H * 4 * D + (2 * B * H * p_items * (D + 2) * 4 if p_items > 1 else 0), t_pg,
                 page_tokens=P, pages_per_sequence=n_pg, items_per_sequence=p_items)
             del pools, pws
+        if kb == 4:
+            # a step that appended q_len tokens (speculative / batched verify): their queries over the
+            # same cache, each on its causal prefix, on the matrix cores
+            for q_len in (4, 16):
+                qm = (torch.randn(B, H, q_len, D, device=dev, generator=g) / D ** 0.5).to(torch.float16)
+                outm = torch.empty_like(qm)
+                mws_bytes, m_splits = nqkv.decode_multi_workspace_bytes(desc, S, q_len, 0)
+                mws = torch.empty(max(mws_bytes, 16), dtype=torch.uint8, device=dev)
+
+                def attend_multi(i):
+                    kc, ks, vc, vs = caches[i % r_cache]
+                    nqkv.decode_attention_multi(desc, lv, qm, kc, ks, vc, vs, S, 1.0, out=outm, workspace=mws)
+
+                t_m = tk(attend_multi, n_it * 2, warm=max(2, r_cache))
+                mbytes = packed + B * H * q_len * 4 * D + (2 * B * H * m_splits * q_len * (D + 2) * 4 if m_splits > 1 else 0)
+                flops = 4.0 * B * H * S * D * 16                 # two products, 16 query columns issued whatever q_len is
+                kern[tag + ".decode_attention_multi.q%d" % q_len] = kernel_entry(
+                    mbytes, t_m, splits=m_splits, q_len=q_len, vs_one_query=round(t_m / t_a, 3),
+                    mfma_TFLOPs_issued=round(flops / (t_m * 1e-3) / 1e12, 1))
+                del qm, outm, mws
         if (H * D) % 256 == 0:
             # the paper's own block geometry: 256 consecutive elements of the token's hidden vector,
             # read from token-major storage (the same bytes viewed as [B,S,H,D]); one scale per head

@@ -31,6 +31,8 @@
 // round-robin; per-wave results (m, l per query, O) meet in LDS in the space of the look-up
 // table, which is no longer needed then; with splits > 1 a second small kernel combines the
 // partial results in split order.
+#include <type_traits>
+
 #include "decode_common.h"
 #include "nqkv_internal.h"
 
@@ -40,8 +42,15 @@ namespace {
 constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
 constexpr int kTile = 16;                // tokens per matrix tile
-constexpr int kTilesPerTrip = 2;
+#ifndef NQKV_MULTI_TILES
+#define NQKV_MULTI_TILES 2
+#endif
+#ifndef NQKV_MULTI_WPE
+#define NQKV_MULTI_WPE 4
+#endif
+constexpr int kTilesPerTrip = NQKV_MULTI_TILES;
 constexpr int kTrip = kTile * kTilesPerTrip;
+constexpr int kSplitUnit = 32;           // split boundaries are multiples of this many tokens
 constexpr int kMaxQ = 16;
 
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
@@ -75,7 +84,7 @@ __device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
 }
 
 template <int D, int BLK>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128)))
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQKV_MULTI_WPE, NQKV_MULTI_WPE)))
 void decode_multi_kernel(const MultiParams p) {
   constexpr int KBITS = 4;
   constexpr int NC = D / 64;                 // 64-element chunks of a row
@@ -105,10 +114,10 @@ void decode_multi_kernel(const MultiParams p) {
   // ---- item geometry
   const uint32_t item = blockIdx.x;
   const uint32_t bh = item / (uint32_t)p.splits, sp = item - bh * (uint32_t)p.splits;
-  // splits are whole 32-token trips (so that every four-token scale load is dword aligned)
+  // splits are whole 32-token pieces (so that every four-token scale load is dword aligned)
   const int32_t u0 = (int32_t)sp * p.split_base + min((int32_t)sp, p.split_rem);
-  const int32_t t0 = u0 * kTrip;
-  const int32_t n_tok = min((p.split_base + ((int32_t)sp < p.split_rem ? 1 : 0)) * kTrip, p.seq_len - t0);
+  const int32_t t0 = u0 * kSplitUnit;
+  const int32_t n_tok = min((p.split_base + ((int32_t)sp < p.split_rem ? 1 : 0)) * kSplitUnit, p.seq_len - t0);
   const int64_t row0 = (int64_t)bh * p.cap_tokens + t0;
   // item-relative token limit of this lane's query: query i sees tokens [0, seq_len - q_len + 1 + i)
   const int32_t qi = min((int32_t)i16, p.q_len - 1);
@@ -198,12 +207,15 @@ void decode_multi_kernel(const MultiParams p) {
   float l_run = 0.0f;                    // over this lane's own tokens only
 
   constexpr int32_t stride = kWaves * kTrip;
-  for (; base < n_tok; base += stride) {
+  // One 32-token trip.  FULL: every token of it exists and is visible to every query (all trips but
+  // the sequence's last few); the other copy masks per token and query.  Two copies of the whole
+  // body rather than branches inside it, so that each is one straight-line scheduling region.
+  auto trip_body = [&](auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
     load_v(base);
 
     // ---- scores of the trip's two tiles
     float z[kTilesPerTrip][4];
-    bool full_tile[kTilesPerTrip];
 #pragma unroll
     for (int u = 0; u < kTilesPerTrip; ++u) {
       float4_t c1[NB];
@@ -221,19 +233,21 @@ void decode_multi_kernel(const MultiParams p) {
           c1[c / CPB] = mfma16(x0, x1, qb[c][s][0], qb[c][s][1], c1[c / CPB]);
         }
       }
-      const bool full = base + (u + 1) * kTile <= min(n_tok, lim_first);      // uniform
-      full_tile[u] = full;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         float v = 0.0f;
 #pragma unroll
         for (int b = 0; b < NB; ++b) v = __builtin_fmaf(c1[b][r], scale_of(ksr[u], r, b), v);
-        const bool visible = full || (base + u * kTile + (int32_t)(4u * gq) + r < lim);
-        z[u][r] = visible ? v * p.scale_log2e : -INFINITY;
+        v *= p.scale_log2e;
+        // tokens past the item or not yet visible to this lane's query (a select: the scale of a
+        // row past the item may be anything)
+        if (!FULL) v = (base + u * kTile + (int32_t)(4u * gq) + r < lim) ? v : -INFINITY;
+        z[u][r] = v;
       }
     }
-    float m_trip = fmaxf(fmaxf(fmaxf(z[0][0], z[0][1]), fmaxf(z[0][2], z[0][3])),
-                         fmaxf(fmaxf(z[1][0], z[1][1]), fmaxf(z[1][2], z[1][3])));
+    float m_trip = fmaxf(fmaxf(z[0][0], z[0][1]), fmaxf(z[0][2], z[0][3]));
+#pragma unroll
+    for (int u = 1; u < kTilesPerTrip; ++u) m_trip = fmaxf(m_trip, fmaxf(fmaxf(z[u][0], z[u][1]), fmaxf(z[u][2], z[u][3])));
     m_trip = allreduce_rows(m_trip, [](float a, float b) { return fmaxf(a, b); });
     const float m_new = fmaxf(m_run, m_trip);
     if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {       // uniform: some query's maximum grew
@@ -267,7 +281,7 @@ void decode_multi_kernel(const MultiParams p) {
         for (int r = 0; r < 4; ++r) {
           wv[r] = pw[u][r] * scale_of(vsr[u], r, b);
           // a token past the item has weight 0, but its scale may be anything (0 * NaN): select
-          if (!full_tile[u]) wv[r] = (base + u * kTile + (int32_t)(4u * gq) + r < n_tok) ? wv[r] : 0.0f;
+          if (!FULL) wv[r] = (base + u * kTile + (int32_t)(4u * gq) + r < n_tok) ? wv[r] : 0.0f;
         }
         b2[b][0] = pack_half2(wv[0], wv[1]);
         b2[b][1] = pack_half2(wv[2], wv[3]);
@@ -290,7 +304,10 @@ void decode_multi_kernel(const MultiParams p) {
         }
       }
     }
-  }
+  };
+  const int32_t n_clear = min(n_tok, lim_first);          // tokens every query sees, uniform
+  for (; base + kTrip <= n_clear; base += stride) trip_body(std::true_type{});
+  for (; base < n_tok; base += stride) trip_body(std::false_type{});     // the sequence's ragged / causal end
 
   // ---- merge the eight waves.  The table is dead once every wave is here.
   const float l_wave = allreduce_rows(l_run, [](float a, float b) { return a + b; });
@@ -365,7 +382,7 @@ hipError_t launch_dims(const MultiParams& p, int B_H, hipStream_t stream) {
 
 }  // namespace
 
-int decode_multi_trip_tokens() { return kTrip; }
+int decode_multi_trip_tokens() { return kSplitUnit; }
 int decode_multi_item_tokens() { return kWaves * kTrip; }
 
 hipError_t launch_decode_attention_multi(const MultiParams& p, int D, int k, int blk, hipStream_t stream) {
