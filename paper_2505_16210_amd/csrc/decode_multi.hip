@@ -27,6 +27,10 @@
 //   and odd element).  Rows of one instruction are the 16 code bytes  4 (i16 % 8) + G + 2 (i16 / 8)
 //   (G = 0, 1) of a 32-byte chunk, so that they too stay inside one quantization block.
 //
+// 2-bit codes: a code byte holds four elements, so on the K side one look-up (two dwords) is a
+// whole operand, and on the V side row i16 is code byte i16 of a 16-byte chunk: one look-up per
+// token, re-paired into the operands of four instructions (element % 4).
+//
 // Work split: one workgroup of eight waves per (sequence, split); waves take 32-token trips
 // round-robin; per-wave results (m, l per query, O) meet in LDS in the space of the look-up
 // table, which is no longer needed then; with splits > 1 a second small kernel combines the
@@ -83,10 +87,11 @@ __device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
-template <int D, int BLK>
+template <int KBITS, int D, int BLK>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQKV_MULTI_WPE, NQKV_MULTI_WPE)))
 void decode_multi_kernel(const MultiParams p) {
-  constexpr int KBITS = 4;
+  static_assert(KBITS == 4 || KBITS == 2, "row mappings exist for 4- and 2-bit codes");
+  constexpr int KW = KBITS / 2;              // K side: dwords of codes per lane, chunk and token (16 elements)
   constexpr int NC = D / 64;                 // 64-element chunks of a row
   constexpr int NB = D / BLK;                // quantization blocks of a row
   constexpr int CPB = BLK / 64;              // chunks per block
@@ -106,9 +111,10 @@ void decode_multi_kernel(const MultiParams p) {
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t i16 = lane & 15, gq = lane >> 4;
-  const uint32_t lane_off = lane << 2;
+  const uint32_t lane_off = (KBITS == 4) ? (lane << 2) : ((lane & 31) << 3);
   // V side: the two code bytes of its dword this lane looks up (see the row mapping above)
-  const uint32_t vsel0 = 0x0c0c0000u | ((4u + 2u * (i16 >> 3)) << 8);
+  // (k = 2: a byte holds four elements, the lane looks up byte i16 % 4 of dword i16 / 4)
+  const uint32_t vsel0 = 0x0c0c0000u | ((4u + (KBITS == 4 ? 2u * (i16 >> 3) : (i16 & 3u))) << 8);
   const uint32_t vsel1 = vsel0 + 0x100u;
 
   // ---- item geometry
@@ -136,11 +142,11 @@ void decode_multi_kernel(const MultiParams p) {
 
   // per-lane byte offsets inside a tile (the trip and tile offsets are added to them: only the
   // vector offset takes part in the hardware range check, and rows past the item read zeros)
-  const uint32_t k_voff = i16 * kRowBytes + gq * 8u;                       // + c * kChunkBytes
-  const uint32_t v_voff = (4u * gq) * kRowBytes + (i16 & 7u) * 4u;         // + e * kRowBytes + c * kChunkBytes
+  const uint32_t k_voff = i16 * kRowBytes + gq * (4u * KW);                 // + c * kChunkBytes
+  const uint32_t v_voff = (4u * gq) * kRowBytes + (KBITS == 4 ? (i16 & 7u) : (i16 >> 2)) * 4u;   // + e * kRowBytes + c * kChunkBytes
   const uint32_t s_voff = (4u * gq) * kScaleRowBytes;
 
-  uint32_t kw[kTilesPerTrip][NC][2], vw[kTilesPerTrip][NC][4];
+  uint32_t kw[kTilesPerTrip][NC][KW], vw[kTilesPerTrip][NC][4];
   uint32_t ksr[kTilesPerTrip][SW], vsr[kTilesPerTrip][SW];
 
   auto load_scales = [&](__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t (&s)[SW]) {
@@ -158,8 +164,12 @@ void decode_multi_kernel(const MultiParams p) {
       const uint32_t tok = (uint32_t)tb + u * kTile;
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
-        const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(kc_r, k_voff + tok * kRowBytes + c * kChunkBytes, 0, 0);
-        kw[u][c][0] = v.x; kw[u][c][1] = v.y;
+        if constexpr (KBITS == 4) {
+          const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(kc_r, k_voff + tok * kRowBytes + c * kChunkBytes, 0, 0);
+          kw[u][c][0] = v.x; kw[u][c][1] = v.y;
+        } else {
+          kw[u][c][0] = __builtin_amdgcn_raw_buffer_load_b32(kc_r, k_voff + tok * kRowBytes + c * kChunkBytes, 0, 0);
+        }
       }
       load_scales(ks_r, s_voff + tok * kScaleRowBytes, ksr[u]);
     }
@@ -198,11 +208,11 @@ void decode_multi_kernel(const MultiParams p) {
   }
   build_lut<KBITS>(p, lds.lut);          // ends with a barrier
 
-  float4_t acc[NC][2][2];                // [chunk][G][even, odd element]
+  float4_t acc[NC][4];                   // k = 4: [chunk][2 G + parity of the element]; k = 2: [chunk][element % 4]
 #pragma unroll
   for (int c = 0; c < NC; ++c)
 #pragma unroll
-    for (int G = 0; G < 2; ++G) { acc[c][G][0] = float4_t{0, 0, 0, 0}; acc[c][G][1] = float4_t{0, 0, 0, 0}; }
+    for (int v = 0; v < 4; ++v) acc[c][v] = float4_t{0, 0, 0, 0};
   float m_run = kNoScore;                // this lane's query, log2 domain; equal over gq
   float l_run = 0.0f;                    // over this lane's own tokens only
 
@@ -223,14 +233,25 @@ void decode_multi_kernel(const MultiParams p) {
       for (int b = 0; b < NB; ++b) c1[b] = float4_t{0, 0, 0, 0};
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
-        const uint32_t w0 = kw[u][c][0], w1 = kw[u][c][1];
-        const uint32_t a[8] = {row_addr<0>(w0, lane_off), row_addr<1>(w0, lane_off), row_addr<2>(w0, lane_off), row_addr<3>(w0, lane_off),
-                               row_addr<0>(w1, lane_off), row_addr<1>(w1, lane_off), row_addr<2>(w1, lane_off), row_addr<3>(w1, lane_off)};
+        if constexpr (KBITS == 4) {
+          const uint32_t w0 = kw[u][c][0], w1 = kw[u][c][1];
+          const uint32_t a[8] = {row_addr<0>(w0, lane_off), row_addr<1>(w0, lane_off), row_addr<2>(w0, lane_off), row_addr<3>(w0, lane_off),
+                                 row_addr<0>(w1, lane_off), row_addr<1>(w1, lane_off), row_addr<2>(w1, lane_off), row_addr<3>(w1, lane_off)};
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const uint32_t x0 = *reinterpret_cast<const uint32_t*>(lut + a[2 * s]);
-          const uint32_t x1 = *reinterpret_cast<const uint32_t*>(lut + a[2 * s + 1]);
-          c1[c / CPB] = mfma16(x0, x1, qb[c][s][0], qb[c][s][1], c1[c / CPB]);
+          for (int s = 0; s < 4; ++s) {
+            const uint32_t x0 = *reinterpret_cast<const uint32_t*>(lut + a[2 * s]);
+            const uint32_t x1 = *reinterpret_cast<const uint32_t*>(lut + a[2 * s + 1]);
+            c1[c / CPB] = mfma16(x0, x1, qb[c][s][0], qb[c][s][1], c1[c / CPB]);
+          }
+        } else {
+          // a byte of 2-bit codes is four elements: one look-up is one operand
+          const uint32_t w0 = kw[u][c][0];
+          const uint32_t a[4] = {row_addr<0>(w0, lane_off), row_addr<1>(w0, lane_off), row_addr<2>(w0, lane_off), row_addr<3>(w0, lane_off)};
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            const uint2 x = *reinterpret_cast<const uint2*>(lut + a[s]);
+            c1[c / CPB] = mfma16(x.x, x.y, qb[c][s][0], qb[c][s][1], c1[c / CPB]);
+          }
         }
       }
 #pragma unroll
@@ -255,7 +276,7 @@ void decode_multi_kernel(const MultiParams p) {
 #pragma unroll
       for (int c = 0; c < NC; ++c)
 #pragma unroll
-        for (int G = 0; G < 2; ++G) { acc[c][G][0] *= alpha; acc[c][G][1] *= alpha; }
+        for (int v = 0; v < 4; ++v) acc[c][v] *= alpha;
       l_run *= alpha;
       m_run = m_new;
     }
@@ -288,19 +309,34 @@ void decode_multi_kernel(const MultiParams p) {
       }
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
+        const uint32_t b20 = b2[c / CPB][0], b21 = b2[c / CPB][1];
+        if constexpr (KBITS == 4) {
 #pragma unroll
-        for (int G = 0; G < 2; ++G) {
-          uint32_t h[4];
+          for (int G = 0; G < 2; ++G) {
+            uint32_t h[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const uint32_t addr = __builtin_amdgcn_perm(vw[u][c][e], lane_off, G ? vsel1 : vsel0);
+              h[e] = *reinterpret_cast<const uint32_t*>(lut + addr);
+            }
+            // {h[e].lo} over the four tokens -> even element's operand, {h[e].hi} -> odd element's
+            const uint32_t e0 = __builtin_amdgcn_perm(h[1], h[0], 0x05040100u), e1 = __builtin_amdgcn_perm(h[3], h[2], 0x05040100u);
+            const uint32_t o0 = __builtin_amdgcn_perm(h[1], h[0], 0x07060302u), o1 = __builtin_amdgcn_perm(h[3], h[2], 0x07060302u);
+            acc[c][2 * G] = mfma16(e0, e1, b20, b21, acc[c][2 * G]);
+            acc[c][2 * G + 1] = mfma16(o0, o1, b20, b21, acc[c][2 * G + 1]);
+          }
+        } else {
+          // one look-up per token: elements 4 i16 + 0..3 of the chunk; re-paired over the four tokens
+          uint2 h[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const uint32_t addr = __builtin_amdgcn_perm(vw[u][c][e], lane_off, G ? vsel1 : vsel0);
-            h[e] = *reinterpret_cast<const uint32_t*>(lut + addr);
+            const uint32_t addr = __builtin_amdgcn_perm(vw[u][c][e], lane_off, vsel0);
+            h[e] = *reinterpret_cast<const uint2*>(lut + addr);
           }
-          // {h[e].lo} over the four tokens -> even element's operand, {h[e].hi} -> odd element's
-          const uint32_t e0 = __builtin_amdgcn_perm(h[1], h[0], 0x05040100u), e1 = __builtin_amdgcn_perm(h[3], h[2], 0x05040100u);
-          const uint32_t o0 = __builtin_amdgcn_perm(h[1], h[0], 0x07060302u), o1 = __builtin_amdgcn_perm(h[3], h[2], 0x07060302u);
-          acc[c][G][0] = mfma16(e0, e1, b2[c / CPB][0], b2[c / CPB][1], acc[c][G][0]);
-          acc[c][G][1] = mfma16(o0, o1, b2[c / CPB][0], b2[c / CPB][1], acc[c][G][1]);
+          acc[c][0] = mfma16(__builtin_amdgcn_perm(h[1].x, h[0].x, 0x05040100u), __builtin_amdgcn_perm(h[3].x, h[2].x, 0x05040100u), b20, b21, acc[c][0]);
+          acc[c][1] = mfma16(__builtin_amdgcn_perm(h[1].x, h[0].x, 0x07060302u), __builtin_amdgcn_perm(h[3].x, h[2].x, 0x07060302u), b20, b21, acc[c][1]);
+          acc[c][2] = mfma16(__builtin_amdgcn_perm(h[1].y, h[0].y, 0x05040100u), __builtin_amdgcn_perm(h[3].y, h[2].y, 0x05040100u), b20, b21, acc[c][2]);
+          acc[c][3] = mfma16(__builtin_amdgcn_perm(h[1].y, h[0].y, 0x07060302u), __builtin_amdgcn_perm(h[3].y, h[2].y, 0x07060302u), b20, b21, acc[c][3]);
         }
       }
     }
@@ -316,15 +352,14 @@ void decode_multi_kernel(const MultiParams p) {
 #pragma unroll
     for (int c = 0; c < NC; ++c)
 #pragma unroll
-      for (int G = 0; G < 2; ++G)
+      for (int v = 0; v < 4; ++v)
 #pragma unroll
-        for (int par = 0; par < 2; ++par)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const uint32_t row = 4u * gq + r;                       // the instruction's output row
-            const uint32_t d = 64u * c + 8u * (row & 7u) + 2u * (G + 2u * (row >> 3)) + par;
-            lds.xo[wave][i16][d] = acc[c][G][par][r];
-          }
+        for (int r = 0; r < 4; ++r) {
+          const uint32_t row = 4u * gq + r;                       // the instruction's output row
+          const uint32_t d = (KBITS == 4) ? 64u * c + 8u * (row & 7u) + 2u * ((v >> 1) + 2u * (row >> 3)) + (v & 1)
+                                          : 64u * c + 4u * row + v;
+          lds.xo[wave][i16][d] = acc[c][v][r];
+        }
     if (gq == 0) { lds.wm[wave][i16] = m_run; lds.wl[wave][i16] = l_wave; }
   }
   __syncthreads();
@@ -371,13 +406,21 @@ __global__ __launch_bounds__(D) void combine_multi_kernel(const MultiParams p) {
   p.out[bq * D + d] = __builtin_bit_cast(unsigned short, (_Float16)(oo * p.inv_gamma / ll));
 }
 
-template <int D, int BLK>
+template <int KBITS, int D, int BLK>
 hipError_t launch_dims(const MultiParams& p, int B_H, hipStream_t stream) {
-  hipLaunchKernelGGL((decode_multi_kernel<D, BLK>), dim3((unsigned)p.n_items), dim3(kThreads), 0, stream, p);
+  hipLaunchKernelGGL((decode_multi_kernel<KBITS, D, BLK>), dim3((unsigned)p.n_items), dim3(kThreads), 0, stream, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.splits == 1) return e;
   hipLaunchKernelGGL((combine_multi_kernel<D>), dim3((unsigned)(B_H * p.q_len)), dim3(D), 0, stream, p);
   return hipGetLastError();
+}
+
+template <int KBITS>
+hipError_t launch_k(const MultiParams& p, int bh, int D, int blk, hipStream_t stream) {
+  if (D == 64 && blk == 64) return launch_dims<KBITS, 64, 64>(p, bh, stream);
+  if (D == 128 && blk == 64) return launch_dims<KBITS, 128, 64>(p, bh, stream);
+  if (D == 128 && blk == 128) return launch_dims<KBITS, 128, 128>(p, bh, stream);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace
@@ -386,11 +429,10 @@ int decode_multi_trip_tokens() { return kSplitUnit; }
 int decode_multi_item_tokens() { return kWaves * kTrip; }
 
 hipError_t launch_decode_attention_multi(const MultiParams& p, int D, int k, int blk, hipStream_t stream) {
-  if (k != 4 || p.q_len < 1 || p.q_len > kMaxQ || p.splits < 1 || p.n_items % p.splits) return hipErrorInvalidValue;
+  if (p.q_len < 1 || p.q_len > kMaxQ || p.splits < 1 || p.n_items % p.splits) return hipErrorInvalidValue;
   const int bh = p.n_items / p.splits;
-  if (D == 64 && blk == 64) return launch_dims<64, 64>(p, bh, stream);
-  if (D == 128 && blk == 64) return launch_dims<128, 64>(p, bh, stream);
-  if (D == 128 && blk == 128) return launch_dims<128, 128>(p, bh, stream);
+  if (k == 4) return launch_k<4>(p, bh, D, blk, stream);
+  if (k == 2) return launch_k<2>(p, bh, D, blk, stream);
   return hipErrorInvalidValue;
 }
 

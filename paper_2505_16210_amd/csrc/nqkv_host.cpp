@@ -745,7 +745,7 @@ int nqkv_decode_attention_multi(const nqkv_cache_desc* desc, const float* levels
   for (const void* ptr : ptrs) {
     if (!ptr || !aligned16(ptr)) return NQKV_EINVAL;
   }
-  if (desc->k != 4) return NQKV_EUNSUPPORTED;
+  if (desc->k == 3) return NQKV_EUNSUPPORTED;       // 3-bit codes are not byte aligned: no row mapping built
   // four-token scale loads need dword-aligned rows
   if ((desc->cap_tokens * (desc->D / desc->block)) % 2) return NQKV_EUNSUPPORTED;
   const size_t need = multi_workspace_need(desc, q_len, splits);

@@ -85,6 +85,35 @@ def test_c5_sweep_sampled_slabs(env, oracle, k, blk):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("name,q_len,rows", [("C3", 4, (0, 31)), ("C4", 16, (0,)), ("C2", 5, (0, 7))])
+def test_multi_query_attention_full_size(env, oracle, name, q_len, rows):
+    """Several queries per sequence at the bench sizes and the library's own split count: the
+    queries of the last q_len cached tokens, each over its causal prefix, against the oracle on
+    whole batch rows."""
+    nqkv, workloads = env
+    cfg = workloads.CONFIGS[name]
+    dev = torch.device("cuda:0")
+    g = workloads.make_generator(cfg, dev)
+    K, V = workloads.make_kv(cfg, dev, g)
+    q = (torch.randn(cfg.B, cfg.H, q_len, cfg.D, device=dev, generator=g) / cfg.D ** 0.5).to(torch.float16)
+    lv = nqkv.build_codebook(4)
+    desc = nqkv.make_desc(cfg.B, cfg.H, cfg.D, 4, 64, cfg.S)
+    kc, ks = nqkv.alloc_cache(desc, dev)
+    vc, vs = nqkv.alloc_cache(desc, dev)
+    nqkv.quantize_kv_pair(desc, lv, K, V, kc, ks, vc, vs, 0)
+    if name == "C4":
+        assert nqkv.decode_multi_workspace_bytes(desc, cfg.S, q_len, 0)[1] > 1
+    out = nqkv.decode_attention_multi(desc, lv, q, kc, ks, vc, vs, cfg.S, 1.0)
+    torch.cuda.synchronize()
+    for b in rows:
+        sl = slice(b, b + 1)
+        ref = oracle.decode_attention_multi(bits(q[sl]), bits(kc[sl]), bits(ks[sl]), bits(vc[sl]), bits(vs[sl]),
+                                            4, 64, lv, cfg.S, 1.0, n_threads=THREADS)
+        o = out[sl].cpu().numpy().reshape(1, -1, cfg.D)
+        assert np.isfinite(o.astype(np.float32)).all()
+        assert attn_err(o, ref.reshape(1, -1, cfg.D)) <= ATTN_TOL, (name, q_len, b)
+
+
 @pytest.mark.parametrize("fused", [False, True])
 def test_c2_prefill_then_128_decode_steps(env, oracle, fused):
     """The bench workload itself: quantize the 2048-token prefill, then 128 x (append one token,
