@@ -464,10 +464,10 @@ def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, time
                 packed + B * H * 4 * D + (2 * B * H * p_items * (D + 2) * 4 if p_items > 1 else 0), t_pg,
                 page_tokens=P, pages_per_sequence=n_pg, items_per_sequence=p_items)
             del pools, pws
-        if kb == 4:
+        if True:
             # a step that appended q_len tokens (speculative / batched verify): their queries over the
             # same cache, each on its causal prefix, on the matrix cores
-            for q_len in (4, 16):
+            for q_len in ((4, 16) if kb == 4 else (4,)):
                 qm = (torch.randn(B, H, q_len, D, device=dev, generator=g) / D ** 0.5).to(torch.float16)
                 outm = torch.empty_like(qm)
                 mws_bytes, m_splits = nqkv.decode_multi_workspace_bytes(desc, S, q_len, 0)

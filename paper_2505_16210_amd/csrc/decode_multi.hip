@@ -31,6 +31,11 @@
 // whole operand, and on the V side row i16 is code byte i16 of a 16-byte chunk: one look-up per
 // token, re-paired into the operands of four instructions (element % 4).
 //
+// 3-bit codes: pairs of codes are 6-bit fields that do not align with bytes.  K side: the lane's
+// 16 elements are 48 bits starting at byte 6 gq of the 24-byte chunk.  V side: row i16 is fields
+// 2 i16 and 2 i16 + 1 (12 bits at bit 12 i16), which may straddle a dword, so every V look-up pair
+// holds two dwords and a trip is one tile instead of two.
+//
 // Work split: one workgroup of eight waves per (sequence, split); waves take 32-token trips
 // round-robin; per-wave results (m, l per query, O) meet in LDS in the space of the look-up
 // table, which is no longer needed then; with splits > 1 a second small kernel combines the
@@ -90,8 +95,12 @@ __device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
 template <int KBITS, int D, int BLK>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQKV_MULTI_WPE, NQKV_MULTI_WPE)))
 void decode_multi_kernel(const MultiParams p) {
-  static_assert(KBITS == 4 || KBITS == 2, "row mappings exist for 4- and 2-bit codes");
-  constexpr int KW = KBITS / 2;              // K side: dwords of codes per lane, chunk and token (16 elements)
+  constexpr int KW = (KBITS == 2) ? 1 : 2;   // K side: dwords of codes per lane, chunk and token (16 elements)
+  constexpr int VW = (KBITS == 3) ? 2 : 1;   // V side: dwords per lane, chunk and token
+  // 3-bit rows need two dwords per V look-up pair (fields straddle dwords): one tile per trip
+  // keeps the code registers at the other widths' count
+  constexpr int TPT = (KBITS == 3) ? 1 : kTilesPerTrip;
+  constexpr int TRIP = kTile * TPT;
   constexpr int NC = D / 64;                 // 64-element chunks of a row
   constexpr int NB = D / BLK;                // quantization blocks of a row
   constexpr int CPB = BLK / 64;              // chunks per block
@@ -111,7 +120,7 @@ void decode_multi_kernel(const MultiParams p) {
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t i16 = lane & 15, gq = lane >> 4;
-  const uint32_t lane_off = (KBITS == 4) ? (lane << 2) : ((lane & 31) << 3);
+  const uint32_t lane_off = (KBITS == 4) ? (lane << 2) : (KBITS == 2) ? ((lane & 31) << 3) : ((lane & 31) << 2);
   // V side: the two code bytes of its dword this lane looks up (see the row mapping above)
   // (k = 2: a byte holds four elements, the lane looks up byte i16 % 4 of dword i16 / 4)
   const uint32_t vsel0 = 0x0c0c0000u | ((4u + (KBITS == 4 ? 2u * (i16 >> 3) : (i16 & 3u))) << 8);
@@ -142,12 +151,18 @@ void decode_multi_kernel(const MultiParams p) {
 
   // per-lane byte offsets inside a tile (the trip and tile offsets are added to them: only the
   // vector offset takes part in the hardware range check, and rows past the item read zeros)
-  const uint32_t k_voff = i16 * kRowBytes + gq * (4u * KW);                 // + c * kChunkBytes
-  const uint32_t v_voff = (4u * gq) * kRowBytes + (KBITS == 4 ? (i16 & 7u) : (i16 >> 2)) * 4u;   // + e * kRowBytes + c * kChunkBytes
+  // k = 3: the lane's 48 bits of a K row (16 elements) start at byte 6 gq of the chunk -- a 64-bit
+  // load from the dword below it, shifted by 0 or 16; its 12 bits of a V row (fields 2 i16 and
+  // 2 i16 + 1 of the chunk) start at bit 12 i16 -- a 64-bit load from dword min(12 i16 / 32, 4)
+  const uint32_t v3_dw = min((12u * i16) >> 5, 4u);
+  const uint32_t k3_shift = (gq & 1u) * 16u, v3_shift = 12u * i16 - 32u * v3_dw;
+  const uint32_t k_voff = i16 * kRowBytes + (KBITS == 3 ? ((6u * gq) & ~3u) : gq * (4u * KW));      // + c * kChunkBytes
+  const uint32_t v_voff = (4u * gq) * kRowBytes +
+                          (KBITS == 4 ? (i16 & 7u) : KBITS == 2 ? (i16 >> 2) : v3_dw) * 4u;           // + e * kRowBytes + c * kChunkBytes
   const uint32_t s_voff = (4u * gq) * kScaleRowBytes;
 
-  uint32_t kw[kTilesPerTrip][NC][KW], vw[kTilesPerTrip][NC][4];
-  uint32_t ksr[kTilesPerTrip][SW], vsr[kTilesPerTrip][SW];
+  uint32_t kw[TPT][NC][KW], vw[TPT][NC][4][VW];
+  uint32_t ksr[TPT][SW], vsr[TPT][SW];
 
   auto load_scales = [&](__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t (&s)[SW]) {
     if constexpr (NB == 1) {
@@ -160,11 +175,11 @@ void decode_multi_kernel(const MultiParams p) {
   };
   auto load_k = [&](int32_t tb) {
 #pragma unroll
-    for (int u = 0; u < kTilesPerTrip; ++u) {
+    for (int u = 0; u < TPT; ++u) {
       const uint32_t tok = (uint32_t)tb + u * kTile;
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
-        if constexpr (KBITS == 4) {
+        if constexpr (KBITS != 2) {
           const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(kc_r, k_voff + tok * kRowBytes + c * kChunkBytes, 0, 0);
           kw[u][c][0] = v.x; kw[u][c][1] = v.y;
         } else {
@@ -176,13 +191,20 @@ void decode_multi_kernel(const MultiParams p) {
   };
   auto load_v = [&](int32_t tb) {
 #pragma unroll
-    for (int u = 0; u < kTilesPerTrip; ++u) {
+    for (int u = 0; u < TPT; ++u) {
       const uint32_t tok = (uint32_t)tb + u * kTile;
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          vw[u][c][e] = __builtin_amdgcn_raw_buffer_load_b32(vc_r, v_voff + (tok + e) * kRowBytes + c * kChunkBytes, 0, 0);
+        {
+          if constexpr (KBITS == 3) {
+            const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(vc_r, v_voff + (tok + e) * kRowBytes + c * kChunkBytes, 0, 0);
+            vw[u][c][e][0] = v.x; vw[u][c][e][1] = v.y;
+          } else {
+            vw[u][c][e][0] = __builtin_amdgcn_raw_buffer_load_b32(vc_r, v_voff + (tok + e) * kRowBytes + c * kChunkBytes, 0, 0);
+          }
+        }
       }
       load_scales(vs_r, s_voff + tok * kScaleRowBytes, vsr[u]);
     }
@@ -193,7 +215,7 @@ void decode_multi_kernel(const MultiParams p) {
     return (idx & 1) ? half_hi(s[idx >> 1]) : half_lo(s[idx >> 1]);
   };
 
-  int32_t base = (int32_t)wave * kTrip;
+  int32_t base = (int32_t)wave * TRIP;
   load_k(base);
   // the query operand: q[query i16][64 c + 16 gq + 4 s + 0..3] for c, s -- 32 bytes per chunk;
   // rows beyond q_len read zeros
@@ -216,7 +238,7 @@ void decode_multi_kernel(const MultiParams p) {
   float m_run = kNoScore;                // this lane's query, log2 domain; equal over gq
   float l_run = 0.0f;                    // over this lane's own tokens only
 
-  constexpr int32_t stride = kWaves * kTrip;
+  constexpr int32_t stride = kWaves * TRIP;
   // One 32-token trip.  FULL: every token of it exists and is visible to every query (all trips but
   // the sequence's last few); the other copy masks per token and query.  Two copies of the whole
   // body rather than branches inside it, so that each is one straight-line scheduling region.
@@ -225,9 +247,9 @@ void decode_multi_kernel(const MultiParams p) {
     load_v(base);
 
     // ---- scores of the trip's two tiles
-    float z[kTilesPerTrip][4];
+    float z[TPT][4];
 #pragma unroll
-    for (int u = 0; u < kTilesPerTrip; ++u) {
+    for (int u = 0; u < TPT; ++u) {
       float4_t c1[NB];
 #pragma unroll
       for (int b = 0; b < NB; ++b) c1[b] = float4_t{0, 0, 0, 0};
@@ -241,6 +263,17 @@ void decode_multi_kernel(const MultiParams p) {
           for (int s = 0; s < 4; ++s) {
             const uint32_t x0 = *reinterpret_cast<const uint32_t*>(lut + a[2 * s]);
             const uint32_t x1 = *reinterpret_cast<const uint32_t*>(lut + a[2 * s + 1]);
+            c1[c / CPB] = mfma16(x0, x1, qb[c][s][0], qb[c][s][1], c1[c / CPB]);
+          }
+        } else if constexpr (KBITS == 3) {
+          // eight 6-bit pairs from the lane's 48 bits
+          const uint64_t x64 = (((uint64_t)kw[u][c][1] << 32) | kw[u][c][0]) >> k3_shift;
+          const uint32_t xw[2] = {(uint32_t)x64, (uint32_t)(x64 >> 32)};
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            const uint32_t f0 = field<2>(xw, 12 * s, 6), f1 = field<2>(xw, 12 * s + 6, 6);
+            const uint32_t x0 = *reinterpret_cast<const uint32_t*>(lut + ((f0 << 7) | lane_off));
+            const uint32_t x1 = *reinterpret_cast<const uint32_t*>(lut + ((f1 << 7) | lane_off));
             c1[c / CPB] = mfma16(x0, x1, qb[c][s][0], qb[c][s][1], c1[c / CPB]);
           }
         } else {
@@ -268,7 +301,7 @@ void decode_multi_kernel(const MultiParams p) {
     }
     float m_trip = fmaxf(fmaxf(z[0][0], z[0][1]), fmaxf(z[0][2], z[0][3]));
 #pragma unroll
-    for (int u = 1; u < kTilesPerTrip; ++u) m_trip = fmaxf(m_trip, fmaxf(fmaxf(z[u][0], z[u][1]), fmaxf(z[u][2], z[u][3])));
+    for (int u = 1; u < TPT; ++u) m_trip = fmaxf(m_trip, fmaxf(fmaxf(z[u][0], z[u][1]), fmaxf(z[u][2], z[u][3])));
     m_trip = allreduce_rows(m_trip, [](float a, float b) { return fmaxf(a, b); });
     const float m_new = fmaxf(m_run, m_trip);
     if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {       // uniform: some query's maximum grew
@@ -280,9 +313,9 @@ void decode_multi_kernel(const MultiParams p) {
       l_run *= alpha;
       m_run = m_new;
     }
-    float pw[kTilesPerTrip][4];
+    float pw[TPT][4];
 #pragma unroll
-    for (int u = 0; u < kTilesPerTrip; ++u)
+    for (int u = 0; u < TPT; ++u)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         pw[u][r] = __builtin_amdgcn_exp2f(z[u][r] - m_run);
@@ -293,7 +326,7 @@ void decode_multi_kernel(const MultiParams p) {
 
     // ---- weighted values
 #pragma unroll
-    for (int u = 0; u < kTilesPerTrip; ++u) {
+    for (int u = 0; u < TPT; ++u) {
       uint32_t b2[NB][2];       // P^T of the tile times the V block scale, fp16
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
@@ -316,7 +349,7 @@ void decode_multi_kernel(const MultiParams p) {
             uint32_t h[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const uint32_t addr = __builtin_amdgcn_perm(vw[u][c][e], lane_off, G ? vsel1 : vsel0);
+              const uint32_t addr = __builtin_amdgcn_perm(vw[u][c][e][0], lane_off, G ? vsel1 : vsel0);
               h[e] = *reinterpret_cast<const uint32_t*>(lut + addr);
             }
             // {h[e].lo} over the four tokens -> even element's operand, {h[e].hi} -> odd element's
@@ -325,12 +358,25 @@ void decode_multi_kernel(const MultiParams p) {
             acc[c][2 * G] = mfma16(e0, e1, b20, b21, acc[c][2 * G]);
             acc[c][2 * G + 1] = mfma16(o0, o1, b20, b21, acc[c][2 * G + 1]);
           }
+        } else if constexpr (KBITS == 3) {
+          // two look-ups per token (fields 2 i16, 2 i16 + 1: elements 4 i16 + 0..3 of the chunk)
+          uint32_t h0[4], h1[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const uint32_t x = (uint32_t)(((((uint64_t)vw[u][c][e][1]) << 32) | vw[u][c][e][0]) >> v3_shift);
+            h0[e] = *reinterpret_cast<const uint32_t*>(lut + (((x & 63u) << 7) | lane_off));
+            h1[e] = *reinterpret_cast<const uint32_t*>(lut + ((((x >> 6) & 63u) << 7) | lane_off));
+          }
+          acc[c][0] = mfma16(__builtin_amdgcn_perm(h0[1], h0[0], 0x05040100u), __builtin_amdgcn_perm(h0[3], h0[2], 0x05040100u), b20, b21, acc[c][0]);
+          acc[c][1] = mfma16(__builtin_amdgcn_perm(h0[1], h0[0], 0x07060302u), __builtin_amdgcn_perm(h0[3], h0[2], 0x07060302u), b20, b21, acc[c][1]);
+          acc[c][2] = mfma16(__builtin_amdgcn_perm(h1[1], h1[0], 0x05040100u), __builtin_amdgcn_perm(h1[3], h1[2], 0x05040100u), b20, b21, acc[c][2]);
+          acc[c][3] = mfma16(__builtin_amdgcn_perm(h1[1], h1[0], 0x07060302u), __builtin_amdgcn_perm(h1[3], h1[2], 0x07060302u), b20, b21, acc[c][3]);
         } else {
           // one look-up per token: elements 4 i16 + 0..3 of the chunk; re-paired over the four tokens
           uint2 h[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const uint32_t addr = __builtin_amdgcn_perm(vw[u][c][e], lane_off, vsel0);
+            const uint32_t addr = __builtin_amdgcn_perm(vw[u][c][e][0], lane_off, vsel0);
             h[e] = *reinterpret_cast<const uint2*>(lut + addr);
           }
           acc[c][0] = mfma16(__builtin_amdgcn_perm(h[1].x, h[0].x, 0x05040100u), __builtin_amdgcn_perm(h[3].x, h[2].x, 0x05040100u), b20, b21, acc[c][0]);
@@ -342,7 +388,7 @@ void decode_multi_kernel(const MultiParams p) {
     }
   };
   const int32_t n_clear = min(n_tok, lim_first);          // tokens every query sees, uniform
-  for (; base + kTrip <= n_clear; base += stride) trip_body(std::true_type{});
+  for (; base + TRIP <= n_clear; base += stride) trip_body(std::true_type{});
   for (; base < n_tok; base += stride) trip_body(std::false_type{});     // the sequence's ragged / causal end
 
   // ---- merge the eight waves.  The table is dead once every wave is here.
@@ -426,13 +472,14 @@ hipError_t launch_k(const MultiParams& p, int bh, int D, int blk, hipStream_t st
 }  // namespace
 
 int decode_multi_trip_tokens() { return kSplitUnit; }
-int decode_multi_item_tokens() { return kWaves * kTrip; }
+int decode_multi_item_tokens() { return kWaves * kTrip; }     // (the 3-bit kernel's sweep is half of this)
 
 hipError_t launch_decode_attention_multi(const MultiParams& p, int D, int k, int blk, hipStream_t stream) {
   if (p.q_len < 1 || p.q_len > kMaxQ || p.splits < 1 || p.n_items % p.splits) return hipErrorInvalidValue;
   const int bh = p.n_items / p.splits;
   if (k == 4) return launch_k<4>(p, bh, D, blk, stream);
   if (k == 2) return launch_k<2>(p, bh, D, blk, stream);
+  if (k == 3) return launch_k<3>(p, bh, D, blk, stream);
   return hipErrorInvalidValue;
 }
 

@@ -115,7 +115,7 @@ hipError_t launch_quantize_hidden(const QuantParams& p, int D, int k, int blk_hi
 // fuse: also quantize and append the new token (p.k_new / p.v_new) and attend over it
 hipError_t launch_decode_attention(const DecodeParams& p, int D, int k, int blk, bool fuse, hipStream_t stream);
 
-// q_len in [1, 16]; k = 4 or 2
+// q_len in [1, 16]
 hipError_t launch_decode_attention_multi(const MultiParams& p, int D, int k, int blk, hipStream_t stream);
 int decode_multi_trip_tokens();    // split boundaries of that kernel are multiples of this
 int decode_multi_item_tokens();    // tokens one workgroup of it consumes per sweep of its waves

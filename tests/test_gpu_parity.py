@@ -742,7 +742,7 @@ def _multi_err(out: torch.Tensor, ref: np.ndarray) -> float:
     return attn_err(o.reshape(1, -1, o.shape[-1]), ref.reshape(1, -1, ref.shape[-1]))
 
 
-@pytest.mark.parametrize("k,D,blk", [(4, 64, 64), (4, 128, 64), (4, 128, 128), (2, 64, 64), (2, 128, 64), (2, 128, 128)])
+@pytest.mark.parametrize("k,D,blk", COMBOS)
 def test_decode_attention_multi_matches_oracle(nqkv, oracle, k, D, blk):
     """q_len queries of the last q_len cached tokens, each over its own causal prefix; lengths
     that end inside a 16-token tile, on a tile and on a 32-token piece; every split count."""
