@@ -334,7 +334,7 @@ int nqkv_quantize_kv_hidden(const nqkv_cache_desc* desc, const float* levels,
  *              (partial results only: no zero-fill needed); may be NULL when that is 0
  * Errors: NQKV_EINVAL for null / misaligned pointers, q_len < 1, seq_len outside
  * [q_len, cap_tokens], num_splits above the number of 32-token pieces of the sequence;
- * NQKV_EUNSUPPORTED for q_len > 16 or an odd cap_tokens * (D / block);
+ * NQKV_EUNSUPPORTED for q_len > 16;
  * NQKV_EWORKSPACE for a short workspace.
  */
 int nqkv_decode_multi_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, int q_len, int num_splits,

@@ -16,7 +16,8 @@
 //   K (row = token i16), B = q^T.  The contraction index of one instruction is 16 head-dim
 //   elements of one 64-element chunk, element  64 c + 16 gq + 4 s + e  for step s, so a lane
 //   needs 8 contiguous code bytes per chunk (one 64-bit load) and the chunk lies inside one
-//   quantization block; the block scale of the token multiplies C1 afterwards, in fp32.
+//   quantization block; the block scale of the token multiplies C1 afterwards, in fp32 (a lane
+//   fetches the scales of one token of its quad of rows, the quad shares them by DPP).
 // Softmax.  A lane holds scores of tokens 4 gq + r (r = 0..3) of the tile for query i16: the
 //   running maximum and sum are per lane (= per query), reduced over gq with lane swaps.
 // Output.   O^T[d][query] = sum_token V[token][d] P[token][query]:  B = P^T is exactly the layout
@@ -105,7 +106,6 @@ void decode_multi_kernel(const MultiParams p) {
   constexpr int NB = D / BLK;                // quantization blocks of a row
   constexpr int CPB = BLK / 64;              // chunks per block
   constexpr uint32_t kRowBytes = D * KBITS / 8, kChunkBytes = 8 * KBITS, kScaleRowBytes = NB * 2;
-  constexpr int SW = NB * 2;                 // dwords of scales of four tokens
   constexpr int XS = D + 1;                  // padded row of the merge buffer
   struct Lds {
     float wm[kWaves][kMaxQ], wl[kWaves][kMaxQ];
@@ -129,7 +129,7 @@ void decode_multi_kernel(const MultiParams p) {
   // ---- item geometry
   const uint32_t item = blockIdx.x;
   const uint32_t bh = item / (uint32_t)p.splits, sp = item - bh * (uint32_t)p.splits;
-  // splits are whole 32-token pieces (so that every four-token scale load is dword aligned)
+  // splits are whole 32-token pieces
   const int32_t u0 = (int32_t)sp * p.split_base + min((int32_t)sp, p.split_rem);
   const int32_t t0 = u0 * kSplitUnit;
   const int32_t n_tok = min((p.split_base + ((int32_t)sp < p.split_rem ? 1 : 0)) * kSplitUnit, p.seq_len - t0);
@@ -139,10 +139,7 @@ void decode_multi_kernel(const MultiParams p) {
   const int32_t lim = min(n_tok, p.seq_len - p.q_len + 1 + qi - t0);
   const int32_t lim_first = p.seq_len - p.q_len + 1 - t0;           // query 0's, uniform
 
-  // Scale ranges end on a dword: with one 2-byte scale per token and an odd token count the last
-  // dword also holds the scale of the row after the item (the host makes sure that row exists);
-  // tokens past the item are masked below, whatever their scales hold.
-  const int scale_bytes = (n_tok * (int)kScaleRowBytes + 3) & ~3;
+  const int scale_bytes = n_tok * (int)kScaleRowBytes;
   const __amdgpu_buffer_rsrc_t kc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.k_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
   const __amdgpu_buffer_rsrc_t vc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.v_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
   const __amdgpu_buffer_rsrc_t ks_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.k_scales) + row0 * NB, 0, scale_bytes, kBufferFlags);
@@ -159,19 +156,15 @@ void decode_multi_kernel(const MultiParams p) {
   const uint32_t k_voff = i16 * kRowBytes + (KBITS == 3 ? ((6u * gq) & ~3u) : gq * (4u * KW));      // + c * kChunkBytes
   const uint32_t v_voff = (4u * gq) * kRowBytes +
                           (KBITS == 4 ? (i16 & 7u) : KBITS == 2 ? (i16 >> 2) : v3_dw) * 4u;           // + e * kRowBytes + c * kChunkBytes
-  const uint32_t s_voff = (4u * gq) * kScaleRowBytes;
+  // scales: lane (i16, gq) fetches those of token 4 gq + i16 % 4 only; the quad shares them by DPP
+  const uint32_t s_voff = (4u * gq + (i16 & 3u)) * kScaleRowBytes;
 
   uint32_t kw[TPT][NC][KW], vw[TPT][NC][4][VW];
-  uint32_t ksr[TPT][SW], vsr[TPT][SW];
+  uint32_t ksr[TPT], vsr[TPT];
 
-  auto load_scales = [&](__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t (&s)[SW]) {
-    if constexpr (NB == 1) {
-      const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, 0, 0);
-      s[0] = v.x; s[1] = v.y;
-    } else {
-      const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, 0, 0);
-      s[0] = v.x; s[1] = v.y; s[2] = v.z; s[3] = v.w;
-    }
+  auto load_scales = [&](__amdgpu_buffer_rsrc_t r, uint32_t voff) -> uint32_t {
+    if constexpr (NB == 1) return __builtin_amdgcn_raw_buffer_load_b16(r, voff, 0, 0);
+    else return __builtin_amdgcn_raw_buffer_load_b32(r, voff, 0, 0);
   };
   auto load_k = [&](int32_t tb) {
 #pragma unroll
@@ -186,7 +179,7 @@ void decode_multi_kernel(const MultiParams p) {
           kw[u][c][0] = __builtin_amdgcn_raw_buffer_load_b32(kc_r, k_voff + tok * kRowBytes + c * kChunkBytes, 0, 0);
         }
       }
-      load_scales(ks_r, s_voff + tok * kScaleRowBytes, ksr[u]);
+      ksr[u] = load_scales(ks_r, s_voff + tok * kScaleRowBytes);
     }
   };
   auto load_v = [&](int32_t tb) {
@@ -206,15 +199,15 @@ void decode_multi_kernel(const MultiParams p) {
           }
         }
       }
-      load_scales(vs_r, s_voff + tok * kScaleRowBytes, vsr[u]);
+      vsr[u] = load_scales(vs_r, s_voff + tok * kScaleRowBytes);
     }
   };
-  // scale of token 4 gq + r, block b, from the four-token scale words
-  auto scale_of = [&](const uint32_t (&s)[SW], int r, int b) {
-    const int idx = r * NB + b;
-    return (idx & 1) ? half_hi(s[idx >> 1]) : half_lo(s[idx >> 1]);
+  // scale of token 4 gq + r, block b: held by lane r of this lane's quad (quad_perm broadcast)
+  auto scale_of = [&](uint32_t s, auto r_tag, int b) {
+    constexpr int R = decltype(r_tag)::value;
+    const uint32_t w = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s, R * 0x55, 0xf, 0xf, true);
+    return b ? half_hi(w) : half_lo(w);
   };
-
   int32_t base = (int32_t)wave * TRIP;
   load_k(base);
   // the query operand: q[query i16][64 c + 16 gq + 4 s + 0..3] for c, s -- 32 bytes per chunk;
@@ -287,17 +280,18 @@ void decode_multi_kernel(const MultiParams p) {
           }
         }
       }
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
+      auto score = [&](auto r_tag) {
+        constexpr int r = decltype(r_tag)::value;
         float v = 0.0f;
 #pragma unroll
-        for (int b = 0; b < NB; ++b) v = __builtin_fmaf(c1[b][r], scale_of(ksr[u], r, b), v);
+        for (int b = 0; b < NB; ++b) v = __builtin_fmaf(c1[b][r], scale_of(ksr[u], r_tag, b), v);
         v *= p.scale_log2e;
-        // tokens past the item or not yet visible to this lane's query (a select: the scale of a
-        // row past the item may be anything)
+        // tokens past the item or not yet visible to this lane's query
         if (!FULL) v = (base + u * kTile + (int32_t)(4u * gq) + r < lim) ? v : -INFINITY;
         z[u][r] = v;
-      }
+      };
+      score(std::integral_constant<int, 0>{}); score(std::integral_constant<int, 1>{});
+      score(std::integral_constant<int, 2>{}); score(std::integral_constant<int, 3>{});
     }
     float m_trip = fmaxf(fmaxf(z[0][0], z[0][1]), fmaxf(z[0][2], z[0][3]));
 #pragma unroll
@@ -330,13 +324,11 @@ void decode_multi_kernel(const MultiParams p) {
       uint32_t b2[NB][2];       // P^T of the tile times the V block scale, fp16
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
-        float wv[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          wv[r] = pw[u][r] * scale_of(vsr[u], r, b);
-          // a token past the item has weight 0, but its scale may be anything (0 * NaN): select
-          if (!FULL) wv[r] = (base + u * kTile + (int32_t)(4u * gq) + r < n_tok) ? wv[r] : 0.0f;
-        }
+        // (a token past the item reads scale 0 through the range check, and its weight is 0 anyway)
+        const float wv[4] = {pw[u][0] * scale_of(vsr[u], std::integral_constant<int, 0>{}, b),
+                             pw[u][1] * scale_of(vsr[u], std::integral_constant<int, 1>{}, b),
+                             pw[u][2] * scale_of(vsr[u], std::integral_constant<int, 2>{}, b),
+                             pw[u][3] * scale_of(vsr[u], std::integral_constant<int, 3>{}, b)};
         b2[b][0] = pack_half2(wv[0], wv[1]);
         b2[b][1] = pack_half2(wv[2], wv[3]);
       }

@@ -746,8 +746,6 @@ int nqkv_decode_attention_multi(const nqkv_cache_desc* desc, const float* levels
   for (const void* ptr : ptrs) {
     if (!ptr || !aligned16(ptr)) return NQKV_EINVAL;
   }
-  // four-token scale loads need dword-aligned rows
-  if ((desc->cap_tokens * (desc->D / desc->block)) % 2) return NQKV_EUNSUPPORTED;
   const size_t need = multi_workspace_need(desc, q_len, splits);
   if (need > 0) {
     if (!workspace || !aligned16(workspace)) return NQKV_EINVAL;
