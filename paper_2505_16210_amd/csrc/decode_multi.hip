@@ -4,29 +4,33 @@
 // needs its output -- query i sees the cache up to and including its own token.
 //
 // With up to 16 query rows per head the two products are real (if skinny) matrix products, so
-// they run on the matrix cores: v_mfma_f32_16x16x16_f16, fp32 accumulate.  The table look-up that
-// turns codes into fp16 levels is the same byte-indexed LDS table as in the one-query kernel and
-// costs the same per cached element whatever q_len is; the arithmetic that the one-query kernel
-// spends vector instructions on (dot products, weighted sums) moves to the matrix pipe.
+// they run on the matrix cores, fp32 accumulate: v_mfma_f32_16x16x32_f16 (the 16-deep
+// v_mfma_f32_16x16x16_f16 for the value product of 3-bit caches).  The table look-up that turns
+// codes into fp16 levels is the same byte-indexed LDS table as in the one-query kernel and costs
+// the same per cached element whatever q_len is; the arithmetic that the one-query kernel spends
+// vector instructions on (dot products, weighted sums) moves to the matrix pipe.
 //
-// Operand layouts of the 16x16x16 instruction (lane l, i16 = l % 16, gq = l / 16):
-//   A[row i16][k = 4 gq + 0..3],  B[k = 4 gq + 0..3][col i16],  C/D[row 4 gq + 0..3][col i16].
+// Operand layouts (lane l, i16 = l % 16, gq = l / 16) of the 32-deep instruction (the 16-deep one:
+// four k per lane, k = 4 gq + 0..3):
+//   A[row i16][k = 8 gq + 0..7],  B[k = 8 gq + 0..7][col i16],  C/D[row 4 gq + 0..3][col i16].
 //
 // Scores.   C1[token][query] = sum_d K[token][d] q[query][d]:  A = levels of a 16-token tile of
-//   K (row = token i16), B = q^T.  The contraction index of one instruction is 16 head-dim
-//   elements of one 64-element chunk, element  64 c + 16 gq + 4 s + e  for step s, so a lane
-//   needs 8 contiguous code bytes per chunk (one 64-bit load) and the chunk lies inside one
-//   quantization block; the block scale of the token multiplies C1 afterwards, in fp32 (a lane
-//   fetches the scales of one token of its quad of rows, the quad shares them by DPP).
+//   K (row = token i16), B = q^T.  One instruction contracts over 32 head-dim elements of one
+//   64-element chunk, this lane's being  64 c + 16 gq + 8 h + 0..7  for half h, so a lane needs 8
+//   contiguous code bytes per chunk (one 64-bit load; dword h is one operand) and the chunk lies
+//   inside one quantization block; the block scale of the token multiplies C1 afterwards, in fp32
+//   (a lane fetches the scales of one token of its quad of rows, the quad shares them by DPP).
 // Softmax.  A lane holds scores of tokens 4 gq + r (r = 0..3) of the tile for query i16: the
 //   running maximum and sum are per lane (= per query), reduced over gq with lane swaps.
 // Output.   O^T[d][query] = sum_token V[token][d] P[token][query]:  B = P^T is exactly the layout
 //   C1 came out in (k = token 4 gq + r, col = query), converted to fp16 after multiplying in
-//   the token's V block scale.  A = V^T needs, per lane, one head-dim element of four tokens; a
-//   look-up yields two adjacent elements of ONE token, so four look-ups (tokens 4 gq + 0..3, the
-//   same code byte) are re-paired with v_perm_b32 into the operands of two instructions (even
-//   and odd element).  Rows of one instruction are the 16 code bytes  4 (i16 % 8) + G + 2 (i16 / 8)
-//   (G = 0, 1) of a 32-byte chunk, so that they too stay inside one quantization block.
+//   the token's V block scale; one instruction contracts over the 32 tokens of two tiles (this
+//   lane's eight: 4 gq + 0..3 of each).  A = V^T needs, per lane, one head-dim element of those
+//   eight tokens; a look-up yields two adjacent elements of ONE token, so eight look-ups (the same
+//   code byte of each token) are re-paired with v_perm_b32 into the operands of two instructions
+//   (even and odd element).  Rows of one instruction are the 16 code bytes
+//   4 (i16 % 8) + G + 2 (i16 / 8)  (G = 0, 1) of a 32-byte chunk, so that they too stay inside
+//   one quantization block.
 //
 // 2-bit codes: a code byte holds four elements, so on the K side one look-up (two dwords) is a
 // whole operand, and on the V side row i16 is code byte i16 of a 16-byte chunk: one look-up per
@@ -35,7 +39,8 @@
 // 3-bit codes: pairs of codes are 6-bit fields that do not align with bytes.  K side: the lane's
 // 16 elements are 48 bits starting at byte 6 gq of the 24-byte chunk.  V side: row i16 is fields
 // 2 i16 and 2 i16 + 1 (12 bits at bit 12 i16), which may straddle a dword, so every V look-up pair
-// holds two dwords and a trip is one tile instead of two.
+// holds two dwords, a trip is one tile instead of two, and the value product uses the 16-deep
+// instruction over that tile's tokens.
 //
 // Work split: one workgroup of eight waves per (sequence, split); waves take 32-token trips
 // round-robin; per-wave results (m, l per query, O) meet in LDS in the space of the look-up
@@ -66,9 +71,16 @@ constexpr int kMaxQ = 16;
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 
+// v_mfma_f32_16x16x16_f16: four fp16 per lane and operand (two dwords)
 __device__ __forceinline__ float4_t mfma16(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, float4_t c) {
   const u32x2_t a = {a0, a1}, b = {b0, b1};
   return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4_t, a), __builtin_bit_cast(half4_t, b), c, 0, 0, 0);
+}
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+// v_mfma_f32_16x16x32_f16: eight fp16 per lane and operand (four dwords)
+__device__ __forceinline__ float4_t mfma32(const uint32_t (&a)[4], const uint32_t (&b)[4], float4_t c) {
+  const u32x4_t av = {a[0], a[1], a[2], a[3]}, bv = {b[0], b[1], b[2], b[3]};
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av), __builtin_bit_cast(half8_t, bv), c, 0, 0, 0);
 }
 
 // All-reduce over the four 16-lane rows of a wave (lane bits 4 and 5): v_permlane32_swap exchanges
@@ -98,9 +110,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQKV_M
 void decode_multi_kernel(const MultiParams p) {
   constexpr int KW = (KBITS == 2) ? 1 : 2;   // K side: dwords of codes per lane, chunk and token (16 elements)
   constexpr int VW = (KBITS == 3) ? 2 : 1;   // V side: dwords per lane, chunk and token
-  // 3-bit rows need two dwords per V look-up pair (fields straddle dwords): one tile per trip
-  // keeps the code registers at the other widths' count
+  // 3-bit rows need two dwords per V look-up pair (fields straddle dwords): one tile per trip keeps
+  // the code registers at the other widths' count, and the value product contracts over that one
+  // tile with the 16-deep instruction
   constexpr int TPT = (KBITS == 3) ? 1 : kTilesPerTrip;
+  static_assert(KBITS == 3 || TPT % 2 == 0, "the value product contracts over two 16-token tiles");
   constexpr int TRIP = kTile * TPT;
   constexpr int NC = D / 64;                 // 64-element chunks of a row
   constexpr int NB = D / BLK;                // quantization blocks of a row
@@ -212,13 +226,13 @@ void decode_multi_kernel(const MultiParams p) {
   load_k(base);
   // the query operand: q[query i16][64 c + 16 gq + 4 s + 0..3] for c, s -- 32 bytes per chunk;
   // rows beyond q_len read zeros
-  uint32_t qb[NC][4][2];
+  uint32_t qb[NC][2][4];
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
 #pragma unroll
     for (int hlf = 0; hlf < 2; ++hlf) {
       const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(q_r, (i16 * D + 64u * c + 16u * gq + 8u * hlf) * 2u, 0, 0);
-      qb[c][2 * hlf][0] = v.x; qb[c][2 * hlf][1] = v.y; qb[c][2 * hlf + 1][0] = v.z; qb[c][2 * hlf + 1][1] = v.w;
+      qb[c][hlf][0] = v.x; qb[c][hlf][1] = v.y; qb[c][hlf][2] = v.z; qb[c][hlf][3] = v.w;
     }
   }
   build_lut<KBITS>(p, lds.lut);          // ends with a barrier
@@ -249,35 +263,38 @@ void decode_multi_kernel(const MultiParams p) {
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
         if constexpr (KBITS == 4) {
-          const uint32_t w0 = kw[u][c][0], w1 = kw[u][c][1];
-          const uint32_t a[8] = {row_addr<0>(w0, lane_off), row_addr<1>(w0, lane_off), row_addr<2>(w0, lane_off), row_addr<3>(w0, lane_off),
-                                 row_addr<0>(w1, lane_off), row_addr<1>(w1, lane_off), row_addr<2>(w1, lane_off), row_addr<3>(w1, lane_off)};
+          // dword h of the lane's eight code bytes: elements 8 h .. 8 h + 7 of its sixteen
 #pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            const uint32_t x0 = *reinterpret_cast<const uint32_t*>(lut + a[2 * s]);
-            const uint32_t x1 = *reinterpret_cast<const uint32_t*>(lut + a[2 * s + 1]);
-            c1[c / CPB] = mfma16(x0, x1, qb[c][s][0], qb[c][s][1], c1[c / CPB]);
+          for (int hlf = 0; hlf < 2; ++hlf) {
+            const uint32_t w = kw[u][c][hlf];
+            const uint32_t x[4] = {*reinterpret_cast<const uint32_t*>(lut + row_addr<0>(w, lane_off)),
+                                   *reinterpret_cast<const uint32_t*>(lut + row_addr<1>(w, lane_off)),
+                                   *reinterpret_cast<const uint32_t*>(lut + row_addr<2>(w, lane_off)),
+                                   *reinterpret_cast<const uint32_t*>(lut + row_addr<3>(w, lane_off))};
+            c1[c / CPB] = mfma32(x, qb[c][hlf], c1[c / CPB]);
           }
         } else if constexpr (KBITS == 3) {
           // eight 6-bit pairs from the lane's 48 bits
           const uint64_t x64 = (((uint64_t)kw[u][c][1] << 32) | kw[u][c][0]) >> k3_shift;
           const uint32_t xw[2] = {(uint32_t)x64, (uint32_t)(x64 >> 32)};
 #pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            const uint32_t f0 = field<2>(xw, 12 * s, 6), f1 = field<2>(xw, 12 * s + 6, 6);
-            const uint32_t x0 = *reinterpret_cast<const uint32_t*>(lut + ((f0 << 7) | lane_off));
-            const uint32_t x1 = *reinterpret_cast<const uint32_t*>(lut + ((f1 << 7) | lane_off));
-            c1[c / CPB] = mfma16(x0, x1, qb[c][s][0], qb[c][s][1], c1[c / CPB]);
+          for (int hlf = 0; hlf < 2; ++hlf) {
+            uint32_t x[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              x[j] = *reinterpret_cast<const uint32_t*>(lut + ((field<2>(xw, 24 * hlf + 6 * j, 6) << 7) | lane_off));
+            c1[c / CPB] = mfma32(x, qb[c][hlf], c1[c / CPB]);
           }
         } else {
-          // a byte of 2-bit codes is four elements: one look-up is one operand
+          // a byte of 2-bit codes is four elements: two look-ups are one operand
           const uint32_t w0 = kw[u][c][0];
-          const uint32_t a[4] = {row_addr<0>(w0, lane_off), row_addr<1>(w0, lane_off), row_addr<2>(w0, lane_off), row_addr<3>(w0, lane_off)};
-#pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            const uint2 x = *reinterpret_cast<const uint2*>(lut + a[s]);
-            c1[c / CPB] = mfma16(x.x, x.y, qb[c][s][0], qb[c][s][1], c1[c / CPB]);
-          }
+          const uint2 y0 = *reinterpret_cast<const uint2*>(lut + row_addr<0>(w0, lane_off));
+          const uint2 y1 = *reinterpret_cast<const uint2*>(lut + row_addr<1>(w0, lane_off));
+          const uint2 y2 = *reinterpret_cast<const uint2*>(lut + row_addr<2>(w0, lane_off));
+          const uint2 y3 = *reinterpret_cast<const uint2*>(lut + row_addr<3>(w0, lane_off));
+          const uint32_t xa[4] = {y0.x, y0.y, y1.x, y1.y}, xb[4] = {y2.x, y2.y, y3.x, y3.y};
+          c1[c / CPB] = mfma32(xa, qb[c][0], c1[c / CPB]);
+          c1[c / CPB] = mfma32(xb, qb[c][1], c1[c / CPB]);
         }
       }
       auto score = [&](auto r_tag) {
@@ -318,64 +335,97 @@ void decode_multi_kernel(const MultiParams p) {
 
     load_k(base + stride);      // past the end on the last trip: reads zeros
 
-    // ---- weighted values
+    // ---- weighted values: one instruction contracts over the 32 tokens of two tiles (this lane's
+    // eight: 4 gq + 0..3 of each)
+    constexpr uint32_t kLo = 0x05040100u, kHi = 0x07060302u;     // v_perm_b32: low / high halves of two dwords
+    if constexpr (KBITS != 3) {
 #pragma unroll
-    for (int u = 0; u < TPT; ++u) {
-      uint32_t b2[NB][2];       // P^T of the tile times the V block scale, fp16
+    for (int up = 0; up < TPT; up += 2) {
+      uint32_t b2[NB][4];       // P^T of the two tiles times the V block scale, fp16
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
-        // (a token past the item reads scale 0 through the range check, and its weight is 0 anyway)
-        const float wv[4] = {pw[u][0] * scale_of(vsr[u], std::integral_constant<int, 0>{}, b),
-                             pw[u][1] * scale_of(vsr[u], std::integral_constant<int, 1>{}, b),
-                             pw[u][2] * scale_of(vsr[u], std::integral_constant<int, 2>{}, b),
-                             pw[u][3] * scale_of(vsr[u], std::integral_constant<int, 3>{}, b)};
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const int u = up + t;
+          // (a token past the item reads scale 0 through the range check, and its weight is 0 anyway)
+          const float wv[4] = {pw[u][0] * scale_of(vsr[u], std::integral_constant<int, 0>{}, b),
+                               pw[u][1] * scale_of(vsr[u], std::integral_constant<int, 1>{}, b),
+                               pw[u][2] * scale_of(vsr[u], std::integral_constant<int, 2>{}, b),
+                               pw[u][3] * scale_of(vsr[u], std::integral_constant<int, 3>{}, b)};
+          b2[b][2 * t] = pack_half2(wv[0], wv[1]);
+          b2[b][2 * t + 1] = pack_half2(wv[2], wv[3]);
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const uint32_t (&bb)[4] = b2[c / CPB];
+        if constexpr (KBITS == 4) {
+#pragma unroll
+          for (int G = 0; G < 2; ++G) {
+            uint32_t h[8];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const uint32_t addr = __builtin_amdgcn_perm(vw[up + t][c][e][0], lane_off, G ? vsel1 : vsel0);
+                h[4 * t + e] = *reinterpret_cast<const uint32_t*>(lut + addr);
+              }
+            // {h.lo} over the eight tokens -> even element's operand, {h.hi} -> odd element's
+            const uint32_t ev[4] = {__builtin_amdgcn_perm(h[1], h[0], kLo), __builtin_amdgcn_perm(h[3], h[2], kLo),
+                                    __builtin_amdgcn_perm(h[5], h[4], kLo), __builtin_amdgcn_perm(h[7], h[6], kLo)};
+            const uint32_t od[4] = {__builtin_amdgcn_perm(h[1], h[0], kHi), __builtin_amdgcn_perm(h[3], h[2], kHi),
+                                    __builtin_amdgcn_perm(h[5], h[4], kHi), __builtin_amdgcn_perm(h[7], h[6], kHi)};
+            acc[c][2 * G] = mfma32(ev, bb, acc[c][2 * G]);
+            acc[c][2 * G + 1] = mfma32(od, bb, acc[c][2 * G + 1]);
+          }
+        } else {
+          // elements 4 i16 + 0..3 of the chunk: hx = {0, 1}, hy = {2, 3} per token
+          uint32_t hx[8], hy[8];
+#pragma unroll
+          for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const uint32_t addr = __builtin_amdgcn_perm(vw[up + t][c][e][0], lane_off, vsel0);
+              const uint2 y = *reinterpret_cast<const uint2*>(lut + addr);
+              hx[4 * t + e] = y.x; hy[4 * t + e] = y.y;
+            }
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const uint32_t (&hh)[8] = (v < 2) ? hx : hy;
+            const uint32_t sel = (v & 1) ? kHi : kLo;
+            const uint32_t a[4] = {__builtin_amdgcn_perm(hh[1], hh[0], sel), __builtin_amdgcn_perm(hh[3], hh[2], sel),
+                                   __builtin_amdgcn_perm(hh[5], hh[4], sel), __builtin_amdgcn_perm(hh[7], hh[6], sel)};
+            acc[c][v] = mfma32(a, bb, acc[c][v]);
+          }
+        }
+      }
+    }
+    } else {
+      // 3-bit codes: one tile, fields 2 i16 and 2 i16 + 1 of the chunk (elements 4 i16 + 0..3)
+      uint32_t b2[NB][2];
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const float wv[4] = {pw[0][0] * scale_of(vsr[0], std::integral_constant<int, 0>{}, b),
+                             pw[0][1] * scale_of(vsr[0], std::integral_constant<int, 1>{}, b),
+                             pw[0][2] * scale_of(vsr[0], std::integral_constant<int, 2>{}, b),
+                             pw[0][3] * scale_of(vsr[0], std::integral_constant<int, 3>{}, b)};
         b2[b][0] = pack_half2(wv[0], wv[1]);
         b2[b][1] = pack_half2(wv[2], wv[3]);
       }
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
         const uint32_t b20 = b2[c / CPB][0], b21 = b2[c / CPB][1];
-        if constexpr (KBITS == 4) {
+        uint32_t hx[4], hy[4];
 #pragma unroll
-          for (int G = 0; G < 2; ++G) {
-            uint32_t h[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const uint32_t addr = __builtin_amdgcn_perm(vw[u][c][e][0], lane_off, G ? vsel1 : vsel0);
-              h[e] = *reinterpret_cast<const uint32_t*>(lut + addr);
-            }
-            // {h[e].lo} over the four tokens -> even element's operand, {h[e].hi} -> odd element's
-            const uint32_t e0 = __builtin_amdgcn_perm(h[1], h[0], 0x05040100u), e1 = __builtin_amdgcn_perm(h[3], h[2], 0x05040100u);
-            const uint32_t o0 = __builtin_amdgcn_perm(h[1], h[0], 0x07060302u), o1 = __builtin_amdgcn_perm(h[3], h[2], 0x07060302u);
-            acc[c][2 * G] = mfma16(e0, e1, b20, b21, acc[c][2 * G]);
-            acc[c][2 * G + 1] = mfma16(o0, o1, b20, b21, acc[c][2 * G + 1]);
-          }
-        } else if constexpr (KBITS == 3) {
-          // two look-ups per token (fields 2 i16, 2 i16 + 1: elements 4 i16 + 0..3 of the chunk)
-          uint32_t h0[4], h1[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const uint32_t x = (uint32_t)(((((uint64_t)vw[u][c][e][1]) << 32) | vw[u][c][e][0]) >> v3_shift);
-            h0[e] = *reinterpret_cast<const uint32_t*>(lut + (((x & 63u) << 7) | lane_off));
-            h1[e] = *reinterpret_cast<const uint32_t*>(lut + ((((x >> 6) & 63u) << 7) | lane_off));
-          }
-          acc[c][0] = mfma16(__builtin_amdgcn_perm(h0[1], h0[0], 0x05040100u), __builtin_amdgcn_perm(h0[3], h0[2], 0x05040100u), b20, b21, acc[c][0]);
-          acc[c][1] = mfma16(__builtin_amdgcn_perm(h0[1], h0[0], 0x07060302u), __builtin_amdgcn_perm(h0[3], h0[2], 0x07060302u), b20, b21, acc[c][1]);
-          acc[c][2] = mfma16(__builtin_amdgcn_perm(h1[1], h1[0], 0x05040100u), __builtin_amdgcn_perm(h1[3], h1[2], 0x05040100u), b20, b21, acc[c][2]);
-          acc[c][3] = mfma16(__builtin_amdgcn_perm(h1[1], h1[0], 0x07060302u), __builtin_amdgcn_perm(h1[3], h1[2], 0x07060302u), b20, b21, acc[c][3]);
-        } else {
-          // one look-up per token: elements 4 i16 + 0..3 of the chunk; re-paired over the four tokens
-          uint2 h[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const uint32_t addr = __builtin_amdgcn_perm(vw[u][c][e][0], lane_off, vsel0);
-            h[e] = *reinterpret_cast<const uint2*>(lut + addr);
-          }
-          acc[c][0] = mfma16(__builtin_amdgcn_perm(h[1].x, h[0].x, 0x05040100u), __builtin_amdgcn_perm(h[3].x, h[2].x, 0x05040100u), b20, b21, acc[c][0]);
-          acc[c][1] = mfma16(__builtin_amdgcn_perm(h[1].x, h[0].x, 0x07060302u), __builtin_amdgcn_perm(h[3].x, h[2].x, 0x07060302u), b20, b21, acc[c][1]);
-          acc[c][2] = mfma16(__builtin_amdgcn_perm(h[1].y, h[0].y, 0x05040100u), __builtin_amdgcn_perm(h[3].y, h[2].y, 0x05040100u), b20, b21, acc[c][2]);
-          acc[c][3] = mfma16(__builtin_amdgcn_perm(h[1].y, h[0].y, 0x07060302u), __builtin_amdgcn_perm(h[3].y, h[2].y, 0x07060302u), b20, b21, acc[c][3]);
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t x = (uint32_t)(((((uint64_t)vw[0][c][e][1]) << 32) | vw[0][c][e][0]) >> v3_shift);
+          hx[e] = *reinterpret_cast<const uint32_t*>(lut + (((x & 63u) << 7) | lane_off));
+          hy[e] = *reinterpret_cast<const uint32_t*>(lut + ((((x >> 6) & 63u) << 7) | lane_off));
         }
+        acc[c][0] = mfma16(__builtin_amdgcn_perm(hx[1], hx[0], kLo), __builtin_amdgcn_perm(hx[3], hx[2], kLo), b20, b21, acc[c][0]);
+        acc[c][1] = mfma16(__builtin_amdgcn_perm(hx[1], hx[0], kHi), __builtin_amdgcn_perm(hx[3], hx[2], kHi), b20, b21, acc[c][1]);
+        acc[c][2] = mfma16(__builtin_amdgcn_perm(hy[1], hy[0], kLo), __builtin_amdgcn_perm(hy[3], hy[2], kLo), b20, b21, acc[c][2]);
+        acc[c][3] = mfma16(__builtin_amdgcn_perm(hy[1], hy[0], kHi), __builtin_amdgcn_perm(hy[3], hy[2], kHi), b20, b21, acc[c][3]);
       }
     }
   };
