@@ -57,13 +57,7 @@ namespace {
 constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
 constexpr int kTile = 16;                // tokens per matrix tile
-#ifndef NQKV_MULTI_TILES
-#define NQKV_MULTI_TILES 2
-#endif
-#ifndef NQKV_MULTI_WPE
-#define NQKV_MULTI_WPE 4
-#endif
-constexpr int kTilesPerTrip = NQKV_MULTI_TILES;
+constexpr int kTilesPerTrip = 2;
 constexpr int kTrip = kTile * kTilesPerTrip;
 constexpr int kSplitUnit = 32;           // split boundaries are multiples of this many tokens
 constexpr int kMaxQ = 16;
@@ -106,7 +100,7 @@ __device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
 }
 
 template <int KBITS, int D, int BLK>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(NQKV_MULTI_WPE, NQKV_MULTI_WPE)))
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))     // 128 registers: two workgroups per CU
 void decode_multi_kernel(const MultiParams p) {
   constexpr int KW = (KBITS == 2) ? 1 : 2;   // K side: dwords of codes per lane, chunk and token (16 elements)
   constexpr int VW = (KBITS == 3) ? 2 : 1;   // V side: dwords per lane, chunk and token
