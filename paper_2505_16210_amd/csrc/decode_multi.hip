@@ -197,8 +197,7 @@ void decode_multi_kernel(const MultiParams p) {
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-        {
+        for (int e = 0; e < 4; ++e) {
           if constexpr (KBITS == 3) {
             const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(vc_r, v_voff + (tok + e) * kRowBytes + c * kChunkBytes, 0, 0);
             vw[u][c][e][0] = v.x; vw[u][c][e][1] = v.y;
@@ -218,7 +217,7 @@ void decode_multi_kernel(const MultiParams p) {
   };
   int32_t base = (int32_t)wave * TRIP;
   load_k(base);
-  // the query operand: q[query i16][64 c + 16 gq + 4 s + 0..3] for c, s -- 32 bytes per chunk;
+  // the query operand: q[query i16][64 c + 16 gq + 8 h + 0..7] for chunk c, half h -- 32 bytes per chunk;
   // rows beyond q_len read zeros
   uint32_t qb[NC][2][4];
 #pragma unroll
@@ -231,7 +230,7 @@ void decode_multi_kernel(const MultiParams p) {
   }
   build_lut<KBITS>(p, lds.lut);          // ends with a barrier
 
-  float4_t acc[NC][4];                   // k = 4: [chunk][2 G + parity of the element]; k = 2: [chunk][element % 4]
+  float4_t acc[NC][4];                   // k = 4: [chunk][2 G + parity of the element]; k = 2, 3: [chunk][element % 4]
 #pragma unroll
   for (int c = 0; c < NC; ++c)
 #pragma unroll
@@ -240,7 +239,7 @@ void decode_multi_kernel(const MultiParams p) {
   float l_run = 0.0f;                    // over this lane's own tokens only
 
   constexpr int32_t stride = kWaves * TRIP;
-  // One 32-token trip.  FULL: every token of it exists and is visible to every query (all trips but
+  // One trip (32 tokens; 16 for 3-bit codes).  FULL: every token of it exists and is visible to every query (all trips but
   // the sequence's last few); the other copy masks per token and query.  Two copies of the whole
   // body rather than branches inside it, so that each is one straight-line scheduling region.
   auto trip_body = [&](auto full_tag) {
