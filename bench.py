@@ -464,7 +464,7 @@ def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, time
                 packed + B * H * 4 * D + (2 * B * H * p_items * (D + 2) * 4 if p_items > 1 else 0), t_pg,
                 page_tokens=P, pages_per_sequence=n_pg, items_per_sequence=p_items)
             del pools, pws
-        if True:
+        if True:     # (every code width)
             # a step that appended q_len tokens (speculative / batched verify): their queries over the
             # same cache, each on its causal prefix, on the matrix cores
             for q_len in ((4, 16) if kb == 4 else (4,)):
@@ -483,6 +483,21 @@ def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, time
                 kern[tag + ".decode_attention_multi.q%d" % q_len] = kernel_entry(
                     mbytes, t_m, splits=m_splits, q_len=q_len, vs_one_query=round(t_m / t_a, 3),
                     mfma_TFLOPs_issued=round(flops / (t_m * 1e-3) / 1e12, 1))
+                if B >= 8 and q_len == 4 and kb == 4:
+                    # the same step for the length mix of the per-sequence-length entry
+                    mlens_host = torch.linspace(S / 8, S, B).round().to(torch.int32)
+                    mlens_host = mlens_host[torch.randperm(B, generator=torch.Generator().manual_seed(0))]
+                    mlens = mlens_host.to(dev)
+
+                    def attend_multi_varlen(i):
+                        kc, ks, vc, vs = caches[i % r_cache]
+                        nqkv.decode_attention_multi_varlen(desc, lv, qm, kc, ks, vc, vs, mlens, S, 1.0, out=outm, workspace=mws)
+
+                    t_mv = tk(attend_multi_varlen, n_it * 2, warm=max(2, r_cache))
+                    mvbytes = int(mlens_host.sum()) * H * workloads.decode_bytes_per_token_head(D, kb, bl) \
+                        + B * H * q_len * 4 * D + (2 * B * H * m_splits * q_len * (D + 2) * 4 if m_splits > 1 else 0)
+                    kern[tag + ".decode_attention_multi_varlen.q%d" % q_len] = kernel_entry(
+                        mvbytes, t_mv, splits=m_splits, q_len=q_len, lengths="%d..%d evenly spread" % (S // 8, S))
                 del qm, outm, mws
         if (H * D) % 256 == 0:
             # the paper's own block geometry: 256 consecutive elements of the token's hidden vector,

@@ -17,7 +17,7 @@
  *   nqkv_decode_attention_paged / nqkv_decode_step_paged  the same over a paged cache
  *   nqkv_quantize_kv_hidden  blocks over the token's hidden vector, token-major source
  *                                                                    (Fig. 5, Sec. 4.1)
- *   nqkv_decode_attention_multi  several new tokens' queries in one step (Sec. 1, Sec. 3.2)
+ *   nqkv_decode_attention_multi (_varlen)  several new tokens' queries in one step (Sec. 1, Sec. 3.2)
  *
  * General rules
  *   - Every function returns NQKV_OK (0) or a negative NQKV_E* code.  Nothing throws,
@@ -343,6 +343,20 @@ int nqkv_decode_attention_multi(const nqkv_cache_desc* desc, const float* levels
                                 const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
                                 int64_t seq_len, int q_len, float softmax_scale, void* out,
                                 void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream);
+
+/*
+ * The same for a batch whose sequences differ in length: sequence b holds seq_lens[b] cached
+ * tokens (device int32 [B], 4-byte aligned, q_len..max_seq_len; values outside are clamped into
+ * that range, the result for such a sequence is then unspecified), its q_len queries are those of
+ * its own last q_len tokens.  Splits and workspace are planned for max_seq_len
+ * (nqkv_decode_multi_workspace_bytes(desc, max_seq_len, q_len, ...)).  Equals
+ * nqkv_decode_attention_multi when all entries are max_seq_len.
+ * Errors: as there, plus NQKV_EINVAL for a null / misaligned array.
+ */
+int nqkv_decode_attention_multi_varlen(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                                       const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                                       const int32_t* seq_lens, int64_t max_seq_len, int q_len, float softmax_scale, void* out,
+                                       void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream);
 
 /*
  * Measurement helper, not part of the method: reads `bytes` (a multiple of 16) of device memory

@@ -50,6 +50,7 @@
 
 #include "decode_common.h"
 #include "nqkv_internal.h"
+#include "scalar_read.h"
 
 namespace nqkv {
 namespace {
@@ -140,12 +141,16 @@ void decode_multi_kernel(const MultiParams p) {
   // splits are whole 32-token pieces
   const int32_t u0 = (int32_t)sp * p.split_base + min((int32_t)sp, p.split_rem);
   const int32_t t0 = u0 * kSplitUnit;
-  const int32_t n_tok = min((p.split_base + ((int32_t)sp < p.split_rem ? 1 : 0)) * kSplitUnit, p.seq_len - t0);
+  // the sequence's own length when the batch is ragged (whatever the array holds, stay inside
+  // [q_len, the length the host planned for]); pieces past its end are empty
+  int32_t seq_len = p.seq_len;
+  if (p.seq_lens) seq_len = __builtin_amdgcn_readfirstlane(min(max(scalar_read(p.seq_lens + bh / (uint32_t)p.H), p.q_len), p.seq_len));
+  const int32_t n_tok = max(min((p.split_base + ((int32_t)sp < p.split_rem ? 1 : 0)) * kSplitUnit, seq_len - t0), 0);
   const int64_t row0 = (int64_t)bh * p.cap_tokens + t0;
   // item-relative token limit of this lane's query: query i sees tokens [0, seq_len - q_len + 1 + i)
   const int32_t qi = min((int32_t)i16, p.q_len - 1);
-  const int32_t lim = min(n_tok, p.seq_len - p.q_len + 1 + qi - t0);
-  const int32_t lim_first = p.seq_len - p.q_len + 1 - t0;           // query 0's, uniform
+  const int32_t lim = min(n_tok, seq_len - p.q_len + 1 + qi - t0);
+  const int32_t lim_first = seq_len - p.q_len + 1 - t0;             // query 0's, uniform
 
   const int scale_bytes = n_tok * (int)kScaleRowBytes;
   const __amdgpu_buffer_rsrc_t kc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.k_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);

@@ -731,10 +731,11 @@ int nqkv_decode_multi_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_l
   return NQKV_OK;
 }
 
-int nqkv_decode_attention_multi(const nqkv_cache_desc* desc, const float* levels, const void* q,
-                                const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
-                                int64_t seq_len, int q_len, float softmax_scale, void* out,
-                                void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
+// Shared by nqkv_decode_attention_multi (lens == nullptr) and its per-sequence-length form.
+static int decode_multi_impl(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                             const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                             const int32_t* lens, int64_t seq_len, int q_len, float softmax_scale, void* out,
+                             void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
   int rc = check_desc(desc);
   if (rc) return rc;
   LevelTable checked;
@@ -771,12 +772,31 @@ int nqkv_decode_attention_multi(const nqkv_cache_desc* desc, const float* levels
   p.seq_len = (int)seq_len;
   p.q_len = q_len;
   p.cap_tokens = desc->cap_tokens;
+  p.seq_lens = lens;
+  p.H = desc->H;
   const LutChoice& lut = choose_lut_scale(checked.v, 1 << desc->k);
   std::memcpy(p.lut_levels, lut.bits, sizeof(uint16_t) * (1 << desc->k));
   p.inv_gamma = 1.0f / lut.gamma;
   p.scale_log2e = (float)((double)softmax_scale * 1.44269504088896340736 / (double)lut.gamma);
   const hipError_t e = launch_decode_attention_multi(p, desc->D, desc->k, desc->block, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
+}
+
+int nqkv_decode_attention_multi(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                                const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                                int64_t seq_len, int q_len, float softmax_scale, void* out,
+                                void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
+  return decode_multi_impl(desc, levels, q, k_codes, k_scales, v_codes, v_scales, nullptr, seq_len, q_len, softmax_scale, out,
+                           workspace, workspace_bytes, num_splits, hip_stream);
+}
+
+int nqkv_decode_attention_multi_varlen(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                                       const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                                       const int32_t* seq_lens, int64_t max_seq_len, int q_len, float softmax_scale, void* out,
+                                       void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
+  if (!seq_lens || (reinterpret_cast<uintptr_t>(seq_lens) & 3u)) return NQKV_EINVAL;
+  return decode_multi_impl(desc, levels, q, k_codes, k_scales, v_codes, v_scales, seq_lens, max_seq_len, q_len, softmax_scale, out,
+                           workspace, workspace_bytes, num_splits, hip_stream);
 }
 
 int nqkv_probe_read_stream(const void* src, size_t bytes, void* checksums, void* hip_stream) {

@@ -94,11 +94,14 @@ struct MultiParams {
   int n_items;               // B*H*splits
   int splits;
   int split_base, split_rem; // in 32-token trips: ceil(seq_len / 32) = splits * split_base + split_rem
-  int seq_len, q_len;
+  int seq_len, q_len;        // seq_len: cached tokens (with seq_lens: the largest, which the splits are laid out for)
   int64_t cap_tokens;
   float scale_log2e;         // softmax_scale * log2(e) / gamma
   float inv_gamma;
   uint16_t lut_levels[kMaxLevels];
+  // per-sequence lengths (NULL: every sequence has seq_len): cached tokens of sequence b
+  const int32_t* seq_lens;
+  int H;
 };
 
 // Bytes at the start of the split-K workspace that hold the ticket counters (one uint32 per

@@ -22,7 +22,7 @@ EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_set_tuning", "nqkv_build_codeb
            "nqkv_quantize_kv", "nqkv_quantize_kv_pair", "nqkv_dequantize_kv",
            "nqkv_decode_workspace_bytes", "nqkv_decode_attention", "nqkv_decode_step",
            "nqkv_probe_read_stream", "nqkv_quantize_kv_hidden",
-           "nqkv_decode_multi_workspace_bytes", "nqkv_decode_attention_multi",
+           "nqkv_decode_multi_workspace_bytes", "nqkv_decode_attention_multi", "nqkv_decode_attention_multi_varlen",
            "nqkv_decode_attention_varlen", "nqkv_decode_step_varlen",
            "nqkv_decode_paged_workspace_bytes", "nqkv_decode_attention_paged", "nqkv_decode_step_paged",
            "nqkv_quantize_kv_paged")
@@ -70,6 +70,9 @@ def _load() -> ctypes.CDLL:
     lib.nqkv_decode_attention_multi.restype = i32
     lib.nqkv_decode_attention_multi.argtypes = [dp, fp, vp, vp, vp, vp, vp, i64, i32, c.c_float, vp, vp,
                                                 c.c_size_t, i32, vp]
+    lib.nqkv_decode_attention_multi_varlen.restype = i32
+    lib.nqkv_decode_attention_multi_varlen.argtypes = [dp, fp, vp, vp, vp, vp, vp, vp, i64, i32, c.c_float, vp, vp,
+                                                       c.c_size_t, i32, vp]
     lib.nqkv_decode_attention.restype = i32
     lib.nqkv_decode_attention.argtypes = [dp, fp, vp, vp, vp, vp, vp, i64, c.c_float, vp, vp,
                                           c.c_size_t, i32, vp]
@@ -274,6 +277,32 @@ def decode_attention_multi(desc: CacheDesc, levels, q: torch.Tensor, k_codes, k_
                                          _dev_ptr(v_codes), _dev_ptr(v_scales), seq_len, q_len, float(softmax_scale),
                                          _dev_ptr(out), _dev_ptr(workspace), ws_bytes, num_splits, _stream(stream))
     _check(rc, "nqkv_decode_attention_multi")
+    return out
+
+
+def decode_attention_multi_varlen(desc: CacheDesc, levels, q: torch.Tensor, k_codes, k_scales, v_codes, v_scales,
+                                  seq_lens: torch.Tensor, max_seq_len: int, softmax_scale: float = 1.0,
+                                  out: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
+                                  num_splits: int = 0, stream=None) -> torch.Tensor:
+    """nqkv_decode_attention_multi_varlen: seq_lens int32 [B] on the device; q fp16 [B,H,Q,D]."""
+    lv, lvp = _levels_ptr(levels)
+    assert q.dtype == torch.float16 and q.is_contiguous() and q.dim() == 4
+    assert seq_lens.dtype == torch.int32 and seq_lens.is_contiguous() and seq_lens.numel() == desc.B
+    q_len = q.shape[2]
+    if out is None:
+        out = torch.empty_like(q)
+    ws_bytes = 0
+    if workspace is None:
+        need, _ = decode_multi_workspace_bytes(desc, max_seq_len, q_len, num_splits)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    if workspace is not None:
+        ws_bytes = workspace.numel() * workspace.element_size()
+    rc = lib.nqkv_decode_attention_multi_varlen(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_codes), _dev_ptr(k_scales),
+                                                _dev_ptr(v_codes), _dev_ptr(v_scales), _dev_ptr(seq_lens), max_seq_len,
+                                                q_len, float(softmax_scale), _dev_ptr(out), _dev_ptr(workspace), ws_bytes,
+                                                num_splits, _stream(stream))
+    _check(rc, "nqkv_decode_attention_multi_varlen")
     return out
 
 

@@ -816,3 +816,38 @@ def test_decode_attention_multi_peaked_flat_and_tiny_value_scales(nqkv, oracle):
             out = nqkv.decode_attention_multi(desc, lv, q, kc, ks, vc, vs, S, scale, num_splits=ns)
             torch.cuda.synchronize()
             assert _multi_err(out, ref) <= ATTN_TOL, (scale, ns)
+
+
+@pytest.mark.parametrize("k,D,blk", [(4, 64, 64), (4, 128, 64), (3, 128, 128), (2, 64, 64)])
+def test_decode_attention_multi_varlen_matches_oracle_per_sequence(nqkv, oracle, k, D, blk):
+    """Several queries per sequence in a batch of different lengths (exactly q_len tokens, a ragged
+    tail, less than one split's share, the full cache): every sequence equals the oracle run on it
+    alone for every split count; equal lengths give the fixed-length call's bits; wild entries are
+    clamped without touching the other sequences."""
+    B, H, S, cap, Q = 5, 3, 1500, 1536, 6
+    lv, desc, _, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, S, cap, seed=19 * k + D + blk)
+    kc[:, :, S:] = 0xFF
+    ks[:, :, S:] = 60000.0
+    vs[:, :, S:] = 60000.0
+    g = torch.Generator(device="cuda").manual_seed(41)
+    q = (torch.randn(B, H, Q, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+    hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+    lens = [Q, 65, 700, 1237, S]
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    ref = np.concatenate([oracle.decode_attention_multi(*[a[b:b + 1] for a in hk], k, blk, lv, lens[b], 0.9, n_threads=4)
+                          for b in range(B)], 0)
+    for ns in (0, 1, 2, 7, 40):
+        out = nqkv.decode_attention_multi_varlen(desc, lv, q, kc, ks, vc, vs, lens_dev, S, 0.9, num_splits=ns)
+        torch.cuda.synchronize()
+        assert _multi_err(out, ref) <= ATTN_TOL, (k, D, blk, ns)
+    same = torch.full((B,), 1000, dtype=torch.int32, device="cuda")
+    for ns in (1, 5):
+        a = nqkv.decode_attention_multi_varlen(desc, lv, q, kc, ks, vc, vs, same, 1000, 0.9, num_splits=ns)
+        b_ = nqkv.decode_attention_multi(desc, lv, q, kc, ks, vc, vs, 1000, 0.9, num_splits=ns)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b_)
+    wild = torch.tensor([Q, 65, -5, 10 ** 9, S], dtype=torch.int32, device="cuda")
+    out = nqkv.decode_attention_multi_varlen(desc, lv, q, kc, ks, vc, vs, wild, S, 0.9)
+    torch.cuda.synchronize()
+    for b in (0, 1, 4):
+        assert _multi_err(out[b:b + 1], ref[b:b + 1]) <= ATTN_TOL

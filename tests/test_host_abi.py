@@ -204,6 +204,14 @@ def test_decode_multi_argument_errors_and_planning(nqkv):
     assert call(ns=1025) == nqkv.EINVAL
     assert call(seq=100, ns=5) == nqkv.EINVAL                    # 100 tokens are four 32-token pieces
     assert call(levels=None) == nqkv.EINVAL
+    fv = nqkv.lib.nqkv_decode_attention_multi_varlen
+    def callv(lens=FAKE, mx=32768, q_len=4, q=FAKE):
+        return fv(ctypes.byref(d), lvp, q, FAKE, FAKE, FAKE, FAKE, lens, mx, q_len, 1.0, FAKE, FAKE, 1 << 30, 0, None)
+    assert callv(lens=None) == nqkv.EINVAL
+    assert callv(lens=FAKE + 2) == nqkv.EINVAL
+    assert callv(mx=32769) == nqkv.EINVAL
+    assert callv(mx=3) == nqkv.EINVAL
+    assert callv(q=None) == nqkv.EINVAL
     # workspace: partial results only, [B*H][splits][q_len][D+2] floats
     assert nqkv.decode_multi_workspace_bytes(d, 32768, 4, 1) == (0, 1)
     assert nqkv.decode_multi_workspace_bytes(d, 32768, 4, 7) == (32 * 7 * 4 * 130 * 4, 7)
