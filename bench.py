@@ -463,6 +463,21 @@ def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, time
             kern[tag + ".decode_attention_paged"] = kernel_entry(
                 packed + B * H * 4 * D + (2 * B * H * p_items * (D + 2) * 4 if p_items > 1 else 0), t_pg,
                 page_tokens=P, pages_per_sequence=n_pg, items_per_sequence=p_items)
+            if kb == 4:
+                qmp = (torch.randn(B, H, 4, D, device=dev, generator=g) / D ** 0.5).to(torch.float16)
+                outmp = torch.empty_like(qmp)
+                mpws_bytes, mp_splits = nqkv.decode_multi_paged_workspace_bytes(pdesc, S, 4, 0)
+                mpws = torch.empty(max(mpws_bytes, 16), dtype=torch.uint8, device=dev)
+
+                def attend_multi_paged(i):
+                    nqkv.decode_attention_multi_paged(pdesc, lv, qmp, *pools[i % r_cache], table, full, S, 1.0, out=outmp,
+                                                      workspace=mpws)
+
+                t_mp = tk(attend_multi_paged, n_it * 2, warm=max(2, r_cache))
+                kern[tag + ".decode_attention_multi_paged.q4"] = kernel_entry(
+                    packed + B * H * 4 * 4 * D + (2 * B * H * mp_splits * 4 * (D + 2) * 4 if mp_splits > 1 else 0), t_mp,
+                    page_tokens=P, splits=mp_splits, q_len=4)
+                del qmp, outmp, mpws
             del pools, pws
         if True:     # (every code width)
             # a step that appended q_len tokens (speculative / batched verify): their queries over the

@@ -17,7 +17,8 @@
  *   nqkv_decode_attention_paged / nqkv_decode_step_paged  the same over a paged cache
  *   nqkv_quantize_kv_hidden  blocks over the token's hidden vector, token-major source
  *                                                                    (Fig. 5, Sec. 4.1)
- *   nqkv_decode_attention_multi (_varlen)  several new tokens' queries in one step (Sec. 1, Sec. 3.2)
+ *   nqkv_decode_attention_multi (_varlen, _paged)  several new tokens' queries in one step
+ *                                                                    (Sec. 1, Sec. 3.2)
  *
  * General rules
  *   - Every function returns NQKV_OK (0) or a negative NQKV_E* code.  Nothing throws,
@@ -357,6 +358,25 @@ int nqkv_decode_attention_multi_varlen(const nqkv_cache_desc* desc, const float*
                                        const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
                                        const int32_t* seq_lens, int64_t max_seq_len, int q_len, float softmax_scale, void* out,
                                        void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream);
+
+/*
+ * And over a PAGED cache (pool layout, block table and page size as for
+ * nqkv_decode_attention_paged; desc->cap_tokens is the page size P): the q_len queries of sequence
+ * b are those of its last q_len tokens, seq_lens[b] of them cached in the pages its table row
+ * names.  The new tokens are appended first with nqkv_quantize_kv_paged (call per sequence when
+ * the positions differ).  max_seq_len is bound by table_stride * P; the workspace comes from
+ * nqkv_decode_multi_paged_workspace_bytes(desc, max_seq_len, q_len, num_splits, ...).
+ * Errors: as nqkv_decode_attention_multi_varlen, plus NQKV_EINVAL for a null / misaligned table or
+ * a bad table_stride / num_pages, NQKV_EUNSUPPORTED for a page size that is not a power of two
+ * >= 128.
+ */
+int nqkv_decode_multi_paged_workspace_bytes(const nqkv_cache_desc* desc, int64_t max_seq_len, int q_len, int num_splits,
+                                            size_t* bytes_out, int* splits_out);
+int nqkv_decode_attention_multi_paged(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                                      const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                                      const int32_t* block_table, int64_t table_stride, int64_t num_pages,
+                                      const int32_t* seq_lens, int64_t max_seq_len, int q_len, float softmax_scale, void* out,
+                                      void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream);
 
 /*
  * Measurement helper, not part of the method: reads `bytes` (a multiple of 16) of device memory

@@ -100,7 +100,7 @@ __device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
-template <int KBITS, int D, int BLK>
+template <int KBITS, int D, int BLK, bool PAGED>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))     // 128 registers: two workgroups per CU
 void decode_multi_kernel(const MultiParams p) {
   constexpr int KW = (KBITS == 2) ? 1 : 2;   // K side: dwords of codes per lane, chunk and token (16 elements)
@@ -146,15 +146,17 @@ void decode_multi_kernel(const MultiParams p) {
   int32_t seq_len = p.seq_len;
   if (p.seq_lens) seq_len = __builtin_amdgcn_readfirstlane(min(max(scalar_read(p.seq_lens + bh / (uint32_t)p.H), p.q_len), p.seq_len));
   const int32_t n_tok = max(min((p.split_base + ((int32_t)sp < p.split_rem ? 1 : 0)) * kSplitUnit, seq_len - t0), 0);
-  const int64_t row0 = (int64_t)bh * p.cap_tokens + t0;
+  // PAGED: the cache is a pool of pages behind a block table; descriptors are made per trip
+  // (page_trip below) and this row is not used
+  const int64_t row0 = PAGED ? 0 : (int64_t)bh * p.cap_tokens + t0;
   // item-relative token limit of this lane's query: query i sees tokens [0, seq_len - q_len + 1 + i)
   const int32_t qi = min((int32_t)i16, p.q_len - 1);
   const int32_t lim = min(n_tok, seq_len - p.q_len + 1 + qi - t0);
   const int32_t lim_first = seq_len - p.q_len + 1 - t0;             // query 0's, uniform
 
-  const int scale_bytes = n_tok * (int)kScaleRowBytes;
-  const __amdgpu_buffer_rsrc_t kc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.k_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
-  const __amdgpu_buffer_rsrc_t vc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.v_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
+  const int scale_bytes = PAGED ? 0 : n_tok * (int)kScaleRowBytes;
+  const __amdgpu_buffer_rsrc_t kc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.k_codes) + row0 * kRowBytes, 0, PAGED ? 0 : n_tok * (int)kRowBytes, kBufferFlags);
+  const __amdgpu_buffer_rsrc_t vc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.v_codes) + row0 * kRowBytes, 0, PAGED ? 0 : n_tok * (int)kRowBytes, kBufferFlags);
   const __amdgpu_buffer_rsrc_t ks_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.k_scales) + row0 * NB, 0, scale_bytes, kBufferFlags);
   const __amdgpu_buffer_rsrc_t vs_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.v_scales) + row0 * NB, 0, scale_bytes, kBufferFlags);
   const __amdgpu_buffer_rsrc_t q_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.q) + (int64_t)bh * p.q_len * D, 0, p.q_len * D * 2, kBufferFlags);
@@ -179,23 +181,51 @@ void decode_multi_kernel(const MultiParams p) {
     if constexpr (NB == 1) return __builtin_amdgcn_raw_buffer_load_b16(r, voff, 0, 0);
     else return __builtin_amdgcn_raw_buffer_load_b32(r, voff, 0, 0);
   };
+  // PAGED: pool rows of the trip that starts at item-relative token tb.  Items and trips start at
+  // multiples of 32 tokens and a page is a larger power of two, so a trip never straddles two
+  // pages.  Table index and entry are clamped: nothing the table holds (and no trip past the end
+  // of the sequence, whose row count is 0) can address memory outside the pool.
+  int64_t trip_rows = 0;
+  int32_t trip_left = 0;
+  auto page_trip = [&](int32_t tb) {
+    const uint32_t b = bh / (uint32_t)p.H, h = bh - b * (uint32_t)p.H;
+    const int32_t tok = t0 + tb;
+    const int32_t lp = min(tok >> p.page_shift, p.table_stride - 1);
+    const int32_t phys = min(max(scalar_read(p.block_table + ((int64_t)b * p.table_stride + lp)), 0), p.num_pages - 1);
+    trip_rows = ((((int64_t)phys * p.H + h)) << p.page_shift) + (tok & ((1 << p.page_shift) - 1));
+    trip_left = __builtin_amdgcn_readfirstlane(min(max(n_tok - tb, 0), TRIP));
+  };
   auto load_k = [&](int32_t tb) {
+    __amdgpu_buffer_rsrc_t cr = kc_r, sr = ks_r;
+    if constexpr (PAGED) {
+      page_trip(tb);
+      cr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.k_codes) + trip_rows * kRowBytes, 0, trip_left * (int)kRowBytes, kBufferFlags);
+      sr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.k_scales) + trip_rows * NB, 0, trip_left * (int)kScaleRowBytes, kBufferFlags);
+      tb = 0;
+    }
 #pragma unroll
     for (int u = 0; u < TPT; ++u) {
       const uint32_t tok = (uint32_t)tb + u * kTile;
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
         if constexpr (KBITS != 2) {
-          const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(kc_r, k_voff + tok * kRowBytes + c * kChunkBytes, 0, 0);
+          const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(cr, k_voff + tok * kRowBytes + c * kChunkBytes, 0, 0);
           kw[u][c][0] = v.x; kw[u][c][1] = v.y;
         } else {
-          kw[u][c][0] = __builtin_amdgcn_raw_buffer_load_b32(kc_r, k_voff + tok * kRowBytes + c * kChunkBytes, 0, 0);
+          kw[u][c][0] = __builtin_amdgcn_raw_buffer_load_b32(cr, k_voff + tok * kRowBytes + c * kChunkBytes, 0, 0);
         }
       }
-      ksr[u] = load_scales(ks_r, s_voff + tok * kScaleRowBytes);
+      ksr[u] = load_scales(sr, s_voff + tok * kScaleRowBytes);
     }
   };
+  // (PAGED: the V rows of the trip whose K loads went out last -- load_k(tb) always precedes load_v(tb))
   auto load_v = [&](int32_t tb) {
+    __amdgpu_buffer_rsrc_t cr = vc_r, sr = vs_r;
+    if constexpr (PAGED) {
+      cr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.v_codes) + trip_rows * kRowBytes, 0, trip_left * (int)kRowBytes, kBufferFlags);
+      sr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.v_scales) + trip_rows * NB, 0, trip_left * (int)kScaleRowBytes, kBufferFlags);
+      tb = 0;
+    }
 #pragma unroll
     for (int u = 0; u < TPT; ++u) {
       const uint32_t tok = (uint32_t)tb + u * kTile;
@@ -204,14 +234,14 @@ void decode_multi_kernel(const MultiParams p) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           if constexpr (KBITS == 3) {
-            const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(vc_r, v_voff + (tok + e) * kRowBytes + c * kChunkBytes, 0, 0);
+            const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(cr, v_voff + (tok + e) * kRowBytes + c * kChunkBytes, 0, 0);
             vw[u][c][e][0] = v.x; vw[u][c][e][1] = v.y;
           } else {
-            vw[u][c][e][0] = __builtin_amdgcn_raw_buffer_load_b32(vc_r, v_voff + (tok + e) * kRowBytes + c * kChunkBytes, 0, 0);
+            vw[u][c][e][0] = __builtin_amdgcn_raw_buffer_load_b32(cr, v_voff + (tok + e) * kRowBytes + c * kChunkBytes, 0, 0);
           }
         }
       }
-      vsr[u] = load_scales(vs_r, s_voff + tok * kScaleRowBytes);
+      vsr[u] = load_scales(sr, s_voff + tok * kScaleRowBytes);
     }
   };
   // scale of token 4 gq + r, block b: held by lane r of this lane's quad (quad_perm broadcast)
@@ -494,7 +524,8 @@ __global__ __launch_bounds__(D) void combine_multi_kernel(const MultiParams p) {
 
 template <int KBITS, int D, int BLK>
 hipError_t launch_dims(const MultiParams& p, int B_H, hipStream_t stream) {
-  hipLaunchKernelGGL((decode_multi_kernel<KBITS, D, BLK>), dim3((unsigned)p.n_items), dim3(kThreads), 0, stream, p);
+  if (p.block_table) hipLaunchKernelGGL((decode_multi_kernel<KBITS, D, BLK, true>), dim3((unsigned)p.n_items), dim3(kThreads), 0, stream, p);
+  else hipLaunchKernelGGL((decode_multi_kernel<KBITS, D, BLK, false>), dim3((unsigned)p.n_items), dim3(kThreads), 0, stream, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.splits == 1) return e;
   hipLaunchKernelGGL((combine_multi_kernel<D>), dim3((unsigned)(B_H * p.q_len)), dim3(D), 0, stream, p);

@@ -183,9 +183,9 @@ int plan_splits(const nqkv_cache_desc* d, int64_t seq_len, int num_splits, int* 
 // piece, each building its own look-up table, so pieces are kept at one sweep of the eight waves
 // or longer; measured on MI355X, one workgroup per compute unit is as fast as two (13.7 vs 14.5 us
 // at B8 H32 D64 S2048, 39.5 vs 39.0 us at B1 H32 D128 S32768) and costs half the partial results.
-int plan_multi(const nqkv_cache_desc* d, int64_t seq_len, int q_len, int num_splits, int* splits) {
+int plan_multi(const nqkv_cache_desc* d, int64_t seq_len, int64_t max_tokens, int q_len, int num_splits, int* splits) {
   if (q_len < 1 || q_len > 16) return q_len < 1 ? NQKV_EINVAL : NQKV_EUNSUPPORTED;
-  if (seq_len < q_len || seq_len > d->cap_tokens || seq_len >= ((int64_t)1 << 31) - 64) return NQKV_EINVAL;
+  if (seq_len < q_len || seq_len > max_tokens || seq_len >= ((int64_t)1 << 31) - 64) return NQKV_EINVAL;
   if (num_splits < 0 || num_splits > 1024) return NQKV_EINVAL;
   const int64_t trips = (seq_len + decode_multi_trip_tokens() - 1) / decode_multi_trip_tokens();
   if (num_splits > 0) {
@@ -725,7 +725,7 @@ int nqkv_decode_multi_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_l
   if (rc) return rc;
   if (!bytes_out) return NQKV_EINVAL;
   int splits = 1;
-  if ((rc = plan_multi(desc, seq_len, q_len, num_splits, &splits))) return rc;
+  if ((rc = plan_multi(desc, seq_len, desc->cap_tokens, q_len, num_splits, &splits))) return rc;
   *bytes_out = multi_workspace_need(desc, q_len, splits);
   if (splits_out) *splits_out = splits;
   return NQKV_OK;
@@ -734,14 +734,27 @@ int nqkv_decode_multi_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_l
 // Shared by nqkv_decode_attention_multi (lens == nullptr) and its per-sequence-length form.
 static int decode_multi_impl(const nqkv_cache_desc* desc, const float* levels, const void* q,
                              const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                             const int32_t* block_table, int64_t table_stride, int64_t num_pages,
                              const int32_t* lens, int64_t seq_len, int q_len, float softmax_scale, void* out,
                              void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
   int rc = check_desc(desc);
   if (rc) return rc;
   LevelTable checked;
   if ((rc = check_levels(levels, desc->k, &checked))) return rc;
+  int64_t max_tokens = desc->cap_tokens;
+  int page_shift = 0;
+  if (block_table) {
+    // desc->cap_tokens is the page size; a sequence may hold as many tokens as its table row has pages
+    PagedPlan pages;
+    if ((rc = plan_paged(desc, 1, &pages))) return rc;
+    if (reinterpret_cast<uintptr_t>(block_table) & 3u) return NQKV_EINVAL;
+    if (num_pages < 1 || num_pages > ((int64_t)1 << 31) - 1) return NQKV_EINVAL;
+    if (table_stride < 1 || table_stride > ((int64_t)1 << 31) - 1) return NQKV_EINVAL;
+    page_shift = pages.page_shift;
+    max_tokens = table_stride * desc->cap_tokens;
+  }
   int splits = 1;
-  if ((rc = plan_multi(desc, seq_len, q_len, num_splits, &splits))) return rc;
+  if ((rc = plan_multi(desc, seq_len, max_tokens, q_len, num_splits, &splits))) return rc;
   if (!std::isfinite(softmax_scale)) return NQKV_EINVAL;
   const void* ptrs[] = {q, k_codes, k_scales, v_codes, v_scales, out};
   for (const void* ptr : ptrs) {
@@ -774,6 +787,10 @@ static int decode_multi_impl(const nqkv_cache_desc* desc, const float* levels, c
   p.cap_tokens = desc->cap_tokens;
   p.seq_lens = lens;
   p.H = desc->H;
+  p.block_table = block_table;
+  p.table_stride = (int)table_stride;
+  p.num_pages = (int)num_pages;
+  p.page_shift = page_shift;
   const LutChoice& lut = choose_lut_scale(checked.v, 1 << desc->k);
   std::memcpy(p.lut_levels, lut.bits, sizeof(uint16_t) * (1 << desc->k));
   p.inv_gamma = 1.0f / lut.gamma;
@@ -786,7 +803,7 @@ int nqkv_decode_attention_multi(const nqkv_cache_desc* desc, const float* levels
                                 const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
                                 int64_t seq_len, int q_len, float softmax_scale, void* out,
                                 void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
-  return decode_multi_impl(desc, levels, q, k_codes, k_scales, v_codes, v_scales, nullptr, seq_len, q_len, softmax_scale, out,
+  return decode_multi_impl(desc, levels, q, k_codes, k_scales, v_codes, v_scales, nullptr, 0, 0, nullptr, seq_len, q_len, softmax_scale, out,
                            workspace, workspace_bytes, num_splits, hip_stream);
 }
 
@@ -795,8 +812,32 @@ int nqkv_decode_attention_multi_varlen(const nqkv_cache_desc* desc, const float*
                                        const int32_t* seq_lens, int64_t max_seq_len, int q_len, float softmax_scale, void* out,
                                        void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
   if (!seq_lens || (reinterpret_cast<uintptr_t>(seq_lens) & 3u)) return NQKV_EINVAL;
-  return decode_multi_impl(desc, levels, q, k_codes, k_scales, v_codes, v_scales, seq_lens, max_seq_len, q_len, softmax_scale, out,
+  return decode_multi_impl(desc, levels, q, k_codes, k_scales, v_codes, v_scales, nullptr, 0, 0, seq_lens, max_seq_len, q_len, softmax_scale, out,
                            workspace, workspace_bytes, num_splits, hip_stream);
+}
+
+int nqkv_decode_multi_paged_workspace_bytes(const nqkv_cache_desc* desc, int64_t max_seq_len, int q_len, int num_splits,
+                                            size_t* bytes_out, int* splits_out) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!bytes_out) return NQKV_EINVAL;
+  PagedPlan pages;
+  if ((rc = plan_paged(desc, 1, &pages))) return rc;
+  int splits = 1;
+  if ((rc = plan_multi(desc, max_seq_len, ((int64_t)1 << 31) - 65, q_len, num_splits, &splits))) return rc;
+  *bytes_out = multi_workspace_need(desc, q_len, splits);
+  if (splits_out) *splits_out = splits;
+  return NQKV_OK;
+}
+
+int nqkv_decode_attention_multi_paged(const nqkv_cache_desc* desc, const float* levels, const void* q,
+                                      const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
+                                      const int32_t* block_table, int64_t table_stride, int64_t num_pages,
+                                      const int32_t* seq_lens, int64_t max_seq_len, int q_len, float softmax_scale, void* out,
+                                      void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
+  if (!seq_lens || (reinterpret_cast<uintptr_t>(seq_lens) & 3u) || !block_table) return NQKV_EINVAL;
+  return decode_multi_impl(desc, levels, q, k_codes, k_scales, v_codes, v_scales, block_table, table_stride, num_pages,
+                           seq_lens, max_seq_len, q_len, softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
 }
 
 int nqkv_probe_read_stream(const void* src, size_t bytes, void* checksums, void* hip_stream) {

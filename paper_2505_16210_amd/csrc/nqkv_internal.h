@@ -102,6 +102,11 @@ struct MultiParams {
   // per-sequence lengths (NULL: every sequence has seq_len): cached tokens of sequence b
   const int32_t* seq_lens;
   int H;
+  // paged cache (NULL: contiguous rows), as in DecodeParams; needs seq_lens
+  const int32_t* block_table;
+  int table_stride;
+  int num_pages;
+  int page_shift;
 };
 
 // Bytes at the start of the split-K workspace that hold the ticket counters (one uint32 per

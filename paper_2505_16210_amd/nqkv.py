@@ -23,6 +23,7 @@ EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_set_tuning", "nqkv_build_codeb
            "nqkv_decode_workspace_bytes", "nqkv_decode_attention", "nqkv_decode_step",
            "nqkv_probe_read_stream", "nqkv_quantize_kv_hidden",
            "nqkv_decode_multi_workspace_bytes", "nqkv_decode_attention_multi", "nqkv_decode_attention_multi_varlen",
+           "nqkv_decode_multi_paged_workspace_bytes", "nqkv_decode_attention_multi_paged",
            "nqkv_decode_attention_varlen", "nqkv_decode_step_varlen",
            "nqkv_decode_paged_workspace_bytes", "nqkv_decode_attention_paged", "nqkv_decode_step_paged",
            "nqkv_quantize_kv_paged")
@@ -73,6 +74,11 @@ def _load() -> ctypes.CDLL:
     lib.nqkv_decode_attention_multi_varlen.restype = i32
     lib.nqkv_decode_attention_multi_varlen.argtypes = [dp, fp, vp, vp, vp, vp, vp, vp, i64, i32, c.c_float, vp, vp,
                                                        c.c_size_t, i32, vp]
+    lib.nqkv_decode_multi_paged_workspace_bytes.restype = i32
+    lib.nqkv_decode_multi_paged_workspace_bytes.argtypes = [dp, i64, i32, i32, c.POINTER(c.c_size_t), c.POINTER(i32)]
+    lib.nqkv_decode_attention_multi_paged.restype = i32
+    lib.nqkv_decode_attention_multi_paged.argtypes = [dp, fp, vp, vp, vp, vp, vp, vp, i64, i64, vp, i64, i32, c.c_float,
+                                                      vp, vp, c.c_size_t, i32, vp]
     lib.nqkv_decode_attention.restype = i32
     lib.nqkv_decode_attention.argtypes = [dp, fp, vp, vp, vp, vp, vp, i64, c.c_float, vp, vp,
                                           c.c_size_t, i32, vp]
@@ -450,6 +456,39 @@ def decode_attention_paged(desc: CacheDesc, levels, q, k_codes, k_scales, v_code
                                          _lens_arg(seq_lens, desc.B), max_seq_len, float(softmax_scale), _dev_ptr(out),
                                          _dev_ptr(workspace), ws_bytes, _stream(stream))
     _check(rc, "nqkv_decode_attention_paged")
+    return out
+
+
+def decode_multi_paged_workspace_bytes(desc: CacheDesc, max_seq_len: int, q_len: int, num_splits: int = 0):
+    """nqkv_decode_multi_paged_workspace_bytes -> (bytes, splits)."""
+    nbytes = ctypes.c_size_t(0)
+    splits = ctypes.c_int(0)
+    rc = lib.nqkv_decode_multi_paged_workspace_bytes(ctypes.byref(desc), max_seq_len, q_len, num_splits,
+                                                     ctypes.byref(nbytes), ctypes.byref(splits))
+    _check(rc, "nqkv_decode_multi_paged_workspace_bytes")
+    return int(nbytes.value), int(splits.value)
+
+
+def decode_attention_multi_paged(desc: CacheDesc, levels, q, k_codes, k_scales, v_codes, v_scales,
+                                 block_table: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int,
+                                 softmax_scale: float = 1.0, out=None, workspace=None, num_splits: int = 0,
+                                 stream=None) -> torch.Tensor:
+    """nqkv_decode_attention_multi_paged: pools [num_pages,H,P,*], block_table int32 [B,max_pages], q fp16 [B,H,Q,D]."""
+    lv, lvp = _levels_ptr(levels)
+    assert q.dtype == torch.float16 and q.is_contiguous() and q.dim() == 4
+    q_len = q.shape[2]
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        need, _ = decode_multi_paged_workspace_bytes(desc, max_seq_len, q_len, num_splits)
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device) if need else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    tp, ts = _table_arg(block_table, desc.B)
+    rc = lib.nqkv_decode_attention_multi_paged(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_codes), _dev_ptr(k_scales),
+                                               _dev_ptr(v_codes), _dev_ptr(v_scales), tp, ts, k_codes.shape[0],
+                                               _lens_arg(seq_lens, desc.B), max_seq_len, q_len, float(softmax_scale),
+                                               _dev_ptr(out), _dev_ptr(workspace), ws_bytes, num_splits, _stream(stream))
+    _check(rc, "nqkv_decode_attention_multi_paged")
     return out
 
 

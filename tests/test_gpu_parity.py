@@ -851,3 +851,37 @@ def test_decode_attention_multi_varlen_matches_oracle_per_sequence(nqkv, oracle,
     torch.cuda.synchronize()
     for b in (0, 1, 4):
         assert _multi_err(out[b:b + 1], ref[b:b + 1]) <= ATTN_TOL
+
+
+@pytest.mark.parametrize("k,D,blk,P", [(4, 64, 64, 128), (4, 128, 64, 256), (3, 128, 128, 128), (2, 64, 64, 512)])
+def test_decode_attention_multi_paged_matches_oracle(nqkv, oracle, k, D, blk, P):
+    """Several queries per sequence over a shuffled pool of pages: sequence by sequence equal to the
+    oracle on the contiguous cache, for every split count, with garbage in the unused table
+    entries, and equal to the contiguous per-sequence-length call up to rounding."""
+    B, H, cap, Q = 4, 3, 1536, 5
+    lv, desc, _, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, cap, cap, seed=43 * k + D + P)
+    g = torch.Generator(device="cuda").manual_seed(P)
+    q = (torch.randn(B, H, Q, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+    n_pages_seq = cap // P
+    perm = torch.randperm(2 * B * n_pages_seq, generator=torch.Generator().manual_seed(P + 1))[:B * n_pages_seq]
+    table = perm.reshape(B, n_pages_seq).to(torch.int32).cuda()
+    pools = [_scatter_to_pages(t, table, P) for t in (kc, ks, vc, vs)]
+    lens = [Q, P, P + 1, cap]
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    wild = table.clone()
+    for b in range(B):
+        used = -(-lens[b] // P)
+        wild[b, used:] = torch.tensor([-7, 10 ** 9] * n_pages_seq, dtype=torch.int32)[:n_pages_seq - used].cuda()
+    pdesc = nqkv.make_desc(B, H, D, k, blk, P)
+    hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+    ref = np.concatenate([oracle.decode_attention_multi(*[a[b:b + 1] for a in hk], k, blk, lv, lens[b], 0.9, n_threads=4)
+                          for b in range(B)], 0)
+    for tb in (table, wild):
+        for ns in (0, 1, 3, 17):
+            out = nqkv.decode_attention_multi_paged(pdesc, lv, q, *pools, tb, lens_dev, max(lens), 0.9, num_splits=ns)
+            torch.cuda.synchronize()
+            assert _multi_err(out, ref) <= ATTN_TOL, (k, D, blk, P, ns)
+    contig = nqkv.decode_attention_multi_varlen(desc, lv, q, kc, ks, vc, vs, lens_dev, cap, 0.9)
+    torch.cuda.synchronize()
+    d = (out.float() - contig.float()).abs().amax(-1) / contig.float().abs().amax(-1)
+    assert d.max().item() <= 2e-3

@@ -212,6 +212,25 @@ def test_decode_multi_argument_errors_and_planning(nqkv):
     assert callv(mx=32769) == nqkv.EINVAL
     assert callv(mx=3) == nqkv.EINVAL
     assert callv(q=None) == nqkv.EINVAL
+    fp_ = nqkv.lib.nqkv_decode_attention_multi_paged
+    pd = nqkv.make_desc(4, 8, 128, 4, 64, 256)                   # pages of 256 tokens
+    def callp(table=FAKE, stride=16, pages=64, lens=FAKE, mx=4096, q_len=4, desc=pd, ns=0, ws=FAKE):
+        return fp_(ctypes.byref(desc), lvp, FAKE, FAKE, FAKE, FAKE, FAKE, table, stride, pages, lens, mx, q_len, 1.0,
+                   FAKE, ws, 1 << 30, ns, None)
+    assert callp(table=None) == nqkv.EINVAL
+    assert callp(table=FAKE + 2) == nqkv.EINVAL
+    assert callp(lens=None) == nqkv.EINVAL
+    assert callp(stride=0) == nqkv.EINVAL
+    assert callp(pages=0) == nqkv.EINVAL
+    assert callp(mx=4097) == nqkv.EINVAL                         # more tokens than the table row has pages for
+    assert callp(mx=3) == nqkv.EINVAL
+    assert callp(q_len=17) == nqkv.EUNSUPPORTED
+    assert callp(desc=nqkv.make_desc(4, 8, 128, 4, 64, 200)) == nqkv.EUNSUPPORTED     # page size not a power of two
+    assert callp(ns=4, ws=None) == nqkv.EINVAL
+    assert nqkv.decode_multi_paged_workspace_bytes(pd, 4096, 4, 4) == (4 * 8 * 4 * 4 * 130 * 4, 4)
+    assert nqkv.decode_multi_paged_workspace_bytes(pd, 100000, 4, 1) == (0, 1)       # not bound by the page size
+    with pytest.raises(nqkv.NqkvError):
+        nqkv.decode_multi_paged_workspace_bytes(nqkv.make_desc(4, 8, 128, 4, 64, 200), 4096, 4, 0)
     # workspace: partial results only, [B*H][splits][q_len][D+2] floats
     assert nqkv.decode_multi_workspace_bytes(d, 32768, 4, 1) == (0, 1)
     assert nqkv.decode_multi_workspace_bytes(d, 32768, 4, 7) == (32 * 7 * 4 * 130 * 4, 7)
