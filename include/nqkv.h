@@ -141,6 +141,23 @@ int nqkv_quantize_kv_pair(const nqkv_cache_desc* desc, const float* levels,
                           void* hip_stream);
 
 /*
+ * nqkv_quantize_kv_pair for a batch whose sequences stand at different positions (a step that
+ * appends n_tokens tokens to every sequence of a ragged batch): sequence b's tokens go to cache
+ * rows [dst_token_offsets[b], dst_token_offsets[b] + n_tokens).
+ *   dst_token_offsets  device int32 [B], 4-byte aligned, read by the kernel only; values are
+ *                      clamped into [0, max_offset] (no out-of-bounds write; the rows written for
+ *                      a sequence whose entry was out of range are then unspecified)
+ *   max_offset         host upper bound of the entries, max_offset + n_tokens <= cap_tokens
+ * Errors: as nqkv_quantize_kv_pair, plus NQKV_EINVAL for a null / misaligned array.
+ */
+int nqkv_quantize_kv_pair_varlen(const nqkv_cache_desc* desc, const float* levels,
+                                 const void* k_src, const void* v_src,
+                                 int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                                 int64_t n_tokens, const int32_t* dst_token_offsets, int64_t max_offset,
+                                 void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                                 void* hip_stream);
+
+/*
  * Dequantize cache rows [token_offset, token_offset + n_tokens) to fp16
  * (Fig. 5 caption: indices are looked up in the table and restored to FP16):
  *     dst = fp16_round_to_nearest_even( fl32( levels[code] * (float)scale ) )
@@ -280,6 +297,15 @@ int nqkv_quantize_kv_paged(const nqkv_cache_desc* desc, const float* levels,
                            const int32_t* block_table, int64_t table_stride, int64_t num_pages,
                            void* k_codes, void* k_scales, void* v_codes, void* v_scales,
                            void* hip_stream);
+/* The same with a first row per sequence (dst_token_offsets / max_offset as for
+ * nqkv_quantize_kv_pair_varlen; max_offset + n_tokens <= table_stride * P). */
+int nqkv_quantize_kv_paged_varlen(const nqkv_cache_desc* desc, const float* levels,
+                                  const void* k_src, const void* v_src,
+                                  int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                                  int64_t n_tokens, const int32_t* dst_token_offsets, int64_t max_offset,
+                                  const int32_t* block_table, int64_t table_stride, int64_t num_pages,
+                                  void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                                  void* hip_stream);
 int nqkv_decode_paged_workspace_bytes(const nqkv_cache_desc* desc, int64_t max_tokens,
                                       size_t* bytes_out, int* items_out);
 int nqkv_decode_attention_paged(const nqkv_cache_desc* desc, const float* levels, const void* q,
@@ -326,7 +352,8 @@ int nqkv_quantize_kv_hidden(const nqkv_cache_desc* desc, const float* levels,
  * queries of a (batch, head) belong to the LAST q_len of the first seq_len cached tokens, and
  * query i attends over tokens [0, seq_len - q_len + 1 + i) -- what nqkv_decode_attention would
  * give it at that sequence length.  The new tokens must already be in the cache
- * (nqkv_quantize_kv_pair with n_tokens = q_len appends them).  The products run on the matrix
+ * (nqkv_quantize_kv_pair with n_tokens = q_len appends them; nqkv_quantize_kv_pair_varlen when the
+ * sequences stand at different positions).  The products run on the matrix
  * cores (fp16 inputs, fp32 accumulation); weights times the value scale are rounded to fp16, so
  * value scales below 2^-14 lose precision.  Tolerance as for nqkv_decode_attention.
  *   q, out     device fp16 [B][H][q_len][D] contiguous
@@ -363,8 +390,8 @@ int nqkv_decode_attention_multi_varlen(const nqkv_cache_desc* desc, const float*
  * And over a PAGED cache (pool layout, block table and page size as for
  * nqkv_decode_attention_paged; desc->cap_tokens is the page size P): the q_len queries of sequence
  * b are those of its last q_len tokens, seq_lens[b] of them cached in the pages its table row
- * names.  The new tokens are appended first with nqkv_quantize_kv_paged (call per sequence when
- * the positions differ).  max_seq_len is bound by table_stride * P; the workspace comes from
+ * names.  The new tokens are appended first with nqkv_quantize_kv_paged or, when the positions
+ * differ, nqkv_quantize_kv_paged_varlen.  max_seq_len is bound by table_stride * P; the workspace comes from
  * nqkv_decode_multi_paged_workspace_bytes(desc, max_seq_len, q_len, num_splits, ...).
  * Errors: as nqkv_decode_attention_multi_varlen, plus NQKV_EINVAL for a null / misaligned table or
  * a bad table_stride / num_pages, NQKV_EUNSUPPORTED for a page size that is not a power of two

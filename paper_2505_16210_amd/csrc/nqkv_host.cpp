@@ -269,12 +269,14 @@ int nqkv_build_codebook(int k, int variant, float* levels_out) {
   return NQKV_OK;
 }
 
-int nqkv_quantize_kv_pair(const nqkv_cache_desc* desc, const float* levels,
-                          const void* k_src, const void* v_src,
-                          int64_t stride_b, int64_t stride_h, int64_t stride_t,
-                          int64_t n_tokens, int64_t dst_token_offset,
-                          void* k_codes, void* k_scales, void* v_codes, void* v_scales,
-                          void* hip_stream) {
+// Shared by nqkv_quantize_kv_pair (offsets == nullptr) and its per-sequence-offset form, where
+// dst_token_offset is the largest offset the array may hold.
+static int quantize_pair_impl(const nqkv_cache_desc* desc, const float* levels,
+                              const void* k_src, const void* v_src,
+                              int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                              int64_t n_tokens, const int32_t* offsets, int64_t dst_token_offset,
+                              void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                              void* hip_stream) {
   int rc = check_desc(desc);
   if (rc) return rc;
   QuantParams p;
@@ -303,10 +305,34 @@ int nqkv_quantize_kv_pair(const nqkv_cache_desc* desc, const float* levels,
   p.stride_t = stride_t;
   p.n_tokens = n_tokens;
   p.tok_off = dst_token_offset;
+  p.tok_offs = offsets;
+  p.max_off = (int)std::min<int64_t>(dst_token_offset, ((int64_t)1 << 31) - 1);
   p.cap_tokens = desc->cap_tokens;
   p.impl = (g_quantize_impl == 0 && build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) ? 0 : 1;
   const hipError_t e = launch_quantize(p, desc->D, desc->k, desc->block, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
+}
+
+int nqkv_quantize_kv_pair(const nqkv_cache_desc* desc, const float* levels,
+                          const void* k_src, const void* v_src,
+                          int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                          int64_t n_tokens, int64_t dst_token_offset,
+                          void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                          void* hip_stream) {
+  return quantize_pair_impl(desc, levels, k_src, v_src, stride_b, stride_h, stride_t, n_tokens, nullptr, dst_token_offset,
+                            k_codes, k_scales, v_codes, v_scales, hip_stream);
+}
+
+int nqkv_quantize_kv_pair_varlen(const nqkv_cache_desc* desc, const float* levels,
+                                 const void* k_src, const void* v_src,
+                                 int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                                 int64_t n_tokens, const int32_t* dst_token_offsets, int64_t max_offset,
+                                 void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                                 void* hip_stream) {
+  if (!dst_token_offsets || (reinterpret_cast<uintptr_t>(dst_token_offsets) & 3u)) return NQKV_EINVAL;
+  if (max_offset > ((int64_t)1 << 31) - 1) return NQKV_EINVAL;
+  return quantize_pair_impl(desc, levels, k_src, v_src, stride_b, stride_h, stride_t, n_tokens, dst_token_offsets, max_offset,
+                            k_codes, k_scales, v_codes, v_scales, hip_stream);
 }
 
 int nqkv_quantize_kv(const nqkv_cache_desc* desc, const float* levels,
@@ -643,13 +669,13 @@ static int decode_paged_impl(const nqkv_cache_desc* desc, const float* levels, c
   return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
 }
 
-int nqkv_quantize_kv_paged(const nqkv_cache_desc* desc, const float* levels,
-                           const void* k_src, const void* v_src,
-                           int64_t stride_b, int64_t stride_h, int64_t stride_t,
-                           int64_t n_tokens, int64_t dst_token_offset,
-                           const int32_t* block_table, int64_t table_stride, int64_t num_pages,
-                           void* k_codes, void* k_scales, void* v_codes, void* v_scales,
-                           void* hip_stream) {
+static int quantize_paged_impl(const nqkv_cache_desc* desc, const float* levels,
+                               const void* k_src, const void* v_src,
+                               int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                               int64_t n_tokens, const int32_t* offsets, int64_t dst_token_offset,
+                               const int32_t* block_table, int64_t table_stride, int64_t num_pages,
+                               void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                               void* hip_stream) {
   int rc = check_desc(desc);
   if (rc) return rc;
   QuantParams p;
@@ -686,6 +712,8 @@ int nqkv_quantize_kv_paged(const nqkv_cache_desc* desc, const float* levels,
   p.stride_t = stride_t;
   p.n_tokens = n_tokens;
   p.tok_off = dst_token_offset;
+  p.tok_offs = offsets;
+  p.max_off = (int)dst_token_offset;                   // (< 2^31 by the check above)
   p.cap_tokens = P;
   p.impl = (g_quantize_impl == 0 && build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) ? 0 : 1;
   p.block_table = block_table;
@@ -694,6 +722,29 @@ int nqkv_quantize_kv_paged(const nqkv_cache_desc* desc, const float* levels,
   p.page_shift = plan.page_shift;
   const hipError_t e = launch_quantize_paged(p, desc->D, desc->k, desc->block, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
+}
+
+int nqkv_quantize_kv_paged(const nqkv_cache_desc* desc, const float* levels,
+                           const void* k_src, const void* v_src,
+                           int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                           int64_t n_tokens, int64_t dst_token_offset,
+                           const int32_t* block_table, int64_t table_stride, int64_t num_pages,
+                           void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                           void* hip_stream) {
+  return quantize_paged_impl(desc, levels, k_src, v_src, stride_b, stride_h, stride_t, n_tokens, nullptr, dst_token_offset,
+                             block_table, table_stride, num_pages, k_codes, k_scales, v_codes, v_scales, hip_stream);
+}
+
+int nqkv_quantize_kv_paged_varlen(const nqkv_cache_desc* desc, const float* levels,
+                                  const void* k_src, const void* v_src,
+                                  int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                                  int64_t n_tokens, const int32_t* dst_token_offsets, int64_t max_offset,
+                                  const int32_t* block_table, int64_t table_stride, int64_t num_pages,
+                                  void* k_codes, void* k_scales, void* v_codes, void* v_scales,
+                                  void* hip_stream) {
+  if (!dst_token_offsets || (reinterpret_cast<uintptr_t>(dst_token_offsets) & 3u)) return NQKV_EINVAL;
+  return quantize_paged_impl(desc, levels, k_src, v_src, stride_b, stride_h, stride_t, n_tokens, dst_token_offsets, max_offset,
+                             block_table, table_stride, num_pages, k_codes, k_scales, v_codes, v_scales, hip_stream);
 }
 
 int nqkv_decode_attention_paged(const nqkv_cache_desc* desc, const float* levels, const void* q,

@@ -30,6 +30,10 @@ struct QuantParams {
   int64_t stride_b, stride_h, stride_t;  // fp16 tensor strides, in elements
   int64_t n_tokens;      // tokens to process
   int64_t tok_off;       // first cache row
+  // per-sequence first rows (NULL: tok_off for every sequence): device int32 [B], clamped into
+  // [0, max_off] by the kernels
+  const int32_t* tok_offs;
+  int max_off;
   int64_t cap_tokens;
   LevelTable levels;
   int impl;              // 0 = cell-table quantizer, 1 = plain threshold scan

@@ -58,6 +58,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantParams p)
   uint4 w[kUnroll];
   bool valid[kUnroll];
   uint32_t bh_[kUnroll], t_[kUnroll], part_[kUnroll];
+  int32_t off_[kUnroll];          // first cache row of the lane's sequence
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const uint32_t c = tile0 + u * kThreads;
@@ -79,7 +80,9 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantParams p)
     const uint32_t part = c % CPR;
     bh_[u] = bh; t_[u] = t; part_[u] = part;
     w[u] = make_uint4(0, 0, 0, 0);
+    off_[u] = (int32_t)p.tok_off;
     if (valid[u]) {
+      if (p.tok_offs) off_[u] = min(max(p.tok_offs[b], 0), p.max_off);      // whatever the array holds, stay inside the cache
       const uint16_t* src = tp.src + (int64_t)b * p.stride_b + (int64_t)h * p.stride_h +
                             (int64_t)t * p.stride_t + part * 8;
       w[u] = *reinterpret_cast<const uint4*>(src);
@@ -105,7 +108,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantParams p)
     const uint32_t packed = encode_chunk<KBITS, FAST>(w[u], s_bits, p.levels, cells);
 
     // destination chunk index inside the (b,h) slab of the cache
-    const int64_t slab_row0 = (int64_t)bh_[u] * p.cap_tokens + p.tok_off;
+    const int64_t slab_row0 = (int64_t)bh_[u] * p.cap_tokens + off_[u];
     const int64_t chunk = (slab_row0 + t_[u]) * CPR + part_[u];
     uint32_t* codes32 = reinterpret_cast<uint32_t*>(tp.codes);
     if (KBITS == 4) {
@@ -155,8 +158,12 @@ __global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantPara
   // that a tile -- 64 or 128 tokens, which divides the page size -- lies inside one page
   // whatever tok_off is; the tile's destination is that page's rows of head h.
   constexpr uint32_t kTileTok = kThreads * kUnroll / CPR;
-  const uint32_t abs_tok0 = PAGED ? ((uint32_t)p.tok_off / kTileTok + blockIdx.x) * kTileTok : 0u;
-  int64_t row0 = ((int64_t)b * p.H + h) * p.cap_tokens + p.tok_off;
+  // the sequence's own first row when the batch is ragged (clamped: whatever the array holds, the
+  // rows written stay inside the cache / the table)
+  uint32_t tok_off = (uint32_t)p.tok_off;
+  if (p.tok_offs) tok_off = (uint32_t)__builtin_amdgcn_readfirstlane(min(max(scalar_read(p.tok_offs + b), 0), p.max_off));
+  const uint32_t abs_tok0 = PAGED ? (tok_off / kTileTok + blockIdx.x) * kTileTok : 0u;
+  int64_t row0 = ((int64_t)b * p.H + h) * p.cap_tokens + tok_off;
   if (PAGED) {
     const int32_t lp = min((int32_t)(abs_tok0 >> p.page_shift), p.table_stride - 1);
     const int32_t phys = min(max(scalar_read(p.block_table + ((int64_t)b * p.table_stride + lp)), 0), p.num_pages - 1);
@@ -173,7 +180,7 @@ __global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantPara
   // c0: this lane's first SOURCE chunk.  PAGED: absolute chunk minus the chunks before tok_off;
   // for lanes of the first tile that lie before tok_off this wraps to a huge number: past the
   // end, like the tail.  d0: the same lane's chunk inside the destination descriptor.
-  const uint32_t c0 = PAGED ? abs_tok0 * CPR + threadIdx.x - (uint32_t)p.tok_off * CPR
+  const uint32_t c0 = PAGED ? abs_tok0 * CPR + threadIdx.x - tok_off * CPR
                             : blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
   const uint32_t d0 = PAGED ? threadIdx.x : c0;
   const uint32_t total = n * CPR;
@@ -431,8 +438,12 @@ namespace {
 template <int KBITS, int D, int BLK>
 hipError_t launch_paged_one(const QuantParams& p, hipStream_t stream) {
   constexpr int kTileTok = kThreads * kUnroll / (D / 8);
+  // tiles lie over absolute token positions: the run [tok_off, tok_off + n) touches last - first + 1
+  // of them; with per-sequence offsets, as many as a run of n tokens can touch at worst (workgroups
+  // past a sequence's run find nothing to do)
   const int64_t first = p.tok_off / kTileTok, last = (p.tok_off + p.n_tokens - 1) / kTileTok;
-  const dim3 grid((unsigned)(last - first + 1), (unsigned)p.H, (unsigned)(p.B * p.n_tensors));
+  const int64_t tiles = p.tok_offs ? (p.n_tokens - 1 + kTileTok - 1) / kTileTok + 1 : last - first + 1;
+  const dim3 grid((unsigned)tiles, (unsigned)p.H, (unsigned)(p.B * p.n_tensors));
   const bool fast = p.impl == 0, contig = p.stride_t == D;
   if (fast && contig)       hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, true, true, true>), grid, dim3(kThreads), 0, stream, p);
   else if (fast)            hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, true, false, true>), grid, dim3(kThreads), 0, stream, p);

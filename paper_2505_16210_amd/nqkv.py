@@ -24,6 +24,7 @@ EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_set_tuning", "nqkv_build_codeb
            "nqkv_probe_read_stream", "nqkv_quantize_kv_hidden",
            "nqkv_decode_multi_workspace_bytes", "nqkv_decode_attention_multi", "nqkv_decode_attention_multi_varlen",
            "nqkv_decode_multi_paged_workspace_bytes", "nqkv_decode_attention_multi_paged",
+           "nqkv_quantize_kv_pair_varlen", "nqkv_quantize_kv_paged_varlen",
            "nqkv_decode_attention_varlen", "nqkv_decode_step_varlen",
            "nqkv_decode_paged_workspace_bytes", "nqkv_decode_attention_paged", "nqkv_decode_step_paged",
            "nqkv_quantize_kv_paged")
@@ -62,6 +63,11 @@ def _load() -> ctypes.CDLL:
     lib.nqkv_quantize_kv.argtypes = [dp, fp, vp, i64, i64, i64, i64, i64, vp, vp, vp]
     lib.nqkv_quantize_kv_pair.restype = i32
     lib.nqkv_quantize_kv_pair.argtypes = [dp, fp, vp, vp, i64, i64, i64, i64, i64, vp, vp, vp, vp, vp]
+    lib.nqkv_quantize_kv_pair_varlen.restype = i32
+    lib.nqkv_quantize_kv_pair_varlen.argtypes = [dp, fp, vp, vp, i64, i64, i64, i64, vp, i64, vp, vp, vp, vp, vp]
+    lib.nqkv_quantize_kv_paged_varlen.restype = i32
+    lib.nqkv_quantize_kv_paged_varlen.argtypes = [dp, fp, vp, vp, i64, i64, i64, i64, vp, i64, vp, i64, i64,
+                                                  vp, vp, vp, vp, vp]
     lib.nqkv_dequantize_kv.restype = i32
     lib.nqkv_dequantize_kv.argtypes = [dp, fp, vp, vp, i64, i64, vp, i64, i64, i64, vp]
     lib.nqkv_decode_workspace_bytes.restype = i32
@@ -189,6 +195,20 @@ def quantize_kv_pair(desc: CacheDesc, levels, k_src: torch.Tensor, v_src: torch.
                                    k_src.shape[2], dst_token_offset, _dev_ptr(k_codes), _dev_ptr(k_scales),
                                    _dev_ptr(v_codes), _dev_ptr(v_scales), _stream(stream))
     _check(rc, "nqkv_quantize_kv_pair")
+
+
+def quantize_kv_pair_varlen(desc: CacheDesc, levels, k_src: torch.Tensor, v_src: torch.Tensor,
+                            k_codes, k_scales, v_codes, v_scales, dst_token_offsets: torch.Tensor, max_offset: int,
+                            stream=None) -> None:
+    """nqkv_quantize_kv_pair_varlen: sequence b's tokens go to rows [offsets[b], offsets[b] + n)."""
+    lv, lvp = _levels_ptr(levels)
+    sb, sh, st = _src_strides(k_src)
+    assert _src_strides(v_src) == (sb, sh, st) and v_src.shape == k_src.shape
+    rc = lib.nqkv_quantize_kv_pair_varlen(ctypes.byref(desc), lvp, _dev_ptr(k_src), _dev_ptr(v_src), sb, sh, st,
+                                          k_src.shape[2], _lens_arg(dst_token_offsets, desc.B), max_offset,
+                                          _dev_ptr(k_codes), _dev_ptr(k_scales), _dev_ptr(v_codes), _dev_ptr(v_scales),
+                                          _stream(stream))
+    _check(rc, "nqkv_quantize_kv_pair_varlen")
 
 
 def quantize_kv_hidden(desc: CacheDesc, levels, k_src: torch.Tensor, v_src, k_codes, k_scales, v_codes, v_scales,
@@ -436,6 +456,23 @@ def quantize_kv_paged(desc: CacheDesc, levels, k_src: torch.Tensor, v_src, k_cod
                                     _dev_ptr(k_codes), _dev_ptr(k_scales), _dev_ptr(v_codes), _dev_ptr(v_scales),
                                     _stream(stream))
     _check(rc, "nqkv_quantize_kv_paged")
+
+
+def quantize_kv_paged_varlen(desc: CacheDesc, levels, k_src: torch.Tensor, v_src, k_codes, k_scales, v_codes, v_scales,
+                             block_table: torch.Tensor, dst_token_offsets: torch.Tensor, max_offset: int,
+                             stream=None) -> None:
+    """nqkv_quantize_kv_paged_varlen: rows [offsets[b], offsets[b] + n) of sequence b, in its pages."""
+    lv, lvp = _levels_ptr(levels)
+    sb, sh, st = _src_strides(k_src)
+    if v_src is not None:
+        assert v_src.shape == k_src.shape and v_src.stride() == k_src.stride()
+    tp, ts = _table_arg(block_table, desc.B)
+    rc = lib.nqkv_quantize_kv_paged_varlen(ctypes.byref(desc), lvp, _dev_ptr(k_src), _dev_ptr(v_src), sb, sh, st,
+                                           k_src.shape[2], _lens_arg(dst_token_offsets, desc.B), max_offset,
+                                           tp, ts, k_codes.shape[0],
+                                           _dev_ptr(k_codes), _dev_ptr(k_scales), _dev_ptr(v_codes), _dev_ptr(v_scales),
+                                           _stream(stream))
+    _check(rc, "nqkv_quantize_kv_paged_varlen")
 
 
 def decode_attention_paged(desc: CacheDesc, levels, q, k_codes, k_scales, v_codes, v_scales,

@@ -885,3 +885,137 @@ def test_decode_attention_multi_paged_matches_oracle(nqkv, oracle, k, D, blk, P)
     torch.cuda.synchronize()
     d = (out.float() - contig.float()).abs().amax(-1) / contig.float().abs().amax(-1)
     assert d.max().item() <= 2e-3
+
+
+# --------------------------------------------------------------------------- appends at per-sequence rows
+@pytest.mark.parametrize("impl", [0, 1])
+@pytest.mark.parametrize("k,D,blk,n", [(4, 64, 64, 5), (4, 128, 64, 16), (3, 128, 128, 3), (2, 64, 64, 7),
+                                       (4, 128, 128, 300), (3, 64, 64, 260), (2, 128, 64, 515)])
+def test_quantize_pair_varlen_bit_exact(nqkv, oracle, k, D, blk, n, impl):
+    """Every sequence appends n tokens at its own row (few tokens: the flat kernel; many: the slab
+    kernel), from a strided source.  The caches must equal the oracle's, sequence by sequence, and
+    every other row must stay as it was; entries outside [0, max_offset] are clamped into it."""
+    B, H, cap = 4, 3, 1100
+    lv = nqkv.build_codebook(k)
+    g = torch.Generator(device="cuda").manual_seed(5 * k + D + n)
+    Kt = (torch.randn(B, n, H, D, device="cuda", generator=g) * 2.0).to(torch.float16)
+    Vt = torch.randn(B, n, H, D, device="cuda", generator=g).to(torch.float16)
+    Kv, Vv = Kt.transpose(1, 2), Vt.transpose(1, 2)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    kc, ks = nqkv.alloc_cache(desc)
+    vc, vs = nqkv.alloc_cache(desc)
+    for t in (kc, vc):
+        t.fill_(0xAB)
+    max_off = cap - n
+    offs = [0, 37, 512, max_off]
+    offs_dev = torch.tensor(offs, dtype=torch.int32, device="cuda")
+    nqkv.set_tuning(0, impl)
+    try:
+        nqkv.quantize_kv_pair_varlen(desc, lv, Kv, Vv, kc, ks, vc, vs, offs_dev, max_off)
+        torch.cuda.synchronize()
+    finally:
+        nqkv.set_tuning(0, 0)
+    okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
+    ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
+    okc[:] = 0xAB
+    ovc[:] = 0xAB
+    for b in range(B):
+        oracle.quantize_kv(h2n(Kv[b:b + 1]), k, blk, lv, okc[b:b + 1], oks[b:b + 1], dst_off=offs[b], n_threads=4)
+        oracle.quantize_kv(h2n(Vv[b:b + 1]), k, blk, lv, ovc[b:b + 1], ovs[b:b + 1], dst_off=offs[b], n_threads=4)
+    for got, ref in ((kc, okc), (ks, oks), (vc, ovc), (vs, ovs)):
+        assert np.array_equal(h2n(got), ref)
+    # wild entries: clamped, and the sequences with sane entries are written exactly as before
+    kc2, ks2 = nqkv.alloc_cache(desc)
+    vc2, vs2 = nqkv.alloc_cache(desc)
+    wild = torch.tensor([0, -9, 10 ** 9, max_off], dtype=torch.int32, device="cuda")
+    nqkv.quantize_kv_pair_varlen(desc, lv, Kv, Vv, kc2, ks2, vc2, vs2, wild, max_off)
+    torch.cuda.synchronize()
+    for b in (0, 3):
+        assert np.array_equal(h2n(ks2)[b], oks[b])
+        assert np.array_equal(h2n(kc2)[b, :, offs[b]:offs[b] + n], okc[b, :, offs[b]:offs[b] + n])
+    assert np.array_equal(h2n(ks2)[1, :, :n], oks[1, :, offs[1]:offs[1] + n])                  # -9 -> row 0
+    assert np.array_equal(h2n(ks2)[2, :, max_off:], oks[2, :, offs[2]:offs[2] + n])            # 1e9 -> max_offset
+
+
+@pytest.mark.parametrize("k,D,blk,P,n", [(4, 64, 64, 128, 6), (4, 128, 64, 256, 16), (3, 128, 128, 128, 200), (2, 64, 64, 256, 131)])
+def test_quantize_paged_varlen_bit_exact(nqkv, oracle, k, D, blk, P, n):
+    """The same into a paged pool: runs that start at a page's last rows, cross a boundary, or sit
+    in the middle of a page; the pool gathered back through the table equals the oracle's cache and
+    everything else keeps its fill."""
+    B, H, n_pages_seq = 4, 2, 5
+    cap = n_pages_seq * P
+    lv = nqkv.build_codebook(k)
+    g = torch.Generator(device="cuda").manual_seed(7 * k + D + P + n)
+    Kv = (torch.randn(B, H, n, D, device="cuda", generator=g) * 1.7).to(torch.float16)
+    Vv = torch.randn(B, H, n, D, device="cuda", generator=g).to(torch.float16)
+    num_pages = B * n_pages_seq + 2
+    perm = torch.randperm(num_pages, generator=torch.Generator().manual_seed(P + n))[:B * n_pages_seq]
+    table = perm.reshape(B, n_pages_seq).to(torch.int32).cuda()
+    pdesc = nqkv.make_desc(B, H, D, k, blk, P)
+    kcp, ksp = nqkv.alloc_paged_pool(pdesc, num_pages)
+    vcp, vsp = nqkv.alloc_paged_pool(pdesc, num_pages)
+    for t in (kcp, vcp):
+        t.fill_(0xAB)
+    max_off = cap - n
+    offs = [0, P - 2, 2 * P + 17, max_off]
+    offs_dev = torch.tensor(offs, dtype=torch.int32, device="cuda")
+    nqkv.quantize_kv_paged_varlen(pdesc, lv, Kv, Vv, kcp, ksp, vcp, vsp, table, offs_dev, max_off)
+    torch.cuda.synchronize()
+    okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
+    ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
+    okc[:] = 0xAB
+    ovc[:] = 0xAB
+    for b in range(B):
+        oracle.quantize_kv(h2n(Kv[b:b + 1]), k, blk, lv, okc[b:b + 1], oks[b:b + 1], dst_off=offs[b], n_threads=4)
+        oracle.quantize_kv(h2n(Vv[b:b + 1]), k, blk, lv, ovc[b:b + 1], ovs[b:b + 1], dst_off=offs[b], n_threads=4)
+    tb = table.cpu().numpy()
+    owned = set(tb.reshape(-1).tolist())
+    for pool, ref, fill in ((kcp, okc, 0xAB), (ksp, oks, 0), (vcp, ovc, 0xAB), (vsp, ovs, 0)):
+        hp = h2n(pool)
+        for b in range(B):
+            for j in range(n_pages_seq):
+                assert np.array_equal(hp[tb[b, j]], ref[b, :, j * P:(j + 1) * P]), (b, j)
+        for pg in range(num_pages):
+            if pg not in owned:
+                assert (hp[pg] == fill).all(), pg
+
+
+def test_ragged_batch_multi_token_step(nqkv, oracle):
+    """A whole step for a batch at different positions: append q_len tokens to every sequence at its
+    own row (one launch), then attend with their queries over each sequence's own length (one
+    launch) -- caches bit-exact, outputs within tolerance, against the oracle run per sequence."""
+    k, D, blk = 4, 128, 64
+    B, H, Q, cap = 4, 4, 5, 1024
+    lv = nqkv.build_codebook(k)
+    pos = [0, 31, 500, cap - Q]                                   # rows already cached per sequence
+    g = torch.Generator(device="cuda").manual_seed(51)
+    Kx = rand_kv((B, H, cap, D), seed=52)
+    Vx = torch.randn(B, H, cap, D, device="cuda", generator=g).to(torch.float16)
+    q = (torch.randn(B, H, Q, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    kc, ks = nqkv.alloc_cache(desc)
+    vc, vs = nqkv.alloc_cache(desc)
+    one = nqkv.make_desc(1, H, D, k, blk, cap)
+    for b in range(B):                                            # the history of each sequence
+        if pos[b]:
+            nqkv.quantize_kv_pair(one, lv, Kx[b:b + 1, :, :pos[b]], Vx[b:b + 1, :, :pos[b]],
+                                  kc[b:b + 1], ks[b:b + 1], vc[b:b + 1], vs[b:b + 1], 0)
+    k_new = torch.stack([Kx[b, :, pos[b]:pos[b] + Q] for b in range(B)])
+    v_new = torch.stack([Vx[b, :, pos[b]:pos[b] + Q] for b in range(B)])
+    pos_dev = torch.tensor(pos, dtype=torch.int32, device="cuda")
+    lens_dev = pos_dev + Q
+    nqkv.quantize_kv_pair_varlen(desc, lv, k_new, v_new, kc, ks, vc, vs, pos_dev, cap - Q)
+    out = nqkv.decode_attention_multi_varlen(desc, lv, q, kc, ks, vc, vs, lens_dev, cap, 0.8)
+    torch.cuda.synchronize()
+    okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
+    ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
+    refs = []
+    for b in range(B):
+        n = pos[b] + Q
+        oracle.quantize_kv(h2n(Kx[b:b + 1, :, :n]), k, blk, lv, okc[b:b + 1], oks[b:b + 1], n_threads=4)
+        oracle.quantize_kv(h2n(Vx[b:b + 1, :, :n]), k, blk, lv, ovc[b:b + 1], ovs[b:b + 1], n_threads=4)
+        refs.append(oracle.decode_attention_multi(h2n(q[b:b + 1]), okc[b:b + 1], oks[b:b + 1], ovc[b:b + 1], ovs[b:b + 1],
+                                                  k, blk, lv, n, 0.8, n_threads=4))
+    for got, ref in ((kc, okc), (ks, oks), (vc, ovc), (vs, ovs)):
+        assert np.array_equal(h2n(got), ref)
+    assert _multi_err(out, np.concatenate(refs, 0)) <= ATTN_TOL

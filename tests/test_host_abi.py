@@ -328,6 +328,36 @@ def test_quantize_paged_argument_errors(nqkv):
     assert call(desc=nqkv.make_desc(2, 8, 64, 4, 64, 100)) == nqkv.EUNSUPPORTED   # page size not a power of two
 
 
+def test_quantize_varlen_argument_errors(nqkv):
+    lv, lvp = _levels(nqkv)
+    d = nqkv.make_desc(2, 4, 64, 4, 64, 1000)
+    f = nqkv.lib.nqkv_quantize_kv_pair_varlen
+
+    def call(offs=FAKE, mx=900, n=100, ks=FAKE, desc=d):
+        return f(ctypes.byref(desc), lvp, FAKE, FAKE, 0, 0, 64, n, offs, mx, FAKE, ks, FAKE, FAKE, None)
+
+    assert call(offs=None) == nqkv.EINVAL
+    assert call(offs=FAKE + 2) == nqkv.EINVAL
+    assert call(mx=901) == nqkv.EINVAL                           # max_offset + n_tokens beyond the capacity
+    assert call(mx=-1) == nqkv.EINVAL
+    assert call(mx=1 << 31) == nqkv.EINVAL
+    assert call(ks=None) == nqkv.EINVAL
+    assert call(n=0) == nqkv.OK                                  # nothing to do
+    fp_ = nqkv.lib.nqkv_quantize_kv_paged_varlen
+    pd = nqkv.make_desc(2, 4, 64, 4, 64, 256)
+
+    def callp(offs=FAKE, mx=1000, n=24, table=FAKE, stride=4, pages=16, desc=pd):
+        return fp_(ctypes.byref(desc), lvp, FAKE, FAKE, 0, 0, 64, n, offs, mx, table, stride, pages, FAKE, FAKE, FAKE, FAKE, None)
+
+    assert callp(offs=None) == nqkv.EINVAL
+    assert callp(offs=FAKE + 1) == nqkv.EINVAL
+    assert callp(mx=1001) == nqkv.EINVAL                         # rows beyond table_stride * P
+    assert callp(table=None) == nqkv.EINVAL
+    assert callp(pages=0) == nqkv.EINVAL
+    assert callp(desc=nqkv.make_desc(2, 4, 64, 4, 64, 100)) == nqkv.EUNSUPPORTED
+    assert callp(n=0) == nqkv.OK
+
+
 def test_quantize_hidden_argument_errors(nqkv):
     lv, lvp = _levels(nqkv)
     f = nqkv.lib.nqkv_quantize_kv_hidden
