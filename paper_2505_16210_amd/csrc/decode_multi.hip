@@ -510,14 +510,26 @@ __global__ __launch_bounds__(D) void combine_multi_kernel(const MultiParams p) {
   const int64_t bh = bq / p.q_len, qy = bq % p.q_len;
   const int d = threadIdx.x;
   float mm = kNoScore, ll = 0.0f, oo = 0.0f;
-  for (int s = 0; s < p.splits; ++s) {
-    const float* rec = p.partials + ((bh * p.splits + s) * p.q_len + qy) * (D + 2);
-    const float m_s = rec[0], l_s = rec[1], o_s = rec[2 + d];
-    const float m_new = fmaxf(mm, m_s);
-    const float f_old = __builtin_amdgcn_exp2f(mm - m_new), f_s = __builtin_amdgcn_exp2f(m_s - m_new);
-    ll = ll * f_old + l_s * f_s;
-    oo = oo * f_old + o_s * f_s;
-    mm = m_new;
+  // eight splits per round, so that their loads are in flight together; a record past the last
+  // split is a clamped duplicate that enters with weight 0
+  constexpr int U = 8;
+  for (int s0 = 0; s0 < p.splits; s0 += U) {
+    float ms[U], ls[U], os[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int s = min(s0 + u, p.splits - 1);
+      const float* rec = p.partials + ((bh * p.splits + s) * p.q_len + qy) * (D + 2);
+      ms[u] = rec[0]; ls[u] = rec[1]; os[u] = rec[2 + d];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float m_s = (s0 + u < p.splits) ? ms[u] : -INFINITY;
+      const float m_new = fmaxf(mm, m_s);
+      const float f_old = __builtin_amdgcn_exp2f(mm - m_new), f_s = __builtin_amdgcn_exp2f(m_s - m_new);
+      ll = ll * f_old + ls[u] * f_s;
+      oo = oo * f_old + os[u] * f_s;
+      mm = m_new;
+    }
   }
   p.out[bq * D + d] = __builtin_bit_cast(unsigned short, (_Float16)(oo * p.inv_gamma / ll));
 }
