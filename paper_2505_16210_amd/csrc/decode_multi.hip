@@ -191,7 +191,9 @@ void decode_multi_kernel(const MultiParams p) {
     const uint32_t b = bh / (uint32_t)p.H, h = bh - b * (uint32_t)p.H;
     const int32_t tok = t0 + tb;
     const int32_t lp = min(tok >> p.page_shift, p.table_stride - 1);
-    const int32_t phys = min(max(scalar_read(p.block_table + ((int64_t)b * p.table_stride + lp)), 0), p.num_pages - 1);
+    // (the clamps select as vector instructions: readfirstlane brings the results back to scalar
+    // registers, so that the row arithmetic and the descriptors built from it stay scalar)
+    const int32_t phys = __builtin_amdgcn_readfirstlane(min(max(scalar_read(p.block_table + ((int64_t)b * p.table_stride + lp)), 0), p.num_pages - 1));
     trip_rows = ((((int64_t)phys * p.H + h)) << p.page_shift) + (tok & ((1 << p.page_shift) - 1));
     trip_left = __builtin_amdgcn_readfirstlane(min(max(n_tok - tb, 0), TRIP));
   };
