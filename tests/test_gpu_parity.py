@@ -1019,3 +1019,24 @@ def test_ragged_batch_multi_token_step(nqkv, oracle):
     for got, ref in ((kc, okc), (ks, oks), (vc, ovc), (vs, ovs)):
         assert np.array_equal(h2n(got), ref)
     assert _multi_err(out, np.concatenate(refs, 0)) <= ATTN_TOL
+
+
+def test_decode_attention_multi_random_geometries(nqkv, oracle):
+    """Seeded random sweep over code width, head size, batch, length, query count and split count
+    (40 cases): lengths that end anywhere inside a tile, split counts up to one per 32-token piece."""
+    rng = np.random.default_rng(2025)
+    for case in range(40):
+        k, D, blk = COMBOS[int(rng.integers(len(COMBOS)))]
+        B, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        Q = int(rng.integers(1, 17))
+        S = int(rng.integers(Q, 700))
+        cap = S + int(rng.integers(0, 9))
+        ns = int(rng.integers(0, (S + 31) // 32 + 1))
+        lv, desc, _, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, S, cap, seed=1000 + case)
+        g = torch.Generator(device="cuda").manual_seed(case)
+        q = (torch.randn(B, H, Q, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+        scale = float(rng.choice([0.5, 1.0, 2.0]))
+        out = nqkv.decode_attention_multi(desc, lv, q, kc, ks, vc, vs, S, scale, num_splits=ns)
+        torch.cuda.synchronize()
+        ref = oracle.decode_attention_multi(h2n(q), h2n(kc), h2n(ks), h2n(vc), h2n(vs), k, blk, lv, S, scale, n_threads=4)
+        assert _multi_err(out, ref) <= ATTN_TOL, (case, k, D, blk, B, H, Q, S, cap, ns, scale)
