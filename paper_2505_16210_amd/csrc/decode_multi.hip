@@ -373,17 +373,21 @@ void decode_multi_kernel(const MultiParams p) {
     for (int up = 0; up < TPT; up += 2) {
       uint32_t b2[NB][4];       // P^T of the two tiles times the V block scale, fp16
 #pragma unroll
-      for (int b = 0; b < NB; ++b) {
+      for (int t = 0; t < 2; ++t) {
+        const int u = up + t;
+        // weights to fp16 pairs first, then one packed multiply per pair and block with the scales
+        // of the pair's two tokens (fetched from the quad by DPP, re-paired by v_perm_b32)
+        const uint32_t p01 = pack_half2(pw[u][0], pw[u][1]), p23 = pack_half2(pw[u][2], pw[u][3]);
+        const uint32_t w0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)vsr[u], 0x00, 0xf, 0xf, true);
+        const uint32_t w1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)vsr[u], 0x55, 0xf, 0xf, true);
+        const uint32_t w2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)vsr[u], 0xaa, 0xf, 0xf, true);
+        const uint32_t w3 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)vsr[u], 0xff, 0xf, 0xf, true);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const int u = up + t;
-          // (a token past the item reads scale 0 through the range check, and its weight is 0 anyway)
-          const float wv[4] = {pw[u][0] * scale_of(vsr[u], std::integral_constant<int, 0>{}, b),
-                               pw[u][1] * scale_of(vsr[u], std::integral_constant<int, 1>{}, b),
-                               pw[u][2] * scale_of(vsr[u], std::integral_constant<int, 2>{}, b),
-                               pw[u][3] * scale_of(vsr[u], std::integral_constant<int, 3>{}, b)};
-          b2[b][2 * t] = pack_half2(wv[0], wv[1]);
-          b2[b][2 * t + 1] = pack_half2(wv[2], wv[3]);
+        for (int b = 0; b < NB; ++b) {
+          const uint32_t sel = b ? 0x07060302u : 0x05040100u;
+          const uint32_t s01 = __builtin_amdgcn_perm(w1, w0, sel), s23 = __builtin_amdgcn_perm(w3, w2, sel);
+          b2[b][2 * t] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, p01) * __builtin_bit_cast(half2_t, s01));
+          b2[b][2 * t + 1] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, p23) * __builtin_bit_cast(half2_t, s23));
         }
       }
 #pragma unroll
