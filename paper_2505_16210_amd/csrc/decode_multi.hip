@@ -104,23 +104,32 @@ template <int KBITS, int D, int BLK, bool PAGED>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))     // 128 registers: two workgroups per CU
 void decode_multi_kernel(const MultiParams p) {
   constexpr int KW = (KBITS == 2) ? 1 : 2;   // K side: dwords of codes per lane, chunk and token (16 elements)
-  constexpr int VW = (KBITS == 3) ? 2 : 1;   // V side: dwords per lane, chunk and token
   // 3-bit rows need two dwords per V look-up pair (fields straddle dwords): one tile per trip keeps
   // the code registers at the other widths' count, and the value product contracts over that one
   // tile with the 16-deep instruction
   constexpr int TPT = (KBITS == 3) ? 1 : kTilesPerTrip;
   static_assert(KBITS == 3 || TPT % 2 == 0, "the value product contracts over two 16-token tiles");
   constexpr int TRIP = kTile * TPT;
+  constexpr bool kStage = !(KBITS == 4 && D == 128);     // value codes through an LDS staging area (see below)
   constexpr int NC = D / 64;                 // 64-element chunks of a row
   constexpr int NB = D / BLK;                // quantization blocks of a row
   constexpr int CPB = BLK / 64;              // chunks per block
   constexpr uint32_t kRowBytes = D * KBITS / 8, kChunkBytes = 8 * KBITS, kScaleRowBytes = NB * 2;
   constexpr int XS = D + 1;                  // padded row of the merge buffer
+  constexpr uint32_t kTileBytes = kTile * kRowBytes;          // one 16-token tile of value codes
+  // Streaming phase: the table and, per wave, a staging area for the value tiles of a trip.
+  // Merge phase (everything above is dead by then): the per-wave results.  80 KiB at D 128, 4 bits:
+  // two workgroups fill the 160 KiB of a compute unit exactly.
   struct Lds {
-    float wm[kWaves][kMaxQ], wl[kWaves][kMaxQ];
     union {
-      __attribute__((aligned(256))) uint32_t lut[kLutWords];
-      float xo[kWaves][kMaxQ][XS];           // per-wave outputs, after the table's last use
+      struct {
+        __attribute__((aligned(256))) uint32_t lut[kLutWords];
+        uint32_t stage[kStage ? kWaves : 1][TPT][kTileBytes / 4];
+      };
+      struct {
+        float xo[kWaves][kMaxQ][XS];
+        float wm[kWaves][kMaxQ], wl[kWaves][kMaxQ];
+      };
     };
   };
   __shared__ Lds lds;
@@ -169,12 +178,37 @@ void decode_multi_kernel(const MultiParams p) {
   const uint32_t v3_dw = min((12u * i16) >> 5, 4u);
   const uint32_t k3_shift = (gq & 1u) * 16u, v3_shift = 12u * i16 - 32u * v3_dw;
   const uint32_t k_voff = i16 * kRowBytes + (KBITS == 3 ? ((6u * gq) & ~3u) : gq * (4u * KW));      // + c * kChunkBytes
-  const uint32_t v_voff = (4u * gq) * kRowBytes +
-                          (KBITS == 4 ? (i16 & 7u) : KBITS == 2 ? (i16 >> 2) : v3_dw) * 4u;           // + e * kRowBytes + c * kChunkBytes
+  // Except for 4-bit codes at head size 128 (kStage below; there the direct loads measured 2 %
+  // faster), value codes go through LDS: a tile (16 consecutive rows, contiguous in the cache) is fetched
+  // with ONE 128-bit load per lane -- lane L takes bytes [16 L, 16 L + 16) of the tile -- and
+  // written to this wave's staging area, from which every lane reads the dwords the matrix-operand
+  // layout wants (token 4 gq + e, dword v_dw of chunk c).  Fetching those dwords straight from
+  // memory costs one load instruction per lane and token: 2.4x the memory instructions of the
+  // whole kernel, which is what bound it.  Inside each group of four rows the rows are stored
+  // permuted (row e of group g at slot e ^ g), so that the four lane groups gq, which read rows
+  // 64 or 32 bytes apart, spread over the banks; 3-bit rows (48 / 24 bytes) stay in place.
+  constexpr bool kSwizzle = KBITS != 3;
+  const uint32_t v_dw = (KBITS == 4) ? (i16 & 7u) : (KBITS == 2) ? (i16 >> 2) : v3_dw;
+  const uint32_t st_byte = lane * 16u;                           // this lane's bytes of a tile
+  const bool st_live = st_byte < kTileBytes;
+  uint32_t st_addr = st_byte;
+  if (kSwizzle) {
+    const uint32_t t = st_byte / kRowBytes;
+    st_addr = ((t & ~3u) | ((t & 3u) ^ ((t >> 2) & 3u))) * kRowBytes + st_byte % kRowBytes;
+  }
+  uint32_t* const st_wave = &lds.stage[kStage ? wave : 0][0][0];
+  const char* rd_row[4];                                         // staged row of token 4 gq + e, at this lane's dword
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    rd_row[e] = reinterpret_cast<const char*>(st_wave) + (4u * gq + (kSwizzle ? (e ^ gq) : (uint32_t)e)) * kRowBytes + v_dw * 4u;
+  // (direct path) this lane's dword of token 4 gq + e, chunk c, relative to the tile
+  const uint32_t v_voff = (4u * gq) * kRowBytes + v_dw * 4u;            // + e * kRowBytes + c * kChunkBytes
   // scales: lane (i16, gq) fetches those of token 4 gq + i16 % 4 only; the quad shares them by DPP
   const uint32_t s_voff = (4u * gq + (i16 & 3u)) * kScaleRowBytes;
 
-  uint32_t kw[TPT][NC][KW], vw[TPT][NC][4][VW];
+  uint32_t kw[TPT][NC][KW];
+  u32x4_t vst[kStage ? TPT : 1];         // value tiles on their way to the staging area
+  uint32_t vw[kStage ? 1 : TPT][NC][4];  // or, direct path, this lane's dword of token 4 gq + e, chunk c
   uint32_t ksr[TPT], vsr[TPT];
 
   auto load_scales = [&](__amdgpu_buffer_rsrc_t r, uint32_t voff) -> uint32_t {
@@ -231,17 +265,15 @@ void decode_multi_kernel(const MultiParams p) {
 #pragma unroll
     for (int u = 0; u < TPT; ++u) {
       const uint32_t tok = (uint32_t)tb + u * kTile;
+      if constexpr (kStage) {
+        // (lanes past the tile, and rows past the item, read zeros: the offset is out of range)
+        vst[u] = __builtin_amdgcn_raw_buffer_load_b128(cr, st_live ? tok * kRowBytes + st_byte : 0xffffffffu, 0, 0);
+      } else {
 #pragma unroll
-      for (int c = 0; c < NC; ++c) {
+        for (int c = 0; c < NC; ++c)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if constexpr (KBITS == 3) {
-            const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(cr, v_voff + (tok + e) * kRowBytes + c * kChunkBytes, 0, 0);
-            vw[u][c][e][0] = v.x; vw[u][c][e][1] = v.y;
-          } else {
-            vw[u][c][e][0] = __builtin_amdgcn_raw_buffer_load_b32(cr, v_voff + (tok + e) * kRowBytes + c * kChunkBytes, 0, 0);
-          }
-        }
+          for (int e = 0; e < 4; ++e)
+            vw[u][c][e] = __builtin_amdgcn_raw_buffer_load_b32(cr, v_voff + (tok + e) * kRowBytes + c * kChunkBytes, 0, 0);
       }
       vsr[u] = load_scales(sr, s_voff + tok * kScaleRowBytes);
     }
@@ -365,6 +397,24 @@ void decode_multi_kernel(const MultiParams p) {
 
     load_k(base + stride);      // past the end on the last trip: reads zeros
 
+    // ---- the trip's value tiles: registers -> staging area.  Written and read by different lanes of
+    // this one wave: LDS operations of a wave complete in order, the fences keep the compiler from
+    // reordering them (and from moving the next trip's writes above this trip's reads).
+    if constexpr (kStage) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int u = 0; u < TPT; ++u)
+        if (st_live) *reinterpret_cast<u32x4_t*>(reinterpret_cast<char*>(st_wave) + u * kTileBytes + st_addr) = vst[u];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    auto staged = [&](int u, int c, int e, int word) {
+      if constexpr (kStage) return *reinterpret_cast<const uint32_t*>(rd_row[e] + u * kTileBytes + c * kChunkBytes + word * 4);
+      else return vw[u][c][e];
+    };
+
     // ---- weighted values: one instruction contracts over the 32 tokens of two tiles (this lane's
     // eight: 4 gq + 0..3 of each)
     constexpr uint32_t kLo = 0x05040100u, kHi = 0x07060302u;     // v_perm_b32: low / high halves of two dwords
@@ -401,7 +451,7 @@ void decode_multi_kernel(const MultiParams p) {
             for (int t = 0; t < 2; ++t)
 #pragma unroll
               for (int e = 0; e < 4; ++e) {
-                const uint32_t addr = __builtin_amdgcn_perm(vw[up + t][c][e][0], lane_off, G ? vsel1 : vsel0);
+                const uint32_t addr = __builtin_amdgcn_perm(staged(up + t, c, e, 0), lane_off, G ? vsel1 : vsel0);
                 h[4 * t + e] = *reinterpret_cast<const uint32_t*>(lut + addr);
               }
             // {h.lo} over the eight tokens -> even element's operand, {h.hi} -> odd element's
@@ -419,7 +469,7 @@ void decode_multi_kernel(const MultiParams p) {
           for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const uint32_t addr = __builtin_amdgcn_perm(vw[up + t][c][e][0], lane_off, vsel0);
+              const uint32_t addr = __builtin_amdgcn_perm(staged(up + t, c, e, 0), lane_off, vsel0);
               const uint2 y = *reinterpret_cast<const uint2*>(lut + addr);
               hx[4 * t + e] = y.x; hy[4 * t + e] = y.y;
             }
@@ -452,7 +502,7 @@ void decode_multi_kernel(const MultiParams p) {
         uint32_t hx[4], hy[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const uint32_t x = (uint32_t)(((((uint64_t)vw[0][c][e][1]) << 32) | vw[0][c][e][0]) >> v3_shift);
+          const uint32_t x = (uint32_t)(((((uint64_t)staged(0, c, e, 1)) << 32) | staged(0, c, e, 0)) >> v3_shift);
           hx[e] = *reinterpret_cast<const uint32_t*>(lut + (((x & 63u) << 7) | lane_off));
           hy[e] = *reinterpret_cast<const uint32_t*>(lut + ((((x >> 6) & 63u) << 7) | lane_off));
         }
