@@ -4,14 +4,12 @@
 // needs its output -- query i sees the cache up to and including its own token.
 //
 // With up to 16 query rows per head the two products are real (if skinny) matrix products, so
-// they run on the matrix cores, fp32 accumulate: v_mfma_f32_16x16x32_f16 (the 16-deep
-// v_mfma_f32_16x16x16_f16 for the value product of 3-bit caches).  The table look-up that turns
-// codes into fp16 levels is the same byte-indexed LDS table as in the one-query kernel and costs
+// they run on the matrix cores, fp32 accumulate: v_mfma_f32_16x16x32_f16.  The table look-up that
+// turns codes into fp16 levels is the same byte-indexed LDS table as in the one-query kernel and costs
 // the same per cached element whatever q_len is; the arithmetic that the one-query kernel spends
 // vector instructions on (dot products, weighted sums) moves to the matrix pipe.
 //
-// Operand layouts (lane l, i16 = l % 16, gq = l / 16) of the 32-deep instruction (the 16-deep one:
-// four k per lane, k = 4 gq + 0..3):
+// Operand layouts (lane l, i16 = l % 16, gq = l / 16):
 //   A[row i16][k = 8 gq + 0..7],  B[k = 8 gq + 0..7][col i16],  C/D[row 4 gq + 0..3][col i16].
 //
 // Scores.   C1[token][query] = sum_d K[token][d] q[query][d]:  A = levels of a 16-token tile of
@@ -38,9 +36,8 @@
 //
 // 3-bit codes: pairs of codes are 6-bit fields that do not align with bytes.  K side: the lane's
 // 16 elements are 48 bits starting at byte 6 gq of the 24-byte chunk.  V side: row i16 is fields
-// 2 i16 and 2 i16 + 1 (12 bits at bit 12 i16), which may straddle a dword, so every V look-up pair
-// holds two dwords, a trip is one tile instead of two, and the value product uses the 16-deep
-// instruction over that tile's tokens.
+// 2 i16 and 2 i16 + 1 (12 bits at bit 12 i16), which may straddle a dword: two staged dwords and a
+// 64-bit shift per look-up pair.
 //
 // Work split: one workgroup of eight waves per (sequence, split); waves take 32-token trips
 // round-robin; per-wave results (m, l per query, O) meet in LDS in the space of the look-up
@@ -63,14 +60,8 @@ constexpr int kTrip = kTile * kTilesPerTrip;
 constexpr int kSplitUnit = 32;           // split boundaries are multiples of this many tokens
 constexpr int kMaxQ = 16;
 
-typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 
-// v_mfma_f32_16x16x16_f16: four fp16 per lane and operand (two dwords)
-__device__ __forceinline__ float4_t mfma16(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, float4_t c) {
-  const u32x2_t a = {a0, a1}, b = {b0, b1};
-  return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4_t, a), __builtin_bit_cast(half4_t, b), c, 0, 0, 0);
-}
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 // v_mfma_f32_16x16x32_f16: eight fp16 per lane and operand (four dwords)
 __device__ __forceinline__ float4_t mfma32(const uint32_t (&a)[4], const uint32_t (&b)[4], float4_t c) {
@@ -104,11 +95,8 @@ template <int KBITS, int D, int BLK, bool PAGED>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))     // 128 registers: two workgroups per CU
 void decode_multi_kernel(const MultiParams p) {
   constexpr int KW = (KBITS == 2) ? 1 : 2;   // K side: dwords of codes per lane, chunk and token (16 elements)
-  // 3-bit rows need two dwords per V look-up pair (fields straddle dwords): one tile per trip keeps
-  // the code registers at the other widths' count, and the value product contracts over that one
-  // tile with the 16-deep instruction
-  constexpr int TPT = (KBITS == 3) ? 1 : kTilesPerTrip;
-  static_assert(KBITS == 3 || TPT % 2 == 0, "the value product contracts over two 16-token tiles");
+  constexpr int TPT = kTilesPerTrip;
+  static_assert(TPT % 2 == 0, "the value product contracts over two 16-token tiles");
   constexpr int TRIP = kTile * TPT;
   constexpr bool kStage = !(KBITS == 4 && D == 128);     // value codes through an LDS staging area (see below)
   constexpr int NC = D / 64;                 // 64-element chunks of a row
@@ -308,7 +296,7 @@ void decode_multi_kernel(const MultiParams p) {
   float l_run = 0.0f;                    // over this lane's own tokens only
 
   constexpr int32_t stride = kWaves * TRIP;
-  // One trip (32 tokens; 16 for 3-bit codes).  FULL: every token of it exists and is visible to every query (all trips but
+  // One 32-token trip.  FULL: every token of it exists and is visible to every query (all trips but
   // the sequence's last few); the other copy masks per token and query.  Two copies of the whole
   // body rather than branches inside it, so that each is one straight-line scheduling region.
   auto trip_body = [&](auto full_tag) {
@@ -418,7 +406,6 @@ void decode_multi_kernel(const MultiParams p) {
     // ---- weighted values: one instruction contracts over the 32 tokens of two tiles (this lane's
     // eight: 4 gq + 0..3 of each)
     constexpr uint32_t kLo = 0x05040100u, kHi = 0x07060302u;     // v_perm_b32: low / high halves of two dwords
-    if constexpr (KBITS != 3) {
 #pragma unroll
     for (int up = 0; up < TPT; up += 2) {
       uint32_t b2[NB][4];       // P^T of the two tiles times the V block scale, fp16
@@ -469,9 +456,16 @@ void decode_multi_kernel(const MultiParams p) {
           for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const uint32_t addr = __builtin_amdgcn_perm(staged(up + t, c, e, 0), lane_off, vsel0);
-              const uint2 y = *reinterpret_cast<const uint2*>(lut + addr);
-              hx[4 * t + e] = y.x; hy[4 * t + e] = y.y;
+              if constexpr (KBITS == 3) {
+                // fields 2 i16 and 2 i16 + 1 of the chunk: 12 bits that may straddle a dword
+                const uint32_t x = (uint32_t)(((((uint64_t)staged(up + t, c, e, 1)) << 32) | staged(up + t, c, e, 0)) >> v3_shift);
+                hx[4 * t + e] = *reinterpret_cast<const uint32_t*>(lut + (((x & 63u) << 7) | lane_off));
+                hy[4 * t + e] = *reinterpret_cast<const uint32_t*>(lut + ((((x >> 6) & 63u) << 7) | lane_off));
+              } else {
+                const uint32_t addr = __builtin_amdgcn_perm(staged(up + t, c, e, 0), lane_off, vsel0);
+                const uint2 y = *reinterpret_cast<const uint2*>(lut + addr);
+                hx[4 * t + e] = y.x; hy[4 * t + e] = y.y;
+              }
             }
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
@@ -482,34 +476,6 @@ void decode_multi_kernel(const MultiParams p) {
             acc[c][v] = mfma32(a, bb, acc[c][v]);
           }
         }
-      }
-    }
-    } else {
-      // 3-bit codes: one tile, fields 2 i16 and 2 i16 + 1 of the chunk (elements 4 i16 + 0..3)
-      uint32_t b2[NB][2];
-#pragma unroll
-      for (int b = 0; b < NB; ++b) {
-        const float wv[4] = {pw[0][0] * scale_of(vsr[0], std::integral_constant<int, 0>{}, b),
-                             pw[0][1] * scale_of(vsr[0], std::integral_constant<int, 1>{}, b),
-                             pw[0][2] * scale_of(vsr[0], std::integral_constant<int, 2>{}, b),
-                             pw[0][3] * scale_of(vsr[0], std::integral_constant<int, 3>{}, b)};
-        b2[b][0] = pack_half2(wv[0], wv[1]);
-        b2[b][1] = pack_half2(wv[2], wv[3]);
-      }
-#pragma unroll
-      for (int c = 0; c < NC; ++c) {
-        const uint32_t b20 = b2[c / CPB][0], b21 = b2[c / CPB][1];
-        uint32_t hx[4], hy[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const uint32_t x = (uint32_t)(((((uint64_t)staged(0, c, e, 1)) << 32) | staged(0, c, e, 0)) >> v3_shift);
-          hx[e] = *reinterpret_cast<const uint32_t*>(lut + (((x & 63u) << 7) | lane_off));
-          hy[e] = *reinterpret_cast<const uint32_t*>(lut + ((((x >> 6) & 63u) << 7) | lane_off));
-        }
-        acc[c][0] = mfma16(__builtin_amdgcn_perm(hx[1], hx[0], kLo), __builtin_amdgcn_perm(hx[3], hx[2], kLo), b20, b21, acc[c][0]);
-        acc[c][1] = mfma16(__builtin_amdgcn_perm(hx[1], hx[0], kHi), __builtin_amdgcn_perm(hx[3], hx[2], kHi), b20, b21, acc[c][1]);
-        acc[c][2] = mfma16(__builtin_amdgcn_perm(hy[1], hy[0], kLo), __builtin_amdgcn_perm(hy[3], hy[2], kLo), b20, b21, acc[c][2]);
-        acc[c][3] = mfma16(__builtin_amdgcn_perm(hy[1], hy[0], kHi), __builtin_amdgcn_perm(hy[3], hy[2], kHi), b20, b21, acc[c][3]);
       }
     }
   };
@@ -611,7 +577,7 @@ hipError_t launch_k(const MultiParams& p, int bh, int D, int blk, hipStream_t st
 }  // namespace
 
 int decode_multi_trip_tokens() { return kSplitUnit; }
-int decode_multi_item_tokens() { return kWaves * kTrip; }     // (the 3-bit kernel's sweep is half of this)
+int decode_multi_item_tokens() { return kWaves * kTrip; }
 
 hipError_t launch_decode_attention_multi(const MultiParams& p, int D, int k, int blk, hipStream_t stream) {
   if (p.q_len < 1 || p.q_len > kMaxQ || p.splits < 1 || p.n_items % p.splits) return hipErrorInvalidValue;
