@@ -1040,3 +1040,27 @@ def test_decode_attention_multi_random_geometries(nqkv, oracle):
         torch.cuda.synchronize()
         ref = oracle.decode_attention_multi(h2n(q), h2n(kc), h2n(ks), h2n(vc), h2n(vs), k, blk, lv, S, scale, n_threads=4)
         assert _multi_err(out, ref) <= ATTN_TOL, (case, k, D, blk, B, H, Q, S, cap, ns, scale)
+
+
+@pytest.mark.parametrize("k,D,blk", [(4, 128, 64), (3, 64, 64), (2, 128, 128)])
+def test_decode_attention_multi_zero_preserving_table(nqkv, oracle, k, D, blk):
+    """The several-queries kernel is table-agnostic too: the zero-preserving (asymmetric) table, whose
+    levels are not mirror images, through quantize and attention."""
+    B, H, S, Q = 2, 3, 777, 7
+    lv = nqkv.build_codebook(k, 1)
+    g = torch.Generator(device="cuda").manual_seed(61 + k)
+    Kx = rand_kv((B, H, S, D), seed=62 + k)
+    Vx = torch.randn(B, H, S, D, device="cuda", generator=g).to(torch.float16)
+    Vx[:, :, ::5] = 0                                              # exact zeros must survive the table
+    q = (torch.randn(B, H, Q, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+    desc = nqkv.make_desc(B, H, D, k, blk, S)
+    kc, ks = nqkv.alloc_cache(desc)
+    vc, vs = nqkv.alloc_cache(desc)
+    nqkv.quantize_kv_pair(desc, lv, Kx, Vx, kc, ks, vc, vs, 0)
+    torch.cuda.synchronize()
+    hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+    ref = oracle.decode_attention_multi(*hk, k, blk, lv, S, 1.1, n_threads=8)
+    for ns in (0, 3):
+        out = nqkv.decode_attention_multi(desc, lv, q, kc, ks, vc, vs, S, 1.1, num_splits=ns)
+        torch.cuda.synchronize()
+        assert _multi_err(out, ref) <= ATTN_TOL, (k, D, blk, ns)
