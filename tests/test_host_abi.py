@@ -29,6 +29,34 @@ def test_library_exports_every_declared_symbol(nqkv):
     assert nqkv.strerror(0) == "ok" and "workspace" in nqkv.strerror(nqkv.EWORKSPACE)
 
 
+def test_header_is_plain_c_and_links(nqkv, tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 and as C++11 with pedantic warnings as
+    errors, and a C program that uses it links against the library and runs (host-only calls)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_nqkv.c"
+    src.write_text('#include "nqkv.h"\n#include <stdio.h>\n'
+                   'int main(void) {\n  float lv[16];\n  nqkv_cache_desc d = {1, 2, 64, 4, 64, 0, 128};\n'
+                   '  size_t bytes = 1; int splits = 0;\n'
+                   '  if (nqkv_build_codebook(4, 0, lv) != NQKV_OK || lv[0] != -1.0f || lv[15] != 1.0f) return 1;\n'
+                   '  if (nqkv_decode_workspace_bytes(&d, 100, 1, &bytes, &splits) != NQKV_OK || bytes != 0 || splits != 1) return 2;\n'
+                   '  if (nqkv_build_codebook(0, 0, lv) != NQKV_EINVAL) return 3;\n'
+                   '  printf("%d %s\\n", nqkv_version(), nqkv_strerror(NQKV_EWORKSPACE));\n  return 0;\n}\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)],
+                   check=True)
+    exe = tmp_path / "use_nqkv"
+    libdir = os.path.dirname(nqkv.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-l:libnqkv.so",
+                    "-Wl,-rpath," + libdir], check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    assert r.stdout.split()[0] == "100"
+
+
 def test_desc_struct_layout(nqkv):
     assert ctypes.sizeof(nqkv.CacheDesc) == 32
     assert nqkv.CacheDesc.cap_tokens.offset == 24
