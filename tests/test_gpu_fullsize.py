@@ -85,8 +85,9 @@ def test_c5_sweep_sampled_slabs(env, oracle, k, blk):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("name,q_len,rows", [("C3", 4, (0, 31)), ("C4", 16, (0,)), ("C2", 5, (0, 7))])
-def test_multi_query_attention_full_size(env, oracle, name, q_len, rows):
+@pytest.mark.parametrize("name,q_len,rows,k", [("C3", 4, (0, 31), 4), ("C4", 16, (0,), 4), ("C2", 5, (0, 7), 4),
+                                               ("C3", 7, (5,), 3), ("C3", 16, (17,), 2), ("C2", 3, (3,), 3)])
+def test_multi_query_attention_full_size(env, oracle, name, q_len, rows, k):
     """Several queries per sequence at the bench sizes and the library's own split count: the
     queries of the last q_len cached tokens, each over its causal prefix, against the oracle on
     whole batch rows."""
@@ -96,8 +97,8 @@ def test_multi_query_attention_full_size(env, oracle, name, q_len, rows):
     g = workloads.make_generator(cfg, dev)
     K, V = workloads.make_kv(cfg, dev, g)
     q = (torch.randn(cfg.B, cfg.H, q_len, cfg.D, device=dev, generator=g) / cfg.D ** 0.5).to(torch.float16)
-    lv = nqkv.build_codebook(4)
-    desc = nqkv.make_desc(cfg.B, cfg.H, cfg.D, 4, 64, cfg.S)
+    lv = nqkv.build_codebook(k)
+    desc = nqkv.make_desc(cfg.B, cfg.H, cfg.D, k, 64, cfg.S)
     kc, ks = nqkv.alloc_cache(desc, dev)
     vc, vs = nqkv.alloc_cache(desc, dev)
     nqkv.quantize_kv_pair(desc, lv, K, V, kc, ks, vc, vs, 0)
@@ -108,10 +109,10 @@ def test_multi_query_attention_full_size(env, oracle, name, q_len, rows):
     for b in rows:
         sl = slice(b, b + 1)
         ref = oracle.decode_attention_multi(bits(q[sl]), bits(kc[sl]), bits(ks[sl]), bits(vc[sl]), bits(vs[sl]),
-                                            4, 64, lv, cfg.S, 1.0, n_threads=THREADS)
+                                            k, 64, lv, cfg.S, 1.0, n_threads=THREADS)
         o = out[sl].cpu().numpy().reshape(1, -1, cfg.D)
         assert np.isfinite(o.astype(np.float32)).all()
-        assert attn_err(o, ref.reshape(1, -1, cfg.D)) <= ATTN_TOL, (name, q_len, b)
+        assert attn_err(o, ref.reshape(1, -1, cfg.D)) <= ATTN_TOL, (name, q_len, k, b)
 
 
 @pytest.mark.parametrize("fused", [False, True])
