@@ -26,24 +26,30 @@ SOURCES = [
 ]
 
 
-def build_library(verbose: bool = False, save_temps: bool = False) -> str:
+def _compile(src: str, extra: list, verbose: bool, save_temps: bool) -> str:
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+    cmd = [HIPCC, *COMMON, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    if save_temps:
+        cmd.append("--save-temps=obj")
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, capture_output=True, text=True, cwd=OBJ)
+    err = "\n".join(l for l in r.stderr.splitlines()
+                    if "packed-fp32-ops" not in l)      # the host pass does not know the feature
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for %s:\n%s" % (src, err))
+    if verbose and err.strip():
+        print(err, file=sys.stderr)
+    return obj
+
+
+def build_library(verbose: bool = False, save_temps: bool = False, jobs: int = 4) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    objs = []
-    for src, extra in SOURCES:
-        obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-        cmd = [HIPCC, *COMMON, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
-        if save_temps:
-            cmd.append("--save-temps=obj")
-        if verbose:
-            print(" ".join(cmd), flush=True)
-        r = subprocess.run(cmd, capture_output=True, text=True, cwd=OBJ)
-        err = "\n".join(l for l in r.stderr.splitlines()
-                        if "packed-fp32-ops" not in l)      # the host pass does not know the feature
-        if r.returncode != 0:
-            raise RuntimeError("hipcc failed for %s:\n%s" % (src, err))
-        if verbose and err.strip():
-            print(err, file=sys.stderr)
-        objs.append(obj)
+    # the translation units are independent: compile them side by side (a few hipcc processes,
+    # each a few hundred MB)
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=max(1, jobs)) as pool:
+        objs = list(pool.map(lambda se: _compile(se[0], se[1], verbose, save_temps), SOURCES))
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
