@@ -1064,3 +1064,36 @@ def test_decode_attention_multi_zero_preserving_table(nqkv, oracle, k, D, blk):
         out = nqkv.decode_attention_multi(desc, lv, q, kc, ks, vc, vs, S, 1.1, num_splits=ns)
         torch.cuda.synchronize()
         assert _multi_err(out, ref) <= ATTN_TOL, (k, D, blk, ns)
+
+
+def test_decode_attention_and_step_random_geometries(nqkv, oracle):
+    """Seeded random sweep (40 cases) over code width, head size, batch, cached length and split
+    count for the one-query attention and the fused step (which must leave exactly the quantizer's
+    bytes in the cache)."""
+    rng = np.random.default_rng(777)
+    for case in range(40):
+        k, D, blk = COMBOS[int(rng.integers(len(COMBOS)))]
+        B, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        S = int(rng.integers(1, 900))
+        cap = S + 1 + int(rng.integers(0, 5))
+        lv, desc, q, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, S, cap, seed=3000 + case)
+        scale = float(rng.choice([0.5, 1.0, 2.0]))
+        ns = int(rng.integers(0, min(S, 40) + 1))
+        out = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, scale, num_splits=ns)
+        torch.cuda.synchronize()
+        hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+        ref = oracle.decode_attention(*hk, k, blk, lv, S, scale, n_threads=4)
+        assert attn_err(h2n(out).view(np.float16), ref) <= ATTN_TOL, ("attention", case, k, D, blk, B, H, S, ns)
+        # one fused step on top: the new token at row S
+        g = torch.Generator(device="cuda").manual_seed(case)
+        k_new = rand_kv((B, H, 1, D), seed=4000 + case)
+        v_new = torch.randn(B, H, 1, D, device="cuda", generator=g).to(torch.float16)
+        kc2, ks2, vc2, vs2 = kc.clone(), ks.clone(), vc.clone(), vs.clone()
+        nqkv.quantize_kv_pair(desc, lv, k_new, v_new, kc2, ks2, vc2, vs2, S)
+        out_f = nqkv.decode_step(desc, lv, q, k_new, v_new, kc, ks, vc, vs, S, scale, num_splits=ns)
+        torch.cuda.synchronize()
+        for a, b_ in ((kc, kc2), (ks, ks2), (vc, vc2), (vs, vs2)):
+            assert torch.equal(a, b_), ("append", case)
+        hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+        ref = oracle.decode_attention(*hk, k, blk, lv, S + 1, scale, n_threads=4)
+        assert attn_err(h2n(out_f).view(np.float16), ref) <= ATTN_TOL, ("step", case, k, D, blk, B, H, S, ns)
