@@ -234,3 +234,129 @@ def test_largest_batch_row_of_the_hidden_block_quantizer(env, oracle):
     oracle.quantize_kv_hidden(bits(X).transpose(0, 2, 1, 3)[:, :, :n], k, 256, lv, okc, oks, n_threads=THREADS)
     assert np.array_equal(bits(ks), oks)
     assert np.array_equal(bits(kc), okc)
+
+
+def test_c2_step_as_hip_graph_replays(env, oracle):
+    """The launch configuration bench.py times: the C2 step (prefill + 128 fused decode launches)
+    captured once into a HIP graph and replayed.  Three replays, with the program's own eager
+    work between them (caches and outputs overwritten with other data, an eager split-K call that
+    dirties the workspace counters' neighbourhood), must each reproduce the eager run bit for
+    bit; the eager run itself is checked against the oracle at six steps."""
+    nqkv, workloads = env
+    cfg = workloads.C2
+    dev = torch.device("cuda:0")
+    g = workloads.make_generator(cfg, dev)
+    B, H, D, S, n_dec, cap = cfg.B, cfg.H, cfg.D, cfg.S, cfg.decode_steps, cfg.cap_tokens
+    K, V = workloads.make_kv(cfg, dev, g, n_tokens=cap)
+    qs = [workloads.make_q(cfg, dev, g) for _ in range(n_dec)]
+    k, blk = cfg.bits, cfg.block
+    lv = nqkv.build_codebook(k)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    kc, ks = nqkv.alloc_cache(desc, dev)
+    vc, vs = nqkv.alloc_cache(desc, dev)
+    outs = torch.zeros(n_dec, B, H, D, dtype=torch.float16, device=dev)
+    ws_bytes, _ = nqkv.decode_workspace_bytes(desc, cap, 0)
+    ws = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    new = [(K[:, :, S + i:S + i + 1], V[:, :, S + i:S + i + 1]) for i in range(n_dec)]
+
+    def step():
+        nqkv.quantize_kv_pair(desc, lv, K[:, :, :S], V[:, :, :S], kc, ks, vc, vs, 0)
+        for i in range(n_dec):
+            nqkv.decode_step(desc, lv, qs[i], *new[i], kc, ks, vc, vs, S + i, 1.0, out=outs[i], workspace=ws)
+
+    step()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in (outs, kc, ks, vc, vs)]
+    okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
+    ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
+    oracle.quantize_kv(bits(K), k, blk, lv, okc, oks, n_threads=THREADS)
+    oracle.quantize_kv(bits(V), k, blk, lv, ovc, ovs, n_threads=THREADS)
+    assert np.array_equal(bits(kc), okc) and np.array_equal(bits(vs), ovs)
+    for i in (0, 1, 31, 64, 126, 127):
+        ref = oracle.decode_attention(bits(qs[i]), okc, oks, ovc, ovs, k, blk, lv, S + i + 1, 1.0, n_threads=THREADS)
+        assert attn_err(outs[i].cpu().numpy(), ref) <= ATTN_TOL, i
+
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    side.wait_stream(main)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    # a second, split-K shape for the eager work between replays (its own workspace and caches)
+    d2 = nqkv.make_desc(1, 4, D, k, blk, 4096)
+    kc2, ks2 = nqkv.alloc_cache(d2, dev)
+    vc2, vs2 = nqkv.alloc_cache(d2, dev)
+    nqkv.quantize_kv_pair(d2, lv, K[:1, :4, :cap].repeat(1, 1, 2, 1)[:, :, :4096].contiguous(),
+                          V[:1, :4, :cap].repeat(1, 1, 2, 1)[:, :, :4096].contiguous(), kc2, ks2, vc2, vs2, 0)
+    ref2 = nqkv.decode_attention(d2, lv, qs[0][:1, :4].contiguous(), kc2, ks2, vc2, vs2, 4096, 1.0, num_splits=8).clone()
+    for rep in range(3):
+        for t in (kc, vc):
+            t.fill_(0x5A)
+        for t in (ks, vs, outs):
+            t.fill_(1.0)
+        o2 = nqkv.decode_attention(d2, lv, qs[0][:1, :4].contiguous(), kc2, ks2, vc2, vs2, 4096, 1.0, num_splits=8)
+        torch.cuda.synchronize()
+        assert torch.equal(o2, ref2)
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, got, want in zip(("outs", "kc", "ks", "vc", "vs"), (outs, kc, ks, vc, vs), eager):
+            assert torch.equal(got, want), (rep, name)
+
+
+@pytest.mark.parametrize("q_len", [1, 4])
+def test_split_k_launches_as_hip_graph_replays(env, oracle, q_len):
+    """Split-K attention (the ticket counters of the one-query kernel, the partial buffers and
+    combine launch of the several-queries kernel) captured into a HIP graph: every replay equals
+    the eager result bit for bit, with eager calls on the same workspace between the replays."""
+    nqkv, workloads = env
+    dev = torch.device("cuda:0")
+    k, D, blk, B, H, S = 4, 128, 64, 1, 8, 8192 + 37
+    lv = nqkv.build_codebook(k)
+    desc = nqkv.make_desc(B, H, D, k, blk, S)
+    g = torch.Generator(device=dev).manual_seed(5)
+    Kx = torch.randn(B, H, S, D, device=dev, generator=g).to(torch.float16)
+    Vx = torch.randn(B, H, S, D, device=dev, generator=g).to(torch.float16)
+    kc, ks = nqkv.alloc_cache(desc, dev)
+    vc, vs = nqkv.alloc_cache(desc, dev)
+    nqkv.quantize_kv_pair(desc, lv, Kx, Vx, kc, ks, vc, vs, 0)
+    n_calls = 6
+    if q_len == 1:
+        q = (torch.randn(n_calls, B, H, D, device=dev, generator=g) / D ** 0.5).to(torch.float16)
+        nbytes, splits = nqkv.decode_workspace_bytes(desc, S, 0)
+        call = lambda i, o, w: nqkv.decode_attention(desc, lv, q[i], kc, ks, vc, vs, S - i, 1.0, out=o[i], workspace=w)
+        ref_of = lambda i: oracle.decode_attention(bits(q[i]), bits(kc), bits(ks), bits(vc), bits(vs), k, blk, lv, S - i, 1.0,
+                                                   n_threads=THREADS)
+    else:
+        q = (torch.randn(n_calls, B, H, q_len, D, device=dev, generator=g) / D ** 0.5).to(torch.float16)
+        nbytes, splits = nqkv.decode_multi_workspace_bytes(desc, S, q_len, 0)
+        call = lambda i, o, w: nqkv.decode_attention_multi(desc, lv, q[i], kc, ks, vc, vs, S - i, 1.0, out=o[i], workspace=w)
+        ref_of = lambda i: oracle.decode_attention_multi(bits(q[i]), bits(kc), bits(ks), bits(vc), bits(vs), k, blk, lv,
+                                                         S - i, 1.0, n_threads=THREADS)
+    assert splits > 1 and nbytes > 0
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+    out = torch.zeros_like(q)
+    for i in range(n_calls):
+        call(i, out, ws)
+    torch.cuda.synchronize()
+    eager = out.clone()
+    for i in (0, n_calls - 1):
+        assert attn_err(eager[i].cpu().numpy(), ref_of(i)) <= ATTN_TOL
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(n_calls):
+                call(i, out, ws)
+    torch.cuda.synchronize()
+    scratch_out = torch.zeros_like(q)
+    for rep in range(3):
+        out.fill_(2.0)
+        call(rep, scratch_out, ws)                  # eager work on the same workspace
+        torch.cuda.synchronize()
+        assert torch.equal(scratch_out[rep], eager[rep])
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), rep
