@@ -411,6 +411,12 @@ def bench_config(nqkv, workloads, torch, dev, stream, base, variants, kern, time
             probs16 = torch.empty_like(scores)
             out_pf = torch.empty(B, H, 1, D, dtype=torch.float16, device=dev)
             t_p = timed(paper_flow, max(3, n_it // 2), warm=2)
+            # nqkv_dequantize_kv by itself, K and V of one cache copy per call pair (packed codes and
+            # scales in, fp16 out)
+            t_d = timed(lambda i: (nqkv.dequantize_kv(desc, lv, *caches[i % r_cache][:2], 0, S, out=k_full),
+                                   nqkv.dequantize_kv(desc, lv, *caches[i % r_cache][2:], 0, S, out=v_full)),
+                        max(3, n_it // 2), warm=2)
+            kern[tag + ".dequantize"] = kernel_entry(packed + fp16_bytes, t_d, launches=2)
             # bytes this flow moves: packed cache in, fp16 cache out, fp16 cache back in
             kern[tag + ".paper_flow_decode"] = kernel_entry(packed + 2 * fp16_bytes, t_p, fused_speedup=round(t_p / t_a, 2))
             del k_full, v_full, scores, probs32, probs16, out_pf

@@ -1,70 +1,104 @@
 // Packed cache -> fp16 (paper Fig. 5 caption and Sec. 3.2: X' = dequantize(I); the index is
 // looked up in the table and restored to FP16).  out = fp16_rne(fl32(level[code] * scale)).
-// gfx950 only.  One lane owns 32 consecutive elements of a token row: it reads their 4*k bytes
-// of codes as k dwords plus one fp16 scale and writes 64 bytes of fp16.
+// gfx950 only.  The kernel writes four times the bytes it reads, so the mapping follows the
+// stores: one lane owns 8 consecutive elements of a token row -- k bytes of codes in, one 16-byte
+// store out -- and consecutive lanes own consecutive chunks, so a store instruction of a wave
+// covers 1 KiB of whole rows (contiguous when the rows are) and a code load 64 k bytes.  A
+// workgroup walks over kPasses row groups with all of their loads issued before the first use.
+#include "decode_common.h"
 #include "nqkv_internal.h"
 
 namespace nqkv {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kPasses = 4;
+constexpr uint32_t kDropStore = 0xffffffffu;      // an offset outside every buffer: the store is dropped
+constexpr int64_t kCacheableOutputBytes = 64ll << 20;   // a quarter of the 256 MB last-level cache
 
-// bits [pos, pos+n) of a little-endian dword array, n <= 8, positions known at compile time
-template <int NDW>
-__device__ __forceinline__ uint32_t field(const uint32_t (&w)[NDW], int pos, int n) {
-  const int i = pos >> 5, sh = pos & 31;
-  uint32_t v = w[i] >> sh;
-  if (sh + n > 32 && i + 1 < NDW) v |= w[i + 1] << (32 - sh);
-  return v & ((1u << n) - 1u);
-}
-
-template <int KBITS, int D, int BLK>
+// NT: the stores carry the non-temporal hint (output too large for the last-level cache to keep
+// for its reader: measured 3-5 % faster at 0.5-7 GB, while a 64 MiB output is better left cacheable).
+template <int KBITS, int D, int BLK, bool NT>
 __global__ __launch_bounds__(kThreads) void dequantize_kernel(const QuantParams p) {
-  constexpr int LPT = D / 32;     // lanes per token row
-  constexpr int NB = D / BLK;
+  constexpr uint32_t CPR = D / 8;              // 8-element chunks per row
+  constexpr uint32_t RPP = kThreads / CPR;     // rows per pass of the workgroup
+  constexpr uint32_t NB = D / BLK;
+  constexpr uint32_t kRowBytes = D * KBITS / 8, kScaleRowBytes = NB * 2;
+  constexpr uint32_t kMask = (1u << KBITS) - 1u;
   __shared__ float lv[1 << KBITS];
   if (threadIdx.x < (1 << KBITS)) lv[threadIdx.x] = p.levels.v[threadIdx.x];
   __syncthreads();
 
-  const uint32_t c = blockIdx.x * kThreads + threadIdx.x;
-  const uint32_t t = c / LPT, j = c % LPT;
-  if (t >= (uint32_t)p.n_tokens) return;
   const uint32_t b = blockIdx.z, h = blockIdx.y;
-  const int64_t row = ((int64_t)b * p.H + h) * p.cap_tokens + p.tok_off + t;
+  const int64_t row0 = ((int64_t)b * p.H + h) * p.cap_tokens + p.tok_off;
+  const uint32_t n = (uint32_t)p.n_tokens;
+  // Descriptors of this (batch, head) slab: rows past n_tokens read zeros and their stores are
+  // dropped, so every pass issues the same unconditional instructions.  (The host has checked
+  // that all three byte ranges fit 31 bits.)
+  const __amdgpu_buffer_rsrc_t code_r = __builtin_amdgcn_make_buffer_rsrc(
+      p.t[0].codes + row0 * kRowBytes, 0, (int)(n * kRowBytes), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t scale_r = __builtin_amdgcn_make_buffer_rsrc(
+      p.t[0].scales + row0 * NB, 0, (int)(n * kScaleRowBytes), kBufferFlags);
+  const uint32_t st = (uint32_t)p.stride_t;
+  const __amdgpu_buffer_rsrc_t dst_r = __builtin_amdgcn_make_buffer_rsrc(
+      p.t[0].dst + (int64_t)b * p.stride_b + (int64_t)h * p.stride_h, 0, (int)(((n - 1u) * st + D) * 2u), kBufferFlags);
 
-  uint32_t w[KBITS];
-  const uint32_t* src = reinterpret_cast<const uint32_t*>(p.t[0].codes) + (row * LPT + j) * KBITS;
-#pragma unroll
-  for (int i = 0; i < KBITS; ++i) w[i] = src[i];
-  const uint16_t s_bits = p.t[0].scales[row * NB + (j * 32) / BLK];
-  const float s32 = (float)__builtin_bit_cast(_Float16, s_bits);
+  const uint32_t r = threadIdx.x / CPR, c = threadIdx.x % CPR;
+  const uint32_t t0 = blockIdx.x * (kPasses * RPP) + r;
 
-  uint32_t outw[16];
+  uint32_t w[kPasses];
+  uint16_t sc[kPasses];
 #pragma unroll
-  for (int e = 0; e < 32; e += 2) {
-    float lo = lv[field<KBITS>(w, KBITS * e, KBITS)] * s32;                // one fp32 rounding
-    float hi = lv[field<KBITS>(w, KBITS * (e + 1), KBITS)] * s32;
-    // Keep the fp32 product as its own instruction: without this the compiler merges the
-    // multiply and the conversion into one mixed-precision fma with a +0 addend, which rounds
-    // once instead of twice and turns -0 products into +0.
-    asm volatile("" : "+v"(lo), "+v"(hi));
-    const uint32_t l16 = __builtin_bit_cast(unsigned short, (_Float16)lo);  // round to nearest even
-    const uint32_t h16 = __builtin_bit_cast(unsigned short, (_Float16)hi);
-    outw[e >> 1] = l16 | (h16 << 16);
+  for (int u = 0; u < kPasses; ++u) {
+    const uint32_t t = t0 + u * RPP;
+    const uint32_t off = t * kRowBytes + c * KBITS;
+    if constexpr (KBITS == 4) {
+      w[u] = __builtin_amdgcn_raw_buffer_load_b32(code_r, off, 0, 0);
+    } else if constexpr (KBITS == 2) {
+      w[u] = __builtin_amdgcn_raw_buffer_load_b16(code_r, off, 0, 0);
+    } else {
+      // 3 bytes at any byte offset: the two aligned dwords around them (each range-checked on
+      // its own), shifted down by the offset's low bits
+      const uint32_t a = off & ~3u;
+      const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b32(code_r, a, 0, 0);
+      const uint32_t hi = __builtin_amdgcn_raw_buffer_load_b32(code_r, a + 4u, 0, 0);
+      w[u] = __builtin_amdgcn_alignbyte(hi, lo, off & 3u);
+    }
+    sc[u] = __builtin_amdgcn_raw_buffer_load_b16(scale_r, t * kScaleRowBytes + ((c * 8u) / BLK) * 2u, 0, 0);
   }
-  uint16_t* dst = p.t[0].dst + (int64_t)b * p.stride_b + (int64_t)h * p.stride_h +
-                  (int64_t)t * p.stride_t + j * 32;
-  uint4* dst4 = reinterpret_cast<uint4*>(dst);
+
 #pragma unroll
-  for (int i = 0; i < 4; ++i) dst4[i] = make_uint4(outw[4 * i], outw[4 * i + 1], outw[4 * i + 2], outw[4 * i + 3]);
+  for (int u = 0; u < kPasses; ++u) {
+    const uint32_t t = t0 + u * RPP;
+    const float s32 = (float)__builtin_bit_cast(_Float16, sc[u]);
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      float lo = lv[(w[u] >> (KBITS * e)) & kMask] * s32;                // one fp32 rounding
+      float hi = lv[(w[u] >> (KBITS * (e + 1))) & kMask] * s32;
+      // Keep the fp32 product as its own instruction: without this the compiler merges the
+      // multiply and the conversion into one mixed-precision fma with a +0 addend, which rounds
+      // once instead of twice and turns -0 products into +0.
+      asm volatile("" : "+v"(lo), "+v"(hi));
+      const uint32_t l16 = __builtin_bit_cast(unsigned short, (_Float16)lo);  // round to nearest even
+      const uint32_t h16 = __builtin_bit_cast(unsigned short, (_Float16)hi);
+      o[e >> 1] = l16 | (h16 << 16);
+    }
+    const u32x4_t v = {o[0], o[1], o[2], o[3]};
+    // (the row test rather than the range check alone: t * stride may wrap for rows past the end)
+    __builtin_amdgcn_raw_buffer_store_b128(v, dst_r, t < n ? (t * st + c * 8u) * 2u : kDropStore, 0, NT ? 2 : 0);
+  }
 }
 
 template <int KBITS, int D, int BLK>
 hipError_t launch_one(const QuantParams& p, hipStream_t stream) {
-  constexpr int LPT = D / 32;
-  const int64_t lanes = p.n_tokens * LPT;
-  dim3 grid((unsigned)((lanes + kThreads - 1) / kThreads), (unsigned)p.H, (unsigned)p.B);
-  hipLaunchKernelGGL((dequantize_kernel<KBITS, D, BLK>), grid, dim3(kThreads), 0, stream, p);
+  constexpr int64_t kTileRows = kPasses * (kThreads / (D / 8));
+  dim3 grid((unsigned)((p.n_tokens + kTileRows - 1) / kTileRows), (unsigned)p.H, (unsigned)p.B);
+  const int64_t out_bytes = (int64_t)p.B * p.H * p.n_tokens * D * 2;
+  if (out_bytes > kCacheableOutputBytes)
+    hipLaunchKernelGGL((dequantize_kernel<KBITS, D, BLK, true>), grid, dim3(kThreads), 0, stream, p);
+  else
+    hipLaunchKernelGGL((dequantize_kernel<KBITS, D, BLK, false>), grid, dim3(kThreads), 0, stream, p);
   return hipGetLastError();
 }
 

@@ -360,3 +360,32 @@ def test_split_k_launches_as_hip_graph_replays(env, oracle, q_len):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(out, eager), rep
+
+
+@pytest.mark.parametrize("name,k,blk,rows", [("C2", 4, 64, (0, 7)), ("C3", 4, 64, (0, 31)), ("C4", 4, 64, (0,)),
+                                             ("C5", 4, 64, (0, 15)), ("C5", 3, 128, (15,)), ("C5", 2, 64, (7,))])
+def test_dequantize_full_size(env, oracle, name, k, blk, rows):
+    """nqkv_dequantize_kv over a whole cache of the benchmark's size in one call (random code bytes,
+    every finite non-negative fp16 scale), whole batch rows compared bit for bit; then a ragged
+    token window into a token-major destination."""
+    nqkv, workloads = env
+    cfg = workloads.CONFIGS[name]
+    dev = torch.device("cuda:0")
+    B, H, D, S = cfg.B, cfg.H, cfg.D, cfg.S
+    lv = nqkv.build_codebook(k)
+    desc = nqkv.make_desc(B, H, D, k, blk, S)
+    codes, scales = nqkv.alloc_cache(desc, dev)
+    g = torch.Generator(device=dev).manual_seed(1000 + k)
+    codes.copy_(torch.randint(0, 256, codes.shape, device=dev, generator=g, dtype=torch.uint8))
+    scales.view(torch.int16).copy_(torch.randint(0, 0x7C00, scales.shape, device=dev, generator=g, dtype=torch.int16))
+    out = nqkv.dequantize_kv(desc, lv, codes, scales, 0, S)
+    off, n = 1003, S - 2007
+    out_tm = torch.zeros(B, n + 2, H, D, dtype=torch.float16, device=dev)         # rows 0 and n + 1 stay untouched
+    nqkv.dequantize_kv(desc, lv, codes, scales, off, n, out=out_tm[:, 1:n + 1].permute(0, 2, 1, 3))
+    torch.cuda.synchronize()
+    assert not out_tm[:, 0].any() and not out_tm[:, n + 1].any()
+    for b in rows:
+        sl = slice(b, b + 1)
+        ref = oracle.dequantize_kv(bits(codes[sl]), bits(scales[sl]), k, blk, lv, 0, S, n_threads=THREADS)
+        assert np.array_equal(bits(out[sl]), ref), (name, k, blk, b)
+        assert np.array_equal(bits(out_tm[sl, 1:n + 1].permute(0, 2, 1, 3).contiguous()), ref[:, :, off:off + n]), (name, b)
