@@ -14,6 +14,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kPasses = 4;
 constexpr uint32_t kDropStore = 0xffffffffu;      // an offset outside every buffer: the store is dropped
+constexpr int kNonTemporal = 2;                   // cache-policy bit of a buffer instruction: read or written once
 constexpr int64_t kCacheableOutputBytes = 64ll << 20;   // a quarter of the 256 MB last-level cache
 
 // NT: the stores carry the non-temporal hint (output too large for the last-level cache to keep
@@ -53,9 +54,9 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const QuantParams 
     const uint32_t t = t0 + u * RPP;
     const uint32_t off = t * kRowBytes + c * KBITS;
     if constexpr (KBITS == 4) {
-      w[u] = __builtin_amdgcn_raw_buffer_load_b32(code_r, off, 0, 0);
+      w[u] = __builtin_amdgcn_raw_buffer_load_b32(code_r, off, 0, kNonTemporal);
     } else if constexpr (KBITS == 2) {
-      w[u] = __builtin_amdgcn_raw_buffer_load_b16(code_r, off, 0, 0);
+      w[u] = __builtin_amdgcn_raw_buffer_load_b16(code_r, off, 0, kNonTemporal);
     } else {
       // 3 bytes at any byte offset: the two aligned dwords around them (each range-checked on
       // its own), shifted down by the offset's low bits
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const QuantParams 
     }
     const u32x4_t v = {o[0], o[1], o[2], o[3]};
     // (the row test rather than the range check alone: t * stride may wrap for rows past the end)
-    __builtin_amdgcn_raw_buffer_store_b128(v, dst_r, t < n ? (t * st + c * 8u) * 2u : kDropStore, 0, NT ? 2 : 0);
+    __builtin_amdgcn_raw_buffer_store_b128(v, dst_r, t < n ? (t * st + c * 8u) * 2u : kDropStore, 0, NT ? kNonTemporal : 0);
   }
 }
 

@@ -137,6 +137,10 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const QuantParams p)
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kBufferFlags = 0x00020000;       // raw buffer, 32-bit data format (gfx9 family)
 constexpr uint32_t kDropStore = 0xffffffffu;   // voffset outside every descriptor
+// Cache-policy bits of the source loads and code stores: the non-temporal hint.  Both streams pass
+// once, a whole cache line per instruction; with the hint the prefill quantizer measured 7-13 %
+// faster (1.67 -> 1.52 ms on 3.8 G elements per tensor).
+constexpr int kNonTemporal = 2;
 
 template <int KBITS, int D, int BLK, bool FAST, bool CONTIG, bool PAGED = false>
 __global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantParams p) {
@@ -196,7 +200,7 @@ __global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantPara
       voff = (c / CPR) * (uint32_t)(p.stride_t * 2) + (c % CPR) * 16;
     }
     if (c >= total) voff = kDropStore;                         // past the slab: reads zeros
-    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(src_r, voff, 0, 0);
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(src_r, voff, 0, kNonTemporal);
     w[u] = make_uint4(v.x, v.y, v.z, v.w);
   }
 
@@ -221,17 +225,17 @@ __global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantPara
     const bool live = c < total;
     const uint32_t dc = d0 + u * kThreads;               // chunk inside the destination descriptor
     if (KBITS == 4) {
-      __builtin_amdgcn_raw_buffer_store_b32(packed, code_r, live ? dc * 4 : kDropStore, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b32(packed, code_r, live ? dc * 4 : kDropStore, 0, kNonTemporal);
     } else if (KBITS == 2) {
       const uint32_t odd = dpp<kQuadOdd>(packed);
       const bool writer = live && !(threadIdx.x & 1);
-      __builtin_amdgcn_raw_buffer_store_b32(packed | (odd << 16), code_r, writer ? dc * 2 : kDropStore, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b32(packed | (odd << 16), code_r, writer ? dc * 2 : kDropStore, 0, kNonTemporal);
     } else {  // KBITS == 3: four lanes hold 4 x 24 bits = three dwords
       const uint32_t next = dpp<kQuadNext>(packed);
       const uint32_t q = threadIdx.x & 3;
       const uint32_t word = (packed >> (8 * q)) | (next << (24 - 8 * q));
       const bool writer = live && q != 3;
-      __builtin_amdgcn_raw_buffer_store_b32(word, code_r, writer ? (dc >> 2) * 12 + q * 4 : kDropStore, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b32(word, code_r, writer ? (dc >> 2) * 12 + q * 4 : kDropStore, 0, kNonTemporal);
     }
     const bool scale_writer = live && (dc % LPB) == 0;
     __builtin_amdgcn_raw_buffer_store_b16((unsigned short)s_bits, scale_r, scale_writer ? (dc / LPB) * 2 : kDropStore, 0, 0);
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(kThreads) void quantize_hidden_kernel(const QuantPa
   for (int u = 0; u < kUnroll; ++u) {
     const uint32_t t = t_first + u * TOK;
     const uint32_t voff = t < n ? src_lane + t * (uint32_t)(p.stride_t * 2) : kDropStore;   // past the end: reads zeros
-    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(src_r, voff, 0, 0);
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(src_r, voff, 0, kNonTemporal);
     w[u] = make_uint4(v.x, v.y, v.z, v.w);
   }
 
@@ -337,7 +341,7 @@ __global__ __launch_bounds__(kThreads) void quantize_hidden_kernel(const QuantPa
     const uint32_t hl = i / kHeadDwords, off = i % kHeadDwords;          // head of the block, dword inside its rows
     const bool live = tile_t0 + off / (kRowBytes / 4) < n;
     const uint32_t voff = (row0 + hl * (uint32_t)p.cap_tokens) * kRowBytes + off * 4;
-    __builtin_amdgcn_raw_buffer_store_b32(stage[hl * kHeadPitch + off], code_r, live ? voff : kDropStore, 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b32(stage[hl * kHeadPitch + off], code_r, live ? voff : kDropStore, 0, kNonTemporal);
   }
   if (threadIdx.x < HPB * TILE_TOK) {
     const uint32_t hl = threadIdx.x / TILE_TOK, tl = threadIdx.x % TILE_TOK;
