@@ -14,10 +14,11 @@
 //
 // Scores.   C1[token][query] = sum_d K[token][d] q[query][d]:  A = levels of a 16-token tile of
 //   K (row = token i16), B = q^T.  One instruction contracts over 32 head-dim elements of one
-//   64-element chunk, this lane's being  64 c + 16 gq + 8 h + 0..7  for half h, so a lane needs 8
-//   contiguous code bytes per chunk (one 64-bit load; dword h is one operand) and the chunk lies
-//   inside one quantization block; the block scale of the token multiplies C1 afterwards, in fp32
-//   (a lane fetches the scales of one token of its quad of rows, the quad shares them by DPP).
+//   64-element chunk, this lane's being  64 c + 16 a + 8 h + 0..7  for half h (a = gq, or a fixed
+//   permutation of it, see load_k), so a lane needs 8 contiguous code bytes per chunk (dword h is
+//   one operand) and the chunk lies inside one quantization block; the block scale of the token
+//   multiplies C1 afterwards, in fp32 (a lane fetches the scales of one token of its quad of
+//   rows, the quad shares them by DPP).
 // Softmax.  A lane holds scores of tokens 4 gq + r (r = 0..3) of the tile for query i16: the
 //   running maximum and sum are per lane (= per query), reduced over gq with lane swaps.
 // Output.   O^T[d][query] = sum_token V[token][d] P[token][query]:  B = P^T is exactly the layout
@@ -98,8 +99,10 @@ void decode_multi_kernel(const MultiParams p) {
   constexpr int TPT = kTilesPerTrip;
   static_assert(TPT % 2 == 0, "the value product contracts over two 16-token tiles");
   constexpr int TRIP = kTile * TPT;
-  constexpr bool kStage = !(KBITS == 4 && D == 128);     // value codes through an LDS staging area (see below)
   constexpr int NC = D / 64;                 // 64-element chunks of a row
+  // Two chunks per row, whole bytes per lane: the lane's codes of BOTH chunks come with one load
+  // (see load_k), so that a load instruction consumes whole rows.
+  constexpr bool kWideK = D == 128 && KBITS != 3;
   constexpr int NB = D / BLK;                // quantization blocks of a row
   constexpr int CPB = BLK / 64;              // chunks per block
   constexpr uint32_t kRowBytes = D * KBITS / 8, kChunkBytes = 8 * KBITS, kScaleRowBytes = NB * 2;
@@ -112,7 +115,7 @@ void decode_multi_kernel(const MultiParams p) {
     union {
       struct {
         __attribute__((aligned(256))) uint32_t lut[kLutWords];
-        uint32_t stage[kStage ? kWaves : 1][TPT][kTileBytes / 4];
+        uint32_t stage[kWaves][TPT][kTileBytes / 4];
       };
       struct {
         float xo[kWaves][kMaxQ][XS];
@@ -165,14 +168,19 @@ void decode_multi_kernel(const MultiParams p) {
   // 2 i16 + 1 of the chunk) start at bit 12 i16 -- a 64-bit load from dword min(12 i16 / 32, 4)
   const uint32_t v3_dw = min((12u * i16) >> 5, 4u);
   const uint32_t k3_shift = (gq & 1u) * 16u, v3_shift = 12u * i16 - 32u * v3_dw;
-  const uint32_t k_voff = i16 * kRowBytes + (KBITS == 3 ? ((6u * gq) & ~3u) : gq * (4u * KW));      // + c * kChunkBytes
-  // Except for 4-bit codes at head size 128 (kStage below; there the direct loads measured 2 %
-  // faster), value codes go through LDS: a tile (16 consecutive rows, contiguous in the cache) is fetched
+  const uint32_t k_voff = i16 * kRowBytes + (KBITS == 3 ? ((6u * gq) & ~3u) : gq * (4u * KW) * (kWideK ? 2u : 1u));      // + c * kChunkBytes
+  // kWideK: lane group gq fetches bytes [8 KW gq, 8 KW (gq + 1)) of the row -- the 4 KW-byte units
+  // 2 gq and 2 gq + 1 of the row's eight -- and v_permlane32_swap (lanes 32..63 of the first
+  // operand <-> lanes 0..31 of the second) then leaves group gq with units a and a + 4, a = aq:
+  // its 16 elements of chunk 0 and of chunk 1, as the operand layout wants, for the unit a below.
+  const uint32_t aq = kWideK ? ((gq >> 1) | ((gq & 1u) << 1)) : gq;
+  // Value codes go through LDS: a tile (16 consecutive rows, contiguous in the cache) is fetched
   // with ONE 128-bit load per lane -- lane L takes bytes [16 L, 16 L + 16) of the tile -- and
   // written to this wave's staging area, from which every lane reads the dwords the matrix-operand
   // layout wants (token 4 gq + e, dword v_dw of chunk c).  Fetching those dwords straight from
-  // memory costs one load instruction per lane and token: 2.4x the memory instructions of the
-  // whole kernel, which is what bound it.  Inside each group of four rows the rows are stored
+  // memory costs one load instruction per lane and token (2.4x the memory instructions of the
+  // whole kernel, which is what bound it at 2 and 3 bits) and takes every cache line in pieces,
+  // which rules out the non-temporal hint.  Inside each group of four rows the rows are stored
   // permuted (row e of group g at slot e ^ g), so that the four lane groups gq, which read rows
   // 64 or 32 bytes apart, spread over the banks; 3-bit rows (48 / 24 bytes) stay in place.
   constexpr bool kSwizzle = KBITS != 3;
@@ -184,19 +192,16 @@ void decode_multi_kernel(const MultiParams p) {
     const uint32_t t = st_byte / kRowBytes;
     st_addr = ((t & ~3u) | ((t & 3u) ^ ((t >> 2) & 3u))) * kRowBytes + st_byte % kRowBytes;
   }
-  uint32_t* const st_wave = &lds.stage[kStage ? wave : 0][0][0];
+  uint32_t* const st_wave = &lds.stage[wave][0][0];
   const char* rd_row[4];                                         // staged row of token 4 gq + e, at this lane's dword
 #pragma unroll
   for (int e = 0; e < 4; ++e)
     rd_row[e] = reinterpret_cast<const char*>(st_wave) + (4u * gq + (kSwizzle ? (e ^ gq) : (uint32_t)e)) * kRowBytes + v_dw * 4u;
-  // (direct path) this lane's dword of token 4 gq + e, chunk c, relative to the tile
-  const uint32_t v_voff = (4u * gq) * kRowBytes + v_dw * 4u;            // + e * kRowBytes + c * kChunkBytes
   // scales: lane (i16, gq) fetches those of token 4 gq + i16 % 4 only; the quad shares them by DPP
   const uint32_t s_voff = (4u * gq + (i16 & 3u)) * kScaleRowBytes;
 
   uint32_t kw[TPT][NC][KW];
-  u32x4_t vst[kStage ? TPT : 1];         // value tiles on their way to the staging area
-  uint32_t vw[kStage ? 1 : TPT][NC][4];  // or, direct path, this lane's dword of token 4 gq + e, chunk c
+  u32x4_t vst[TPT];                      // value tiles on their way to the staging area
   uint32_t ksr[TPT], vsr[TPT];
 
   auto load_scales = [&](__amdgpu_buffer_rsrc_t r, uint32_t voff) -> uint32_t {
@@ -232,11 +237,21 @@ void decode_multi_kernel(const MultiParams p) {
       const uint32_t tok = (uint32_t)tb + u * kTile;
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
-        if constexpr (KBITS != 2) {
-          const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(cr, k_voff + tok * kRowBytes + c * kChunkBytes, 0, 0);
+        if constexpr (kWideK) {
+          if (c == 0) {
+            if constexpr (KBITS == 4) {
+              const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(cr, k_voff + tok * kRowBytes, 0, kStreamOnce);
+              kw[u][0][0] = v.x; kw[u][0][1] = v.y; kw[u][1][0] = v.z; kw[u][1][1] = v.w;
+            } else {
+              const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(cr, k_voff + tok * kRowBytes, 0, kStreamOnce);
+              kw[u][0][0] = v.x; kw[u][1][0] = v.y;
+            }
+          }
+        } else if constexpr (KBITS != 2) {
+          const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(cr, k_voff + tok * kRowBytes + c * kChunkBytes, 0, NC == 1 ? kStreamOnce : 0);
           kw[u][c][0] = v.x; kw[u][c][1] = v.y;
         } else {
-          kw[u][c][0] = __builtin_amdgcn_raw_buffer_load_b32(cr, k_voff + tok * kRowBytes + c * kChunkBytes, 0, 0);
+          kw[u][c][0] = __builtin_amdgcn_raw_buffer_load_b32(cr, k_voff + tok * kRowBytes + c * kChunkBytes, 0, NC == 1 ? kStreamOnce : 0);
         }
       }
       ksr[u] = load_scales(sr, s_voff + tok * kScaleRowBytes);
@@ -253,16 +268,8 @@ void decode_multi_kernel(const MultiParams p) {
 #pragma unroll
     for (int u = 0; u < TPT; ++u) {
       const uint32_t tok = (uint32_t)tb + u * kTile;
-      if constexpr (kStage) {
-        // (lanes past the tile, and rows past the item, read zeros: the offset is out of range)
-        vst[u] = __builtin_amdgcn_raw_buffer_load_b128(cr, st_live ? tok * kRowBytes + st_byte : 0xffffffffu, 0, 0);
-      } else {
-#pragma unroll
-        for (int c = 0; c < NC; ++c)
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            vw[u][c][e] = __builtin_amdgcn_raw_buffer_load_b32(cr, v_voff + (tok + e) * kRowBytes + c * kChunkBytes, 0, 0);
-      }
+      // (lanes past the tile, and rows past the item, read zeros: the offset is out of range)
+      vst[u] = __builtin_amdgcn_raw_buffer_load_b128(cr, st_live ? tok * kRowBytes + st_byte : 0xffffffffu, 0, kStreamOnce);
       vsr[u] = load_scales(sr, s_voff + tok * kScaleRowBytes);
     }
   };
@@ -274,14 +281,14 @@ void decode_multi_kernel(const MultiParams p) {
   };
   int32_t base = (int32_t)wave * TRIP;
   load_k(base);
-  // the query operand: q[query i16][64 c + 16 gq + 8 h + 0..7] for chunk c, half h -- 32 bytes per chunk;
+  // the query operand: q[query i16][64 c + 16 aq + 8 h + 0..7] for chunk c, half h -- 32 bytes per chunk;
   // rows beyond q_len read zeros
   uint32_t qb[NC][2][4];
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
 #pragma unroll
     for (int hlf = 0; hlf < 2; ++hlf) {
-      const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(q_r, (i16 * D + 64u * c + 16u * gq + 8u * hlf) * 2u, 0, 0);
+      const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(q_r, (i16 * D + 64u * c + 16u * aq + 8u * hlf) * 2u, 0, 0);
       qb[c][hlf][0] = v.x; qb[c][hlf][1] = v.y; qb[c][hlf][2] = v.z; qb[c][hlf][3] = v.w;
     }
   }
@@ -304,6 +311,13 @@ void decode_multi_kernel(const MultiParams p) {
     load_v(base);
 
     // ---- scores of the trip's two tiles
+    if constexpr (kWideK) {
+      // (the s_nop covers the wait states between a write of the operands and the swap)
+#pragma unroll
+      for (int u = 0; u < TPT; ++u)
+#pragma unroll
+        for (int i = 0; i < KW; ++i) asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(kw[u][0][i]), "+v"(kw[u][1][i]));
+    }
     float z[TPT][4];
 #pragma unroll
     for (int u = 0; u < TPT; ++u) {
@@ -388,19 +402,16 @@ void decode_multi_kernel(const MultiParams p) {
     // ---- the trip's value tiles: registers -> staging area.  Written and read by different lanes of
     // this one wave: LDS operations of a wave complete in order, the fences keep the compiler from
     // reordering them (and from moving the next trip's writes above this trip's reads).
-    if constexpr (kStage) {
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int u = 0; u < TPT; ++u)
-        if (st_live) *reinterpret_cast<u32x4_t*>(reinterpret_cast<char*>(st_wave) + u * kTileBytes + st_addr) = vst[u];
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    }
+    for (int u = 0; u < TPT; ++u)
+      if (st_live) *reinterpret_cast<u32x4_t*>(reinterpret_cast<char*>(st_wave) + u * kTileBytes + st_addr) = vst[u];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     auto staged = [&](int u, int c, int e, int word) {
-      if constexpr (kStage) return *reinterpret_cast<const uint32_t*>(rd_row[e] + u * kTileBytes + c * kChunkBytes + word * 4);
-      else return vw[u][c][e];
+      return *reinterpret_cast<const uint32_t*>(rd_row[e] + u * kTileBytes + c * kChunkBytes + word * 4);
     };
 
     // ---- weighted values: one instruction contracts over the 32 tokens of two tiles (this lane's
