@@ -78,8 +78,8 @@ int nqkv_version(void);
  * its tolerance), only which kernel variant or launch shape is used.
  *   knob 0  quantizer: 0 = cell-table code search (default), 1 = plain scan of all thresholds
  *   knob 1  decode attention: workgroups aimed for when num_splits == 0 (0 = default)
- *   knob 2  decode attention: upper limit of the persistent grid in workgroups (0 = default:
- *           two per compute unit)
+ *   knob 2  decode attention: upper limit of the grid in workgroups (0 = default: a persistent
+ *           grid of two per compute unit, or one per work item when items are 4096 tokens or longer)
  * Returns NQKV_EINVAL for an unknown knob or value.
  */
 int nqkv_set_tuning(int knob, int value);
