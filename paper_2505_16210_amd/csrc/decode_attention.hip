@@ -474,14 +474,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
 #pragma unroll
       for (int r = 0; r < kRounds; ++r) {
         float part = k_dot<KBITS>(kw[r], q2, lut, lane_off);
-        part *= (float)__builtin_bit_cast(_Float16, ksc[r]);
+        // (an fma with a zero addend: it takes the fp16 scale as it is, where a multiply needs a conversion first)
+        part = __builtin_fmaf(part, (float)__builtin_bit_cast(_Float16, ksc[r]), 0.0f);
         part += dpp_f<kQuadXor1>(part);
         if (LPT == 4) part += dpp_f<kQuadXor2>(part);
         const bool valid = full || (base + r * TPR + (int32_t)g < n_tok);
         z[r] = valid ? part * p.scale_log2e : -INFINITY;
       }
       float m_trip = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
-      m_trip = wave_max(m_trip);
+      m_trip = wave_max<LPT>(m_trip);          // the LPT lanes of a token hold the same scores
       if (m_trip > m_run) {            // uniform across the wave
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_trip);
 #pragma unroll
@@ -500,7 +501,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
 
 #pragma unroll
       for (int r = 0; r < kRounds; ++r) {
-        const float wgt = pw[r] * (float)__builtin_bit_cast(_Float16, vsc[r]);
+        const float wgt = __builtin_fmaf(pw[r], (float)__builtin_bit_cast(_Float16, vsc[r]), 0.0f);
         v_axpy<KBITS>(vw[r], wgt, acc, lut, lane_off);
       }
     }

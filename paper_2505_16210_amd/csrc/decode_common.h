@@ -24,9 +24,11 @@ __device__ __forceinline__ float dpp_f(float v) {
 }
 constexpr int kQuadXor1 = 0xB1, kQuadXor2 = 0x4E, kRowHalfMirror = 0x141, kRowMirror = 0x140;
 
+// SAME: lanes that already hold equal values -- 1, 2 or 4 neighbours (an aligned pair, a quad)
+template <int SAME = 1>
 __device__ __forceinline__ float wave_max(float v) {
-  v = fmaxf(v, dpp_f<kQuadXor1>(v));
-  v = fmaxf(v, dpp_f<kQuadXor2>(v));
+  if (SAME < 2) v = fmaxf(v, dpp_f<kQuadXor1>(v));
+  if (SAME < 4) v = fmaxf(v, dpp_f<kQuadXor2>(v));
   v = fmaxf(v, dpp_f<kRowHalfMirror>(v));
   v = fmaxf(v, dpp_f<kRowMirror>(v));
   const int i = __builtin_bit_cast(int, v);
