@@ -4,11 +4,13 @@
 // registers between the HBM read of the packed codes and the dot products, so a decode step
 // moves only the packed bytes.  gfx950 only; no matrix cores (one query row per head).
 //
-// Mapping.  The grid is persistent: at most two eight-wave workgroups per compute unit, each
-// building the look-up table once and then walking over work items (batch*head, split) with the
-// grid as stride; an item's token range is streamed once.  A lane owns 32 consecutive head-dim
-// elements of a token (4*k bytes of codes, one block scale), so LPT = D/32 adjacent lanes hold one token and a wave load covers
-// 64/LPT tokens with one fully coalesced request (1 KiB at k = 4).  Four such loads of K and
+// Mapping.  Eight-wave workgroups, each building the look-up table once and then walking over
+// work items (batch*head, split) with the grid as stride; an item's token range is streamed
+// once.  The host sizes the grid: at most two workgroups per compute unit (a persistent grid) for
+// short items, one workgroup per item for long ones.  A lane owns 32 consecutive head-dim elements
+// of a token (4*k bytes of codes, one block scale), so LPT = D/32 adjacent lanes hold one token and
+// a wave load covers 64/LPT tokens with one fully coalesced request (1 KiB at k = 4), marked
+// non-temporal: the cache is read once.  Four such loads of K and
 // four of V are in flight per wave; the first trip's loads are issued before the look-up table
 // is built and the next trip's K loads before the current trip's V arithmetic.
 //
@@ -187,7 +189,7 @@ __device__ __forceinline__ void reduce_groups(const float (&acc)[32], uint32_t l
 }
 
 // ------------------------------------------------------------------ main kernel
-// grid: x = persistent workgroups; item i -> (bh = i / splits, split = i % splits)
+// grid: x = workgroups, each taking items i = blockIdx.x, + gridDim.x, ...; item i -> (bh = i / splits, split = i % splits)
 // SPLIT: sequences are cut into p.splits > 1 items whose partial results are combined by the
 // workgroup that finishes last; without it (p.splits == 1) that code and the item -> (sequence,
 // split) division are compiled out.

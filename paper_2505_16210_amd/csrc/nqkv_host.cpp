@@ -15,7 +15,7 @@ using namespace nqkv;
 // Experiment switches (see nqkv_set_tuning).  Plain ints: set them before issuing work.
 int g_quantize_impl = 0;       // 0 cell table, 1 threshold scan
 int g_decode_target_wgs = 0;   // 0 = default
-int g_decode_grid_limit = 0;   // 0 = default (persistent grid); > 0 = at most this many workgroups
+int g_decode_grid_limit = 0;   // 0 = default (see fill_decode_common); > 0 = at most this many workgroups
 
 constexpr int64_t kLongItemTokens = 4096;   // see fill_decode_common
 

@@ -59,7 +59,7 @@ struct DecodeParams {
   int n_items;               // B*H*splits
   int splits;
   int split_base, split_rem; // seq_len = splits * split_base + split_rem
-  int max_workgroups;        // persistent grid size limit (2 per compute unit)
+  int max_workgroups;        // grid size limit (2 per compute unit, or the item count: see fill_decode_common)
   int64_t cap_tokens;
   float scale_log2e;         // softmax_scale * log2(e) / gamma
   float inv_gamma;           // 1 / gamma: undoes the table scaling on the value side
