@@ -468,7 +468,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
     }
 
     for (; base < n_tok; base += stride) {
-      const bool full = base + CHUNK <= n_tok;
+      const int32_t left = n_tok - base;      // tokens of the item from this trip on (uniform)
       load_v(base);
 
       // scores of this trip's tokens (log2 domain)
@@ -480,7 +480,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
         part = __builtin_fmaf(part, (float)__builtin_bit_cast(_Float16, ksc[r]), 0.0f);
         part += dpp_f<kQuadXor1>(part);
         if (LPT == 4) part += dpp_f<kQuadXor2>(part);
-        const bool valid = full || (base + r * TPR + (int32_t)g < n_tok);
+        // (the lane's token of round r exists: a per-lane constant against a scalar)
+        const bool valid = (int32_t)g < left - r * TPR;
         z[r] = valid ? part * p.scale_log2e : -INFINITY;
       }
       float m_trip = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
