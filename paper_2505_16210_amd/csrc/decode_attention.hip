@@ -275,6 +275,24 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
     int64_t row0 = (int64_t)bh * p.cap_tokens + t0;
     if (VARLEN) {
       b = bh / (uint32_t)p.H; h = bh - b * (uint32_t)p.H;
+      if (p.longest_first) {
+        // b so far is a rank: take the sequence whose length has that rank (ties by index).  Lane l
+        // holds the length of sequence l (at most 64 of them); its rank is the number of sequences
+        // that come before it.  Items are dispatched in index order, so the long sequences start
+        // first and the short ones fill the tail of the grid.
+        const uint32_t nb = (uint32_t)p.n_seqs;
+        int32_t len_l = -1;
+        if (lane < nb) len_l = min(max(p.seq_lens[lane], 0), p.max_len);
+        uint32_t before = 0;
+        for (uint32_t s = 0; s < nb; ++s) {
+          const int32_t len_s = __builtin_amdgcn_readlane(len_l, (int)s);
+          before += (len_s > len_l || (len_s == len_l && s < lane)) ? 1u : 0u;
+        }
+        const uint64_t hit = __builtin_amdgcn_ballot_w64(lane < nb && before == b);
+        b = hit ? (uint32_t)__builtin_ctzll(hit) : b;       // exactly one lane: the ranks are a permutation
+        bh = b * (uint32_t)p.H + h;
+        row0 = (int64_t)bh * p.cap_tokens + t0;
+      }
       const int32_t len = min(max(scalar_read(p.seq_lens + b), 0), p.max_len);     // whatever the array holds, stay inside the cache
       n_tok = min(n_tok, max(len - (int32_t)t0, 0));
       pos = len;

@@ -440,6 +440,13 @@ int nqkv_decode_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, in
   return NQKV_OK;
 }
 
+// Ragged batch on a grid of one workgroup per item, more items than can be resident: dispatch
+// the long sequences first (the kernel ranks the lengths itself; it handles up to 64 of them).
+// Measured at B16 H56 S<=16384, lengths spread over [S/8, S] in random batch order: 211 -> 175 us.
+static int longest_first_pays(const DecodeParams& p, const int32_t* lens, int B) {
+  return lens && B >= 2 && B <= 64 && p.max_workgroups >= p.n_items && p.n_items > max_decode_workgroups();
+}
+
 // The part of DecodeParams every decode entry point fills the same way.
 static void fill_decode_common(DecodeParams* p, const nqkv_cache_desc* desc, const LevelTable& checked,
                                const void* q, const void* k_new, const void* v_new,
@@ -463,6 +470,7 @@ static void fill_decode_common(DecodeParams* p, const nqkv_cache_desc* desc, con
   // fixed deal (measured: 896 items of 16384 tokens 332 -> 319 us; 8192 items of 128 tokens 52 -> 65 us).
   p->max_workgroups = g_decode_grid_limit > 0 ? g_decode_grid_limit
                       : item_tokens >= kLongItemTokens ? p->n_items : max_decode_workgroups();
+  p->n_seqs = desc->B;
   p->cap_tokens = desc->cap_tokens;
   const LutChoice& lut = choose_lut_scale(checked.v, 1 << desc->k);
   std::memcpy(p->lut_levels, lut.bits, sizeof(uint16_t) * (1 << desc->k));
@@ -533,6 +541,7 @@ static int decode_impl(const nqkv_cache_desc* desc, const float* levels, const v
   p.pos = seq_len - 1;
   p.seq_lens = lens;                                    // fused: lens[b] = cached rows = the new token's row
   p.max_len = (int)n_cached;
+  p.longest_first = longest_first_pays(p, lens, desc->B);
   const hipError_t e = launch_decode_attention(p, desc->D, desc->k, desc->block, fuse, stream);
   return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
 }
@@ -669,6 +678,7 @@ static int decode_paged_impl(const nqkv_cache_desc* desc, const float* levels, c
   p.split_rem = 0;
   p.seq_lens = lens;
   p.max_len = (int)n_cached;
+  p.longest_first = longest_first_pays(p, lens, desc->B);
   p.block_table = block_table;
   p.table_stride = (int)table_stride;
   p.num_pages = (int)num_pages;

@@ -75,6 +75,10 @@ struct DecodeParams {
   // the length the split geometry is laid out for
   const int32_t* seq_lens;
   int max_len;
+  // longest first (one workgroup per item, at most 64 sequences): work item i goes to the
+  // sequence whose length ranks i / (H * splits)-th, so that the long ones are dispatched first
+  int longest_first;
+  int n_seqs;                // B
   // paged cache (NULL: contiguous [B][H][cap_tokens] rows): physical page of logical page j of
   // sequence b at block_table[b * table_stride + j]; the pool holds num_pages pages of
   // [H][1 << page_shift] rows; items cover split_base tokens, a multiple of the page size

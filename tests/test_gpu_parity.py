@@ -1097,3 +1097,71 @@ def test_decode_attention_and_step_random_geometries(nqkv, oracle):
         hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
         ref = oracle.decode_attention(*hk, k, blk, lv, S + 1, scale, n_threads=4)
         assert attn_err(h2n(out_f).view(np.float16), ref) <= ATTN_TOL, ("step", case, k, D, blk, B, H, S, ns)
+
+
+@pytest.mark.parametrize("k,D,blk,B,H", [(4, 64, 64, 9, 64), (3, 128, 64, 64, 9), (2, 128, 128, 2, 300), (4, 128, 128, 65, 9)])
+def test_varlen_longest_first_dispatch(nqkv, oracle, k, D, blk, B, H):
+    """Ragged batches on a grid of one workgroup per item with more items than can be resident:
+    the kernel then hands the items of the longest sequences out first (it ranks up to 64 lengths
+    itself; 65 sequences take the plain order).  Lengths with ties, empty sequences and values
+    outside the range; attention, the fused step and the paged form, each sequence against the
+    oracle; the fused step's appended rows land in the right sequence bit for bit."""
+    S, cap = 300, 304
+    lv, desc, q, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, cap, cap, seed=77 + B)
+    rng = np.random.default_rng(B * 1000 + H)
+    lens = rng.integers(0, S + 1, B)
+    lens[0] = lens[-1] = 123                      # a tie
+    if B > 4:
+        lens[1], lens[2], lens[3] = 0, S, S       # an empty sequence, two of the longest
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+    ref = np.zeros((B, H, D))
+    for b in range(B):
+        if lens[b]:
+            ref[b] = oracle.decode_attention(*[a[b:b + 1] for a in hk], k, blk, lv, int(lens[b]), 0.8, n_threads=8)[0]
+    live = lens > 0
+    nqkv.set_tuning(2, 1 << 20)                   # one workgroup per item whatever the item length
+    try:
+        for ns in (1, 2):
+            out = nqkv.decode_attention_varlen(desc, lv, q, kc, ks, vc, vs, lens_dev, S, 0.8, num_splits=ns)
+            torch.cuda.synchronize()
+            assert attn_err(h2n(out).view(np.float16)[live], ref[live]) <= ATTN_TOL, (k, D, B, H, ns)
+        if B > 4:                                 # sequence 1 is empty: a negative length must read as 0
+            wild = lens_dev.clone()
+            wild[1] = -9
+            out = nqkv.decode_attention_varlen(desc, lv, q, kc, ks, vc, vs, wild, S, 0.8)
+            torch.cuda.synchronize()
+            assert attn_err(h2n(out).view(np.float16)[live], ref[live]) <= ATTN_TOL
+        # paged form over an identity-shuffled pool (page = 128 tokens)
+        if True:
+            P, capp = 128, 384
+            pk = [torch.zeros(B, H, capp, t.shape[-1], dtype=t.dtype, device="cuda") for t in (kc, ks, vc, vs)]
+            for dst, src in zip(pk, (kc, ks, vc, vs)):
+                dst[:, :, :cap] = src
+            n_pg = capp // P
+            perm = torch.randperm(B * n_pg, generator=torch.Generator().manual_seed(B))
+            table = perm.reshape(B, n_pg).to(torch.int32).cuda()
+            pools = [_scatter_to_pages(t, table, P) for t in pk]
+            pdesc = nqkv.make_desc(B, H, D, k, blk, P)
+            out = nqkv.decode_attention_paged(pdesc, lv, q, *pools, table, lens_dev, S, 0.8)
+            torch.cuda.synchronize()
+            assert attn_err(h2n(out).view(np.float16)[live], ref[live]) <= ATTN_TOL, "paged"
+        # fused step: every sequence appends at its own row
+        g = torch.Generator(device="cuda").manual_seed(B + H)
+        kn = rand_kv((B, H, 1, D), seed=5 + B)[:, :, 0].contiguous()
+        vn = torch.randn(B, H, D, device="cuda", generator=g).to(torch.float16)
+        kc2, ks2, vc2, vs2 = kc.clone(), ks.clone(), vc.clone(), vs.clone()
+        out = nqkv.decode_step_varlen(desc, lv, q, kn, vn, kc2, ks2, vc2, vs2, lens_dev, S, 0.8)
+        torch.cuda.synchronize()
+    finally:
+        nqkv.set_tuning(2, 0)
+    okc, oks, ovc, ovs = (h2n(t).copy() for t in (kc, ks, vc, vs))
+    for b in range(B):
+        sl = slice(b, b + 1)
+        oracle.quantize_kv(h2n(kn)[sl, :, None], k, blk, lv, okc[sl], oks[sl], dst_off=int(lens[b]))
+        oracle.quantize_kv(h2n(vn)[sl, :, None], k, blk, lv, ovc[sl], ovs[sl], dst_off=int(lens[b]))
+    assert np.array_equal(h2n(kc2), okc) and np.array_equal(h2n(ks2), oks)
+    assert np.array_equal(h2n(vc2), ovc) and np.array_equal(h2n(vs2), ovs)
+    ref2 = np.stack([oracle.decode_attention(h2n(q)[b:b + 1], okc[b:b + 1], oks[b:b + 1], ovc[b:b + 1], ovs[b:b + 1],
+                                             k, blk, lv, int(lens[b]) + 1, 0.8, n_threads=8)[0] for b in range(B)])
+    assert attn_err(h2n(out).view(np.float16), ref2) <= ATTN_TOL
