@@ -137,7 +137,25 @@ void decode_multi_kernel(const MultiParams p) {
 
   // ---- item geometry
   const uint32_t item = blockIdx.x;
-  const uint32_t bh = item / (uint32_t)p.splits, sp = item - bh * (uint32_t)p.splits;
+  uint32_t bh = item / (uint32_t)p.splits;
+  const uint32_t sp = item - bh * (uint32_t)p.splits;
+  if (p.longest_first) {
+    // Ragged batch, more workgroups than can be resident: item / (H * splits) is a RANK, and the
+    // sequence is the one whose length has that rank (ties by index), so that the long sequences
+    // are dispatched first and the short ones fill the tail of the grid.  Lane l holds the length
+    // of sequence l (at most 64 of them); its rank is the number of sequences that come before it.
+    const uint32_t nb = (uint32_t)p.n_seqs, rank = bh / (uint32_t)p.H, h = bh - rank * (uint32_t)p.H;
+    int32_t len_l = -1;
+    if (lane < nb) len_l = min(max(p.seq_lens[lane], p.q_len), p.seq_len);
+    uint32_t before = 0;
+    for (uint32_t s = 0; s < nb; ++s) {
+      const int32_t len_s = __builtin_amdgcn_readlane(len_l, (int)s);
+      before += (len_s > len_l || (len_s == len_l && s < lane)) ? 1u : 0u;
+    }
+    const uint64_t hit = __builtin_amdgcn_ballot_w64(lane < nb && before == rank);
+    const uint32_t b = hit ? (uint32_t)__builtin_ctzll(hit) : rank;     // exactly one lane: the ranks are a permutation
+    bh = b * (uint32_t)p.H + h;
+  }
   // splits are whole 32-token pieces
   const int32_t u0 = (int32_t)sp * p.split_base + min((int32_t)sp, p.split_rem);
   const int32_t t0 = u0 * kSplitUnit;

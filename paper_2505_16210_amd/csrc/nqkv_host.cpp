@@ -860,6 +860,10 @@ static int decode_multi_impl(const nqkv_cache_desc* desc, const float* levels, c
   p.table_stride = (int)table_stride;
   p.num_pages = (int)num_pages;
   p.page_shift = page_shift;
+  // (one workgroup per item always; the order matters once they cannot all be resident)
+  p.n_seqs = desc->B;
+  p.longest_first = lens && desc->B >= 2 && desc->B <= 64 && p.n_items > max_decode_workgroups() &&
+                    trips / splits >= kLongItemTokens / trip;
   const LutChoice& lut = choose_lut_scale(checked.v, 1 << desc->k);
   std::memcpy(p.lut_levels, lut.bits, sizeof(uint16_t) * (1 << desc->k));
   p.inv_gamma = 1.0f / lut.gamma;

@@ -115,6 +115,9 @@ struct MultiParams {
   int table_stride;
   int num_pages;
   int page_shift;
+  // ragged batch, long sequences first: see decode_multi_kernel (seq_lens set, at most 64 sequences)
+  int longest_first;
+  int n_seqs;                // B
 };
 
 // Bytes at the start of the split-K workspace that hold the ticket counters (one uint32 per

@@ -1165,3 +1165,35 @@ def test_varlen_longest_first_dispatch(nqkv, oracle, k, D, blk, B, H):
     ref2 = np.stack([oracle.decode_attention(h2n(q)[b:b + 1], okc[b:b + 1], oks[b:b + 1], ovc[b:b + 1], ovs[b:b + 1],
                                              k, blk, lv, int(lens[b]) + 1, 0.8, n_threads=8)[0] for b in range(B)])
     assert attn_err(h2n(out).view(np.float16), ref2) <= ATTN_TOL
+
+
+@pytest.mark.parametrize("k,D,blk,B,H", [(4, 64, 64, 9, 64), (2, 128, 64, 64, 9)])
+def test_multi_varlen_longest_first_dispatch(nqkv, oracle, k, D, blk, B, H):
+    """The several-queries kernel on a ragged batch whose items are long (>= 4096 tokens) and more
+    than can be resident: the regime in which it hands the longest sequences out first.  Ties and
+    the shortest possible sequence included; contiguous and paged caches; every sequence against
+    the oracle."""
+    S, Q, P = 4352, 3, 256
+    lv, desc, _, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, S, S, seed=500 + B)
+    g = torch.Generator(device="cuda").manual_seed(B)
+    q = (torch.randn(B, H, Q, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+    rng = np.random.default_rng(B)
+    lens = rng.integers(Q, S + 1, B)
+    lens[0] = lens[-1] = 2000
+    lens[1], lens[2] = Q, S
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    assert nqkv.decode_multi_workspace_bytes(desc, S, Q, 0)[1] == 1 and B * H > 512
+    hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+    ref = np.concatenate([oracle.decode_attention_multi(*[a[b:b + 1] for a in hk], k, blk, lv, int(lens[b]), 0.9, n_threads=16)
+                          for b in range(B)], 0)
+    out = nqkv.decode_attention_multi_varlen(desc, lv, q, kc, ks, vc, vs, lens_dev, S, 0.9)
+    torch.cuda.synchronize()
+    assert _multi_err(out, ref) <= ATTN_TOL
+    n_pg = S // P
+    perm = torch.randperm(B * n_pg, generator=torch.Generator().manual_seed(B + 1))
+    table = perm.reshape(B, n_pg).to(torch.int32).cuda()
+    pools = [_scatter_to_pages(t, table, P) for t in (kc, ks, vc, vs)]
+    pdesc = nqkv.make_desc(B, H, D, k, blk, P)
+    out = nqkv.decode_attention_multi_paged(pdesc, lv, q, *pools, table, lens_dev, S, 0.9)
+    torch.cuda.synchronize()
+    assert _multi_err(out, ref) <= ATTN_TOL
