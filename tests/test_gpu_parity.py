@@ -1197,3 +1197,39 @@ def test_multi_varlen_longest_first_dispatch(nqkv, oracle, k, D, blk, B, H):
     out = nqkv.decode_attention_multi_paged(pdesc, lv, q, *pools, table, lens_dev, S, 0.9)
     torch.cuda.synchronize()
     assert _multi_err(out, ref) <= ATTN_TOL
+
+
+def test_quantize_dequantize_random_windows(nqkv, oracle):
+    """Seeded random sweep (30 cases) over code width, head size, batch, token window and source /
+    destination layout: quantize a window of a strided fp16 tensor into the cache at an offset,
+    dequantize another window of the cache into a strided destination; everything bit for bit."""
+    rng = np.random.default_rng(4242)
+    for case in range(30):
+        k, D, blk = COMBOS[int(rng.integers(len(COMBOS)))]
+        B, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        cap = int(rng.integers(1, 700))
+        n = int(rng.integers(1, cap + 1))
+        off = int(rng.integers(0, cap - n + 1))
+        lv = nqkv.build_codebook(k, variant=int(rng.integers(2)))
+        desc = nqkv.make_desc(B, H, D, k, blk, cap)
+        codes, scales = nqkv.alloc_cache(desc)
+        codes.fill_(0)
+        scales.fill_(0)
+        token_major = bool(rng.integers(2))
+        x = rand_kv((B, H, n, D), seed=9000 + case)
+        src = x.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) if token_major else x      # [B,H,n,D] view of [B,n,H,D]
+        nqkv.quantize_kv(desc, lv, src, codes, scales, off)
+        torch.cuda.synchronize()
+        oc, osc = oracle.new_cache(B, H, D, k, blk, cap)
+        oracle.quantize_kv(h2n(x), k, blk, lv, oc, osc, dst_off=off)
+        assert np.array_equal(h2n(codes), oc) and np.array_equal(h2n(scales), osc), ("quantize", case, k, D, blk, B, H, cap, n, off)
+        n2 = int(rng.integers(1, cap + 1))
+        off2 = int(rng.integers(0, cap - n2 + 1))
+        ref = oracle.dequantize_kv(oc, osc, k, blk, lv, off2, n2, n_threads=4)
+        if token_major:
+            out = torch.zeros(B, n2, H, D, dtype=torch.float16, device="cuda").permute(0, 2, 1, 3)
+        else:
+            out = torch.zeros(B, H, n2 + 3, D, dtype=torch.float16, device="cuda")[:, :, 2:2 + n2]
+        nqkv.dequantize_kv(desc, lv, codes, scales, off2, n2, out=out)
+        torch.cuda.synchronize()
+        assert np.array_equal(h2n(out.contiguous()), ref), ("dequantize", case, k, D, blk, B, H, cap, n2, off2)
