@@ -34,8 +34,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--configs", default="C2,C3,C4,C5",
                     help="configurations whose kernels are timed for the `kernels` section")
     ap.add_argument("--sweep", action="store_true", help="C5: also time k in {2,3} and block 128")
