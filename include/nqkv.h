@@ -213,6 +213,28 @@ int nqkv_decode_attention(const nqkv_cache_desc* desc, const float* levels,
                           void* hip_stream);
 
 /*
+ * nqkv_decode_attention for callers that cannot allocate device memory or pass a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors as nqkv_decode_attention (equal bits for equal num_splits), but
+ * the split-K workspace is a fixed array of NQKV_STATIC_SCRATCH_BYTES inside the library's code
+ * object: every GPU the library is used on holds one such array until the process ends.  The call
+ * allocates nothing and frees nothing; it enqueues a small clearing kernel (when the sequence is
+ * cut) and the attention kernel on `hip_stream`.
+ *   - A geometry whose workspace (nqkv_decode_workspace_bytes for the same arguments) exceeds
+ *     NQKV_STATIC_SCRATCH_BYTES is refused with NQKV_EWORKSPACE before any GPU work.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race on it and give undefined results; serialise them.
+ *   - A failed address look-up of the array returns NQKV_EHIP.
+ */
+#define NQKV_STATIC_SCRATCH_BYTES (2u << 20)
+int nqkv_decode_attention_static(const nqkv_cache_desc* desc, const float* levels,
+                                 const void* q,
+                                 const void* k_codes, const void* k_scales,
+                                 const void* v_codes, const void* v_scales,
+                                 int64_t seq_len, float softmax_scale, void* out,
+                                 int num_splits, void* hip_stream);
+
+/*
  * One whole decode step of Sec. 3.2 in a single launch: quantize the new token's key and value
  * (I_tK = quantize(t_K), I_tV = quantize(t_V)), append their indices at cache row `pos`
  * (I <- Concat(I, I_t)), and attend over rows [0, pos] -- the appended token included.

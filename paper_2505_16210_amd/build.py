@@ -23,6 +23,7 @@ SOURCES = [
     ("decode_attention.hip", []),
     ("decode_multi.hip", []),
     ("stream_probe.hip", []),
+    ("static_scratch.hip", []),
 ]
 
 

@@ -489,7 +489,8 @@ static int decode_impl(const nqkv_cache_desc* desc, const float* levels, const v
                        const int32_t* lens,
                        const void* k_codes, const void* k_scales, const void* v_codes, const void* v_scales,
                        int64_t seq_len, float softmax_scale, void* out,
-                       void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream) {
+                       void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream,
+                       bool static_workspace = false) {
   int rc = check_desc(desc);
   if (rc) return rc;
   const bool fuse = k_new != nullptr;
@@ -517,13 +518,19 @@ static int decode_impl(const nqkv_cache_desc* desc, const float* levels, const v
     if (new_stride_b < 0 || new_stride_h < 0 || (new_stride_b % 8) || (new_stride_h % 8)) return NQKV_EINVAL;
   }
   const size_t need = workspace_need(desc, splits);
-  if (need > 0) {
+  if (static_workspace) {
+    if (need > kStaticScratchBytes) return NQKV_EWORKSPACE;       // refused before anything touches the GPU
+  } else if (need > 0) {
     if (!workspace || !aligned16(workspace)) return NQKV_EINVAL;
     if (workspace_bytes < need) return NQKV_EWORKSPACE;
   }
   // one item's byte range is addressed with 32-bit offsets
   if ((n_cached / splits + 1) * (int64_t)(desc->D * desc->k / 8) >= ((int64_t)1 << 31)) return NQKV_EUNSUPPORTED;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (static_workspace && need > 0) {
+    // the library's own array on the current device, by its device address
+    if (static_scratch(&workspace) != hipSuccess) return NQKV_EHIP;
+  }
   if (fuse && !build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) {
     // a table the in-kernel code search cannot take: append with the quantizer, then attend
     if (lens) return NQKV_EUNSUPPORTED;        // (the quantizer appends at one row for the whole batch)
@@ -542,6 +549,8 @@ static int decode_impl(const nqkv_cache_desc* desc, const float* levels, const v
   p.seq_lens = lens;                                    // fused: lens[b] = cached rows = the new token's row
   p.max_len = (int)n_cached;
   p.longest_first = longest_first_pays(p, lens, desc->B);
+  // The array keeps whatever the last call on this GPU left in it: clear the counters this call uses.
+  if (static_workspace && splits > 1 && launch_clear_words(p.tickets, desc->B * desc->H, stream) != hipSuccess) return NQKV_EHIP;
   const hipError_t e = launch_decode_attention(p, desc->D, desc->k, desc->block, fuse, stream);
   return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
 }
@@ -555,6 +564,17 @@ int nqkv_decode_attention(const nqkv_cache_desc* desc, const float* levels,
                           void* hip_stream) {
   return decode_impl(desc, levels, q, nullptr, nullptr, 0, 0, nullptr, k_codes, k_scales, v_codes, v_scales, seq_len,
                      softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
+}
+
+int nqkv_decode_attention_static(const nqkv_cache_desc* desc, const float* levels,
+                                 const void* q,
+                                 const void* k_codes, const void* k_scales,
+                                 const void* v_codes, const void* v_scales,
+                                 int64_t seq_len, float softmax_scale, void* out,
+                                 int num_splits, void* hip_stream) {
+  static_assert(NQKV_STATIC_SCRATCH_BYTES == kStaticScratchBytes, "header and library disagree on the array size");
+  return decode_impl(desc, levels, q, nullptr, nullptr, 0, 0, nullptr, k_codes, k_scales, v_codes, v_scales, seq_len,
+                     softmax_scale, out, nullptr, 0, num_splits, hip_stream, true);
 }
 
 int nqkv_decode_step(const nqkv_cache_desc* desc, const float* levels,

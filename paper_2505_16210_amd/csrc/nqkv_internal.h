@@ -124,6 +124,14 @@ struct MultiParams {
 // (b,h), room for the largest supported B*H), before the partial results.
 constexpr size_t kTicketBytes = 65536 * sizeof(uint32_t);
 
+// Size of the library-owned scratch array behind nqkv_decode_attention_static (per GPU, held until
+// the process ends): the ticket counters plus room for 3528 partial results at head size 128.
+constexpr size_t kStaticScratchBytes = 2u << 20;
+// Device address of that array on the current device (looked up once per device).
+hipError_t static_scratch(void** ptr_out);
+// Zero-fills n 32-bit words with a small kernel (safe to record into a HIP graph).
+hipError_t launch_clear_words(uint32_t* words, int n, hipStream_t stream);
+
 // Each returns hipSuccess or the launch error.  D in {64,128}, k in {2,3,4}, blk in {64,128}.
 hipError_t launch_quantize(const QuantParams& p, int D, int k, int blk, hipStream_t stream);
 hipError_t launch_dequantize(const QuantParams& p, int D, int k, int blk, hipStream_t stream);

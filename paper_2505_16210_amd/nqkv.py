@@ -21,6 +21,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_set_tuning", "nqkv_build_codebook",
            "nqkv_quantize_kv", "nqkv_quantize_kv_pair", "nqkv_dequantize_kv",
            "nqkv_decode_workspace_bytes", "nqkv_decode_attention", "nqkv_decode_step",
+           "nqkv_decode_attention_static",
            "nqkv_probe_read_stream", "nqkv_quantize_kv_hidden",
            "nqkv_decode_multi_workspace_bytes", "nqkv_decode_attention_multi", "nqkv_decode_attention_multi_varlen",
            "nqkv_decode_multi_paged_workspace_bytes", "nqkv_decode_attention_multi_paged",
@@ -88,6 +89,8 @@ def _load() -> ctypes.CDLL:
     lib.nqkv_decode_attention.restype = i32
     lib.nqkv_decode_attention.argtypes = [dp, fp, vp, vp, vp, vp, vp, i64, c.c_float, vp, vp,
                                           c.c_size_t, i32, vp]
+    lib.nqkv_decode_attention_static.restype = i32
+    lib.nqkv_decode_attention_static.argtypes = [dp, fp, vp, vp, vp, vp, vp, i64, c.c_float, vp, i32, vp]
     lib.nqkv_decode_step.restype = i32
     lib.nqkv_decode_step.argtypes = [dp, fp, vp, vp, vp, i64, i64, vp, vp, vp, vp, i64, c.c_float, vp, vp,
                                      c.c_size_t, i32, vp]
@@ -269,6 +272,25 @@ def decode_attention(desc: CacheDesc, levels, q: torch.Tensor, k_codes, k_scales
                                    _dev_ptr(v_codes), _dev_ptr(v_scales), seq_len, float(softmax_scale),
                                    _dev_ptr(out), _dev_ptr(workspace), ws_bytes, num_splits, _stream(stream))
     _check(rc, "nqkv_decode_attention")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 2 << 20
+
+
+def decode_attention_static(desc: CacheDesc, levels, q: torch.Tensor, k_codes, k_scales, v_codes, v_scales,
+                            seq_len: int, softmax_scale: float = 1.0, out: torch.Tensor | None = None,
+                            num_splits: int = 0, stream=None) -> torch.Tensor:
+    """nqkv_decode_attention_static: as decode_attention, the workspace being the library's own fixed
+    array (no allocation inside the call; pass `out` to keep this wrapper from allocating either)."""
+    lv, lvp = _levels_ptr(levels)
+    assert q.dtype == torch.float16 and q.is_contiguous()
+    if out is None:
+        out = torch.empty_like(q)
+    rc = lib.nqkv_decode_attention_static(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_codes), _dev_ptr(k_scales),
+                                          _dev_ptr(v_codes), _dev_ptr(v_scales), seq_len, float(softmax_scale),
+                                          _dev_ptr(out), num_splits, _stream(stream))
+    _check(rc, "nqkv_decode_attention_static")
     return out
 
 

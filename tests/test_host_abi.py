@@ -183,6 +183,31 @@ def test_decode_argument_errors(nqkv):
     assert call(levels=None) == nqkv.EINVAL
 
 
+def test_decode_static_argument_errors(nqkv):
+    """The entry point without a workspace argument: every refusal comes before any GPU call, the
+    size limit of its fixed array included."""
+    lv, lvp = _levels(nqkv)
+    d = nqkv.make_desc(1, 32, 128, 4, 64, 32768)
+    f = nqkv.lib.nqkv_decode_attention_static
+
+    def call(q=FAKE, kc=FAKE, ks=FAKE, vc=FAKE, vs=FAKE, seq=32768, scale=1.0, out=FAKE, ns=0, desc=d, levels=lvp):
+        return f(ctypes.byref(desc), levels, q, kc, ks, vc, vs, seq, scale, out, ns, None)
+
+    assert call(q=None) == nqkv.EINVAL
+    assert call(out=FAKE + 4) == nqkv.EINVAL
+    assert call(seq=0) == nqkv.EINVAL
+    assert call(ns=2000) == nqkv.EINVAL
+    assert call(levels=None) == nqkv.EINVAL
+    assert call(desc=nqkv.make_desc(1, 32, 96, 4, 64, 32768)) == nqkv.EUNSUPPORTED
+    # 32 sequences x 1024 pieces x 130 floats + counters > 2 MiB
+    assert nqkv.decode_workspace_bytes(d, 32768, 1024)[0] > nqkv.STATIC_SCRATCH_BYTES
+    assert call(ns=1024) == nqkv.EWORKSPACE
+    big = nqkv.make_desc(64, 64, 128, 4, 64, 4096)
+    assert call(desc=big, seq=4096, ns=8) == nqkv.EWORKSPACE
+    header = open(os.path.join(ROOT, "include", "nqkv.h")).read()
+    assert "#define NQKV_STATIC_SCRATCH_BYTES (2u << 20)" in header and nqkv.STATIC_SCRATCH_BYTES == 2 << 20
+
+
 def test_decode_step_argument_errors(nqkv):
     lv, lvp = _levels(nqkv)
     d = nqkv.make_desc(1, 32, 128, 4, 64, 32768)
