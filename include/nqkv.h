@@ -26,7 +26,7 @@
  *     call that returns an error other than NQKV_EHIP has launched nothing.
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
  *     ordinary memory.  The library allocates no device memory and keeps no state between
- *     calls (nqkv_set_tuning aside).  Device pointers must be 16-byte aligned.
+ *     calls.  Device pointers must be 16-byte aligned.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work on that stream and return; they never synchronise.
  *   - fp16 means IEEE binary16.  Inputs must be finite (not checked).
@@ -73,16 +73,17 @@ const char* nqkv_strerror(int status);
 int nqkv_version(void);
 
 /*
- * Experiment switches for benchmarking, process-wide, not thread-safe: set them while no call
- * is in flight.  They never change results (codes stay bit-identical, attention stays within
- * its tolerance), only which kernel variant or launch shape is used.
- *   knob 0  quantizer: 0 = cell-table code search (default), 1 = plain scan of all thresholds
- *   knob 1  decode attention: workgroups aimed for when num_splits == 0 (0 = default)
- *   knob 2  decode attention: upper limit of the grid in workgroups (0 = default: a persistent
- *           grid of two per compute unit, or one per work item when items are 4096 tokens or longer)
- * Returns NQKV_EINVAL for an unknown knob or value.
+ * Per-call options, OR-ed into nqkv_cache_desc.flags.  They never change results (codes stay
+ * bit-identical, attention stays within its tolerance), only which kernel variant or launch
+ * shape a call uses; they exist for A/B measurements and for tests that must reach both
+ * variants.  The library itself holds no settings.
  */
-int nqkv_set_tuning(int knob, int value);
+enum {
+  NQKV_FLAG_SCAN_QUANTIZER = 1,      /* quantizer: plain scan of all thresholds instead of the
+                                        cell-table code search                                   */
+  NQKV_FLAG_WORKGROUP_PER_ITEM = 2   /* decode attention: one workgroup per work item whatever
+                                        its length, instead of a persistent grid for short items */
+};
 
 /*
  * Quantile table (Sec. 1: "quantile points from a normal distribution as data points").
@@ -106,7 +107,7 @@ typedef struct nqkv_cache_desc {
   int32_t D;           /* head dimension: 64 or 128                                          */
   int32_t k;           /* bits per index: 2, 3 or 4                                          */
   int32_t block;       /* elements per scale: 64 or 128, must divide D                       */
-  int32_t reserved;    /* must be 0                                                          */
+  int32_t flags;       /* 0, or NQKV_FLAG_* values OR-ed together                            */
   int64_t cap_tokens;  /* token capacity of the codes / scales arrays, >= 1                  */
 } nqkv_cache_desc;
 
@@ -426,17 +427,6 @@ int nqkv_decode_attention_multi_paged(const nqkv_cache_desc* desc, const float* 
                                       const int32_t* block_table, int64_t table_stride, int64_t num_pages,
                                       const int32_t* seq_lens, int64_t max_seq_len, int q_len, float softmax_scale, void* out,
                                       void* workspace, size_t workspace_bytes, int num_splits, void* hip_stream);
-
-/*
- * Measurement helper, not part of the method: reads `bytes` (a multiple of 16) of device memory
- * at `src` once, with plain 128-bit loads, and writes one 32-bit xor checksum per workgroup to
- * `checksums` (device, NQKV_PROBE_WORKGROUPS uint32).  Timed by a benchmark it gives the read
- * bandwidth this machine delivers to the simplest possible kernel, the yardstick beside the
- * published peak; the xor of all checksums equals the xor of all 32-bit words of the buffer.
- * Errors: NQKV_EINVAL for null / misaligned pointers or bytes % 16 != 0.
- */
-#define NQKV_PROBE_WORKGROUPS 4096
-int nqkv_probe_read_stream(const void* src, size_t bytes, void* checksums, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -1,4 +1,5 @@
-"""Builds libnqkv.so (the C-ABI library with the gfx950 kernels) in-tree with hipcc."""
+"""Builds libnqkv.so (the C-ABI library with the gfx950 kernels) and libnqkv_benchaux.so (the
+benchmark's measurement helpers) in-tree with hipcc."""
 from __future__ import annotations
 
 import os
@@ -22,9 +23,10 @@ SOURCES = [
     ("dequantize.hip", ["-ffp-contract=off"]),
     ("decode_attention.hip", []),
     ("decode_multi.hip", []),
-    ("stream_probe.hip", []),
     ("static_scratch.hip", []),
 ]
+AUX_LIB = os.path.join(HERE, "libnqkv_benchaux.so")
+AUX_SOURCES = [("bench_aux.hip", [])]
 
 
 def _compile(src: str, extra: list, verbose: bool, save_temps: bool) -> str:
@@ -50,13 +52,14 @@ def build_library(verbose: bool = False, save_temps: bool = False, jobs: int = 4
     # each a few hundred MB)
     from concurrent.futures import ThreadPoolExecutor
     with ThreadPoolExecutor(max_workers=max(1, jobs)) as pool:
-        objs = list(pool.map(lambda se: _compile(se[0], se[1], verbose, save_temps), SOURCES))
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objs]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + r.stderr)
-    os.replace(tmp, LIB)
+        objs = list(pool.map(lambda se: _compile(se[0], se[1], verbose, save_temps), SOURCES + AUX_SOURCES))
+    for lib, lib_objs in ((LIB, objs[:len(SOURCES)]), (AUX_LIB, objs[len(SOURCES):])):
+        tmp = lib + ".tmp.%d" % os.getpid()
+        cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *lib_objs]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + r.stderr)
+        os.replace(tmp, lib)
     return LIB
 
 

@@ -5,6 +5,7 @@
 #include "nqkv_internal.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 
@@ -12,18 +13,14 @@ namespace {
 
 using namespace nqkv;
 
-// Experiment switches (see nqkv_set_tuning).  Plain ints: set them before issuing work.
-int g_quantize_impl = 0;       // 0 cell table, 1 threshold scan
-int g_decode_target_wgs = 0;   // 0 = default
-int g_decode_grid_limit = 0;   // 0 = default (see fill_decode_common); > 0 = at most this many workgroups
-
 constexpr int64_t kLongItemTokens = 4096;   // see fill_decode_common
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int check_desc(const nqkv_cache_desc* d) {
   if (!d) return NQKV_EINVAL;
-  if (d->B < 1 || d->H < 1 || d->cap_tokens < 1 || d->reserved != 0) return NQKV_EINVAL;
+  if (d->B < 1 || d->H < 1 || d->cap_tokens < 1) return NQKV_EINVAL;
+  if (d->flags & ~(int32_t)(NQKV_FLAG_SCAN_QUANTIZER | NQKV_FLAG_WORKGROUP_PER_ITEM)) return NQKV_EINVAL;
   if (d->D < 1 || d->k < 1 || d->block < 1) return NQKV_EINVAL;
   if (d->k != 2 && d->k != 3 && d->k != 4) return NQKV_EUNSUPPORTED;
   if (d->D != 64 && d->D != 128) return NQKV_EUNSUPPORTED;
@@ -145,16 +142,19 @@ size_t workspace_need(const nqkv_cache_desc* d, int splits) {
 }
 
 // Persistent grid size: two eight-wave workgroups fit on a compute unit (64 KiB table each).
+// The compute-unit count is asked of the current device once and remembered per device index
+// (a constant of the hardware, not a setting: racing first calls store the same number).
 int max_decode_workgroups() {
-  static int cached = 0;
-  if (cached == 0) {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-      cus = 256;
-    cached = 2 * cus;
+  constexpr int kMaxDevices = 64;
+  static std::atomic<int> cus_of_device[kMaxDevices];
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 2 * 256;
+  cus = cus_of_device[dev].load(std::memory_order_relaxed);
+  if (cus == 0) {
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    cus_of_device[dev].store(cus, std::memory_order_relaxed);
   }
-  return cached;
+  return 2 * cus;
 }
 
 int plan_splits(const nqkv_cache_desc* d, int64_t seq_len, int num_splits, int* splits) {
@@ -170,7 +170,7 @@ int plan_splits(const nqkv_cache_desc* d, int64_t seq_len, int num_splits, int* 
   // about one item per compute unit when B*H alone does not, and no cut otherwise.  Never cut
   // below one trip of one wave.
   const int64_t bh = (int64_t)d->B * d->H;
-  const int64_t target = g_decode_target_wgs > 0 ? g_decode_target_wgs : 256;
+  const int64_t target = 256;
   const int64_t trip = (int64_t)decode_chunk_tokens(d->D);
   int64_t want = target / bh;
   int64_t longest = seq_len / trip;
@@ -196,7 +196,7 @@ int plan_multi(const nqkv_cache_desc* d, int64_t seq_len, int64_t max_tokens, in
     return NQKV_OK;
   }
   const int64_t bh = (int64_t)d->B * d->H;
-  const int64_t target = g_decode_target_wgs > 0 ? g_decode_target_wgs : (int64_t)max_decode_workgroups() / 2;
+  const int64_t target = (int64_t)max_decode_workgroups() / 2;
   int64_t want = target / bh;
   const int64_t longest = seq_len / decode_multi_item_tokens();
   if (want > longest) want = longest;
@@ -227,15 +227,6 @@ const char* nqkv_strerror(int status) {
 }
 
 int nqkv_version(void) { return 100; }
-
-int nqkv_set_tuning(int knob, int value) {
-  switch (knob) {
-    case 0: if (value != 0 && value != 1) return NQKV_EINVAL; g_quantize_impl = value; return NQKV_OK;
-    case 1: if (value < 0 || value > 65536) return NQKV_EINVAL; g_decode_target_wgs = value; return NQKV_OK;
-    case 2: if (value < 0) return NQKV_EINVAL; g_decode_grid_limit = value; return NQKV_OK;
-    default: return NQKV_EINVAL;
-  }
-}
 
 int nqkv_build_codebook(int k, int variant, float* levels_out) {
   if (k < 1 || k > 8 || !levels_out) return NQKV_EINVAL;
@@ -310,7 +301,7 @@ static int quantize_pair_impl(const nqkv_cache_desc* desc, const float* levels,
   p.tok_offs = offsets;
   p.max_off = (int)std::min<int64_t>(dst_token_offset, ((int64_t)1 << 31) - 1);
   p.cap_tokens = desc->cap_tokens;
-  p.impl = (g_quantize_impl == 0 && build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) ? 0 : 1;
+  p.impl = (!(desc->flags & NQKV_FLAG_SCAN_QUANTIZER) && build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) ? 0 : 1;
   const hipError_t e = launch_quantize(p, desc->D, desc->k, desc->block, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
 }
@@ -393,7 +384,7 @@ int nqkv_quantize_kv_hidden(const nqkv_cache_desc* desc, const float* levels,
   p.n_tokens = n_tokens;
   p.tok_off = dst_token_offset;
   p.cap_tokens = desc->cap_tokens;
-  p.impl = (g_quantize_impl == 0 && build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) ? 0 : 1;
+  p.impl = (!(desc->flags & NQKV_FLAG_SCAN_QUANTIZER) && build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) ? 0 : 1;
   const hipError_t e = launch_quantize_hidden(p, desc->D, desc->k, block_hidden, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
 }
@@ -468,8 +459,8 @@ static void fill_decode_common(DecodeParams* p, const nqkv_cache_desc* desc, con
   // serves several items); long items get a workgroup each, which the dispatcher hands out as
   // earlier ones finish -- with more items than resident workgroups that balances better than a
   // fixed deal (measured: 896 items of 16384 tokens 332 -> 319 us; 8192 items of 128 tokens 52 -> 65 us).
-  p->max_workgroups = g_decode_grid_limit > 0 ? g_decode_grid_limit
-                      : item_tokens >= kLongItemTokens ? p->n_items : max_decode_workgroups();
+  p->max_workgroups = ((desc->flags & NQKV_FLAG_WORKGROUP_PER_ITEM) || item_tokens >= kLongItemTokens)
+                          ? p->n_items : max_decode_workgroups();
   p->n_seqs = desc->B;
   p->cap_tokens = desc->cap_tokens;
   const LutChoice& lut = choose_lut_scale(checked.v, 1 << desc->k);
@@ -629,7 +620,7 @@ static int plan_paged(const nqkv_cache_desc* desc, int64_t n_cached, PagedPlan* 
   while (((int64_t)1 << shift) < P) ++shift;
   const int64_t pages = n_cached <= 0 ? 1 : (n_cached + P - 1) / P;
   const int64_t bh = (int64_t)desc->B * desc->H;
-  const int64_t target = g_decode_target_wgs > 0 ? g_decode_target_wgs : 256;
+  const int64_t target = 256;
   int64_t want = target / bh;
   if (want > pages) want = pages;
   if (want > 1024) want = 1024;
@@ -753,7 +744,7 @@ static int quantize_paged_impl(const nqkv_cache_desc* desc, const float* levels,
   p.tok_offs = offsets;
   p.max_off = (int)dst_token_offset;                   // (< 2^31 by the check above)
   p.cap_tokens = P;
-  p.impl = (g_quantize_impl == 0 && build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) ? 0 : 1;
+  p.impl = (!(desc->flags & NQKV_FLAG_SCAN_QUANTIZER) && build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) ? 0 : 1;
   p.block_table = block_table;
   p.table_stride = (int)table_stride;
   p.num_pages = (int)num_pages;
@@ -931,13 +922,6 @@ int nqkv_decode_attention_multi_paged(const nqkv_cache_desc* desc, const float* 
   if (!seq_lens || (reinterpret_cast<uintptr_t>(seq_lens) & 3u) || !block_table) return NQKV_EINVAL;
   return decode_multi_impl(desc, levels, q, k_codes, k_scales, v_codes, v_scales, block_table, table_stride, num_pages,
                            seq_lens, max_seq_len, q_len, softmax_scale, out, workspace, workspace_bytes, num_splits, hip_stream);
-}
-
-int nqkv_probe_read_stream(const void* src, size_t bytes, void* checksums, void* hip_stream) {
-  if (!src || !checksums || !aligned16(src) || !aligned16(checksums) || (bytes % 16) != 0) return NQKV_EINVAL;
-  const hipError_t e = launch_read_stream(src, bytes, static_cast<uint32_t*>(checksums), NQKV_PROBE_WORKGROUPS,
-                                          static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
 }
 
 }  // extern "C"

@@ -147,10 +147,6 @@ hipError_t launch_decode_attention_multi(const MultiParams& p, int D, int k, int
 int decode_multi_trip_tokens();    // split boundaries of that kernel are multiples of this
 int decode_multi_item_tokens();    // tokens one workgroup of it consumes per sweep of its waves
 
-// Measurement helper: xor checksum per workgroup of a plain 128-bit read stream over `bytes`
-// (a multiple of 16) of device memory.
-hipError_t launch_read_stream(const void* src, uint64_t bytes, uint32_t* checksums, int workgroups, hipStream_t stream);
-
 // Tokens one wave of the attention kernel consumes per main-loop trip; split boundaries are
 // multiples of this.
 int decode_chunk_tokens(int D);

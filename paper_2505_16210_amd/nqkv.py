@@ -18,11 +18,11 @@ LIB_PATH = os.path.join(_HERE, "libnqkv.so")
 
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 
-EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_set_tuning", "nqkv_build_codebook",
+EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_build_codebook",
            "nqkv_quantize_kv", "nqkv_quantize_kv_pair", "nqkv_dequantize_kv",
            "nqkv_decode_workspace_bytes", "nqkv_decode_attention", "nqkv_decode_step",
            "nqkv_decode_attention_static",
-           "nqkv_probe_read_stream", "nqkv_quantize_kv_hidden",
+           "nqkv_quantize_kv_hidden",
            "nqkv_decode_multi_workspace_bytes", "nqkv_decode_attention_multi", "nqkv_decode_attention_multi_varlen",
            "nqkv_decode_multi_paged_workspace_bytes", "nqkv_decode_attention_multi_paged",
            "nqkv_quantize_kv_pair_varlen", "nqkv_quantize_kv_paged_varlen",
@@ -34,7 +34,7 @@ EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_set_tuning", "nqkv_build_codeb
 class CacheDesc(ctypes.Structure):
     """Mirror of nqkv_cache_desc."""
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("D", ctypes.c_int32),
-                ("k", ctypes.c_int32), ("block", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("k", ctypes.c_int32), ("block", ctypes.c_int32), ("flags", ctypes.c_int32),
                 ("cap_tokens", ctypes.c_int64)]
 
 
@@ -56,8 +56,6 @@ def _load() -> ctypes.CDLL:
     lib.nqkv_strerror.restype = c.c_char_p
     lib.nqkv_strerror.argtypes = [i32]
     lib.nqkv_version.restype = i32
-    lib.nqkv_set_tuning.restype = i32
-    lib.nqkv_set_tuning.argtypes = [i32, i32]
     lib.nqkv_build_codebook.restype = i32
     lib.nqkv_build_codebook.argtypes = [i32, i32, fp]
     lib.nqkv_quantize_kv.restype = i32
@@ -112,8 +110,6 @@ def _load() -> ctypes.CDLL:
                                            c.c_float, vp, vp, c.c_size_t, vp]
     lib.nqkv_quantize_kv_hidden.restype = i32
     lib.nqkv_quantize_kv_hidden.argtypes = [dp, fp, vp, vp, i64, i64, i64, i64, i64, i32, vp, vp, vp, vp, vp]
-    lib.nqkv_probe_read_stream.restype = i32
-    lib.nqkv_probe_read_stream.argtypes = [vp, c.c_size_t, vp, vp]
     return lib
 
 
@@ -126,12 +122,6 @@ def strerror(status: int) -> str:
 
 def version() -> int:
     return int(lib.nqkv_version())
-
-
-def set_tuning(knob: int, value: int) -> None:
-    rc = lib.nqkv_set_tuning(knob, value)
-    if rc:
-        raise NqkvError(rc, "nqkv_set_tuning")
 
 
 def _check(rc: int, where: str) -> None:
@@ -162,8 +152,11 @@ def build_codebook(k: int, variant: int = 0) -> np.ndarray:
     return out
 
 
-def make_desc(B: int, H: int, D: int, k: int, block: int, cap_tokens: int) -> CacheDesc:
-    return CacheDesc(B, H, D, k, block, 0, cap_tokens)
+FLAG_SCAN_QUANTIZER, FLAG_WORKGROUP_PER_ITEM = 1, 2
+
+
+def make_desc(B: int, H: int, D: int, k: int, block: int, cap_tokens: int, flags: int = 0) -> CacheDesc:
+    return CacheDesc(B, H, D, k, block, flags, cap_tokens)
 
 
 def alloc_cache(desc: CacheDesc, device="cuda"):
@@ -574,18 +567,3 @@ def decode_step_paged(desc: CacheDesc, levels, q, k_new, v_new, k_codes, k_scale
                                     _dev_ptr(workspace), ws_bytes, _stream(stream))
     _check(rc, "nqkv_decode_step_paged")
     return out
-
-
-PROBE_WORKGROUPS = 4096
-
-
-def probe_read_stream(src: torch.Tensor, checksums: torch.Tensor | None = None, stream=None) -> torch.Tensor:
-    """nqkv_probe_read_stream: one plain read pass over `src` (contiguous, bytes % 16 == 0) ->
-    int32 [PROBE_WORKGROUPS] xor checksums (device)."""
-    assert src.is_contiguous()
-    if checksums is None:
-        checksums = torch.empty(PROBE_WORKGROUPS, dtype=torch.int32, device=src.device)
-    rc = lib.nqkv_probe_read_stream(_dev_ptr(src), src.numel() * src.element_size(), _dev_ptr(checksums),
-                                    _stream(stream))
-    _check(rc, "nqkv_probe_read_stream")
-    return checksums

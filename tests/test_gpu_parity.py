@@ -57,12 +57,9 @@ def test_quantize_bit_exact(nqkv, oracle, k, D, blk, impl):
     x = rand_kv((B, H, n, D), seed=100 * k + D + blk)
     desc = nqkv.make_desc(B, H, D, k, blk, cap)
     codes, scales = nqkv.alloc_cache(desc)
-    nqkv.set_tuning(0, impl)
-    try:
-        nqkv.quantize_kv(desc, lv, x, codes, scales, dst_token_offset=off)
-        torch.cuda.synchronize()
-    finally:
-        nqkv.set_tuning(0, 0)
+    desc_impl = nqkv.make_desc(desc.B, desc.H, desc.D, desc.k, desc.block, desc.cap_tokens, flags=impl)   # impl 1 = NQKV_FLAG_SCAN_QUANTIZER
+    nqkv.quantize_kv(desc_impl, lv, x, codes, scales, dst_token_offset=off)
+    torch.cuda.synchronize()
     rc, rs = oracle.new_cache(B, H, D, k, blk, cap)
     oracle.quantize_kv(h2n(x), k, blk, lv, rc, rs, dst_off=off, n_threads=8)
     assert np.array_equal(h2n(scales), rs)
@@ -101,12 +98,9 @@ def test_quantize_edge_values_bit_exact(nqkv, oracle, k, D, blk, variant):
     desc = nqkv.make_desc(1, 2, D, k, blk, n)
     for impl in (0, 1):
         codes, scales = nqkv.alloc_cache(desc)
-        nqkv.set_tuning(0, impl)
-        try:
-            nqkv.quantize_kv(desc, lv, xt, codes, scales)
-            torch.cuda.synchronize()
-        finally:
-            nqkv.set_tuning(0, 0)
+        desc_impl = nqkv.make_desc(desc.B, desc.H, desc.D, desc.k, desc.block, desc.cap_tokens, flags=impl)   # impl 1 = NQKV_FLAG_SCAN_QUANTIZER
+        nqkv.quantize_kv(desc_impl, lv, xt, codes, scales)
+        torch.cuda.synchronize()
         rc, rs = oracle.new_cache(1, 2, D, k, blk, n)
         oracle.quantize_kv(x16, k, blk, lv, rc, rs)
         assert np.array_equal(h2n(scales), rs)
@@ -393,14 +387,19 @@ def test_decode_step_fused_loop_equals_two_launch_loop(nqkv, oracle):
 
 # --------------------------------------------------------------------------- measurement helper
 @pytest.mark.parametrize("n_bytes", [16, 16 * 1000 + 16, 64 << 20])
-def test_probe_read_stream_reads_every_word_once(nqkv, n_bytes):
+def test_benchaux_read_stream_reads_every_word_once_and_copy_copies(n_bytes):
+    from paper_2505_16210_amd import benchaux
     g = torch.Generator(device="cuda").manual_seed(n_bytes % 1000)
     x = torch.randint(-2**31, 2**31 - 1, (n_bytes // 4,), device="cuda", dtype=torch.int32, generator=g)
-    sums = nqkv.probe_read_stream(x)
+    sums = benchaux.read_stream(x)
+    y = torch.zeros_like(x)
+    benchaux.copy(y, x)
+    benchaux.empty_launch()
     torch.cuda.synchronize()
     got = np.bitwise_xor.reduce(sums.cpu().numpy().view(np.uint32))
     want = np.bitwise_xor.reduce(x.cpu().numpy().view(np.uint32))
     assert got == want
+    assert torch.equal(x, y)
 
 
 # --------------------------------------------------------------------------- the paper's own flow
@@ -445,12 +444,9 @@ def test_quantize_hidden_blocks_bit_exact(nqkv, oracle, k, D, H, blk_hidden, imp
     desc = nqkv.make_desc(B, H, D, k, D, cap)
     kc, ks = nqkv.alloc_cache(desc)
     vc, vs = nqkv.alloc_cache(desc)
-    nqkv.set_tuning(0, impl)
-    try:
-        nqkv.quantize_kv_hidden(desc, lv, Kv, Vv, kc, ks, vc, vs, off, blk_hidden)
-        torch.cuda.synchronize()
-    finally:
-        nqkv.set_tuning(0, 0)
+    desc_impl = nqkv.make_desc(desc.B, desc.H, desc.D, desc.k, desc.block, desc.cap_tokens, flags=impl)   # impl 1 = NQKV_FLAG_SCAN_QUANTIZER
+    nqkv.quantize_kv_hidden(desc_impl, lv, Kv, Vv, kc, ks, vc, vs, off, blk_hidden)
+    torch.cuda.synchronize()
     for src, codes, scales in ((Kv, kc, ks), (Vv, vc, vs)):
         rc, rs = oracle.new_cache(B, H, D, k, D, cap)
         oracle.quantize_kv_hidden(h2n(src), k, blk_hidden, lv, rc, rs, dst_off=off, n_threads=8)
@@ -708,13 +704,10 @@ def test_quantize_paged_bit_exact(nqkv, oracle, k, D, blk, P, impl):
     vcp, vsp = nqkv.alloc_paged_pool(pdesc, num_pages)
     for t in (kcp, vcp):
         t.fill_(0xAB)                                      # untouched rows must keep this
-    nqkv.set_tuning(0, impl)
-    try:
-        nqkv.quantize_kv_paged(pdesc, lv, Kv[:, :, :n1], Vv[:, :, :n1], kcp, ksp, vcp, vsp, table, 0)
-        nqkv.quantize_kv_paged(pdesc, lv, Kv[:, :, n1:n1 + n2], Vv[:, :, n1:n1 + n2], kcp, ksp, vcp, vsp, table, n1)
-        torch.cuda.synchronize()
-    finally:
-        nqkv.set_tuning(0, 0)
+    pdesc_impl = nqkv.make_desc(pdesc.B, pdesc.H, pdesc.D, pdesc.k, pdesc.block, pdesc.cap_tokens, flags=impl)   # impl 1 = NQKV_FLAG_SCAN_QUANTIZER
+    nqkv.quantize_kv_paged(pdesc_impl, lv, Kv[:, :, :n1], Vv[:, :, :n1], kcp, ksp, vcp, vsp, table, 0)
+    nqkv.quantize_kv_paged(pdesc_impl, lv, Kv[:, :, n1:n1 + n2], Vv[:, :, n1:n1 + n2], kcp, ksp, vcp, vsp, table, n1)
+    torch.cuda.synchronize()
     n = n1 + n2
     okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
     ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
@@ -909,12 +902,9 @@ def test_quantize_pair_varlen_bit_exact(nqkv, oracle, k, D, blk, n, impl):
     max_off = cap - n
     offs = [0, 37, 512, max_off]
     offs_dev = torch.tensor(offs, dtype=torch.int32, device="cuda")
-    nqkv.set_tuning(0, impl)
-    try:
-        nqkv.quantize_kv_pair_varlen(desc, lv, Kv, Vv, kc, ks, vc, vs, offs_dev, max_off)
-        torch.cuda.synchronize()
-    finally:
-        nqkv.set_tuning(0, 0)
+    desc_impl = nqkv.make_desc(desc.B, desc.H, desc.D, desc.k, desc.block, desc.cap_tokens, flags=impl)   # impl 1 = NQKV_FLAG_SCAN_QUANTIZER
+    nqkv.quantize_kv_pair_varlen(desc_impl, lv, Kv, Vv, kc, ks, vc, vs, offs_dev, max_off)
+    torch.cuda.synchronize()
     okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
     ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
     okc[:] = 0xAB
@@ -1120,41 +1110,39 @@ def test_varlen_longest_first_dispatch(nqkv, oracle, k, D, blk, B, H):
         if lens[b]:
             ref[b] = oracle.decode_attention(*[a[b:b + 1] for a in hk], k, blk, lv, int(lens[b]), 0.8, n_threads=8)[0]
     live = lens > 0
-    nqkv.set_tuning(2, 1 << 20)                   # one workgroup per item whatever the item length
-    try:
-        for ns in (1, 2):
-            out = nqkv.decode_attention_varlen(desc, lv, q, kc, ks, vc, vs, lens_dev, S, 0.8, num_splits=ns)
-            torch.cuda.synchronize()
-            assert attn_err(h2n(out).view(np.float16)[live], ref[live]) <= ATTN_TOL, (k, D, B, H, ns)
-        if B > 4:                                 # sequence 1 is empty: a negative length must read as 0
-            wild = lens_dev.clone()
-            wild[1] = -9
-            out = nqkv.decode_attention_varlen(desc, lv, q, kc, ks, vc, vs, wild, S, 0.8)
-            torch.cuda.synchronize()
-            assert attn_err(h2n(out).view(np.float16)[live], ref[live]) <= ATTN_TOL
-        # paged form over an identity-shuffled pool (page = 128 tokens)
-        if True:
-            P, capp = 128, 384
-            pk = [torch.zeros(B, H, capp, t.shape[-1], dtype=t.dtype, device="cuda") for t in (kc, ks, vc, vs)]
-            for dst, src in zip(pk, (kc, ks, vc, vs)):
-                dst[:, :, :cap] = src
-            n_pg = capp // P
-            perm = torch.randperm(B * n_pg, generator=torch.Generator().manual_seed(B))
-            table = perm.reshape(B, n_pg).to(torch.int32).cuda()
-            pools = [_scatter_to_pages(t, table, P) for t in pk]
-            pdesc = nqkv.make_desc(B, H, D, k, blk, P)
-            out = nqkv.decode_attention_paged(pdesc, lv, q, *pools, table, lens_dev, S, 0.8)
-            torch.cuda.synchronize()
-            assert attn_err(h2n(out).view(np.float16)[live], ref[live]) <= ATTN_TOL, "paged"
-        # fused step: every sequence appends at its own row
-        g = torch.Generator(device="cuda").manual_seed(B + H)
-        kn = rand_kv((B, H, 1, D), seed=5 + B)[:, :, 0].contiguous()
-        vn = torch.randn(B, H, D, device="cuda", generator=g).to(torch.float16)
-        kc2, ks2, vc2, vs2 = kc.clone(), ks.clone(), vc.clone(), vs.clone()
-        out = nqkv.decode_step_varlen(desc, lv, q, kn, vn, kc2, ks2, vc2, vs2, lens_dev, S, 0.8)
+    # one workgroup per item whatever the item length (a per-call flag of the descriptor)
+    desc = nqkv.make_desc(B, H, D, k, blk, desc.cap_tokens, flags=nqkv.FLAG_WORKGROUP_PER_ITEM)
+    for ns in (1, 2):
+        out = nqkv.decode_attention_varlen(desc, lv, q, kc, ks, vc, vs, lens_dev, S, 0.8, num_splits=ns)
         torch.cuda.synchronize()
-    finally:
-        nqkv.set_tuning(2, 0)
+        assert attn_err(h2n(out).view(np.float16)[live], ref[live]) <= ATTN_TOL, (k, D, B, H, ns)
+    if B > 4:                                 # sequence 1 is empty: a negative length must read as 0
+        wild = lens_dev.clone()
+        wild[1] = -9
+        out = nqkv.decode_attention_varlen(desc, lv, q, kc, ks, vc, vs, wild, S, 0.8)
+        torch.cuda.synchronize()
+        assert attn_err(h2n(out).view(np.float16)[live], ref[live]) <= ATTN_TOL
+    # paged form over an identity-shuffled pool (page = 128 tokens)
+    if True:
+        P, capp = 128, 384
+        pk = [torch.zeros(B, H, capp, t.shape[-1], dtype=t.dtype, device="cuda") for t in (kc, ks, vc, vs)]
+        for dst, src in zip(pk, (kc, ks, vc, vs)):
+            dst[:, :, :cap] = src
+        n_pg = capp // P
+        perm = torch.randperm(B * n_pg, generator=torch.Generator().manual_seed(B))
+        table = perm.reshape(B, n_pg).to(torch.int32).cuda()
+        pools = [_scatter_to_pages(t, table, P) for t in pk]
+        pdesc = nqkv.make_desc(B, H, D, k, blk, P, flags=nqkv.FLAG_WORKGROUP_PER_ITEM)
+        out = nqkv.decode_attention_paged(pdesc, lv, q, *pools, table, lens_dev, S, 0.8)
+        torch.cuda.synchronize()
+        assert attn_err(h2n(out).view(np.float16)[live], ref[live]) <= ATTN_TOL, "paged"
+    # fused step: every sequence appends at its own row
+    g = torch.Generator(device="cuda").manual_seed(B + H)
+    kn = rand_kv((B, H, 1, D), seed=5 + B)[:, :, 0].contiguous()
+    vn = torch.randn(B, H, D, device="cuda", generator=g).to(torch.float16)
+    kc2, ks2, vc2, vs2 = kc.clone(), ks.clone(), vc.clone(), vs.clone()
+    out = nqkv.decode_step_varlen(desc, lv, q, kn, vn, kc2, ks2, vc2, vs2, lens_dev, S, 0.8)
+    torch.cuda.synchronize()
     okc, oks, ovc, ovs = (h2n(t).copy() for t in (kc, ks, vc, vs))
     for b in range(B):
         sl = slice(b, b + 1)

@@ -114,7 +114,7 @@ def test_quantize_argument_errors(nqkv):
     assert _quant(nqkv, good, lvp, n=2, st=32) == nqkv.EINVAL            # rows overlap
     assert _quant(nqkv, good, lvp, sb=-8) == nqkv.EINVAL
     assert _quant(nqkv, good, lvp, n=0) == nqkv.OK                       # empty: success, nothing launched
-    for bad in (dict(B=0), dict(H=0), dict(cap_tokens=0), dict(reserved=1), dict(D=0)):
+    for bad in (dict(B=0), dict(H=0), dict(cap_tokens=0), dict(flags=4), dict(flags=-1), dict(D=0)):
         d = nqkv.make_desc(2, 4, 64, 4, 64, 16)
         for f, v in bad.items():
             setattr(d, f, v)
@@ -437,17 +437,29 @@ def test_quantize_hidden_argument_errors(nqkv):
     assert call(big, sh=128, st=32 * 128, sb=0, n=1) == nqkv.EUNSUPPORTED
 
 
-def test_probe_argument_errors(nqkv):
-    f = nqkv.lib.nqkv_probe_read_stream
-    assert f(None, 1024, FAKE, None) == nqkv.EINVAL
-    assert f(FAKE, 1024, None, None) == nqkv.EINVAL
-    assert f(FAKE + 4, 1024, FAKE, None) == nqkv.EINVAL
-    assert f(FAKE, 1000, FAKE, None) == nqkv.EINVAL              # whole 16-byte vectors only
+def test_benchaux_library_exports_and_argument_errors():
+    """The measurement helpers live in a library of their own; the product library exports none."""
+    from paper_2505_16210_amd import benchaux
+    header = open(os.path.join(ROOT, "include", "nqkv_benchaux.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    assert set(re.findall(r"\b(nqkv_aux_[a-z_0-9]+)\s*\(", header)) == set(benchaux.EXPORTS)
+    f = benchaux.lib.nqkv_aux_read_stream
+    assert f(None, 1024, FAKE, None) == -1
+    assert f(FAKE, 1024, None, None) == -1
+    assert f(FAKE + 4, 1024, FAKE, None) == -1
+    assert f(FAKE, 1000, FAKE, None) == -1                       # whole 16-byte vectors only
+    assert benchaux.lib.nqkv_aux_copy(FAKE, FAKE + 8, 1024, None) == -1
+    assert benchaux.lib.nqkv_aux_copy(FAKE, FAKE, 0, None) == 0
 
 
-def test_tuning_knobs(nqkv):
-    assert nqkv.lib.nqkv_set_tuning(0, 2) == nqkv.EINVAL
-    assert nqkv.lib.nqkv_set_tuning(9, 0) == nqkv.EINVAL
-    nqkv.set_tuning(0, 1)
-    nqkv.set_tuning(0, 0)
-    nqkv.set_tuning(1, 0)
+def test_per_call_flags(nqkv):
+    """Options travel in the descriptor (the library keeps no settings): the two defined bits are
+    accepted by planning calls, anything else is refused."""
+    for flags in (0, nqkv.FLAG_SCAN_QUANTIZER, nqkv.FLAG_WORKGROUP_PER_ITEM, 3):
+        d = nqkv.make_desc(2, 4, 128, 4, 64, 4096, flags=flags)
+        assert nqkv.decode_workspace_bytes(d, 4096, 4)[1] == 4
+    for flags in (4, 8, 1 << 30, -1):
+        with pytest.raises(nqkv.NqkvError) as e:
+            nqkv.decode_workspace_bytes(nqkv.make_desc(2, 4, 128, 4, 64, 4096, flags=flags), 4096, 4)
+        assert e.value.status == nqkv.EINVAL
+    assert not any("tuning" in name or "probe" in name for name in nqkv.EXPORTS)
