@@ -20,7 +20,8 @@
 // HBM, so the address of a look-up must cost one instruction: for k = 4 and k = 2 every table
 // row is 256 bytes (one private copy per lane, hence no bank conflicts), which lets a single
 // v_perm_b32 assemble  address = code_byte * 256 + lane_offset  from the code dword and a
-// per-lane constant.  (k = 3 pairs are not byte aligned: bfe + shift-or, 128-byte rows.)
+// per-lane constant.  (k = 3 pairs are not byte aligned: the 96-bit stream of a lane is shifted
+// as a whole so that four pairs at a time start on byte boundaries, see for_each_pair_k3.)
 //
 // Table precision.  The table holds fp16 numbers.  Rounding the levels themselves to fp16 would
 // put a systematic relative error of up to 2^-11 on whole classes of elements, which the
@@ -29,8 +30,10 @@
 // scale and the output normalisation.
 //
 // Arithmetic.  K side: v_dot2_f32_f16 of the looked-up pair with the query pair, fp32
-// accumulate, block scale applied once per 32 elements.  V side: fp32 accumulators,
-// v_fma_mix_f32 with the weight p_t * scale.  Softmax is the running-maximum form per wave:
+// accumulate, block scale applied once per 32 elements.  V side: fp32 accumulators; at k = 4 and
+// k = 2 two tokens at a time, their codes merged nibble-wise so that one look-up returns the
+// levels of one element for both tokens and one v_dot2_f32_f16 contracts them with the fp16 pair
+// of weights p_t * scale (k = 3: v_fma_mix_f32 per element and token).  Softmax is the running-maximum form per wave:
 // scores of a trip (64 or 128 tokens) are reduced to a wave maximum with DPP, the accumulators
 // are rescaled only when the maximum grows (a wave-uniform branch), and the exponentials use
 // exp2 with log2(e) folded into the score scale.  At the end of an item the next item's first
@@ -56,6 +59,56 @@ constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
 constexpr int kRounds = 4;               // wave loads of K (and of V) in flight per trip
 
+// ------------------------------------------------------------------ 3-bit codes
+// A lane's 32 codes are a 96-bit stream, pair pr (elements 2 pr, 2 pr + 1) at bits [6 pr, 6 pr + 6):
+// not byte aligned, and an address built by shift-and-mask costs two vector instructions per
+// look-up.  Instead the stream is shifted right as a whole by 0, 6, 12 and 18 bits (three funnel
+// shifts per version): in version v the pairs pr = v, v + 4, v + 8, v + 12 start at bits 0, 24, 48
+// and 72 -- bytes 0 and 3 of dword 0, byte 2 of dword 1, byte 1 of dword 2 -- so one v_perm_b32
+// forms each address, as for the other widths: 25 instructions for 16 look-ups instead of 34.  The
+// two bits above a pair in its byte belong to the next pair; the table is indexed by the whole
+// byte and ignores them (256 rows).  f(pr, address) is called once per pair.
+template <class F>
+__device__ __forceinline__ void for_each_pair_k3(const uint32_t (&w)[3], uint32_t lane_off, F&& f) {
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    uint32_t s0 = w[0], s1 = w[1], s2 = w[2];
+    if (v > 0) {
+      s0 = __builtin_amdgcn_alignbit(w[1], w[0], 6 * v);
+      s1 = __builtin_amdgcn_alignbit(w[2], w[1], 6 * v);
+      s2 = w[2] >> (6 * v);
+    }
+    f(v, row_addr<0>(s0, lane_off));
+    f(v + 4, row_addr<3>(s0, lane_off));
+    f(v + 8, row_addr<2>(s1, lane_off));
+    f(v + 12, row_addr<1>(s2, lane_off));
+  }
+}
+
+// The table for that: row = byte B (bits 6 and 7 ignored), 256 bytes apart, its first 128 bytes
+// 32 copies of the dword {level[B & 7], level[(B >> 3) & 7]}; lane L reads copy L & 31.  Thread t
+// writes copy t & 31 of rows (t >> 5) + 16 i: the low code follows from the thread index, the high
+// code is (t >> 8) + 2 (i & 3).  Ends with a barrier.
+__device__ __forceinline__ void build_lut_bytes_k3(const DecodeParams& p, uint32_t* smem) {
+  const uint32_t copy = threadIdx.x & 31, e0 = threadIdx.x >> 5;       // e0 in [0, 16)
+  const uint32_t lo = pick_level(p, e0 & 7, 8);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const uint32_t hi_a = p.lut_levels[2 * (i & 3)], hi_b = p.lut_levels[2 * (i & 3) + 1];
+    smem[(e0 + 16 * i) * 64 + copy] = lo | (((e0 >> 3) ? hi_b : hi_a) << 16);
+  }
+  __syncthreads();
+}
+
+// First link of a chain of v_dot2_f32_f16: the three-source form with a zero addend (written as
+// an instruction because the compiler otherwise clears a register first and uses the
+// accumulate-in-place form).
+__device__ __forceinline__ float dot2_first(uint32_t a, uint32_t b) {
+  float r;
+  asm("v_dot2_f32_f16 %0, %1, %2, 0" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
 // ------------------------------------------------------------------ per-lane 32-element pieces
 // K side: sum over the lane's 32 elements of q_d * level[code_d]
 template <int KBITS>
@@ -70,7 +123,8 @@ __device__ __forceinline__ float k_dot(const uint32_t (&w)[KBITS], const uint32_
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
         const uint32_t v = *reinterpret_cast<const uint32_t*>(lut + a[b]);
-        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, v), __builtin_bit_cast(half2_t, q2[4 * i + b]), acc, false);
+        if (i == 0 && b == 0) acc = dot2_first(v, q2[0]);
+        else acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, v), __builtin_bit_cast(half2_t, q2[4 * i + b]), acc, false);
       }
     }
   } else if constexpr (KBITS == 2) {
@@ -81,17 +135,17 @@ __device__ __forceinline__ float k_dot(const uint32_t (&w)[KBITS], const uint32_
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
         const uint2 v = *reinterpret_cast<const uint2*>(lut + a[b]);
-        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, v.x), __builtin_bit_cast(half2_t, q2[8 * i + 2 * b]), acc, false);
+        if (i == 0 && b == 0) acc = dot2_first(v.x, q2[0]);
+        else acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, v.x), __builtin_bit_cast(half2_t, q2[8 * i + 2 * b]), acc, false);
         acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, v.y), __builtin_bit_cast(half2_t, q2[8 * i + 2 * b + 1]), acc, false);
       }
     }
   } else {
-#pragma unroll
-    for (int pr = 0; pr < 16; ++pr) {
-      const uint32_t f = field<KBITS>(w, 6 * pr, 6);
-      const uint32_t v = *reinterpret_cast<const uint32_t*>(lut + ((f << 7) | lane_off));
-      acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, v), __builtin_bit_cast(half2_t, q2[pr]), acc, false);
-    }
+    for_each_pair_k3(w, lane_off, [&](int pr, uint32_t addr) {
+      const uint32_t v = *reinterpret_cast<const uint32_t*>(lut + addr);
+      if (pr == 0) acc = dot2_first(v, q2[0]);
+      else acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, v), __builtin_bit_cast(half2_t, q2[pr]), acc, false);
+    });
   }
   return acc;
 }
@@ -129,14 +183,82 @@ __device__ __forceinline__ void v_axpy(const uint32_t (&w)[KBITS], float wgt, fl
       }
     }
   } else {
-#pragma unroll
-    for (int pr = 0; pr < 16; ++pr) {
-      const uint32_t f = field<KBITS>(w, 6 * pr, 6);
-      const half2_t h = __builtin_bit_cast(half2_t, *reinterpret_cast<const uint32_t*>(lut + ((f << 7) | lane_off)));
+    for_each_pair_k3(w, lane_off, [&](int pr, uint32_t addr) {
+      const half2_t h = __builtin_bit_cast(half2_t, *reinterpret_cast<const uint32_t*>(lut + addr));
       acc[2 * pr + 0] = __builtin_fmaf((float)h.x, wgt, acc[2 * pr + 0]);
       acc[2 * pr + 1] = __builtin_fmaf((float)h.y, wgt, acc[2 * pr + 1]);
+    });
+  }
+}
+
+// V side, two tokens at a time: acc[e] += w(t0) * level[code(t0, e)] + w(t1) * level[code(t1, e)]
+// with ONE v_dot2_f32_f16 per element, where the one-token form above spends one v_fma_mix per
+// (token, element).  The code dwords of the two tokens are merged nibble by nibble first --
+//     a = (w0 & 0x0f0f0f0f) | ((w1 << 4) & 0xf0f0f0f0)      low  nibbles of every byte, t0 | t1 << 4
+//     b = ((w0 >> 4) & 0x0f0f0f0f) | (w1 & 0xf0f0f0f0)      high nibbles
+// (four instructions per dword pair) -- so that a byte of `a` or `b` holds the codes of the SAME
+// elements of the two tokens and the byte-indexed table returns them side by side, {level of t0,
+// level of t1}, ready to be contracted with the fp16 pair of weights.  k = 4: a nibble is one code
+// and the table is the key side's own; k = 2: a nibble is two codes (elements e, e + 1) and the
+// pairs come from a second table (see build_lut_pairs).  The weights w = p * value scale are
+// rounded to fp16 (round to nearest): a relative error of 2^-11 per term, of random sign.
+template <int KBITS>
+__device__ __forceinline__ void v_axpy_pair(const uint32_t (&w0)[KBITS], const uint32_t (&w1)[KBITS], half2_t wgt2,
+                                            float (&acc)[32], const char* lut, uint32_t lane_off_v) {
+  static_assert(KBITS == 4 || KBITS == 2, "3-bit codes do not align with nibbles");
+  constexpr uint32_t M = 0x0f0f0f0fu;
+#pragma unroll
+  for (int i = 0; i < KBITS; ++i) {
+    const uint32_t a = (w0[i] & M) | ((w1[i] << 4) & ~M);
+    const uint32_t b = ((w0[i] >> 4) & M) | (w1[i] & ~M);
+    const uint32_t aa[4] = {row_addr<0>(a, lane_off_v), row_addr<1>(a, lane_off_v), row_addr<2>(a, lane_off_v), row_addr<3>(a, lane_off_v)};
+    const uint32_t ab[4] = {row_addr<0>(b, lane_off_v), row_addr<1>(b, lane_off_v), row_addr<2>(b, lane_off_v), row_addr<3>(b, lane_off_v)};
+    if constexpr (KBITS == 4) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t lo = *reinterpret_cast<const uint32_t*>(lut + aa[j]);
+        const uint32_t hi = *reinterpret_cast<const uint32_t*>(lut + ab[j]);
+        acc[8 * i + 2 * j + 0] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, lo), wgt2, acc[8 * i + 2 * j + 0], false);
+        acc[8 * i + 2 * j + 1] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, hi), wgt2, acc[8 * i + 2 * j + 1], false);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint2 lo = *reinterpret_cast<const uint2*>(lut + aa[j]);
+        const uint2 hi = *reinterpret_cast<const uint2*>(lut + ab[j]);
+        const int e = 16 * i + 4 * j;
+        acc[e + 0] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, lo.x), wgt2, acc[e + 0], false);
+        acc[e + 1] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, lo.y), wgt2, acc[e + 1], false);
+        acc[e + 2] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, hi.x), wgt2, acc[e + 2], false);
+        acc[e + 3] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, hi.y), wgt2, acc[e + 3], false);
+      }
     }
   }
+}
+
+// Look-up tables of this kernel at k = 2.  A table row (one per code byte) is 256 bytes, so that
+// one v_perm_b32 forms the address; the row is shared by two tables of 16 lane copies each:
+//   bytes [0, 128)    key side, byte = four codes of one token:       {l[c0], l[c1]}, {l[c2], l[c3]}
+//   bytes [128, 256)  value side, byte = nibble of t0 | nibble of t1 << 4, a nibble = the codes of
+//                     elements e, e + 1:    {l[t0, e], l[t1, e]}, {l[t0, e + 1], l[t1, e + 1]}
+//                     -- with c0..c3 the byte's four 2-bit fields: {l[c0], l[c2]}, {l[c1], l[c3]}
+// Lane L reads copy L & 15 (eight bytes per copy).  Thread t writes dword t & 63 of rows
+// (t >> 6) + 8 i: the fields c0 and c1 follow from the thread index and i & 1, c2 and c3 from the
+// loop counter alone (scalar registers).  Ends with a barrier.
+__device__ __forceinline__ void build_lut_pairs_k2(const DecodeParams& p, uint32_t* smem) {
+  const uint32_t c = threadIdx.x & 63, e0 = threadIdx.x >> 6;            // e0 in [0, 8)
+  const uint32_t l0 = pick_level(p, e0 & 3, 4);
+  const uint32_t l1_even = pick_level(p, e0 >> 2, 4), l1_odd = pick_level(p, (e0 >> 2) + 2, 4);
+  const bool value_side = c >= 32, second = c & 1;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    const uint32_t l1 = (i & 1) ? l1_odd : l1_even;
+    const uint32_t l2 = p.lut_levels[(i >> 1) & 3], l3 = p.lut_levels[i >> 3];
+    const uint32_t key_dw = second ? (l2 | (l3 << 16)) : (l0 | (l1 << 16));
+    const uint32_t val_dw = second ? (l1 | (l3 << 16)) : (l0 | (l2 << 16));
+    smem[(e0 + 8 * i) * 64 + c] = value_side ? val_dw : key_dw;
+  }
+  __syncthreads();
 }
 
 // ------------------------------------------------------------------ in-wave reduce-scatter
@@ -238,7 +360,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   // test) is uniform control flow for the compiler
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t j = lane % LPT, g = lane / LPT;
-  const uint32_t lane_off = (KBITS == 4) ? (lane << 2) : (KBITS == 2) ? ((lane & 31) << 3) : ((lane & 31) << 2);
+  // this lane's copy inside a table row; at k = 2 the row holds the key table and the value-pair
+  // table side by side, 16 copies each (see build_lut_pairs_k2)
+  const uint32_t lane_off = (KBITS == 4) ? (lane << 2) : (KBITS == 2) ? ((lane & 15) << 3) : ((lane & 31) << 2);
+  const uint32_t lane_off_v = (KBITS == 2) ? (128u + ((lane & 15) << 3)) : lane_off;
   const int32_t stride = kWaves * CHUNK;
 
   uint32_t kw[kRounds][KBITS], vw[kRounds][KBITS];
@@ -395,7 +520,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   load_k(base);
   load_q();
   if (FUSE) load_new();
-  build_lut<KBITS>(p, smem);          // ends with a barrier
+  if constexpr (KBITS == 2) build_lut_pairs_k2(p, smem);          // (each ends with a barrier)
+  else if constexpr (KBITS == 3) build_lut_bytes_k3(p, smem);
+  else build_lut<KBITS>(p, smem);
   if (FUSE && wave == kWaves - 1) {
     // only this wave searches codes: it stages the table for itself, no barrier needed (LDS
     // operations of one wave complete in order)
@@ -498,9 +625,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
         part = __builtin_fmaf(part, (float)__builtin_bit_cast(_Float16, ksc[r]), 0.0f);
         part += dpp_f<kQuadXor1>(part);
         if (LPT == 4) part += dpp_f<kQuadXor2>(part);
-        // (the lane's token of round r exists: a per-lane constant against a scalar)
-        const bool valid = (int32_t)g < left - r * TPR;
-        z[r] = valid ? part * p.scale_log2e : -INFINITY;
+        z[r] = part * p.scale_log2e;
+      }
+      if (left < CHUNK) {
+        // the ragged last trip of the item (a uniform branch): tokens past the end read as zero codes
+        // and zero scales, a score of 0, and must not enter the softmax
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) z[r] = ((int32_t)g < left - r * TPR) ? z[r] : -INFINITY;
       }
       float m_trip = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
       m_trip = wave_max<LPT>(m_trip);          // the LPT lanes of a token hold the same scores
@@ -520,10 +651,21 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
 
       load_k(base + stride);     // past the end on the last trip: reads zeros
 
+      if constexpr (KBITS == 3) {
 #pragma unroll
-      for (int r = 0; r < kRounds; ++r) {
-        const float wgt = __builtin_fmaf(pw[r], (float)__builtin_bit_cast(_Float16, vsc[r]), 0.0f);
-        v_axpy<KBITS>(vw[r], wgt, acc, lut, lane_off);
+        for (int r = 0; r < kRounds; ++r) {
+          const float wgt = __builtin_fmaf(pw[r], (float)__builtin_bit_cast(_Float16, vsc[r]), 0.0f);
+          v_axpy<KBITS>(vw[r], wgt, acc, lut, lane_off);
+        }
+      } else {
+        // two tokens per step: one v_dot2 per element instead of two v_fma_mix
+#pragma unroll
+        for (int r = 0; r < kRounds; r += 2) {
+          const float w_a = __builtin_fmaf(pw[r], (float)__builtin_bit_cast(_Float16, vsc[r]), 0.0f);
+          const float w_b = __builtin_fmaf(pw[r + 1], (float)__builtin_bit_cast(_Float16, vsc[r + 1]), 0.0f);
+          const half2_t wgt2 = {(_Float16)w_a, (_Float16)w_b};
+          v_axpy_pair<KBITS>(vw[r], vw[r + 1], wgt2, acc, lut, lane_off_v);
+        }
       }
     }
 
