@@ -28,7 +28,8 @@
  *     ordinary memory.  The library allocates no device memory and keeps no state between
  *     calls.  Device pointers must be 16-byte aligned.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
- *     enqueue work on that stream and return; they never synchronise.
+ *     enqueue work on that stream and return; they never synchronise (the one exception,
+ *     nqkv_decode_workspace_check, says so).
  *   - fp16 means IEEE binary16.  Inputs must be finite (not checked).
  *   - Results are bitwise reproducible for equal arguments (no floating-point atomics).
  *
@@ -86,7 +87,7 @@ enum {
 };
 
 /*
- * Quantile table (Sec. 1: "quantile points from a normal distribution as data points").
+ * Quantile table (Sec. 1: the table entries are quantile points of a normal distribution).
  * Host only; touches no GPU.
  *   k          bits per index, 1..8 (the kernels accept tables for k = 2, 3, 4)
  *   variant    0: symmetric table, level i = Phi^-1((i + 1/2) / 2^k) divided by the largest
@@ -179,12 +180,36 @@ int nqkv_dequantize_kv(const nqkv_cache_desc* desc, const float* levels,
  * Host only.
  *
  * Workspace contract: the first 256 KiB hold arrival counters that must be ZERO when a call
- * starts.  Zero-fill the workspace once after allocating it (hipMemset); every call leaves the
- * counters zero again, so the same workspace can be reused by later calls on the same stream
- * with any geometry.  Calls that share a workspace must not overlap in time.
+ * starts.  Clear the workspace once after allocating it (nqkv_decode_workspace_init, or any
+ * zero-fill); every call leaves the counters zero again, so the same workspace can be reused by
+ * later calls on the same stream with any geometry.  Calls that share a workspace must not
+ * overlap in time.  If the counters are NOT zero when a call starts (memory that was never
+ * cleared, or written by something else since), that call's output is undefined; a kernel that
+ * notices -- it is handed a ticket its own call cannot have issued -- marks the workspace, and
+ * nqkv_decode_workspace_check reports it.
  */
 int nqkv_decode_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, int num_splits,
                                 size_t* bytes_out, int* splits_out);
+
+/*
+ * Clears the counters of a split-K workspace (its first 256 KiB) with a small kernel enqueued on
+ * `hip_stream`: the once-after-allocation step of the contract above, and the way back from a
+ * workspace that nqkv_decode_workspace_check found dirty.  A kernel, not a memset, so it may be
+ * recorded into a HIP graph.
+ * Errors: NQKV_EINVAL for a null / misaligned pointer, NQKV_EWORKSPACE for fewer than 256 KiB.
+ */
+int nqkv_decode_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Host-visible check of that contract, for debugging and for callers that recycle memory: copies
+ * the counters back and returns NQKV_OK when all are zero, NQKV_EWORKSPACE when any is not (a
+ * counter left armed by a call that never finished, memory that was never cleared, or the mark
+ * of a kernel that was handed an impossible ticket).  Unlike every other call this one WAITS for
+ * `hip_stream` (it has to, to look at the memory); use it when no call on this workspace is in
+ * flight on another stream.
+ * Errors: NQKV_EINVAL for a null / misaligned pointer, NQKV_EWORKSPACE also for fewer than 256 KiB.
+ */
+int nqkv_decode_workspace_check(const void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Attention of one new query per (batch, head) over the first seq_len cached tokens
@@ -247,6 +272,11 @@ int nqkv_decode_attention_static(const nqkv_cache_desc* desc, const float* level
  *   pos           0 .. cap_tokens-1; rows [0, pos) must already be valid
  *   workspace     as for nqkv_decode_attention, sized with
  *                 nqkv_decode_workspace_bytes(desc, max(pos, 1), num_splits)
+ * A table whose neighbouring mid-points lie closer than about 1/32 of its range cannot be searched
+ * by the kernel's own quantizer; for such a table the call runs as two launches (append with
+ * nqkv_quantize_kv_pair's kernel, then nqkv_decode_attention over pos + 1 tokens) and the
+ * workspace must satisfy nqkv_decode_workspace_bytes(desc, pos + 1, num_splits) as well.  All of
+ * this is checked before the first launch.
  * Errors: as nqkv_decode_attention, plus NQKV_EINVAL for a null/misaligned k_new or v_new.
  */
 int nqkv_decode_step(const nqkv_cache_desc* desc, const float* levels,
@@ -345,8 +375,8 @@ int nqkv_decode_step_paged(const nqkv_cache_desc* desc, const float* levels,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
- * Quantization with blocks over the token's hidden vector (Fig. 5: "each token ... divided into
- * blocks" of a fixed size; Sec. 4.1: block size 256).  The hidden vector of a token is its H
+ * Quantization with blocks over the token's hidden vector (Fig. 5: every token is cut into
+ * blocks of a fixed size; Sec. 4.1: block size 256).  The hidden vector of a token is its H
  * heads of D elements side by side; a block is `block_hidden` consecutive elements of it and so
  * covers block_hidden / D whole heads.  Each block is quantized exactly like the blocks of
  * nqkv_quantize_kv (same scale, code and packing rules).  The cache keeps the per-head layout of

@@ -11,7 +11,7 @@
 // Conventions (each is a reading of the paper where the paper itself is silent):
 //   * codebook, variant 0: 2^k levels = medians of 2^k equal-probability bins of
 //     N(0,1), divided by the largest one, built for the positive half and mirrored
-//     (Sec. 1 "quantile points from a normal distribution"; Sec. 3.2);
+//     (Sec. 1: the data points are normal-distribution quantiles; Sec. 3.2);
 //     variant 1: zero-preserving asymmetric table in the Normal-Float style the
 //     paper cites for its 4-bit experiments (Sec. 3.2), with this build's own
 //     tail offset delta = 2^-(k+1);
@@ -286,7 +286,7 @@ int oracle_quantize_kv(const uint16_t* src, int64_t sb, int64_t sh, int64_t ss,
   return 0;
 }
 
-// Blocks over the token's hidden vector (Fig. 5: "each token ... divided into blocks" of a fixed
+// Blocks over the token's hidden vector (Fig. 5: every token is cut into blocks of a fixed
 // size; Sec. 4.1: block size 256).  The hidden vector of one token is its H heads of D elements
 // side by side, h-major; a block is `blk_hidden` consecutive elements of it, a multiple of D, so
 // it covers blk_hidden / D whole heads.  Each block is quantized on its own exactly like any

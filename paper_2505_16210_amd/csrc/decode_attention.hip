@@ -754,6 +754,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
       __syncthreads();
       if (tid == 0) ticket_sh = __hip_atomic_fetch_add(p.tickets + cur_bh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __syncthreads();
+      // A ticket this call cannot have handed out: the counter did not start at zero (a workspace
+      // that was never cleared, or clobbered since).  Leave a mark that the host can ask for.
+      if (ticket_sh >= (uint32_t)p.splits && tid == 0)
+        __hip_atomic_fetch_or(p.tickets + kWorkspaceStatusWord, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (ticket_sh == (uint32_t)p.splits - 1u) {           // uniform over the workgroup
         // All 512 threads combine: thread (grp, d) folds the partials of splits grp, grp + G, ...
         // for output element d, four splits per trip so that their loads (which bypass the

@@ -8,6 +8,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstring>
+#include <vector>
 
 namespace {
 
@@ -431,6 +432,27 @@ int nqkv_decode_workspace_bytes(const nqkv_cache_desc* desc, int64_t seq_len, in
   return NQKV_OK;
 }
 
+int nqkv_decode_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!workspace || !aligned16(workspace)) return NQKV_EINVAL;
+  if (workspace_bytes < kTicketBytes) return NQKV_EWORKSPACE;
+  const hipError_t e = launch_clear_words(static_cast<uint32_t*>(workspace), (int)(kTicketBytes / sizeof(uint32_t)),
+                                          static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? NQKV_OK : NQKV_EHIP;
+}
+
+int nqkv_decode_workspace_check(const void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!workspace || !aligned16(workspace)) return NQKV_EINVAL;
+  if (workspace_bytes < kTicketBytes) return NQKV_EWORKSPACE;
+  std::vector<uint32_t> words(kTicketBytes / sizeof(uint32_t));
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (hipMemcpyAsync(words.data(), workspace, kTicketBytes, hipMemcpyDeviceToHost, stream) != hipSuccess) return NQKV_EHIP;
+  if (hipStreamSynchronize(stream) != hipSuccess) return NQKV_EHIP;
+  for (uint32_t w : words) {
+    if (w != 0) return NQKV_EWORKSPACE;       // a counter left armed, or the status word a kernel set
+  }
+  return NQKV_OK;
+}
+
 // Ragged batch on a grid of one workgroup per item, more items than can be resident: dispatch
 // the long sequences first (the kernel ranks the lengths itself; it handles up to 64 of them).
 // Measured at B16 H56 S<=16384, lengths spread over [S/8, S] in random batch order: 211 -> 175 us.
@@ -525,6 +547,17 @@ static int decode_impl(const nqkv_cache_desc* desc, const float* levels, const v
   if (fuse && !build_cell_table(levels, desc->k, p.cell_thr, p.cell_below)) {
     // a table the in-kernel code search cannot take: append with the quantizer, then attend
     if (lens) return NQKV_EUNSUPPORTED;        // (the quantizer appends at one row for the whole batch)
+    // That attention runs over seq_len tokens, one more than the step was planned for above, and
+    // may cut the sequence into one more piece: everything that call checks is checked here
+    // first, so that an error still means nothing was launched and the cache is untouched.
+    int splits_att = 1;
+    if ((rc = plan_splits(desc, seq_len, num_splits, &splits_att))) return rc;
+    const size_t need_att = workspace_need(desc, splits_att);
+    if (need_att > 0) {
+      if (!workspace || !aligned16(workspace)) return NQKV_EINVAL;
+      if (workspace_bytes < need_att) return NQKV_EWORKSPACE;
+    }
+    if ((seq_len / splits_att + 1) * (int64_t)(desc->D * desc->k / 8) >= ((int64_t)1 << 31)) return NQKV_EUNSUPPORTED;
     rc = nqkv_quantize_kv_pair(desc, levels, k_new, v_new, new_stride_b, new_stride_h, desc->D, 1, seq_len - 1,
                                const_cast<void*>(k_codes), const_cast<void*>(k_scales),
                                const_cast<void*>(v_codes), const_cast<void*>(v_scales), hip_stream);

@@ -123,6 +123,9 @@ struct MultiParams {
 // Bytes at the start of the split-K workspace that hold the ticket counters (one uint32 per
 // (b,h), room for the largest supported B*H), before the partial results.
 constexpr size_t kTicketBytes = 65536 * sizeof(uint32_t);
+// The last word of that area (B*H <= 65535, so never a counter) is a status word: a kernel that
+// is handed a ticket its own call cannot have issued sets bit 0 there.
+constexpr uint32_t kWorkspaceStatusWord = 65535;
 
 // Size of the library-owned scratch array behind nqkv_decode_attention_static (per GPU, held until
 // the process ends): the ticket counters plus room for 3528 partial results at head size 128.

@@ -21,7 +21,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 EXPORTS = ("nqkv_strerror", "nqkv_version", "nqkv_build_codebook",
            "nqkv_quantize_kv", "nqkv_quantize_kv_pair", "nqkv_dequantize_kv",
            "nqkv_decode_workspace_bytes", "nqkv_decode_attention", "nqkv_decode_step",
-           "nqkv_decode_attention_static",
+           "nqkv_decode_attention_static", "nqkv_decode_workspace_init", "nqkv_decode_workspace_check",
            "nqkv_quantize_kv_hidden",
            "nqkv_decode_multi_workspace_bytes", "nqkv_decode_attention_multi", "nqkv_decode_attention_multi_varlen",
            "nqkv_decode_multi_paged_workspace_bytes", "nqkv_decode_attention_multi_paged",
@@ -89,6 +89,10 @@ def _load() -> ctypes.CDLL:
                                           c.c_size_t, i32, vp]
     lib.nqkv_decode_attention_static.restype = i32
     lib.nqkv_decode_attention_static.argtypes = [dp, fp, vp, vp, vp, vp, vp, i64, c.c_float, vp, i32, vp]
+    lib.nqkv_decode_workspace_init.restype = i32
+    lib.nqkv_decode_workspace_init.argtypes = [vp, c.c_size_t, vp]
+    lib.nqkv_decode_workspace_check.restype = i32
+    lib.nqkv_decode_workspace_check.argtypes = [vp, c.c_size_t, vp]
     lib.nqkv_decode_step.restype = i32
     lib.nqkv_decode_step.argtypes = [dp, fp, vp, vp, vp, i64, i64, vp, vp, vp, vp, i64, c.c_float, vp, vp,
                                      c.c_size_t, i32, vp]
@@ -138,6 +142,24 @@ def _stream(stream) -> int:
     if stream is None:
         stream = torch.cuda.current_stream()
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _temp_workspace(need: int, device, stream, zero: bool):
+    """A workspace for one call when the caller passed none: allocated (and zero-filled, where the
+    kernel expects zeroed counters) ON THE STREAM THE KERNEL WILL RUN ON, so that the fill is
+    ordered before the kernel, and recorded on that stream so that the allocator does not hand the
+    memory to someone else while the kernel may still be running.  A raw stream handle gives the
+    binding nothing to order the fill against: such callers pass their own workspace."""
+    if not need:
+        return None
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if not isinstance(stream, torch.cuda.Stream):
+        raise ValueError("pass an explicit workspace when launching on a raw stream handle")
+    with torch.cuda.stream(stream):
+        ws = (torch.zeros if zero else torch.empty)(need, dtype=torch.uint8, device=device)
+    ws.record_stream(stream)
+    return ws
 
 
 def _dev_ptr(t):
@@ -257,8 +279,7 @@ def decode_attention(desc: CacheDesc, levels, q: torch.Tensor, k_codes, k_scales
     ws_bytes = 0
     if workspace is None:
         need, _ = decode_workspace_bytes(desc, seq_len, num_splits)
-        if need:
-            workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)   # counters start at zero
+        workspace = _temp_workspace(need, q.device, stream, zero=True)      # counters start at zero
     if workspace is not None:
         ws_bytes = workspace.numel() * workspace.element_size()
     rc = lib.nqkv_decode_attention(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_codes), _dev_ptr(k_scales),
@@ -266,6 +287,20 @@ def decode_attention(desc: CacheDesc, levels, q: torch.Tensor, k_codes, k_scales
                                    _dev_ptr(out), _dev_ptr(workspace), ws_bytes, num_splits, _stream(stream))
     _check(rc, "nqkv_decode_attention")
     return out
+
+
+def decode_workspace_init(workspace: torch.Tensor, stream=None) -> None:
+    """nqkv_decode_workspace_init: clears the counters of a split-K workspace (on the stream)."""
+    rc = lib.nqkv_decode_workspace_init(_dev_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "nqkv_decode_workspace_init")
+
+
+def decode_workspace_check(workspace: torch.Tensor, stream=None) -> int:
+    """nqkv_decode_workspace_check -> OK or EWORKSPACE (waits for the stream)."""
+    rc = lib.nqkv_decode_workspace_check(_dev_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc not in (OK, EWORKSPACE):
+        _check(rc, "nqkv_decode_workspace_check")
+    return rc
 
 
 STATIC_SCRATCH_BYTES = 2 << 20
@@ -310,8 +345,7 @@ def decode_attention_multi(desc: CacheDesc, levels, q: torch.Tensor, k_codes, k_
     ws_bytes = 0
     if workspace is None:
         need, _ = decode_multi_workspace_bytes(desc, seq_len, q_len, num_splits)
-        if need:
-            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        workspace = _temp_workspace(need, q.device, stream, zero=False)
     if workspace is not None:
         ws_bytes = workspace.numel() * workspace.element_size()
     rc = lib.nqkv_decode_attention_multi(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_codes), _dev_ptr(k_scales),
@@ -335,8 +369,7 @@ def decode_attention_multi_varlen(desc: CacheDesc, levels, q: torch.Tensor, k_co
     ws_bytes = 0
     if workspace is None:
         need, _ = decode_multi_workspace_bytes(desc, max_seq_len, q_len, num_splits)
-        if need:
-            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        workspace = _temp_workspace(need, q.device, stream, zero=False)
     if workspace is not None:
         ws_bytes = workspace.numel() * workspace.element_size()
     rc = lib.nqkv_decode_attention_multi_varlen(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_codes), _dev_ptr(k_scales),
@@ -363,8 +396,7 @@ def decode_step(desc: CacheDesc, levels, q: torch.Tensor, k_new: torch.Tensor, v
     ws_bytes = 0
     if workspace is None:
         need, _ = decode_workspace_bytes(desc, max(pos, 1), num_splits)
-        if need:
-            workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)
+        workspace = _temp_workspace(need, q.device, stream, zero=True)      # counters start at zero
     if workspace is not None:
         ws_bytes = workspace.numel() * workspace.element_size()
     rc = lib.nqkv_decode_step(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_new), _dev_ptr(v_new),
@@ -392,8 +424,7 @@ def decode_attention_varlen(desc: CacheDesc, levels, q: torch.Tensor, k_codes, k
     ws_bytes = 0
     if workspace is None:
         need, _ = decode_workspace_bytes(desc, max_seq_len, num_splits)
-        if need:
-            workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)
+        workspace = _temp_workspace(need, q.device, stream, zero=True)      # counters start at zero
     if workspace is not None:
         ws_bytes = workspace.numel() * workspace.element_size()
     rc = lib.nqkv_decode_attention_varlen(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_codes), _dev_ptr(k_scales),
@@ -420,8 +451,7 @@ def decode_step_varlen(desc: CacheDesc, levels, q: torch.Tensor, k_new: torch.Te
     ws_bytes = 0
     if workspace is None:
         need, _ = decode_workspace_bytes(desc, max(max_pos, 1), num_splits)
-        if need:
-            workspace = torch.zeros(need, dtype=torch.uint8, device=q.device)
+        workspace = _temp_workspace(need, q.device, stream, zero=True)      # counters start at zero
     if workspace is not None:
         ws_bytes = workspace.numel() * workspace.element_size()
     rc = lib.nqkv_decode_step_varlen(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_new), _dev_ptr(v_new),
@@ -500,7 +530,7 @@ def decode_attention_paged(desc: CacheDesc, levels, q, k_codes, k_scales, v_code
         out = torch.empty_like(q)
     if workspace is None:
         need, _ = decode_paged_workspace_bytes(desc, max_seq_len)
-        workspace = torch.zeros(need, dtype=torch.uint8, device=q.device) if need else None
+        workspace = _temp_workspace(need, q.device, stream, zero=True)
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     tp, ts = _table_arg(block_table, desc.B)
     rc = lib.nqkv_decode_attention_paged(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_codes), _dev_ptr(k_scales),
@@ -533,7 +563,7 @@ def decode_attention_multi_paged(desc: CacheDesc, levels, q, k_codes, k_scales, 
         out = torch.empty_like(q)
     if workspace is None:
         need, _ = decode_multi_paged_workspace_bytes(desc, max_seq_len, q_len, num_splits)
-        workspace = torch.empty(need, dtype=torch.uint8, device=q.device) if need else None
+        workspace = _temp_workspace(need, q.device, stream, zero=False)
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     tp, ts = _table_arg(block_table, desc.B)
     rc = lib.nqkv_decode_attention_multi_paged(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_codes), _dev_ptr(k_scales),
@@ -557,7 +587,7 @@ def decode_step_paged(desc: CacheDesc, levels, q, k_new, v_new, k_codes, k_scale
         out = torch.empty_like(q)
     if workspace is None:
         need, _ = decode_paged_workspace_bytes(desc, max(max_pos, 1))
-        workspace = torch.zeros(need, dtype=torch.uint8, device=q.device) if need else None
+        workspace = _temp_workspace(need, q.device, stream, zero=True)
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     tp, ts = _table_arg(block_table, desc.B)
     rc = lib.nqkv_decode_step_paged(ctypes.byref(desc), lvp, _dev_ptr(q), _dev_ptr(k_new), _dev_ptr(v_new),

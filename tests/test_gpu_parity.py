@@ -38,6 +38,23 @@ def attn_err(out: np.ndarray, ref: np.ndarray) -> float:
     return float((num / den).max())
 
 
+def attn_err_elementwise(out: np.ndarray, ref: np.ndarray) -> float:
+    """worst element-wise error |out - ref| / max(|ref|, 1e-2 * max_d |ref|): relative to the element
+    itself unless it is smaller than a hundredth of its row's largest."""
+    out = out.astype(np.float64)
+    floor = 1e-2 * np.abs(ref).max(axis=-1, keepdims=True)
+    return float((np.abs(out - ref) / np.maximum(np.abs(ref), floor)).max())
+
+
+# Element-wise bounds of the one-query kernel (the row-wise bound ATTN_TOL is the contract; these
+# pin the finer metric so that a regression in it shows).  k = 4: the fp16 look-up table's rounding
+# shows on outputs near zero (measured up to 4.8e-2).  k = 2: the table is nearly exact, but the
+# value side contracts two tokens per instruction with fp16 weights p * scale, whose 2^-11
+# rounding shows where terms cancel (measured up to 1.0e-2).  k = 3: fp32 weights, nearly exact
+# table (measured up to 1.2e-3).
+ELEMENTWISE_TOL = {4: 6e-2, 3: 2e-3, 2: 2e-2}
+
+
 def rand_kv(shape, seed, chan_spread=True):
     g = torch.Generator(device="cuda").manual_seed(seed)
     x = torch.randn(shape, device="cuda", generator=g)
@@ -238,6 +255,8 @@ def test_decode_attention_matches_oracle(nqkv, oracle, k, D, blk):
             torch.cuda.synchronize()
             err = attn_err(h2n(out).view(np.float16), ref)
             assert err <= ATTN_TOL, (k, D, blk, seq, ns, err)
+            err_el = attn_err_elementwise(h2n(out).view(np.float16), ref)
+            assert err_el <= ELEMENTWISE_TOL[k], (k, D, blk, seq, ns, err_el)
 
 
 def test_decode_attention_repeatable_and_split_consistent(nqkv):
@@ -300,6 +319,145 @@ def test_decode_steps_append_then_attend(nqkv, oracle):
         ref = oracle.decode_attention(h2n(q), okc, oks, ovc, ovs, k, blk, lv, pos + 1, 1.0)
         assert attn_err(h2n(out).view(np.float16), ref) <= ATTN_TOL
     assert np.array_equal(h2n(kc), okc) and np.array_equal(h2n(vs), ovs)
+
+
+@pytest.mark.parametrize("k,D,blk", [(4, 128, 64), (4, 64, 64), (2, 128, 128), (3, 128, 64)])
+def test_decode_attention_peaked_scores_keep_their_headroom(nqkv, oracle, k, D, blk):
+    """Where the scores peak the exponential amplifies the look-up table's fp16 rounding: keys four
+    times wider than the workloads', and a softmax scale of 4 on ordinary keys, at a length that
+    takes many trips.  Both must stay inside the 2e-3 row bound (measured about 1.1e-3 and 1.4e-3
+    at k = 4: this guards the remaining headroom)."""
+    B, H, S = 2, 4, 4096
+    g = torch.Generator(device="cuda").manual_seed(300 + k + D)
+    for k_width, scale in ((4.0, 1.0), (1.5, 4.0)):
+        Kx = (torch.randn(B, H, S, D, device="cuda", generator=g) * k_width).to(torch.float16)
+        Vx = torch.randn(B, H, S, D, device="cuda", generator=g).to(torch.float16)
+        q = (torch.randn(B, H, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+        lv = nqkv.build_codebook(k)
+        desc = nqkv.make_desc(B, H, D, k, blk, S)
+        kc, ks = nqkv.alloc_cache(desc)
+        vc, vs = nqkv.alloc_cache(desc)
+        nqkv.quantize_kv_pair(desc, lv, Kx, Vx, kc, ks, vc, vs, 0)
+        torch.cuda.synchronize()
+        hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+        ref = oracle.decode_attention(*hk, k, blk, lv, S, scale, n_threads=8)
+        for ns in (0, 1):
+            out = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, scale, num_splits=ns)
+            torch.cuda.synchronize()
+            assert attn_err(h2n(out).view(np.float16), ref) <= ATTN_TOL, (k, D, blk, k_width, scale, ns)
+
+
+def _crowded_table(k):
+    """An ascending table the quantizer's cell-table search cannot take (two mid-points closer than a
+    cell is wide): such tables take the plain threshold scan, and the fused step its two-launch form."""
+    L = 1 << k
+    if L == 4:
+        return np.array([-0.03, 0.0, 0.03, 1.0], np.float32)       # mid-points -0.015 and 0.015
+    lv = np.linspace(-1.0, 1.0, L).astype(np.float32)
+    lv[L // 2 - 1], lv[L // 2], lv[L // 2 + 1] = -0.004, 0.004, 0.012   # mid-points 0 and 0.008
+    return lv
+
+
+@pytest.mark.parametrize("k,D,blk", [(4, 128, 64), (3, 64, 64), (2, 128, 128)])
+def test_crowded_custom_table_quantize_and_decode_step_fallback(nqkv, oracle, k, D, blk):
+    """A caller's own table with levels crowded around zero: the quantizer (threshold scan), the
+    decode step (which falls back to append + attention, two launches) and the attention itself
+    against the oracle; the per-sequence and paged steps refuse such a table."""
+    B, H, S0, cap = 2, 3, 255, 300
+    lv = _crowded_table(k)
+    g = torch.Generator(device="cuda").manual_seed(70 + k)
+    Kx = rand_kv((B, H, cap, D), 70 + k)
+    Vx = torch.randn(B, H, cap, D, device="cuda", generator=g).to(torch.float16)
+    Kx[0, 0, :8] *= 0.003                                  # values that land between the crowded levels
+    q = (torch.randn(B, H, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    kc, ks = nqkv.alloc_cache(desc)
+    vc, vs = nqkv.alloc_cache(desc)
+    nqkv.quantize_kv_pair(desc, lv, Kx[:, :, :S0], Vx[:, :, :S0], kc, ks, vc, vs, 0)
+    torch.cuda.synchronize()
+    Kh, Vh = h2n(Kx), h2n(Vx)
+    okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
+    ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
+    oracle.quantize_kv(Kh[:, :, :S0], k, blk, lv, okc, oks)
+    oracle.quantize_kv(Vh[:, :, :S0], k, blk, lv, ovc, ovs)
+    assert np.array_equal(h2n(kc), okc) and np.array_equal(h2n(ks), oks)
+    assert np.array_equal(h2n(vc), ovc) and np.array_equal(h2n(vs), ovs)
+    # the step at pos 255 (B*H = 6: the attention over 256 tokens is cut into one more piece than
+    # the 255 cached tokens would be): a workspace sized for the cached tokens only is refused
+    # BEFORE anything is written, one sized for pos + 1 works
+    pos = S0
+    small, sp_small = nqkv.decode_workspace_bytes(desc, pos, 0)
+    big, sp_big = nqkv.decode_workspace_bytes(desc, pos + 1, 0)
+    assert sp_big == sp_small + 1
+    ws_small = torch.zeros(max(small, 16), dtype=torch.uint8, device="cuda")
+    before = [t.clone() for t in (kc, ks, vc, vs)]
+    with pytest.raises(nqkv.NqkvError) as e:
+        nqkv.decode_step(desc, lv, q, Kx[:, :, pos:pos + 1], Vx[:, :, pos:pos + 1], kc, ks, vc, vs, pos, 0.9, workspace=ws_small)
+    assert e.value.status == nqkv.EWORKSPACE
+    torch.cuda.synchronize()
+    for a, b in zip(before, (kc, ks, vc, vs)):
+        assert torch.equal(a, b)                           # an error: nothing was launched
+    ws_big = torch.zeros(big, dtype=torch.uint8, device="cuda")
+    out = nqkv.decode_step(desc, lv, q, Kx[:, :, pos:pos + 1], Vx[:, :, pos:pos + 1], kc, ks, vc, vs, pos, 0.9, workspace=ws_big)
+    torch.cuda.synchronize()
+    oracle.quantize_kv(Kh[:, :, pos:pos + 1], k, blk, lv, okc, oks, dst_off=pos)
+    oracle.quantize_kv(Vh[:, :, pos:pos + 1], k, blk, lv, ovc, ovs, dst_off=pos)
+    assert np.array_equal(h2n(kc), okc) and np.array_equal(h2n(ks), oks)
+    assert np.array_equal(h2n(vc), ovc) and np.array_equal(h2n(vs), ovs)
+    ref = oracle.decode_attention(h2n(q), okc, oks, ovc, ovs, k, blk, lv, pos + 1, 0.9, n_threads=4)
+    assert attn_err(h2n(out).view(np.float16), ref) <= ATTN_TOL
+    # per-sequence rows and pages: the in-kernel quantizer is the only path there
+    pos_dev = torch.full((B,), pos + 1, dtype=torch.int32, device="cuda")
+    with pytest.raises(nqkv.NqkvError) as e:
+        nqkv.decode_step_varlen(desc, lv, q, Kx[:, :, pos + 1:pos + 2], Vx[:, :, pos + 1:pos + 2], kc, ks, vc, vs, pos_dev, pos + 1, 0.9)
+    assert e.value.status == nqkv.EUNSUPPORTED
+    P = 128
+    pdesc = nqkv.make_desc(B, H, D, k, blk, P)
+    pool = [nqkv.alloc_paged_pool(pdesc, 8) for _ in range(2)]
+    table = torch.arange(8, dtype=torch.int32, device="cuda").reshape(B, 4)
+    pos_p = torch.full((B,), 10, dtype=torch.int32, device="cuda")
+    with pytest.raises(nqkv.NqkvError) as e:
+        nqkv.decode_step_paged(pdesc, lv, q, Kx[:, :, :1], Vx[:, :, :1], pool[0][0], pool[0][1], pool[1][0], pool[1][1], table, pos_p, 10, 0.9)
+    assert e.value.status == nqkv.EUNSUPPORTED
+
+
+def test_split_workspace_counters_init_check_and_poison(nqkv, oracle):
+    """The split-K workspace contract: counters zero on entry, zero again on exit; a workspace whose
+    counters are not zero is reported by the host-visible check (before a call: any non-zero
+    counter; after a call: the mark of a kernel that was handed an impossible ticket), and the
+    clearing kernel brings it back."""
+    k, D, blk = 4, 128, 64
+    B, H, S = 2, 4, 3000
+    lv, desc, q, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, S, S, seed=123)
+    need, splits = nqkv.decode_workspace_bytes(desc, S, 7)
+    assert splits == 7 and need > 256 * 1024
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)                                         # never cleared: every counter 0xffffffff
+    assert nqkv.decode_workspace_check(ws) == nqkv.EWORKSPACE
+    nqkv.decode_workspace_init(ws)
+    assert nqkv.decode_workspace_check(ws) == nqkv.OK
+    hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+    ref = oracle.decode_attention(*hk, k, blk, lv, S, 1.0, n_threads=8)
+    good = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, 1.0, workspace=ws, num_splits=7)
+    torch.cuda.synchronize()
+    assert attn_err(h2n(good).view(np.float16), ref) <= ATTN_TOL
+    assert nqkv.decode_workspace_check(ws) == nqkv.OK       # every call leaves the counters zero
+    # a counter that looks like a call in progress: caught by the check before the call ...
+    ws.view(torch.int32)[3] = 2
+    assert nqkv.decode_workspace_check(ws) == nqkv.EWORKSPACE
+    # ... and a clobbered one is marked by the kernel that meets it
+    nqkv.decode_workspace_init(ws)
+    ws.view(torch.int32)[:B * H] = -1
+    nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, 1.0, workspace=ws, num_splits=7)
+    torch.cuda.synchronize()
+    assert int(ws.view(torch.int32)[65535]) == 1
+    assert nqkv.decode_workspace_check(ws) == nqkv.EWORKSPACE
+    # cleared again, the same workspace gives the same bits as before
+    nqkv.decode_workspace_init(ws)
+    again = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, 1.0, workspace=ws, num_splits=7)
+    torch.cuda.synchronize()
+    assert torch.equal(again, good)
+    assert nqkv.decode_workspace_check(ws) == nqkv.OK
 
 
 # --------------------------------------------------------------------------- fused decode step

@@ -208,6 +208,13 @@ def test_decode_static_argument_errors(nqkv):
     assert "#define NQKV_STATIC_SCRATCH_BYTES (2u << 20)" in header and nqkv.STATIC_SCRATCH_BYTES == 2 << 20
 
 
+def test_workspace_init_and_check_argument_errors(nqkv):
+    for f in (nqkv.lib.nqkv_decode_workspace_init, nqkv.lib.nqkv_decode_workspace_check):
+        assert f(None, 1 << 20, None) == nqkv.EINVAL
+        assert f(FAKE + 8, 1 << 20, None) == nqkv.EINVAL
+        assert f(FAKE, 1000, None) == nqkv.EWORKSPACE             # the counters alone take 256 KiB
+
+
 def test_decode_step_argument_errors(nqkv):
     lv, lvp = _levels(nqkv)
     d = nqkv.make_desc(1, 32, 128, 4, 64, 32768)
