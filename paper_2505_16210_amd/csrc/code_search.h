@@ -8,14 +8,8 @@
 namespace nqkv {
 namespace code_search {
 
-// Cell grid of the fast path: u = 32 * x/s + 32.5 in [0.5, 64.5], cell = floor(u).
-constexpr int kCells = kQuantCells;
-constexpr float kCellScale = 32.0f;
-constexpr float kCellBias = 32.5f;
-// u is produced by an fma whose result is forced onto a 1/8 grid (error <= 1/16) from a
-// reciprocal good to 1 ulp (error < 1e-5 in u); 0.08 leaves > 5e-4 of slack in x/s, far more
-// than the 2^-24 relative rounding of fl32(t * s).
-constexpr float kCellMargin = 0.08f;
+// (the cell grid's constants -- kCells, kCellScale, kCellBias, kCellMargin -- are shared with the
+// host, which builds the table: see nqkv_internal.h)
 // Adding 2^20 puts the integer part of u in mantissa bits [3, 10): (bits & 0x3f8) is then
 // the byte offset of an 8-byte table entry.
 constexpr float kCellMagic = 1048576.0f + kCellBias;

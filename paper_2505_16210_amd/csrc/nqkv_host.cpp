@@ -10,6 +10,36 @@
 #include <cstring>
 #include <vector>
 
+namespace nqkv {
+
+// Entry c = { the one threshold that may lie in cell c widened by the margin (2.0 when there is
+// none: never exceeded, since |x| <= s), number of thresholds certainly below the cell }.
+// Returns false when some widened cell would hold two thresholds or the table leaves [-1, 1]:
+// such tables take the threshold scan.
+bool build_cell_table(const float* levels, int k, uint32_t* thr_bits, uint32_t* below) {
+  const int L = 1 << k;
+  if (!(levels[0] >= -1.0f && levels[L - 1] <= 1.0f)) return false;
+  for (int c = 0; c < code_search::kCells; ++c) {
+    const float lo = (float)c - code_search::kCellMargin;
+    const float hi = (float)c + 1.0f + code_search::kCellMargin;
+    int inside = 0;
+    uint32_t n_below = 0;
+    float cand = 2.0f;
+    for (int j = 1; j < L; ++j) {
+      const float t = (levels[j - 1] + levels[j]) * 0.5f;
+      const float tau = t * code_search::kCellScale + code_search::kCellBias;
+      if (tau < lo) ++n_below;
+      if (tau >= lo && tau <= hi) { cand = t; ++inside; }
+    }
+    if (inside > 1) return false;
+    std::memcpy(&thr_bits[c], &cand, 4);
+    below[c] = n_below;
+  }
+  return true;
+}
+
+}  // namespace nqkv
+
 namespace {
 
 using namespace nqkv;

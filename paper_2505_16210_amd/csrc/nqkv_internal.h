@@ -10,6 +10,17 @@ namespace nqkv {
 constexpr int kMaxLevels = 16;  // kernels take tables for k <= 4
 constexpr int kQuantCells = 65;  // index cells of the quantizer's code search
 
+namespace code_search {
+// Cell grid of the quantizer's fast code search: u = 32 * x/s + 32.5 in [0.5, 64.5], cell = floor(u).
+constexpr int kCells = kQuantCells;
+constexpr float kCellScale = 32.0f;
+constexpr float kCellBias = 32.5f;
+// u is produced by an fma whose result is forced onto a 1/8 grid (error <= 1/16) from a
+// reciprocal good to 1 ulp (error < 1e-5 in u); 0.08 leaves > 5e-4 of slack in x/s, far more
+// than the 2^-24 relative rounding of fl32(t * s).
+constexpr float kCellMargin = 0.08f;
+}  // namespace code_search
+
 // The quantile table travels to the kernels by value (64 bytes of kernel arguments).
 struct LevelTable {
   float v[kMaxLevels];
