@@ -18,7 +18,7 @@
 // (k = 4: two codes -> two fp16 levels in one dword; k = 2: four codes -> four fp16 in two
 // dwords; k = 3: a 6-bit pair -> one dword).  The kernel is bound by VALU issue as much as by
 // HBM, so the address of a look-up must cost one instruction: for k = 4 and k = 2 every table
-// row is 256 bytes (one private copy per lane, hence no bank conflicts), which lets a single
+// row is 256 bytes apart (with a private copy per lane, or per lane modulo 32: no bank conflicts), which lets a single
 // v_perm_b32 assemble  address = code_byte * 256 + lane_offset  from the code dword and a
 // per-lane constant.  (k = 3 pairs are not byte aligned: the 96-bit stream of a lane is shifted
 // as a whole so that four pairs at a time start on byte boundaries, see for_each_pair_k3.)
@@ -96,6 +96,27 @@ __device__ __forceinline__ void build_lut_bytes_k3(const DecodeParams& p, uint32
   for (int i = 0; i < 16; ++i) {
     const uint32_t hi_a = p.lut_levels[2 * (i & 3)], hi_b = p.lut_levels[2 * (i & 3) + 1];
     smem[(e0 + 16 * i) * 64 + copy] = lo | (((e0 >> 3) ? hi_b : hi_a) << 16);
+  }
+  __syncthreads();
+}
+
+// The table at k = 4: row = code byte B, 256 bytes apart, its first 128 bytes 32 copies of the dword
+// {level[B & 15], level[B >> 4]}; lane L reads copy L & 31 (a 64-lane dword read takes two LDS
+// clocks whatever it does, and 32 lanes on 32 distinct banks fit one of them: 32 copies are as
+// conflict-free as 64 and take half the stores).  The copies of a row hold one and the same dword,
+// so a thread writes four of them at a time: thread t takes low nibble t & 15, copies
+// 4 ((t >> 4) & 7) .. + 3 and the four high nibbles (t >> 7) + 4 i -- 4 wide stores per thread
+// where a dword at a time takes 32.  The high nibble is uniform over a wave: a scalar look-up.
+// Ends with a barrier.
+__device__ __forceinline__ void build_lut_k4(const DecodeParams& p, uint32_t* smem) {
+  const uint32_t e_lo = threadIdx.x & 15, quad = (threadIdx.x >> 4) & 7;
+  const uint32_t hi_base = __builtin_amdgcn_readfirstlane(threadIdx.x >> 7);       // 0..3
+  const uint32_t lo = pick_level(p, e_lo, 16);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t e_hi = hi_base + 4 * i;
+    const uint32_t v = lo | ((uint32_t)p.lut_levels[e_hi] << 16);
+    *reinterpret_cast<uint4*>(smem + (e_lo + 16 * e_hi) * 64 + quad * 4) = make_uint4(v, v, v, v);
   }
   __syncthreads();
 }
@@ -325,7 +346,7 @@ __device__ __forceinline__ void reduce_groups(const float (&acc)[32], uint32_t l
 // key and value rows (same code search as the quantizer), stores their codes and scales at row
 // pos, and adds the token to its softmax straight from registers.
 template <int KBITS, int D, int BLK, bool FUSE, bool SPLIT, bool VARLEN, bool PAGED>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) void decode_kernel(const DecodeParams p) {   // 128 VGPRs: two workgroups per CU
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdgpu_waves_per_eu(4, 4))) void decode_kernel(const DecodeParams p) {   // 128 VGPRs, four waves per SIMD: two workgroups per CU
   constexpr int LPT = D / 32;             // lanes per token
   constexpr int TPR = 64 / LPT;           // tokens per wave load
   constexpr int CHUNK = kRounds * TPR;    // tokens per wave trip
@@ -362,7 +383,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   const uint32_t j = lane % LPT, g = lane / LPT;
   // this lane's copy inside a table row; at k = 2 the row holds the key table and the value-pair
   // table side by side, 16 copies each (see build_lut_pairs_k2)
-  const uint32_t lane_off = (KBITS == 4) ? (lane << 2) : (KBITS == 2) ? ((lane & 15) << 3) : ((lane & 31) << 2);
+  const uint32_t lane_off = (KBITS == 2) ? ((lane & 15) << 3) : ((lane & 31) << 2);
   const uint32_t lane_off_v = (KBITS == 2) ? (128u + ((lane & 15) << 3)) : lane_off;
   const int32_t stride = kWaves * CHUNK;
 
@@ -522,7 +543,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128))) voi
   if (FUSE) load_new();
   if constexpr (KBITS == 2) build_lut_pairs_k2(p, smem);          // (each ends with a barrier)
   else if constexpr (KBITS == 3) build_lut_bytes_k3(p, smem);
-  else build_lut<KBITS>(p, smem);
+  else build_lut_k4(p, smem);
   if (FUSE && wave == kWaves - 1) {
     // only this wave searches codes: it stages the table for itself, no barrier needed (LDS
     // operations of one wave complete in order)
