@@ -65,6 +65,10 @@ def parse_args():
                     help="live: measure HBM bytes of the roofline kernel with two rocprofv3 counter passes over a child process")
     ap.add_argument("--kernel-launches", type=int, default=120, help="timed launches per kernel entry (>= 100)")
     ap.add_argument("--cold", type=int, default=1, help="1: rotate buffers to defeat the last-level cache")
+    ap.add_argument("--timeline", default="",
+                    help="instead of the benchmark: per-phase timestamps from inside the decode kernel for these "
+                         "configurations (e.g. C4,C3,C2), using the measurement build libnqkv_timeline.so "
+                         "(python paper_2505_16210_amd/build.py --timeline); prints a text report")
     ap.add_argument("--pmc-child", action="store_true", help=argparse.SUPPRESS)
     return ap.parse_args()
 
@@ -172,6 +176,9 @@ def main():
     args = parse_args()
     if args.pmc_child:
         pmc_child()
+        return
+    if args.timeline:
+        timeline_report(args.timeline.split(","))
         return
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path shards by batch/head with no "
@@ -368,6 +375,72 @@ def main():
         result["cpu_baseline"] = cpu_baseline(workloads, torch, dev)
     log("done")
     print(json.dumps(result))
+
+
+def timeline_report(config_names):
+    """Where the time of one decode launch goes, from inside the kernel: the measurement build of the
+    library records the 100 MHz real-time counter in every wave at eight points of its item's life
+    (paper_2505_16210_amd/csrc/decode_attention.hip, NQKV_TIMELINE).  One launch per rotating cache
+    copy (reads come from HBM); the stamps of the last launch are reported."""
+    import numpy as np
+    import torch
+    from paper_2505_16210_amd import build as lib_build, nqkv, workloads
+    if not os.path.exists(lib_build.TIMELINE_LIB):
+        sys.exit("bench.py --timeline: build the measurement library first (python paper_2505_16210_amd/build.py --timeline)")
+    nqkv.use_library(lib_build.TIMELINE_LIB)
+    dev = torch.device("cuda:0")
+    tick_us = 0.01                            # s_memrealtime counts at 100 MHz
+    names = ["wave running", "first loads issued", "table built", "trips begin", "trips end", "waves merged",
+             "partial published, ticket taken", "result stored"]
+    for cn in config_names:
+        cfg = workloads.CONFIGS[cn]
+        B, H, D, S, k, blk = cfg.B, cfg.H, cfg.D, cfg.S, cfg.bits, cfg.block
+        g = workloads.make_generator(cfg, dev)
+        K, V = workloads.make_kv(cfg, dev, g)
+        q = workloads.make_q(cfg, dev, g)
+        lv = nqkv.build_codebook(k)
+        desc = nqkv.make_desc(B, H, D, k, blk, S)
+        per_tok = workloads.decode_bytes_per_token_head(D, k, blk)
+        copies = max(2, min(32, -(-(1 << 30) // (B * H * S * per_tok))))
+        caches = []
+        for r in range(copies):
+            kc, ks = nqkv.alloc_cache(desc, dev)
+            vc, vs = nqkv.alloc_cache(desc, dev)
+            nqkv.quantize_kv_pair(desc, lv, K, V, kc, ks, vc, vs, 0)
+            caches.append((kc, ks, vc, vs))
+        out = torch.empty(B, H, D, dtype=torch.float16, device=dev)
+        ws = torch.zeros(2 << 20, dtype=torch.uint8, device=dev)
+        for fused in (False, True):
+            splits = nqkv.decode_workspace_bytes(desc, S - 1 if fused else S, 0)[1]
+            n_items = min(B * H * splits, 1024)
+            for _ in range(2):
+                for c in caches:
+                    if fused:
+                        nqkv.decode_step(desc, lv, q, K[:, :, S - 1:S], V[:, :, S - 1:S], *c, S - 1, 1.0, out=out, workspace=ws)
+                    else:
+                        nqkv.decode_attention(desc, lv, q, *c, S, 1.0, out=out, workspace=ws)
+                torch.cuda.synchronize()
+            d = ws[65536:65536 + n_items * 8 * 64].cpu().numpy().view(np.uint64).reshape(n_items, 8, 8).astype(np.int64)
+            ws[:65536 + 1024 * 8 * 64].zero_()
+            if splits == 1:
+                d[:, :, 6] = d[:, :, 5]                                   # no ticket is taken without a split
+            rel = (d - d[:, :, 0].min()) * tick_us
+            what = "fused decode step" if fused else "decode attention"
+            grid = "one workgroup per item" if S // splits >= 4096 else "persistent grid of at most 512 workgroups"
+            print("== %s %s: B %d H %d D %d S %d, %d-bit block %d, %d pieces per sequence, %d work items (%s)"
+                  % (cn, what, B, H, D, S, k, blk, splits, B * H * splits, grid))
+            print("   span inside the kernel (first wave running -> last result stored): %.2f us" % rel[:, :, 7].max())
+            print("   workgroup start   min %.2f  median %.2f  max %.2f us" % (rel[:, 0, 0].min(), float(np.median(rel[:, 0, 0])), rel[:, 0, 0].max()))
+            for j in range(1, 8):
+                x = (d[:, :, j] - d[:, :, j - 1]) * tick_us
+                print("   %-32s -> %-32s mean %6.2f  min %6.2f  max %6.2f us" % (names[j - 1], names[j], x.mean(), x.min(), x.max()))
+            ends = rel[:, :, 7].max(axis=1)
+            print("   workgroup end percentiles 0/25/50/75/100: " + " ".join("%.2f" % v for v in np.percentile(ends, [0, 25, 50, 75, 100])))
+            if B * H * splits > 1024 or S // splits < 4096:
+                print("   (persistent grid: the stamps are those of each workgroup's items as it met them; 'wave running', 'first loads issued' "
+                      "and 'table built' are the workgroup's own start-up and appear once)")
+        del caches
+        torch.cuda.empty_cache()
 
 
 def bench_config(nqkv, workloads, torch, dev, base, variants, configs_out, kern, timed_graph, entry, cold, extras,

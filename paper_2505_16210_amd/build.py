@@ -25,12 +25,13 @@ SOURCES = [
     ("decode_multi.hip", []),
     ("static_scratch.hip", []),
 ]
+TIMELINE_LIB = os.path.join(HERE, "libnqkv_timeline.so")      # measurement build, see build_timeline_library
 AUX_LIB = os.path.join(HERE, "libnqkv_benchaux.so")
 AUX_SOURCES = [("bench_aux.hip", [])]
 
 
-def _compile(src: str, extra: list, verbose: bool, save_temps: bool) -> str:
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+def _compile(src: str, extra: list, verbose: bool, save_temps: bool, tag: str = "") -> str:
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + tag + ".o")
     cmd = [HIPCC, *COMMON, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     if save_temps:
         cmd.append("--save-temps=obj")
@@ -63,5 +64,24 @@ def build_library(verbose: bool = False, save_temps: bool = False, jobs: int = 4
     return LIB
 
 
+def build_timeline_library(verbose: bool = False) -> str:
+    """libnqkv_timeline.so: the library with the decode kernel compiled -DNQKV_TIMELINE (every wave
+    leaves eight timestamps of its item in the workspace).  For `bench.py --timeline` only; needs
+    the objects of build_library()."""
+    os.makedirs(OBJ, exist_ok=True)
+    objs = [os.path.join(OBJ, os.path.splitext(s)[0] + ".o") for s, _ in SOURCES if s != "decode_attention.hip"]
+    if not all(os.path.exists(o) for o in objs):
+        build_library(verbose=verbose)
+    objs.append(_compile("decode_attention.hip", ["-DNQKV_TIMELINE"], verbose, False, tag="_timeline"))
+    tmp = TIMELINE_LIB + ".tmp.%d" % os.getpid()
+    r = subprocess.run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objs], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stderr)
+    os.replace(tmp, TIMELINE_LIB)
+    return TIMELINE_LIB
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True, save_temps="--save-temps" in sys.argv))
+    if "--timeline" in sys.argv:
+        print(build_timeline_library(verbose=True))

@@ -52,9 +52,26 @@
 #include "nqkv_internal.h"
 #include "scalar_read.h"
 
+// Measurement build (-DNQKV_TIMELINE, see build.py --timeline): every wave records the 100 MHz
+// real-time counter at eight points of an item's life and leaves them in the caller's workspace,
+// 64 bytes per wave at byte offset kTimelineOffset + (item * 8 + wave) * 64, for items below
+// kTimelineItems.  The stamps overwrite unused ticket counters (a call has at most 65535 of them and
+// the configurations this is for use a few hundred), so such a build is for timing studies with
+// fewer than 16384 (batch, head) pairs and a workspace of at least 1 MiB, and for nothing else.
+#ifdef NQKV_TIMELINE
+#define NQKV_STAMP(k_)                                     \
+  do {                                                     \
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     \
+    timeline[k_] = __builtin_amdgcn_s_memrealtime();       \
+  } while (0)
+#else
+#define NQKV_STAMP(k_) do { } while (0)
+#endif
+
 namespace nqkv {
 namespace {
 
+constexpr int kTimelineOffset = 65536, kTimelineItems = 1024;
 constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
 constexpr int kRounds = 4;               // wave loads of K (and of V) in flight per trip
@@ -532,6 +549,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
   // The first item's K loads and query slice go out before anything else, so HBM latency
   // overlaps the table build.
   uint32_t item = blockIdx.x;
+#ifdef NQKV_TIMELINE
+  uint64_t timeline[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+  NQKV_STAMP(0);                       // the wave is running
   // FUSE: lane l fetches entry l of the code-search cell table.  These are vector loads from the
   // kernel arguments; they go out first so that waiting for them (the memory counter is
   // positional) never means waiting for the cache prefetches behind them.
@@ -541,9 +562,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
   load_k(base);
   load_q();
   if (FUSE) load_new();
+  NQKV_STAMP(1);                       // first loads issued
   if constexpr (KBITS == 2) build_lut_pairs_k2(p, smem);          // (each ends with a barrier)
   else if constexpr (KBITS == 3) build_lut_bytes_k3(p, smem);
   else build_lut_k4(p, smem);
+  NQKV_STAMP(2);                       // table built
   if (FUSE && wave == kWaves - 1) {
     // only this wave searches codes: it stages the table for itself, no barrier needed (LDS
     // operations of one wave complete in order)
@@ -633,6 +656,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
       __builtin_amdgcn_s_setprio(0);
     }
 
+    NQKV_STAMP(3);                     // trips begin
     for (; base < n_tok; base += stride) {
       const int32_t left = n_tok - base;      // tokens of the item from this trip on (uniform)
       load_v(base);
@@ -690,6 +714,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
       }
     }
 
+    NQKV_STAMP(4);                     // trips end
     // ---- this item is streamed; remember where its result goes, then start the next item's
     // first K loads so that they fly during the merge
     const uint32_t cur_bh = bh, cur_sp = sp;
@@ -745,6 +770,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
         const_cast<uint16_t*>(t ? p.v_scales : p.k_scales)[row * NB + w] = (uint16_t)new_scales[t][w];
       }
     }
+    NQKV_STAMP(5);                     // waves merged (past the barrier)
     float m_all = wave_m[0];
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) m_all = fmaxf(m_all, wave_m[w]);
@@ -777,6 +803,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
       __syncthreads();
       // A ticket this call cannot have handed out: the counter did not start at zero (a workspace
       // that was never cleared, or clobbered since).  Leave a mark that the host can ask for.
+      NQKV_STAMP(6);                   // partial result published, ticket taken
       if (ticket_sh >= (uint32_t)p.splits && tid == 0)
         __hip_atomic_fetch_or(p.tickets + kWorkspaceStatusWord, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (ticket_sh == (uint32_t)p.splits - 1u) {           // uniform over the workgroup
@@ -828,6 +855,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
         if (tid == 0) __hip_atomic_store(p.tickets + cur_bh, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
+#ifdef NQKV_TIMELINE
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    NQKV_STAMP(7);                     // output (or the combined result) stored and acknowledged
+    if (lane == 0 && p.tickets && item < (uint32_t)kTimelineItems) {
+      unsigned long long* rec = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(p.tickets) + kTimelineOffset) +
+                                ((size_t)item * kWaves + wave) * 8;
+      for (int k_ = 0; k_ < 8; ++k_) rec[k_] = timeline[k_];
+    }
+#endif
     settle_q();           // before the exit test, so that every path back to the loop head has it
     if (!more) break;
     item = next_item;

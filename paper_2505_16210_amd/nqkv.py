@@ -44,11 +44,11 @@ class NqkvError(RuntimeError):
         super().__init__("%s: %s (%d)" % (where, strerror(status), status))
 
 
-def _load() -> ctypes.CDLL:
-    if not os.path.exists(LIB_PATH):
-        raise ImportError("libnqkv.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
-                          "(or python paper_2505_16210_amd/build.py) first; there is no fallback path")
-    lib = ctypes.CDLL(LIB_PATH)
+def _load(path: str = LIB_PATH) -> ctypes.CDLL:
+    if not os.path.exists(path):
+        raise ImportError("%s is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(or python paper_2505_16210_amd/build.py) first; there is no fallback path" % os.path.basename(path))
+    lib = ctypes.CDLL(path)
     c = ctypes
     vp, i64, i32 = c.c_void_p, c.c_int64, c.c_int
     dp = c.POINTER(CacheDesc)
@@ -118,6 +118,13 @@ def _load() -> ctypes.CDLL:
 
 
 lib = _load()
+
+
+def use_library(path: str) -> None:
+    """Point the binding at another build of the same C ABI (the timestamp-instrumented measurement
+    build of build.py --timeline); every later call goes there."""
+    global lib
+    lib = _load(path)
 
 
 def strerror(status: int) -> str:
