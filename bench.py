@@ -69,39 +69,53 @@ def parse_args():
                     help="instead of the benchmark: per-phase timestamps from inside the decode kernel for these "
                          "configurations (e.g. C4,C3,C2), using the measurement build libnqkv_timeline.so "
                          "(python paper_2505_16210_amd/build.py --timeline); prints a text report")
-    ap.add_argument("--pmc-child", action="store_true", help=argparse.SUPPRESS)
+    ap.add_argument("--kernels-only", default="",
+                    help="for profiler runs (rocprofv3 --kernel-trace / --pmc ... -- python3 bench.py --kernels-only C3,C4,C5): "
+                         "a plain 1 GiB copy kernel (the yardstick HBM byte counters are scaled by), then quantize, decode "
+                         "attention, fused decode step and dequantize of these configurations, three eager launches each; "
+                         "no timing, no JSON")
     return ap.parse_args()
 
 
 # ---------------------------------------------------------------------------------------------
 # HBM traffic of the roofline kernel, measured in this run: rocprofv3 --pmc over a child process
 # ---------------------------------------------------------------------------------------------
-def pmc_child():
-    """Runs under rocprofv3 --pmc: a plain copy of known size, then the kernels of the C5 step."""
+def kernels_only(config_names, sweep):
+    """Runs under a profiler: a plain copy of known size, then the kernels of the named configurations."""
     import torch
     from paper_2505_16210_amd import benchaux, nqkv, workloads
     dev = torch.device("cuda:0")
-    cfg = workloads.C5
-    B, H, D, S, k, blk = cfg.B, cfg.H, cfg.D, cfg.S, cfg.bits, cfg.block
     a = torch.ones(CALIB_BYTES // 4, dtype=torch.int32, device=dev)
     b = torch.empty_like(a)
     for _ in range(3):
         benchaux.copy(b, a)
     torch.cuda.synchronize()
     del a, b
-    g = workloads.make_generator(cfg, dev)
-    K, V = workloads.make_kv(cfg, dev, g, n_tokens=S + 1)
-    q = workloads.make_q(cfg, dev, g)
-    lv = nqkv.build_codebook(k)
-    desc = nqkv.make_desc(B, H, D, k, blk, S + 1)
-    kc, ks = nqkv.alloc_cache(desc, dev)
-    vc, vs = nqkv.alloc_cache(desc, dev)
-    out = torch.empty_like(q)
-    for _ in range(2):
-        nqkv.quantize_kv_pair(desc, lv, K[:, :, :S], V[:, :, :S], kc, ks, vc, vs, 0)
-        nqkv.decode_step(desc, lv, q, K[:, :, S:], V[:, :, S:], kc, ks, vc, vs, S, 1.0, out=out)
-        nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S + 1, 1.0, out=out)
-    torch.cuda.synchronize()
+    for cn in config_names:
+        cfg = workloads.CONFIGS[cn]
+        B, H, D, S = cfg.B, cfg.H, cfg.D, cfg.S
+        g = workloads.make_generator(cfg, dev)
+        K, V = workloads.make_kv(cfg, dev, g, n_tokens=S + 1)
+        q = workloads.make_q(cfg, dev, g)
+        out = torch.empty_like(q)
+        variants = [(kb, bl) for kb in (4, 3, 2) for bl in (64, 128)] if (cn == "C5" and sweep) else [(cfg.bits, cfg.block)]
+        for kb, bl in variants:
+            lv = nqkv.build_codebook(kb)
+            desc = nqkv.make_desc(B, H, D, kb, bl, S + 1)
+            kc, ks = nqkv.alloc_cache(desc, dev)
+            vc, vs = nqkv.alloc_cache(desc, dev)
+            ws = torch.zeros(2 << 20, dtype=torch.uint8, device=dev)
+            back = torch.empty(B, H, S, D, dtype=torch.float16, device=dev)
+            for _ in range(3):
+                nqkv.quantize_kv_pair(desc, lv, K[:, :, :S], V[:, :, :S], kc, ks, vc, vs, 0)
+                nqkv.decode_step(desc, lv, q, K[:, :, S:], V[:, :, S:], kc, ks, vc, vs, S, 1.0, out=out, workspace=ws)
+                nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S + 1, 1.0, out=out, workspace=ws)
+                nqkv.dequantize_kv(desc, lv, kc, ks, 0, S, out=back)
+            torch.cuda.synchronize()
+            del kc, ks, vc, vs, back
+            torch.cuda.empty_cache()
+        del K, V
+        torch.cuda.empty_cache()
 
 
 def _counter_per_dispatch(db_path, counter):
@@ -134,7 +148,7 @@ def measure_traffic_live():
         outdir = tempfile.mkdtemp(prefix="nqkv_pmc_", dir="/tmp")
         try:
             env = dict(os.environ, TMPDIR="/tmp")
-            cmd = [prof, "--pmc", counter, "-d", outdir, "-o", "p", "--", sys.executable, os.path.join(ROOT, "bench.py"), "--pmc-child"]
+            cmd = [prof, "--pmc", counter, "-d", outdir, "-o", "p", "--", sys.executable, os.path.join(ROOT, "bench.py"), "--kernels-only", "C5", "--no-sweep"]
             r = subprocess.run(cmd, cwd="/tmp", env=env, capture_output=True, text=True, timeout=240)
             if r.returncode != 0:
                 return "rocprofv3 --pmc %s exited with %d: %s" % (counter, r.returncode, (r.stderr or r.stdout)[-200:].replace("\n", " "))
@@ -174,8 +188,8 @@ def measure_traffic_live():
 # ---------------------------------------------------------------------------------------------
 def main():
     args = parse_args()
-    if args.pmc_child:
-        pmc_child()
+    if args.kernels_only:
+        kernels_only([c for c in args.kernels_only.split(",") if c], not args.no_sweep)
         return
     if args.timeline:
         timeline_report(args.timeline.split(","))
