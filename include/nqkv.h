@@ -225,8 +225,11 @@ int nqkv_decode_workspace_check(const void* workspace, size_t workspace_bytes, v
  *                 (see there); may be NULL when that size is 0
  * Arithmetic: table entries are rounded to fp16 for the look-up, products accumulate in
  * fp32, exp in fp32; the result is within 2e-3 (relative to the largest |out| of the row)
- * of the same formula evaluated in fp64.  Different num_splits give results that differ
- * by rounding only; equal arguments give equal bits.
+ * of the same formula evaluated in fp64.  At k = 4 and k = 2 the product softmax weight x
+ * value scale is rounded to fp16 before it multiplies the levels (two tokens share one
+ * instruction): value blocks whose scale is below 2^-14 lose precision, and single outputs
+ * can be off by up to 1e-2 of max(|out|, 1 % of the row's largest |out|).  Different
+ * num_splits give results that differ by rounding only; equal arguments give equal bits.
  * Errors: as above, plus NQKV_EINVAL for seq_len outside [1, cap_tokens] and
  * NQKV_EWORKSPACE for a short workspace.
  */
