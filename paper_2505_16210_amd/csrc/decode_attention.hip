@@ -18,7 +18,8 @@
 // (k = 4: two codes -> two fp16 levels in one dword; k = 2: four codes -> four fp16 in two
 // dwords; k = 3: a 6-bit pair -> one dword).  The kernel is bound by VALU issue as much as by
 // HBM, so the address of a look-up must cost one instruction: for k = 4 and k = 2 every table
-// row is 256 bytes apart (with a private copy per lane, or per lane modulo 32: no bank conflicts), which lets a single
+// row is 256 bytes apart (32 copies of the entry, lane L reading copy L mod 32: no bank
+// conflicts), which lets a single
 // v_perm_b32 assemble  address = code_byte * 256 + lane_offset  from the code dword and a
 // per-lane constant.  (k = 3 pairs are not byte aligned: the 96-bit stream of a lane is shifted
 // as a whole so that four pairs at a time start on byte boundaries, see for_each_pair_k3.)
@@ -231,26 +232,29 @@ __device__ __forceinline__ void v_axpy(const uint32_t (&w)[KBITS], float wgt, fl
 
 // V side, two tokens at a time: acc[e] += w(t0) * level[code(t0, e)] + w(t1) * level[code(t1, e)]
 // with ONE v_dot2_f32_f16 per element, where the one-token form above spends one v_fma_mix per
-// (token, element).  The code dwords of the two tokens are merged nibble by nibble first --
-//     a = (w0 & 0x0f0f0f0f) | ((w1 << 4) & 0xf0f0f0f0)      low  nibbles of every byte, t0 | t1 << 4
-//     b = ((w0 >> 4) & 0x0f0f0f0f) | (w1 & 0xf0f0f0f0)      high nibbles
-// (four instructions per dword pair) -- so that a byte of `a` or `b` holds the codes of the SAME
-// elements of the two tokens and the byte-indexed table returns them side by side, {level of t0,
-// level of t1}, ready to be contracted with the fp16 pair of weights.  k = 4: a nibble is one code
-// and the table is the key side's own; k = 2: a nibble is two codes (elements e, e + 1) and the
-// pairs come from a second table (see build_lut_pairs).  The weights w = p * value scale are
-// rounded to fp16 (round to nearest): a relative error of 2^-11 per term, of random sign.
+// (token, element).  The code dwords of the two tokens are interleaved field by field first, a
+// field being one code (F = k bits, mask M = the even fields of every byte):
+//     a = (w0 & M) | ((w1 << F) & ~M)        even fields of t0, each followed by the same field of t1
+//     b = ((w0 >> F) & M) | (w1 & ~M)        odd fields likewise
+// (four instructions per dword pair), so that in `a` and `b` the code of an element of t0 is
+// followed by the code of the SAME element of t1, and the byte-indexed table of the key side --
+// which maps every field of a byte to its level, whatever the field means -- returns them side by
+// side, {level of t0, level of t1}, ready to be contracted with the fp16 pair of weights.
+// k = 4: a byte of `a` is element 2 j of both tokens, of `b` element 2 j + 1.  k = 2: a byte of `a`
+// is elements 4 j and 4 j + 2 of both tokens (one 64-bit look-up, two contractions), of `b`
+// elements 4 j + 1 and 4 j + 3.  The weights w = p * value scale are rounded to fp16 (round to
+// nearest): a relative error of 2^-11 per term, of random sign.
 template <int KBITS>
 __device__ __forceinline__ void v_axpy_pair(const uint32_t (&w0)[KBITS], const uint32_t (&w1)[KBITS], half2_t wgt2,
-                                            float (&acc)[32], const char* lut, uint32_t lane_off_v) {
-  static_assert(KBITS == 4 || KBITS == 2, "3-bit codes do not align with nibbles");
-  constexpr uint32_t M = 0x0f0f0f0fu;
+                                            float (&acc)[32], const char* lut, uint32_t lane_off) {
+  static_assert(KBITS == 4 || KBITS == 2, "3-bit codes do not align with bytes");
+  constexpr uint32_t M = (KBITS == 4) ? 0x0f0f0f0fu : 0x33333333u;
 #pragma unroll
   for (int i = 0; i < KBITS; ++i) {
-    const uint32_t a = (w0[i] & M) | ((w1[i] << 4) & ~M);
-    const uint32_t b = ((w0[i] >> 4) & M) | (w1[i] & ~M);
-    const uint32_t aa[4] = {row_addr<0>(a, lane_off_v), row_addr<1>(a, lane_off_v), row_addr<2>(a, lane_off_v), row_addr<3>(a, lane_off_v)};
-    const uint32_t ab[4] = {row_addr<0>(b, lane_off_v), row_addr<1>(b, lane_off_v), row_addr<2>(b, lane_off_v), row_addr<3>(b, lane_off_v)};
+    const uint32_t a = (w0[i] & M) | ((w1[i] << KBITS) & ~M);
+    const uint32_t b = ((w0[i] >> KBITS) & M) | (w1[i] & ~M);
+    const uint32_t aa[4] = {row_addr<0>(a, lane_off), row_addr<1>(a, lane_off), row_addr<2>(a, lane_off), row_addr<3>(a, lane_off)};
+    const uint32_t ab[4] = {row_addr<0>(b, lane_off), row_addr<1>(b, lane_off), row_addr<2>(b, lane_off), row_addr<3>(b, lane_off)};
     if constexpr (KBITS == 4) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -262,39 +266,32 @@ __device__ __forceinline__ void v_axpy_pair(const uint32_t (&w0)[KBITS], const u
     } else {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const uint2 lo = *reinterpret_cast<const uint2*>(lut + aa[j]);
-        const uint2 hi = *reinterpret_cast<const uint2*>(lut + ab[j]);
+        const uint2 ev = *reinterpret_cast<const uint2*>(lut + aa[j]);
+        const uint2 od = *reinterpret_cast<const uint2*>(lut + ab[j]);
         const int e = 16 * i + 4 * j;
-        acc[e + 0] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, lo.x), wgt2, acc[e + 0], false);
-        acc[e + 1] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, lo.y), wgt2, acc[e + 1], false);
-        acc[e + 2] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, hi.x), wgt2, acc[e + 2], false);
-        acc[e + 3] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, hi.y), wgt2, acc[e + 3], false);
+        acc[e + 0] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, ev.x), wgt2, acc[e + 0], false);
+        acc[e + 2] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, ev.y), wgt2, acc[e + 2], false);
+        acc[e + 1] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, od.x), wgt2, acc[e + 1], false);
+        acc[e + 3] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, od.y), wgt2, acc[e + 3], false);
       }
     }
   }
 }
 
-// Look-up tables of this kernel at k = 2.  A table row (one per code byte) is 256 bytes, so that
-// one v_perm_b32 forms the address; the row is shared by two tables of 16 lane copies each:
-//   bytes [0, 128)    key side, byte = four codes of one token:       {l[c0], l[c1]}, {l[c2], l[c3]}
-//   bytes [128, 256)  value side, byte = nibble of t0 | nibble of t1 << 4, a nibble = the codes of
-//                     elements e, e + 1:    {l[t0, e], l[t1, e]}, {l[t0, e + 1], l[t1, e + 1]}
-//                     -- with c0..c3 the byte's four 2-bit fields: {l[c0], l[c2]}, {l[c1], l[c3]}
-// Lane L reads copy L & 15 (eight bytes per copy).  Thread t writes dword t & 63 of rows
-// (t >> 6) + 8 i: the fields c0 and c1 follow from the thread index and i & 1, c2 and c3 from the
-// loop counter alone (scalar registers).  Ends with a barrier.
-__device__ __forceinline__ void build_lut_pairs_k2(const DecodeParams& p, uint32_t* smem) {
-  const uint32_t c = threadIdx.x & 63, e0 = threadIdx.x >> 6;            // e0 in [0, 8)
-  const uint32_t l0 = pick_level(p, e0 & 3, 4);
-  const uint32_t l1_even = pick_level(p, e0 >> 2, 4), l1_odd = pick_level(p, (e0 >> 2) + 2, 4);
-  const bool value_side = c >= 32, second = c & 1;
+// The table at k = 2: row = code byte B with 2-bit fields c0..c3, 256 bytes apart: 32 copies of the
+// eight bytes {level[c0], level[c1]}, {level[c2], level[c3]}; lane L reads copy L & 31 (a 64-lane
+// 64-bit read takes four LDS clocks whatever it does, and 32 lanes on distinct bank pairs fit two of
+// them: no conflicts, where 16 copies conflict two ways).  Thread t writes copies 2 (t & 15),
+// 2 (t & 15) + 1 (one 128-bit store) of rows (t >> 4) + 32 i: c0 and c1 follow from the thread
+// index, c2 = (t >> 8) + 2 (i & 1) and c3 = i >> 1 are uniform over a wave.  Ends with a barrier.
+__device__ __forceinline__ void build_lut_k2(const DecodeParams& p, uint32_t* smem) {
+  const uint32_t quad = threadIdx.x & 15, r0 = threadIdx.x >> 4;                 // r0 in [0, 32)
+  const uint32_t c2_base = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);     // 0 or 1
+  const uint32_t lo = pick_level(p, r0 & 3, 4) | (pick_level(p, (r0 >> 2) & 3, 4) << 16);
 #pragma unroll
-  for (int i = 0; i < 32; ++i) {
-    const uint32_t l1 = (i & 1) ? l1_odd : l1_even;
-    const uint32_t l2 = p.lut_levels[(i >> 1) & 3], l3 = p.lut_levels[i >> 3];
-    const uint32_t key_dw = second ? (l2 | (l3 << 16)) : (l0 | (l1 << 16));
-    const uint32_t val_dw = second ? (l1 | (l3 << 16)) : (l0 | (l2 << 16));
-    smem[(e0 + 8 * i) * 64 + c] = value_side ? val_dw : key_dw;
+  for (int i = 0; i < 8; ++i) {
+    const uint32_t hi = (uint32_t)p.lut_levels[c2_base + 2 * (i & 1)] | ((uint32_t)p.lut_levels[i >> 1] << 16);
+    *reinterpret_cast<uint4*>(smem + (r0 + 32 * i) * 64 + quad * 4) = make_uint4(lo, hi, lo, hi);
   }
   __syncthreads();
 }
@@ -398,10 +395,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
   // test) is uniform control flow for the compiler
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t j = lane % LPT, g = lane / LPT;
-  // this lane's copy inside a table row; at k = 2 the row holds the key table and the value-pair
-  // table side by side, 16 copies each (see build_lut_pairs_k2)
-  const uint32_t lane_off = (KBITS == 2) ? ((lane & 15) << 3) : ((lane & 31) << 2);
-  const uint32_t lane_off_v = (KBITS == 2) ? (128u + ((lane & 15) << 3)) : lane_off;
+  // this lane's copy inside a table row: 32 copies of a dword (k = 3, 4) or of a dword pair (k = 2)
+  const uint32_t lane_off = (lane & 31) << (KBITS == 2 ? 3 : 2);
   const int32_t stride = kWaves * CHUNK;
 
   uint32_t kw[kRounds][KBITS], vw[kRounds][KBITS];
@@ -563,7 +558,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
   load_q();
   if (FUSE) load_new();
   NQKV_STAMP(1);                       // first loads issued
-  if constexpr (KBITS == 2) build_lut_pairs_k2(p, smem);          // (each ends with a barrier)
+  if constexpr (KBITS == 2) build_lut_k2(p, smem);          // (each ends with a barrier)
   else if constexpr (KBITS == 3) build_lut_bytes_k3(p, smem);
   else build_lut_k4(p, smem);
   NQKV_STAMP(2);                       // table built
@@ -678,7 +673,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
 #pragma unroll
         for (int r = 0; r < kRounds; ++r) z[r] = ((int32_t)g < left - r * TPR) ? z[r] : -INFINITY;
       }
-      float m_trip = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+      float m_trip = fmaxf(z[0], z[1]);
+#pragma unroll
+      for (int r = 2; r < kRounds; r += 2) m_trip = fmaxf(m_trip, fmaxf(z[r], z[r + 1]));
       m_trip = wave_max<LPT>(m_trip);          // the LPT lanes of a token hold the same scores
       if (m_trip > m_run) {            // uniform across the wave
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_trip);
@@ -709,7 +706,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
           const float w_a = __builtin_fmaf(pw[r], (float)__builtin_bit_cast(_Float16, vsc[r]), 0.0f);
           const float w_b = __builtin_fmaf(pw[r + 1], (float)__builtin_bit_cast(_Float16, vsc[r + 1]), 0.0f);
           const half2_t wgt2 = {(_Float16)w_a, (_Float16)w_b};
-          v_axpy_pair<KBITS>(vw[r], vw[r + 1], wgt2, acc, lut, lane_off_v);
+          v_axpy_pair<KBITS>(vw[r], vw[r + 1], wgt2, acc, lut, lane_off);
         }
       }
     }
