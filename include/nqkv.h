@@ -104,7 +104,8 @@ int nqkv_build_codebook(int k, int variant, float* levels_out);
 /* Geometry of one cache tensor.  Plain data, read during the call only. */
 typedef struct nqkv_cache_desc {
   int32_t B;           /* batch rows, >= 1                                                   */
-  int32_t H;           /* heads, >= 1; B*H <= 65535                                          */
+  int32_t H;           /* heads, 1..65535; B <= 32767, B*H <= 2^24 (<= 65535 when a call   */
+                       /* cuts sequences into pieces: num_splits > 1)                        */
   int32_t D;           /* head dimension: 64 or 128                                          */
   int32_t k;           /* bits per index: 2, 3 or 4                                          */
   int32_t block;       /* elements per scale: 64 or 128, must divide D                       */

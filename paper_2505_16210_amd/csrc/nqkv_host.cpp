@@ -45,6 +45,8 @@ namespace {
 using namespace nqkv;
 
 constexpr int64_t kLongItemTokens = 4096;   // see fill_decode_common
+constexpr int64_t kMaxSequences = (int64_t)1 << 24;      // (batch row, head) pairs of one cache
+constexpr int64_t kMaxCutSequences = 65535;              // ... of a cache whose sequences are cut: one ticket counter each
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -57,7 +59,8 @@ int check_desc(const nqkv_cache_desc* d) {
   if (d->D != 64 && d->D != 128) return NQKV_EUNSUPPORTED;
   if (d->block != 64 && d->block != 128) return NQKV_EUNSUPPORTED;
   if (d->D % d->block != 0) return NQKV_EINVAL;
-  if ((int64_t)d->B * d->H > 65535) return NQKV_EUNSUPPORTED;   // grid dimension and ticket table
+  // 16-bit grid dimensions (heads in y, batch rows of one or two tensors in z) and 32-bit item counts
+  if (d->H > 65535 || d->B > 32767 || (int64_t)d->B * d->H > kMaxSequences) return NQKV_EUNSUPPORTED;
   if (d->cap_tokens > ((int64_t)1 << 31) - 1) return NQKV_EUNSUPPORTED;
   return NQKV_OK;
 }
@@ -193,6 +196,7 @@ int plan_splits(const nqkv_cache_desc* d, int64_t seq_len, int num_splits, int* 
   if (num_splits < 0 || num_splits > 1024) return NQKV_EINVAL;
   if (num_splits > 0) {
     if ((int64_t)num_splits > seq_len) return NQKV_EINVAL;
+    if (num_splits > 1 && (int64_t)d->B * d->H > kMaxCutSequences) return NQKV_EUNSUPPORTED;
     *splits = num_splits;
     return NQKV_OK;
   }
@@ -223,6 +227,7 @@ int plan_multi(const nqkv_cache_desc* d, int64_t seq_len, int64_t max_tokens, in
   const int64_t trips = (seq_len + decode_multi_trip_tokens() - 1) / decode_multi_trip_tokens();
   if (num_splits > 0) {
     if ((int64_t)num_splits > trips) return NQKV_EINVAL;
+    if (num_splits > 1 && (int64_t)d->B * d->H > kMaxCutSequences) return NQKV_EUNSUPPORTED;
     *splits = num_splits;
     return NQKV_OK;
   }

@@ -378,7 +378,8 @@ template <int KBITS, int D, int BLK>
 hipError_t launch_one(const QuantParams& p, hipStream_t stream) {
   constexpr int CPR = D / 8;
   const int64_t chunks_per_slab = p.n_tokens * CPR;
-  const bool flat = chunks_per_slab < 2 * kThreads;     // few tokens per (b,h): one flat grid over all rows
+  // few tokens per (b,h): one flat grid over all rows (its chunk index is a 32-bit number)
+  const bool flat = chunks_per_slab < 2 * kThreads && chunks_per_slab * p.B * p.H < ((int64_t)1 << 31);
   const bool fast = p.impl == 0;
   const int tile = kThreads * kUnroll;
   dim3 grid;

@@ -123,7 +123,7 @@ int main() {
     CHECK(nqkv_quantize_kv(&bad, lv, P, 0, 0, 64, 1, 0, P, P, nullptr) == NQKV_EINVAL);
     bad = d; bad.D = 96;
     CHECK(nqkv_quantize_kv(&bad, lv, P, 0, 0, 64, 1, 0, P, P, nullptr) == NQKV_EUNSUPPORTED);
-    bad = d; bad.B = 4096; bad.H = 16;
+    bad = d; bad.B = 4096; bad.H = 4097;
     CHECK(nqkv_quantize_kv(&bad, lv, P, 0, 0, 64, 1, 0, P, P, nullptr) == NQKV_EUNSUPPORTED);
     CHECK(nqkv_quantize_kv(nullptr, lv, P, 0, 0, 64, 1, 0, P, P, nullptr) == NQKV_EINVAL);
     CHECK(nqkv_quantize_kv(&d, lv, P, 0, 0, 64, 2, 15, P, P, nullptr) == NQKV_EINVAL);

@@ -1379,3 +1379,69 @@ def test_quantize_dequantize_random_windows(nqkv, oracle):
         nqkv.dequantize_kv(desc, lv, codes, scales, off2, n2, out=out)
         torch.cuda.synchronize()
         assert np.array_equal(h2n(out.contiguous()), ref), ("dequantize", case, k, D, blk, B, H, cap, n2, off2)
+
+
+# --------------------------------------------------------------------------- more than 65535 sequences
+@pytest.mark.gpu
+@pytest.mark.parametrize("k,D,blk,B,H,n0", [(4, 64, 64, 1100, 64, 70), (3, 128, 64, 1031, 64, 40), (2, 128, 128, 300, 257, 33)])
+def test_more_than_65535_sequences(nqkv, oracle, k, D, blk, B, H, n0):
+    """B*H beyond the 16-bit range (no kernel may fold batch row and head into a 16-bit grid
+    dimension or a 32-bit element index): prefill through the slab quantizer (n0 tokens: past the
+    flat kernel's reach), a few-token append through the flat one, dequantize, attention, the fused
+    step, per-sequence lengths and the several-queries kernel, each against the oracle for every
+    sequence."""
+    assert B * H > 65535
+    cap = n0 + 8
+    lv = nqkv.build_codebook(k)
+    g = torch.Generator(device="cuda").manual_seed(B + H)
+    Kx = (torch.randn(B, H, cap, D, device="cuda", generator=g) * 1.5).to(torch.float16)
+    Vx = torch.randn(B, H, cap, D, device="cuda", generator=g).to(torch.float16)
+    q = (torch.randn(B, H, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    kc, ks = nqkv.alloc_cache(desc)
+    vc, vs = nqkv.alloc_cache(desc)
+    nqkv.quantize_kv_pair(desc, lv, Kx[:, :, :n0], Vx[:, :, :n0], kc, ks, vc, vs, 0)            # slab kernel
+    nqkv.quantize_kv_pair(desc, lv, Kx[:, :, n0:n0 + 3], Vx[:, :, n0:n0 + 3], kc, ks, vc, vs, n0)   # flat kernel
+    S = n0 + 3
+    torch.cuda.synchronize()
+    Kh, Vh = h2n(Kx), h2n(Vx)
+    okc, oks = oracle.new_cache(B, H, D, k, blk, cap)
+    ovc, ovs = oracle.new_cache(B, H, D, k, blk, cap)
+    oracle.quantize_kv(Kh[:, :, :S], k, blk, lv, okc, oks, n_threads=8)
+    oracle.quantize_kv(Vh[:, :, :S], k, blk, lv, ovc, ovs, n_threads=8)
+    assert np.array_equal(h2n(kc)[:, :, :S], okc[:, :, :S]) and np.array_equal(h2n(ks)[:, :, :S], oks[:, :, :S])
+    assert np.array_equal(h2n(vc)[:, :, :S], ovc[:, :, :S]) and np.array_equal(h2n(vs)[:, :, :S], ovs[:, :, :S])
+    # dequantize
+    deq = nqkv.dequantize_kv(desc, lv, vc, vs, 0, S)
+    torch.cuda.synchronize()
+    assert np.array_equal(h2n(deq), oracle.dequantize_kv(ovc, ovs, k, blk, lv, 0, S, n_threads=8))
+    del deq
+    # attention over all S tokens
+    out = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, S, 1.0)
+    torch.cuda.synchronize()
+    ref = oracle.decode_attention(h2n(q), okc, oks, ovc, ovs, k, blk, lv, S, 1.0, n_threads=8)
+    assert attn_err(h2n(out).view(np.float16), ref) <= ATTN_TOL
+    # the fused step appends row S and attends over S + 1
+    out = nqkv.decode_step(desc, lv, q, Kx[:, :, S:S + 1], Vx[:, :, S:S + 1], kc, ks, vc, vs, S, 1.0)
+    torch.cuda.synchronize()
+    oracle.quantize_kv(Kh[:, :, S:S + 1], k, blk, lv, okc, oks, dst_off=S, n_threads=8)
+    oracle.quantize_kv(Vh[:, :, S:S + 1], k, blk, lv, ovc, ovs, dst_off=S, n_threads=8)
+    assert np.array_equal(h2n(kc)[:, :, :S + 1], okc[:, :, :S + 1]) and np.array_equal(h2n(vs)[:, :, :S + 1], ovs[:, :, :S + 1])
+    ref = oracle.decode_attention(h2n(q), okc, oks, ovc, ovs, k, blk, lv, S + 1, 1.0, n_threads=8)
+    assert attn_err(h2n(out).view(np.float16), ref) <= ATTN_TOL
+    # per-sequence lengths: the last batch rows, where a folded index would have wrapped
+    lens = torch.randint(1, S + 2, (B,), device="cuda", generator=g, dtype=torch.int32)
+    out = nqkv.decode_attention_varlen(desc, lv, q, kc, ks, vc, vs, lens, S + 1, 1.0)
+    torch.cuda.synchronize()
+    lens_h = lens.cpu().numpy()
+    for b in list(range(B - 3, B)) + [0, B // 2]:
+        ref_b = oracle.decode_attention(h2n(q)[b:b + 1], okc[b:b + 1], oks[b:b + 1], ovc[b:b + 1], ovs[b:b + 1],
+                                        k, blk, lv, int(lens_h[b]), 1.0)
+        assert attn_err(h2n(out[b:b + 1]).view(np.float16), ref_b) <= ATTN_TOL, b
+    # several queries per sequence
+    Q = 3
+    qm = (torch.randn(B, H, Q, D, device="cuda", generator=g) / math.sqrt(D)).to(torch.float16)
+    outm = nqkv.decode_attention_multi(desc, lv, qm, kc, ks, vc, vs, S + 1, 1.0)
+    torch.cuda.synchronize()
+    refm = oracle.decode_attention_multi(h2n(qm), okc, oks, ovc, ovs, k, blk, lv, S + 1, 1.0, n_threads=8)
+    assert _multi_err(outm, refm) <= ATTN_TOL

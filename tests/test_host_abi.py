@@ -119,7 +119,7 @@ def test_quantize_argument_errors(nqkv):
         for f, v in bad.items():
             setattr(d, f, v)
         assert _quant(nqkv, d, lvp) == nqkv.EINVAL
-    for bad in (dict(k=5), dict(k=1), dict(D=96), dict(D=256), dict(block=32), dict(B=4096, H=16)):
+    for bad in (dict(k=5), dict(k=1), dict(D=96), dict(D=256), dict(block=32), dict(B=4096, H=4097), dict(H=65536), dict(B=32768, H=1)):
         d = nqkv.make_desc(2, 4, 64, 4, 64, 16)
         for f, v in bad.items():
             setattr(d, f, v)
@@ -442,6 +442,27 @@ def test_quantize_hidden_argument_errors(nqkv):
     assert call(d, levels=None) == nqkv.EINVAL
     big = nqkv.make_desc(1, 32, 128, 4, 128, 1 << 20)              # 2 GiB of codes per batch row
     assert call(big, sh=128, st=32 * 128, sb=0, n=1) == nqkv.EUNSUPPORTED
+
+
+def test_many_sequences_are_accepted_uncut_and_refused_cut(nqkv):
+    """More than 65535 (batch row, head) pairs: fine for every call that keeps sequences whole (the
+    automatic plan never cuts them at that count); cutting them needs one counter per pair and is
+    refused beyond the counter table, before any GPU work."""
+    d = nqkv.make_desc(1100, 64, 64, 4, 64, 4096)                  # 70400 pairs
+    need, splits = nqkv.decode_workspace_bytes(d, 4096, 0)
+    assert (need, splits) == (0, 1)
+    need = ctypes.c_size_t(); sp = ctypes.c_int()
+    f = nqkv.lib.nqkv_decode_workspace_bytes
+    assert f(ctypes.byref(d), 4096, 1, ctypes.byref(need), ctypes.byref(sp)) == nqkv.OK
+    assert f(ctypes.byref(d), 4096, 2, ctypes.byref(need), ctypes.byref(sp)) == nqkv.EUNSUPPORTED
+    fm = nqkv.lib.nqkv_decode_multi_workspace_bytes
+    assert fm(ctypes.byref(d), 4096, 4, 0, ctypes.byref(need), ctypes.byref(sp)) == nqkv.OK and sp.value == 1
+    assert fm(ctypes.byref(d), 4096, 4, 2, ctypes.byref(need), ctypes.byref(sp)) == nqkv.EUNSUPPORTED
+    lv, lvp = _levels(nqkv)
+    fa = nqkv.lib.nqkv_decode_attention
+    args = (lvp, FAKE, FAKE, FAKE, FAKE, FAKE, 4096, 1.0, FAKE)
+    assert fa(ctypes.byref(d), *args, FAKE, 1 << 30, 2, None) == nqkv.EUNSUPPORTED
+    assert nqkv.lib.nqkv_decode_attention_static(ctypes.byref(d), *args, 2, None) == nqkv.EUNSUPPORTED
 
 
 def test_benchaux_library_exports_and_argument_errors():
