@@ -362,6 +362,25 @@ def main():
         roofline["frac_of_read_stream"] = round(roofline["achieved"] / stream_gbps, 4)
         for e in configs_out:
             e["frac_of_read_stream"] = round(e["GBps"] / stream_gbps, 4)
+        # ... and to the simplest kernel with the quantizer's read : write mix (4 : 1; the quantizer's own is
+        # 3.7 : 1) and the dequantizer's (1 : 4): a mixed stream runs well below a pure read stream on
+        # this chip, so these are the yardsticks for those two kernels
+        big = torch.empty(1 << 30, dtype=torch.int32, device=dev).fill_(3)          # 4 GiB
+        small = torch.empty(1 << 28, dtype=torch.int32, device=dev)                 # 1 GiB
+        mix = {}
+        for label, (a_, b_, r_, w_) in {"4r:1w": (big, small, 4, 1), "1r:4w": (small, big, 1, 4)}.items():
+            moved = benchaux.mix_stream(a_, b_, r_, w_)
+            t_mx = timed_graph(lambda i: benchaux.mix_stream(a_, b_, r_, w_), 5, min_launches=20)
+            mix[label] = round(moved / (t_mx[0] * 1e-3) / 1e9, 1)
+        del big, small
+        roofline["mix_stream_GBps"] = mix
+        roofline["frac_of_mix_stream"] = round(roofline["achieved"] / mix["4r:1w"], 4)
+        for e in configs_out:
+            if e["kernel"].startswith("quantize"):
+                e["frac_of_mix_stream"] = round(e["GBps"] / mix["4r:1w"], 4)
+        for name_, e in kern.items():
+            if name_.endswith(".dequantize") and "GBps" in e:
+                e["frac_of_mix_stream"] = round(e["GBps"] / mix["1r:4w"], 4)
 
     result = {
         "metric": "effective KV GB/s (quantize + fused decode attn) & decode tokens/s/layer",

@@ -29,6 +29,18 @@ int nqkv_aux_read_stream(const void* src, size_t bytes, void* checksums, void* h
  * known quantity that HBM byte counters of a profiler run are scaled by. */
 int nqkv_aux_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
+/*
+ * A plain kernel with a fixed read : write mix: per tile it reads `reads` x 4 KiB from src and
+ * writes `writes` x 4 KiB to dst (contiguous, 128-bit, non-temporal), tile after tile, for as many
+ * whole tiles as both buffers hold; *tiles_out (host) receives that count, so the bytes moved are
+ * tiles * 4096 * (reads + writes).  (reads, writes) is (4, 1), (1, 4) or (1, 1); anything else
+ * returns -1.  Timed, it is what the memory system gives the simplest kernel with the mix of the
+ * quantizer (4 : 1) or of the dequantizer (1 : 4) -- the yardstick for those kernels.  dst
+ * receives a function of src (tile-wise xor of the pieces read, plus the piece's index).
+ */
+int nqkv_aux_mix_stream(const void* src, size_t src_bytes, void* dst, size_t dst_bytes, int reads, int writes,
+                        size_t* tiles_out, void* hip_stream);
+
 /* Launches a kernel that does nothing: the fixed cost of one launch. */
 int nqkv_aux_empty_launch(void* hip_stream);
 

@@ -560,6 +560,29 @@ def test_benchaux_read_stream_reads_every_word_once_and_copy_copies(n_bytes):
     assert torch.equal(x, y)
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("reads,writes", [(4, 1), (1, 4), (1, 1)])
+def test_benchaux_mix_stream_moves_whole_tiles_and_nothing_else(reads, writes):
+    """The read : write mix probe: as many whole tiles as both buffers hold, every destination word
+    of those tiles a function of the source tile, every word past them untouched."""
+    from paper_2505_16210_amd import benchaux
+    g = torch.Generator(device="cuda").manual_seed(reads * 10 + writes)
+    n_tiles_src, n_tiles_dst = 37, 29
+    x = torch.randint(-2**31, 2**31 - 1, (n_tiles_src * reads * 1024 + 100,), device="cuda", dtype=torch.int32, generator=g)
+    y = torch.full((n_tiles_dst * writes * 1024 + 52,), 0x5a5a5a5a, device="cuda", dtype=torch.int32)
+    moved = benchaux.mix_stream(x, y, reads, writes)
+    torch.cuda.synchronize()
+    tiles = min(n_tiles_src, n_tiles_dst)
+    assert moved == tiles * 4096 * (reads + writes)
+    xs = x.cpu().numpy().view(np.uint32)[:tiles * reads * 1024].reshape(tiles, reads, 256, 4)
+    want = np.bitwise_xor.reduce(xs, axis=1)                                       # [tiles, 256, 4]
+    ys = y.cpu().numpy().view(np.uint32)
+    got = ys[:tiles * writes * 1024].reshape(tiles, writes, 256, 4)
+    for w in range(writes):
+        assert np.array_equal(got[:, w], want + np.uint32(w))
+    assert (ys[tiles * writes * 1024:] == 0x5a5a5a5a).all()
+
+
 # --------------------------------------------------------------------------- the paper's own flow
 @pytest.mark.parametrize("k,D,blk", [(4, 64, 64), (4, 128, 128), (3, 128, 64), (2, 64, 64)])
 def test_paper_flow_dequantize_then_unfused_attention(nqkv, oracle, k, D, blk):

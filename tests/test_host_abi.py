@@ -478,6 +478,12 @@ def test_benchaux_library_exports_and_argument_errors():
     assert f(FAKE, 1000, FAKE, None) == -1                       # whole 16-byte vectors only
     assert benchaux.lib.nqkv_aux_copy(FAKE, FAKE + 8, 1024, None) == -1
     assert benchaux.lib.nqkv_aux_copy(FAKE, FAKE, 0, None) == 0
+    tiles = ctypes.c_size_t(7)
+    m = benchaux.lib.nqkv_aux_mix_stream
+    assert m(FAKE, 1 << 20, FAKE, 1 << 20, 3, 1, ctypes.byref(tiles), None) == -1     # only 4:1, 1:4, 1:1
+    assert m(None, 1 << 20, FAKE, 1 << 20, 4, 1, ctypes.byref(tiles), None) == -1
+    assert m(FAKE, 1 << 20, FAKE + 4, 1 << 20, 4, 1, ctypes.byref(tiles), None) == -1
+    assert m(FAKE, 16383, FAKE, 1 << 20, 4, 1, ctypes.byref(tiles), None) == 0 and tiles.value == 0   # no whole tile: nothing launched
 
 
 def test_per_call_flags(nqkv):
