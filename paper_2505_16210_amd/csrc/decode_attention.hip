@@ -118,6 +118,21 @@ __device__ __forceinline__ void build_lut_bytes_k3(const DecodeParams& p, uint32
   __syncthreads();
 }
 
+// lut_levels[first + sel] for a constant `first` (a multiple of 2) and a wave-uniform sel in [0, 4),
+// from scalar registers.  Indexed by a register, the kernel-argument array is read with a VECTOR
+// load, and so is a select over constant indices (the compiler selects the address and loads
+// afterwards): such a load queues behind the cache prefetches already in flight -- the memory
+// counter is positional -- and the table build would wait for HBM.  The two dwords that hold the
+// four candidates are therefore pinned in scalar registers as values before the selection.
+__device__ __forceinline__ uint32_t uniform_level(const DecodeParams& p, int first, uint32_t sel) {
+  uint32_t d0, d1;
+  __builtin_memcpy(&d0, &p.lut_levels[first], 4);
+  __builtin_memcpy(&d1, &p.lut_levels[(first + 2) & (kMaxLevels - 2)], 4);
+  asm volatile("" : "+s"(d0), "+s"(d1));
+  const uint32_t d = (sel & 2u) ? d1 : d0;
+  return (sel & 1u) ? (d >> 16) : (d & 0xffffu);
+}
+
 // The table at k = 4: row = code byte B, 256 bytes apart, its first 128 bytes 32 copies of the dword
 // {level[B & 15], level[B >> 4]}; lane L reads copy L & 31 (a 64-lane dword read takes two LDS
 // clocks whatever it does, and 32 lanes on 32 distinct banks fit one of them: 32 copies are as
@@ -133,7 +148,7 @@ __device__ __forceinline__ void build_lut_k4(const DecodeParams& p, uint32_t* sm
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const uint32_t e_hi = hi_base + 4 * i;
-    const uint32_t v = lo | ((uint32_t)p.lut_levels[e_hi] << 16);
+    const uint32_t v = lo | (uniform_level(p, 4 * i, hi_base) << 16);
     *reinterpret_cast<uint4*>(smem + (e_lo + 16 * e_hi) * 64 + quad * 4) = make_uint4(v, v, v, v);
   }
   __syncthreads();
@@ -290,7 +305,7 @@ __device__ __forceinline__ void build_lut_k2(const DecodeParams& p, uint32_t* sm
   const uint32_t lo = pick_level(p, r0 & 3, 4) | (pick_level(p, (r0 >> 2) & 3, 4) << 16);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const uint32_t hi = (uint32_t)p.lut_levels[c2_base + 2 * (i & 1)] | ((uint32_t)p.lut_levels[i >> 1] << 16);
+    const uint32_t hi = uniform_level(p, 2 * (i & 1), c2_base) | ((uint32_t)p.lut_levels[i >> 1] << 16);
     *reinterpret_cast<uint4*>(smem + (r0 + 32 * i) * 64 + quad * 4) = make_uint4(lo, hi, lo, hi);
   }
   __syncthreads();

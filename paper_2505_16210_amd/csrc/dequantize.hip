@@ -29,8 +29,6 @@ __global__ __launch_bounds__(kThreadsFor<KBITS>) void dequantize_kernel(const Qu
   constexpr uint32_t kRowBytes = D * KBITS / 8, kScaleRowBytes = NB * 2;
   constexpr uint32_t kMask = (1u << KBITS) - 1u;
   __shared__ float lv[1 << KBITS];
-  if (threadIdx.x < (1 << KBITS)) lv[threadIdx.x] = p.levels.v[threadIdx.x];
-  __syncthreads();
 
   const uint32_t b = blockIdx.z, h = blockIdx.y;
   const int64_t row0 = ((int64_t)b * p.H + h) * p.cap_tokens + p.tok_off;
@@ -69,6 +67,23 @@ __global__ __launch_bounds__(kThreadsFor<KBITS>) void dequantize_kernel(const Qu
     }
     sc[u] = __builtin_amdgcn_raw_buffer_load_b16(scale_r, t * kScaleRowBytes + ((c * 8u) / BLK) * 2u, 0, 0);
   }
+
+  // The level table goes to LDS only now, with the code loads in flight.  Thread i's entry is
+  // selected from the kernel arguments in scalar registers: indexed by the thread -- or selected
+  // without the pin below -- the array is read with a vector load, which here would queue behind
+  // the code loads (and, issued before them, would put its own latency and a barrier in front of
+  // every workgroup's loads).
+  {
+    float mine = 0.0f;
+#pragma unroll
+    for (int i = 0; i < (1 << KBITS); ++i) {
+      float level_i = p.levels.v[i];
+      asm volatile("" : "+s"(level_i));        // a value in a scalar register, not an address to select
+      mine = (threadIdx.x == (unsigned)i) ? level_i : mine;
+    }
+    if (threadIdx.x < (1 << KBITS)) lv[threadIdx.x] = mine;
+  }
+  __syncthreads();
 
 #pragma unroll
   for (int u = 0; u < kPasses; ++u) {
