@@ -35,6 +35,14 @@ import tempfile
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
+# The step's cache is allocated with room for this many tokens after the prompt (one page of the
+# paged layout).  The capacity sets the distance between the (batch, head) slabs of the cache, and
+# both kernels are sensitive to it: with room for exactly one token (16385 rows of 64 bytes: every
+# other slab starts in the middle of a 128-byte line) the decode launch of the step takes 407 us
+# and the step 1.928 ms; with 16, 256, 512, 1024, 2048 or 4096 tokens of room 361-369 us and
+# 1.89-1.91 ms; with 128 (slabs 1 MiB + 8 KiB apart, which piles them onto few memory channels)
+# 420 us and 1.96 ms.
+STEP_HEADROOM = 256
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -101,7 +109,7 @@ def kernels_only(config_names, sweep):
         variants = [(kb, bl) for kb in (4, 3, 2) for bl in (64, 128)] if (cn == "C5" and sweep) else [(cfg.bits, cfg.block)]
         for kb, bl in variants:
             lv = nqkv.build_codebook(kb)
-            desc = nqkv.make_desc(B, H, D, kb, bl, S + 1)
+            desc = nqkv.make_desc(B, H, D, kb, bl, S + STEP_HEADROOM)
             kc, ks = nqkv.alloc_cache(desc, dev)
             vc, vs = nqkv.alloc_cache(desc, dev)
             ws = torch.zeros(2 << 20, dtype=torch.uint8, device=dev)
@@ -256,7 +264,7 @@ def main():
     K5, V5 = workloads.make_kv(cfg, dev, g, n_tokens=S + 1)          # 7 GiB of fp16: larger than any cache (no rotation needed)
     q5 = workloads.make_q(cfg, dev, g)
     lv = nqkv.build_codebook(k)
-    desc = nqkv.make_desc(B, H, D, k, blk, S + 1)
+    desc = nqkv.make_desc(B, H, D, k, blk, S + STEP_HEADROOM)
     kc, ks = nqkv.alloc_cache(desc, dev)
     vc, vs = nqkv.alloc_cache(desc, dev)
     out5 = torch.empty_like(q5)
@@ -391,7 +399,8 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "C5 OPT-30B-shaped layer: B16 H56 D128, 16384 cached tokens, 4-bit block 64; one step = "
                                "quantize the whole K and V prefill (one launch) + one fused decode step (append the new "
-                               "token + dequantize-fused attention over 16385 tokens, one launch)",
+                               "token + dequantize-fused attention over 16385 tokens, one launch); cache capacity "
+                               "%d tokens" % (S + STEP_HEADROOM),
                    "storage": "fp16 in/out, %d-bit codes, fp16 scales" % k,
                    "arithmetic": "fp32 accumulation, fp16 look-up table"},
         "decode_tokens_per_s_per_layer": round(B / (avg(t_dec) * 1e-3), 1),
