@@ -37,11 +37,10 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 # The step's cache is allocated with room for this many tokens after the prompt (one page of the
 # paged layout).  The capacity sets the distance between the (batch, head) slabs of the cache, and
-# both kernels are sensitive to it: with room for exactly one token (16385 rows of 64 bytes: every
-# other slab starts in the middle of a 128-byte line) the decode launch of the step takes 407 us
-# and the step 1.928 ms; with 16, 256, 512, 1024, 2048 or 4096 tokens of room 361-369 us and
-# 1.89-1.91 ms; with 128 (slabs 1 MiB + 8 KiB apart, which piles them onto few memory channels)
-# 420 us and 1.96 ms.
+# both kernels are sensitive to it: with room for 16 to 4096 tokens the step takes 1.89-1.91 ms, with
+# 128 (slabs 1 MiB + 8 KiB apart, which piles them onto few memory channels) 1.96 ms; with room for
+# exactly one token every other slab starts in the middle of a 128-byte line, which cost the decode
+# launch 11 % before the kernel learnt to start its items on a line.
 STEP_HEADROOM = 256
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)

@@ -43,10 +43,10 @@
  * A block never spans tokens or heads (Fig. 5 caption: every token is cut into blocks).
  * Performance note: cap_tokens sets the distance between the (b,h) slabs of a tensor.  The
  * kernels are fastest when a slab of codes (cap_tokens * D*k/8 bytes) is a multiple of 1 KiB, so
- * that every wave load starts on a cache-line boundary (a capacity of 16385 tokens measured 11 %
- * slower in decode attention than 16400 or 16640), and distances of a power of two plus 8 KiB
- * are worth avoiding (slabs streamed together then share few memory channels).  Any capacity is
- * correct.
+ * that every wave load starts on a cache-line boundary (the one-query attention kernels start an
+ * item on a line themselves when k is 2 or 4; otherwise a capacity of 16385 tokens measured 11 %
+ * slower than 16400 or 16640), and distances of a power of two plus 8 KiB are worth avoiding
+ * (slabs streamed together then share few memory channels).  Any capacity is correct.
  *
  * Quantization rule (the paper leaves rounding details open; this is the library's
  * contract): with s = the block's fp16 scale, t_j = (c[j-1] + c[j]) * 0.5f the fp32

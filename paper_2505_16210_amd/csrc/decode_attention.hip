@@ -426,6 +426,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
   const uint32_t scale_voff = g * kScaleRowBytes + ((j * 32) / BLK) * 2;
   uint32_t bh = 0, sp = 0;
   int32_t n_tok = 0, base = 0;      // tokens in the item; this wave's current trip start (item-relative)
+  int32_t front = 0;                // rows taken in before the item's first token, masked (see set_item)
   int64_t pos = 0;                  // FUSE and VARLEN: the sequence's own row for the new token (else p.pos)
   __amdgpu_buffer_rsrc_t kc_r, vc_r, ks_r, vs_r;
   // PAGED: the item's sequence, head and first token (logical), and the pool rows / row count
@@ -470,6 +471,20 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
       n_tok = min(n_tok, max(len - (int32_t)t0, 0));
       pos = len;
       if (PAGED) { item_b = b; item_h = h; item_t0 = (int32_t)t0; }
+    }
+    // Wave loads cover 512 to 1024 contiguous bytes; they are cheapest when they start on a
+    // 128-byte line.  Whether the item's first row does depends on the caller's capacity (the
+    // distance between slabs) and on where a split begins.  When it does not, and whole rows fit
+    // in between, the item starts up to 7 rows EARLIER -- rows of the same tensor, inside the line
+    // its first row shares anyway -- and the tokens taken in are masked out of the softmax in the
+    // item's first trip.  (Measured at B16 H56 D128 S16384, 4 bits, capacity 16385, where every
+    // other slab is 64 bytes off: 407 -> 36x us per launch.)
+    front = 0;
+    if constexpr (!PAGED && 128 % kRowBytes == 0) {
+      const uint32_t past_line = (uint32_t)(reinterpret_cast<uintptr_t>(p.k_codes) + (uint64_t)row0 * kRowBytes) & 127u;
+      front = n_tok > 0 ? (int32_t)min((int64_t)(past_line / kRowBytes), row0) : 0;
+      row0 -= front;
+      n_tok += front;
     }
     base = (int32_t)wave * CHUNK;
     kc_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.k_codes) + row0 * kRowBytes, 0, n_tok * (int)kRowBytes, kBufferFlags);
@@ -682,11 +697,18 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_num_vgpr(128), amdg
         if (LPT == 4) part += dpp_f<kQuadXor2>(part);
         z[r] = part * p.scale_log2e;
       }
-      if (left < CHUNK) {
+      if (left < CHUNK || (front != 0 && base == 0)) {
         // the ragged last trip of the item (a uniform branch): tokens past the end read as zero codes
-        // and zero scales, a score of 0, and must not enter the softmax
+        // and zero scales, a score of 0, and must not enter the softmax; nor must the rows taken in
+        // before the item's first token (first trip only: they are fewer than one round)
 #pragma unroll
         for (int r = 0; r < kRounds; ++r) z[r] = ((int32_t)g < left - r * TPR) ? z[r] : -INFINITY;
+        if (base == 0) {
+          // (their value scales are whatever memory holds there, possibly not even finite: a zero
+          // weight times such a scale must not reach the accumulators)
+          z[0] = ((int32_t)g >= front) ? z[0] : -INFINITY;
+          vsc[0] = ((int32_t)g >= front) ? vsc[0] : (uint16_t)0;
+        }
       }
       float m_trip = fmaxf(z[0], z[1]);
 #pragma unroll

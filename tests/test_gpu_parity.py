@@ -1468,3 +1468,56 @@ def test_more_than_65535_sequences(nqkv, oracle, k, D, blk, B, H, n0):
     torch.cuda.synchronize()
     refm = oracle.decode_attention_multi(h2n(qm), okc, oks, ovc, ovs, k, blk, lv, S + 1, 1.0, n_threads=8)
     assert _multi_err(outm, refm) <= ATTN_TOL
+
+
+# --------------------------------------------------------------------------- slabs off the cache-line grid
+@pytest.mark.gpu
+@pytest.mark.parametrize("k,D,blk,cap", [(4, 128, 64, 1301), (4, 64, 64, 1303), (2, 128, 128, 1299), (2, 64, 64, 1297), (3, 128, 64, 1301)])
+def test_decode_with_slabs_off_the_cache_line_grid(nqkv, oracle, k, D, blk, cap):
+    """Capacities that put (batch, head) slabs in the middle of a 128-byte line: the kernel then
+    starts an item a few rows early, on the line, and masks those rows.  They are the last rows of
+    the previous slab -- here never written by the quantizer and filled with the worst that memory
+    can hold (NaN scales, all-ones codes): nothing of them may reach the result.  Attention for
+    every split count (pieces start off the grid too), the fused step, per-sequence lengths."""
+    B, H, S = 2, 3, 1237
+    lv, desc, q, kc, ks, vc, vs = _build_cache(nqkv, k, D, blk, B, H, S, cap, seed=cap)
+    kc[:, :, S:] = 0xFF
+    vc[:, :, S:] = 0xFF
+    ks[:, :, S:] = float("nan")
+    vs[:, :, S:] = float("nan")
+    torch.cuda.synchronize()
+    hk = [h2n(t) for t in (q, kc, ks, vc, vs)]
+    for seq in (1, 5, 64, 129, 1000, S):
+        ref = oracle.decode_attention(hk[0], hk[1], hk[2], hk[3], hk[4], k, blk, lv, seq, 0.9, n_threads=8)
+        for ns in (0, 1, 2, 3, 7):
+            if ns > seq:
+                continue
+            out = nqkv.decode_attention(desc, lv, q, kc, ks, vc, vs, seq, 0.9, num_splits=ns)
+            torch.cuda.synchronize()
+            o = h2n(out).view(np.float16)
+            assert np.isfinite(o.astype(np.float32)).all(), (seq, ns)
+            assert attn_err(o, ref) <= ATTN_TOL, (k, D, blk, cap, seq, ns)
+    # per-sequence lengths, one of them 0 tokens short of nothing: lengths 1 and S
+    lens = torch.tensor([1, S], dtype=torch.int32, device="cuda")
+    out = nqkv.decode_attention_varlen(desc, lv, q, kc, ks, vc, vs, lens, S, 0.9)
+    torch.cuda.synchronize()
+    for b, n in enumerate((1, S)):
+        ref_b = oracle.decode_attention(hk[0][b:b + 1], hk[1][b:b + 1], hk[2][b:b + 1], hk[3][b:b + 1], hk[4][b:b + 1],
+                                        k, blk, lv, n, 0.9)
+        assert attn_err(h2n(out[b:b + 1]).view(np.float16), ref_b) <= ATTN_TOL, (b, n)
+    # the fused step at row S: appends there and attends over S + 1 tokens
+    g = torch.Generator(device="cuda").manual_seed(cap + 1)
+    kn = (torch.randn(B, H, 1, D, device="cuda", generator=g) * 1.5).to(torch.float16)
+    vn = torch.randn(B, H, 1, D, device="cuda", generator=g).to(torch.float16)
+    for ns in (0, 2, 5):
+        out = nqkv.decode_step(desc, lv, q, kn, vn, kc, ks, vc, vs, S, 0.9, num_splits=ns)
+        torch.cuda.synchronize()
+        okc, oks, ovc, ovs = (h2n(t).copy() for t in (kc, ks, vc, vs))
+        ck, cs = oracle.new_cache(B, H, D, k, blk, cap)
+        cv, cvs = oracle.new_cache(B, H, D, k, blk, cap)
+        oracle.quantize_kv(h2n(kn), k, blk, lv, ck, cs, dst_off=S)
+        oracle.quantize_kv(h2n(vn), k, blk, lv, cv, cvs, dst_off=S)
+        assert np.array_equal(okc[:, :, S], ck[:, :, S]) and np.array_equal(oks[:, :, S], cs[:, :, S])
+        assert np.array_equal(ovc[:, :, S], cv[:, :, S]) and np.array_equal(ovs[:, :, S], cvs[:, :, S])
+        ref = oracle.decode_attention(hk[0], okc, oks, ovc, ovs, k, blk, lv, S + 1, 0.9, n_threads=8)
+        assert attn_err(h2n(out).view(np.float16), ref) <= ATTN_TOL, (k, D, blk, cap, ns)
