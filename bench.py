@@ -318,8 +318,9 @@ def main():
                     "in_step": {"avg_launch_us": round(avg(t_dec) * 1e3, 2), "min_launch_us": round(t_dec[0] * 1e3, 2),
                                 "achieved": round(dec_gbps, 1), "frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
                                 "note": "launched right behind the quantizer, which has just written 2 GB: this launch also "
-                                        "pays for the dirty lines that pass left in the last-level cache and runs at the shader "
-                                        "clock the power management settled on during it"}}}
+                                        "pays for writing back the dirty lines that pass left in the memory-side last-level "
+                                        "cache (measured: the cost follows recent writes of any kernel, survives 1 ms of "
+                                        "streaming reads in between and is absent behind a read-only kernel)"}}}
     if isinstance(traffic, dict) and traffic.get("quantize"):
         tq = traffic["quantize"]
         roofline["traffic"] = tq["read_bytes"] + tq["written_bytes"]
