@@ -29,6 +29,22 @@ __global__ __launch_bounds__(kThreadsFor<KBITS>) void dequantize_kernel(const Qu
   constexpr uint32_t kRowBytes = D * KBITS / 8, kScaleRowBytes = NB * 2;
   constexpr uint32_t kMask = (1u << KBITS) - 1u;
   __shared__ float lv[1 << KBITS];
+  // The level table (2^k floats in LDS), filled by the first 2^k threads.  Where it is filled
+  // matters by a few per cent and was settled by measurement (B16 H56 D128 S16384, one tensor):
+  //   k = 4: after the code loads have been issued, from scalar registers   758-778 us
+  //          (before them, by a load indexed with the thread: 778-789; before them, from
+  //          scalar registers: 797)
+  //   k = 3: before the loads, by a load indexed with the thread            780 us
+  //          (after them: 800-805; before them from scalar registers: 814)
+  //   k = 2: 704-712 us every way
+  // A thread-indexed read of the kernel-argument array is a vector load with a barrier behind it;
+  // in front of the code loads it delays each workgroup's start a little, which at k = 3 -- twice
+  // the code loads in flight -- spreads the workgroups' phases apart and helps; behind the code
+  // loads it would queue after them (the memory counter is positional), hence the scalar form there.
+  if constexpr (KBITS == 3) {
+    if (threadIdx.x < (1 << KBITS)) lv[threadIdx.x] = p.levels.v[threadIdx.x];
+    __syncthreads();
+  }
 
   const uint32_t b = blockIdx.z, h = blockIdx.y;
   const int64_t row0 = ((int64_t)b * p.H + h) * p.cap_tokens + p.tok_off;
@@ -68,12 +84,7 @@ __global__ __launch_bounds__(kThreadsFor<KBITS>) void dequantize_kernel(const Qu
     sc[u] = __builtin_amdgcn_raw_buffer_load_b16(scale_r, t * kScaleRowBytes + ((c * 8u) / BLK) * 2u, 0, 0);
   }
 
-  // The level table goes to LDS only now, with the code loads in flight.  Thread i's entry is
-  // selected from the kernel arguments in scalar registers: indexed by the thread -- or selected
-  // without the pin below -- the array is read with a vector load, which here would queue behind
-  // the code loads (and, issued before them, would put its own latency and a barrier in front of
-  // every workgroup's loads).
-  {
+  if constexpr (KBITS != 3) {
     float mine = 0.0f;
 #pragma unroll
     for (int i = 0; i < (1 << KBITS); ++i) {
@@ -82,8 +93,8 @@ __global__ __launch_bounds__(kThreadsFor<KBITS>) void dequantize_kernel(const Qu
       mine = (threadIdx.x == (unsigned)i) ? level_i : mine;
     }
     if (threadIdx.x < (1 << KBITS)) lv[threadIdx.x] = mine;
+    __syncthreads();
   }
-  __syncthreads();
 
 #pragma unroll
   for (int u = 0; u < kPasses; ++u) {
