@@ -85,6 +85,43 @@ def test_c5_sweep_sampled_slabs(env, oracle, k, blk):
     torch.cuda.empty_cache()
 
 
+def test_c5_bench_step_prefill_then_fused_decode_step(env, oracle):
+    """The step bench.py times, as it launches it: the whole C5 prefill quantized in one launch into
+    a cache with room after the prompt (the bench's own capacity), then ONE fused decode step that
+    appends row S and attends over S + 1 tokens.  The oracle follows two whole batch rows."""
+    import importlib.util, os
+    nqkv, workloads = env
+    spec = importlib.util.spec_from_file_location("bench", os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    cfg = workloads.C5
+    B, H, D, S, k, blk = cfg.B, cfg.H, cfg.D, cfg.S, cfg.bits, cfg.block
+    cap = S + bench.STEP_HEADROOM
+    dev = torch.device("cuda:0")
+    g = workloads.make_generator(cfg, dev)
+    K, V = workloads.make_kv(cfg, dev, g, n_tokens=S + 1)
+    q = workloads.make_q(cfg, dev, g)
+    lv = nqkv.build_codebook(k)
+    desc = nqkv.make_desc(B, H, D, k, blk, cap)
+    kc, ks = nqkv.alloc_cache(desc, dev)
+    vc, vs = nqkv.alloc_cache(desc, dev)
+    nqkv.quantize_kv_pair(desc, lv, K[:, :, :S], V[:, :, :S], kc, ks, vc, vs, 0)
+    out = nqkv.decode_step(desc, lv, q, K[:, :, S:], V[:, :, S:], kc, ks, vc, vs, S, 1.0)
+    torch.cuda.synchronize()
+    for b in (0, B - 1):
+        sl = slice(b, b + 1)
+        okc, oks = oracle.new_cache(1, H, D, k, blk, S + 1)
+        ovc, ovs = oracle.new_cache(1, H, D, k, blk, S + 1)
+        oracle.quantize_kv(bits(K[sl]), k, blk, lv, okc, oks, n_threads=THREADS)
+        oracle.quantize_kv(bits(V[sl]), k, blk, lv, ovc, ovs, n_threads=THREADS)
+        assert np.array_equal(bits(kc[sl, :, :S + 1]), okc) and np.array_equal(bits(ks[sl, :, :S + 1]), oks), b
+        assert np.array_equal(bits(vc[sl, :, :S + 1]), ovc) and np.array_equal(bits(vs[sl, :, :S + 1]), ovs), b
+        ref = oracle.decode_attention(bits(q[sl]), okc, oks, ovc, ovs, k, blk, lv, S + 1, 1.0, n_threads=THREADS)
+        assert attn_err(out[sl].cpu().numpy(), ref) <= ATTN_TOL, b
+    del K, V, kc, ks, vc, vs
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("name,q_len,rows,k", [("C3", 4, (0, 31), 4), ("C4", 16, (0,), 4), ("C2", 5, (0, 7), 4),
                                                ("C3", 7, (5,), 3), ("C3", 16, (17,), 2), ("C2", 3, (3,), 3)])
 def test_multi_query_attention_full_size(env, oracle, name, q_len, rows, k):
