@@ -86,3 +86,34 @@ def test_static_entry_refuses_what_does_not_fit_and_bad_arguments(nqkv):
     assert bool((out == 7.0).all())
     rc = nqkv.lib.nqkv_decode_attention_static(ctypes.byref(desc), None, None, None, None, None, None, 4096, 1.0, None, 1, None)
     assert rc == nqkv.EINVAL
+
+
+def test_static_entry_captured_into_a_hip_graph_and_replayed(nqkv):
+    """What the entry point is for: a launch that carries no allocation and no workspace argument can
+    be recorded into a HIP graph.  (The array's address is looked up on the first call on a device,
+    so one eager call comes first.)  Three replays with the program's own eager work between them;
+    every replay equals the eager result bit for bit -- the counters are cleared by a kernel, not by
+    a memset node."""
+    args = _cache(nqkv, 4, 128, 64, 2, 4, 9000, seed=9)
+    lv, desc, q, kc, ks, vc, vs = args
+    assert nqkv.decode_workspace_bytes(desc, 9000, 0)[1] > 1
+    eager = torch.empty_like(q)
+    nqkv.decode_attention_static(desc, lv, q, kc, ks, vc, vs, 9000, 0.9, out=eager)
+    torch.cuda.synchronize()
+    out = torch.empty_like(q)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            nqkv.decode_attention_static(desc, lv, q, kc, ks, vc, vs, 9000, 0.9, out=out, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    other = _cache(nqkv, 2, 64, 64, 3, 2, 500, seed=10)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), rep
+        # eager work on the same scratch array between the replays, with another geometry
+        o2, r2 = _both(nqkv, other, 500, 0)
+        assert torch.equal(o2, r2)
