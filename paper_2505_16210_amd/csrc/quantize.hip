@@ -142,8 +142,10 @@ constexpr uint32_t kDropStore = 0xffffffffu;   // voffset outside every descript
 // faster (1.67 -> 1.52 ms on 3.8 G elements per tensor).
 constexpr int kNonTemporal = 2;
 
-template <int KBITS, int D, int BLK, bool FAST, bool CONTIG, bool PAGED = false>
-__global__ __launch_bounds__(kThreads) void quantize_slab_kernel(const QuantParams p) {
+template <int KBITS, int D, int BLK, bool FAST, bool CONTIG, bool PAGED, int THREADS, int UNROLL>
+__global__ __launch_bounds__(THREADS) void quantize_slab_kernel(const QuantParams p) {
+  // (the tile shape of this kernel: see launch_slab)
+  constexpr int kThreads = THREADS, kUnroll = UNROLL;
   constexpr int CPR = D / 8;      // chunks per token row
   constexpr int LPB = BLK / 8;    // lanes that share one block
   constexpr int NB = D / BLK;
@@ -374,31 +376,50 @@ hipError_t launch_hidden_one(const QuantParams& p, int lanes_per_block, hipStrea
   return hipGetLastError();
 }
 
+// Tile shapes of the slab kernel: workgroups of 256 lanes taking 4 chunks each (64 tokens of a
+// 128-wide head per workgroup), or of 128 lanes taking 2 (16 tokens).  Measured on MI355X, K and V
+// in one launch, 4 bits (3 and 2 alike), large / small tile:
+//   B16 H56 D128 S16384   1.48-1.51 ms / 1.41-1.42 ms     (block 128: 1.50-1.53 / 1.42)
+//   B1  H32 D128 S32768   106.7 us     / 107.2 us
+//   B32 H32 D128 S2048    213 us       / 220 us
+//   B8  H32 D64  S2048    28.8 us      / 28.8 us
+// The small tile interleaves the read and the write stream more finely, which the memory system
+// rewards on long runs; short slabs prefer fewer, larger workgroups.  Long runs (8192 tokens per
+// slab and more) take the small tile.  (Register counts -- 47 against 37 -- allow full occupancy
+// either way; 128 lanes x 3 or 256 x 2 land in between, 512 x 1 and 256 x 1 are 10-20 % slower.)
+constexpr int kLargeTileThreads = 256, kLargeTileUnroll = 4;
+constexpr int kSmallTileThreads = 128, kSmallTileUnroll = 2;
+constexpr int64_t kSmallTileFromTokens = 8192;
+
+template <int KBITS, int D, int BLK, bool PAGED, int THREADS, int UNROLL>
+void launch_slab(const QuantParams& p, dim3 grid, hipStream_t stream) {
+  const bool fast = p.impl == 0, contig = p.stride_t == D;
+  if (fast && contig)       hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, true, true, PAGED, THREADS, UNROLL>), grid, dim3(THREADS), 0, stream, p);
+  else if (fast)            hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, true, false, PAGED, THREADS, UNROLL>), grid, dim3(THREADS), 0, stream, p);
+  else if (contig)          hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, false, true, PAGED, THREADS, UNROLL>), grid, dim3(THREADS), 0, stream, p);
+  else                      hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, false, false, PAGED, THREADS, UNROLL>), grid, dim3(THREADS), 0, stream, p);
+}
+
 template <int KBITS, int D, int BLK>
 hipError_t launch_one(const QuantParams& p, hipStream_t stream) {
   constexpr int CPR = D / 8;
   const int64_t chunks_per_slab = p.n_tokens * CPR;
   // few tokens per (b,h): one flat grid over all rows (its chunk index is a 32-bit number)
   const bool flat = chunks_per_slab < 2 * kThreads && chunks_per_slab * p.B * p.H < ((int64_t)1 << 31);
-  const bool fast = p.impl == 0;
-  const int tile = kThreads * kUnroll;
-  dim3 grid;
   if (flat) {
+    const int tile = kThreads * kUnroll;
     const int64_t total = chunks_per_slab * p.B * p.H;
-    grid = dim3((unsigned)((total + tile - 1) / tile), 1, (unsigned)p.n_tensors);
+    const dim3 grid((unsigned)((total + tile - 1) / tile), 1, (unsigned)p.n_tensors);
+    if (p.impl == 0) hipLaunchKernelGGL((quantize_kernel<KBITS, D, BLK, true, true>), grid, dim3(kThreads), 0, stream, p);
+    else             hipLaunchKernelGGL((quantize_kernel<KBITS, D, BLK, false, true>), grid, dim3(kThreads), 0, stream, p);
+  } else if (p.n_tokens >= kSmallTileFromTokens) {
+    constexpr int tile = kSmallTileThreads * kSmallTileUnroll;
+    launch_slab<KBITS, D, BLK, false, kSmallTileThreads, kSmallTileUnroll>(
+        p, dim3((unsigned)((chunks_per_slab + tile - 1) / tile), (unsigned)p.H, (unsigned)(p.B * p.n_tensors)), stream);
   } else {
-    grid = dim3((unsigned)((chunks_per_slab + tile - 1) / tile), (unsigned)p.H,
-                (unsigned)(p.B * p.n_tensors));
-  }
-  if (flat) {
-    if (fast) hipLaunchKernelGGL((quantize_kernel<KBITS, D, BLK, true, true>), grid, dim3(kThreads), 0, stream, p);
-    else      hipLaunchKernelGGL((quantize_kernel<KBITS, D, BLK, false, true>), grid, dim3(kThreads), 0, stream, p);
-  } else {
-    const bool contig = p.stride_t == D;
-    if (fast && contig)       hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, true, true>), grid, dim3(kThreads), 0, stream, p);
-    else if (fast)            hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, true, false>), grid, dim3(kThreads), 0, stream, p);
-    else if (contig)          hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, false, true>), grid, dim3(kThreads), 0, stream, p);
-    else                      hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, false, false>), grid, dim3(kThreads), 0, stream, p);
+    constexpr int tile = kLargeTileThreads * kLargeTileUnroll;
+    launch_slab<KBITS, D, BLK, false, kLargeTileThreads, kLargeTileUnroll>(
+        p, dim3((unsigned)((chunks_per_slab + tile - 1) / tile), (unsigned)p.H, (unsigned)(p.B * p.n_tensors)), stream);
   }
   return hipGetLastError();
 }
@@ -414,21 +435,22 @@ hipError_t launch_k(const QuantParams& p, int D, int blk, hipStream_t stream) {
 }  // namespace
 
 namespace {
-template <int KBITS, int D, int BLK>
-hipError_t launch_paged_one(const QuantParams& p, hipStream_t stream) {
-  constexpr int kTileTok = kThreads * kUnroll / (D / 8);
+template <int KBITS, int D, int BLK, int THREADS, int UNROLL>
+hipError_t launch_paged_tile(const QuantParams& p, hipStream_t stream) {
+  constexpr int kTileTok = THREADS * UNROLL / (D / 8);       // 16 .. 128: divides every page size
   // tiles lie over absolute token positions: the run [tok_off, tok_off + n) touches last - first + 1
   // of them; with per-sequence offsets, as many as a run of n tokens can touch at worst (workgroups
   // past a sequence's run find nothing to do)
   const int64_t first = p.tok_off / kTileTok, last = (p.tok_off + p.n_tokens - 1) / kTileTok;
   const int64_t tiles = p.tok_offs ? (p.n_tokens - 1 + kTileTok - 1) / kTileTok + 1 : last - first + 1;
-  const dim3 grid((unsigned)tiles, (unsigned)p.H, (unsigned)(p.B * p.n_tensors));
-  const bool fast = p.impl == 0, contig = p.stride_t == D;
-  if (fast && contig)       hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, true, true, true>), grid, dim3(kThreads), 0, stream, p);
-  else if (fast)            hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, true, false, true>), grid, dim3(kThreads), 0, stream, p);
-  else if (contig)          hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, false, true, true>), grid, dim3(kThreads), 0, stream, p);
-  else                      hipLaunchKernelGGL((quantize_slab_kernel<KBITS, D, BLK, false, false, true>), grid, dim3(kThreads), 0, stream, p);
+  launch_slab<KBITS, D, BLK, true, THREADS, UNROLL>(p, dim3((unsigned)tiles, (unsigned)p.H, (unsigned)(p.B * p.n_tensors)), stream);
   return hipGetLastError();
+}
+
+template <int KBITS, int D, int BLK>
+hipError_t launch_paged_one(const QuantParams& p, hipStream_t stream) {
+  if (p.n_tokens >= kSmallTileFromTokens) return launch_paged_tile<KBITS, D, BLK, kSmallTileThreads, kSmallTileUnroll>(p, stream);
+  return launch_paged_tile<KBITS, D, BLK, kLargeTileThreads, kLargeTileUnroll>(p, stream);
 }
 
 template <int KBITS>
