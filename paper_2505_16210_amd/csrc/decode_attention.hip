@@ -72,7 +72,7 @@
 namespace nqkv {
 namespace {
 
-constexpr int kTimelineOffset = 65536, kTimelineItems = 1024;
+[[maybe_unused]] constexpr int kTimelineOffset = 65536, kTimelineItems = 1024;   // used by the measurement build only
 constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
 constexpr int kRounds = 4;               // wave loads of K (and of V) in flight per trip
